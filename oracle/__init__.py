@@ -1,0 +1,206 @@
+"""CPU oracle (fp64 direct loops) for the 3-D U-Net step operators.
+
+TEST INFRASTRUCTURE ONLY.  Only tests, the smoke check and the benchmark's
+cpu_baseline leg may import this package; the product path never does.  It
+shares no code with the GPU library.  The arithmetic lives in oracle.c (built
+with gcc into liboracle.so by `oracle.build()`); this file only marshals numpy
+arrays.  See oracle.c for the definitions and what pins them.
+"""
+import ctypes
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SO = os.path.join(_HERE, "liboracle.so")
+_lib = None
+
+_i64 = ctypes.c_int64
+_dp = ctypes.POINTER(ctypes.c_double)
+
+
+def build(force=True):
+    """Compile oracle.c with gcc (-O2, OpenMP over the outer loops only)."""
+    src = os.path.join(_HERE, "oracle.c")
+    if not force and os.path.exists(_SO) and os.path.getmtime(_SO) >= os.path.getmtime(src):
+        return _SO
+    subprocess.check_call(["gcc", "-O2", "-fopenmp", "-fPIC", "-shared", "-std=c99",
+                           "-o", _SO, src, "-lm"])
+    global _lib
+    _lib = None
+    return _SO
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(_SO):
+            build()
+        _lib = ctypes.CDLL(_SO)
+    return _lib
+
+
+def _d(a):
+    a = np.ascontiguousarray(a, dtype=np.float64)
+    return a, a.ctypes.data_as(_dp)
+
+
+def _opt(a):
+    if a is None:
+        return None, None
+    return _d(a)
+
+
+def bf16_to_f64(bits):
+    """bf16 bit patterns (uint16) -> float64, exact."""
+    u = np.ascontiguousarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)
+    return u.view(np.float32).astype(np.float64)
+
+
+def round_bf16(a):
+    """float64 -> nearest-even bf16 value of its float32 rounding, as float64.
+
+    Mirrors a GPU that accumulates in fp32 and stores bf16 (storage emulation for
+    chained comparisons)."""
+    f = np.ascontiguousarray(a, dtype=np.float64).astype(np.float32)
+    u = f.view(np.uint32)
+    r = (u + (np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1)))) & np.uint32(0xFFFF0000)
+    return r.view(np.float32).astype(np.float64)
+
+
+def conv3d_fwd(x, w, b=None, relu=False):
+    N, D, H, W, Ci = x.shape
+    Co = w.shape[4]
+    assert w.shape == (3, 3, 3, Ci, Co)
+    x, xp = _d(x); w, wp = _d(w); b, bp = _opt(b)
+    y = np.empty((N, D, H, W, Co), dtype=np.float64)
+    _load().orc_conv3d_fwd(xp, wp, bp, y.ctypes.data_as(_dp), _i64(N), _i64(D), _i64(H), _i64(W),
+                           _i64(Ci), _i64(Co), ctypes.c_int(int(relu)))
+    return y
+
+
+def conv3d_fwd_points(x, w, b, relu, pts):
+    N, D, H, W, Ci = x.shape
+    Co = w.shape[4]
+    x, xp = _d(x); w, wp = _d(w); b, bp = _opt(b)
+    pts = np.ascontiguousarray(pts, dtype=np.int64)
+    out = np.empty((pts.shape[0], Co), dtype=np.float64)
+    _load().orc_conv3d_fwd_points(xp, wp, bp, out.ctypes.data_as(_dp),
+                                  pts.ctypes.data_as(ctypes.POINTER(_i64)), _i64(pts.shape[0]),
+                                  _i64(N), _i64(D), _i64(H), _i64(W), _i64(Ci), _i64(Co),
+                                  ctypes.c_int(int(relu)))
+    return out
+
+
+def relu_bwd(dy, y):
+    dy, dp_ = _d(dy); y, yp = _d(y)
+    g = np.empty_like(dy)
+    _load().orc_relu_bwd(dp_, yp, g.ctypes.data_as(_dp), _i64(dy.size))
+    return g
+
+
+def conv3d_bwd_data(g, w):
+    N, D, H, W, Co = g.shape
+    Ci = w.shape[3]
+    assert w.shape == (3, 3, 3, Ci, Co)
+    g, gp = _d(g); w, wp = _d(w)
+    dx = np.empty((N, D, H, W, Ci), dtype=np.float64)
+    _load().orc_conv3d_bwd_data(gp, wp, dx.ctypes.data_as(_dp), _i64(N), _i64(D), _i64(H), _i64(W),
+                                _i64(Ci), _i64(Co))
+    return dx
+
+
+def conv3d_bwd_weight(x, g):
+    N, D, H, W, Ci = x.shape
+    Co = g.shape[4]
+    assert g.shape[:4] == x.shape[:4]
+    x, xp = _d(x); g, gp = _d(g)
+    dW = np.empty((3, 3, 3, Ci, Co), dtype=np.float64)
+    db = np.empty((Co,), dtype=np.float64)
+    _load().orc_conv3d_bwd_weight(xp, gp, dW.ctypes.data_as(_dp), db.ctypes.data_as(_dp),
+                                  _i64(N), _i64(D), _i64(H), _i64(W), _i64(Ci), _i64(Co))
+    return dW, db
+
+
+def conv3d_bwd_weight_entries(x, g, entries):
+    N, D, H, W, Ci = x.shape
+    Co = g.shape[4]
+    x, xp = _d(x); g, gp = _d(g)
+    ent = np.ascontiguousarray(entries, dtype=np.int64)
+    out = np.empty((ent.shape[0],), dtype=np.float64)
+    _load().orc_conv3d_bwd_weight_entries(xp, gp, out.ctypes.data_as(_dp),
+                                          ent.ctypes.data_as(ctypes.POINTER(_i64)), _i64(ent.shape[0]),
+                                          _i64(N), _i64(D), _i64(H), _i64(W), _i64(Ci), _i64(Co))
+    return out
+
+
+def pool3d_fwd(x):
+    N, D, H, W, C = x.shape
+    assert D % 2 == 0 and H % 2 == 0 and W % 2 == 0
+    x, xp = _d(x)
+    y = np.empty((N, D // 2, H // 2, W // 2, C), dtype=np.float64)
+    _load().orc_pool3d_fwd(xp, y.ctypes.data_as(_dp), _i64(N), _i64(D), _i64(H), _i64(W), _i64(C))
+    return y
+
+
+def pool3d_bwd(x, dy):
+    N, D, H, W, C = x.shape
+    assert dy.shape == (N, D // 2, H // 2, W // 2, C)
+    x, xp = _d(x); dy, dyp = _d(dy)
+    dx = np.empty_like(x)
+    _load().orc_pool3d_bwd(xp, dyp, dx.ctypes.data_as(_dp), _i64(N), _i64(D), _i64(H), _i64(W), _i64(C))
+    return dx
+
+
+def upconv3d_fwd(x, w, b=None):
+    N, D, H, W, Ci = x.shape
+    Co = w.shape[4]
+    assert w.shape == (2, 2, 2, Ci, Co)
+    x, xp = _d(x); w, wp = _d(w); b, bp = _opt(b)
+    y = np.empty((N, 2 * D, 2 * H, 2 * W, Co), dtype=np.float64)
+    _load().orc_upconv3d_fwd(xp, wp, bp, y.ctypes.data_as(_dp), _i64(N), _i64(D), _i64(H), _i64(W),
+                             _i64(Ci), _i64(Co))
+    return y
+
+
+def upconv3d_bwd_data(dy, w):
+    N, D2, H2, W2, Co = dy.shape
+    Ci = w.shape[3]
+    D, H, W = D2 // 2, H2 // 2, W2 // 2
+    dy, dyp = _d(dy); w, wp = _d(w)
+    dx = np.empty((N, D, H, W, Ci), dtype=np.float64)
+    _load().orc_upconv3d_bwd_data(dyp, wp, dx.ctypes.data_as(_dp), _i64(N), _i64(D), _i64(H), _i64(W),
+                                  _i64(Ci), _i64(Co))
+    return dx
+
+
+def upconv3d_bwd_weight(x, dy):
+    N, D, H, W, Ci = x.shape
+    Co = dy.shape[4]
+    assert dy.shape[:4] == (N, 2 * D, 2 * H, 2 * W)
+    x, xp = _d(x); dy, dyp = _d(dy)
+    dW = np.empty((2, 2, 2, Ci, Co), dtype=np.float64)
+    db = np.empty((Co,), dtype=np.float64)
+    _load().orc_upconv3d_bwd_weight(xp, dyp, dW.ctypes.data_as(_dp), db.ctypes.data_as(_dp),
+                                    _i64(N), _i64(D), _i64(H), _i64(W), _i64(Ci), _i64(Co))
+    return dW, db
+
+
+def head_softmax_ce(a, wh, bh, labels):
+    """Returns dict(loss, logits, da, dW, db); a is [..., C], labels uint8 with a's leading shape."""
+    C = a.shape[-1]
+    K = wh.shape[1]
+    V = a.size // C
+    a_, ap = _d(a); wh, whp = _d(wh); bh, bhp = _opt(bh)
+    lab = np.ascontiguousarray(labels, dtype=np.uint8).reshape(-1)
+    assert lab.size == V
+    loss = ctypes.c_double(0.0)
+    logits = np.empty((V, K), dtype=np.float64)
+    da = np.empty_like(a_)
+    dW = np.empty((C, K), dtype=np.float64)
+    db = np.empty((K,), dtype=np.float64)
+    _load().orc_head_softmax_ce(ap, whp, bhp, lab.ctypes.data_as(ctypes.POINTER(ctypes.c_uint8)),
+                                ctypes.byref(loss), logits.ctypes.data_as(_dp), da.ctypes.data_as(_dp),
+                                dW.ctypes.data_as(_dp), db.ctypes.data_as(_dp), _i64(V), _i64(C), _i64(K))
+    return {"loss": loss.value, "logits": logits.reshape(a.shape[:-1] + (K,)), "da": da, "dW": dW, "db": db}
