@@ -1,0 +1,221 @@
+/*
+ * k3 -- C-ABI boundary of the MI355X (gfx950) 3-D U-Net training-step kernels and the
+ * Large-Model-Support (LMS) activation swap engine.
+ *
+ * What the calls compute follows the paper's statement of the problem: a 3-D
+ * encoder/decoder segmentation network built from 3x3x3 convolution layers, 2x2x2
+ * max-pooling layers, an up-sampling decoder layer and a per-voxel three-class
+ * likelihood (sections 3 and 4.1), trained with activations that are parked in host
+ * memory between their forward and backward use (section 2.2).
+ *
+ * Conventions
+ *  - Every function returns an int status: K3_OK (0) or a negative K3_E_* code.  No
+ *    exceptions, no aborts.  k3_last_hip_error() returns the last HIP error seen by
+ *    the calling thread when the status was K3_E_HIP.
+ *  - "dev" pointers are device (HBM) addresses, "host" pointers are host addresses.
+ *    The caller owns every buffer it passes; the library only borrows pointers for
+ *    the work it enqueues and keeps none after that work has run.
+ *  - Compute calls are asynchronous: they enqueue kernels on the caller's stream
+ *    (`stream` is a hipStream_t passed as void*; NULL is the default stream) and do
+ *    not synchronise.
+ *  - Activations are dense NDHWC (channel fastest).  3x3x3 weights are
+ *    [kd][kh][kw][C_in][C_out]; transposed-conv weights [i][j][k][C_in][C_out]; head
+ *    weights [C][K]; all in the activation dtype except the head (fp32).  Biases,
+ *    weight gradients, bias gradients, logits and the loss are fp32.
+ *  - bf16 tensors hold round-to-nearest-even values; all accumulation is fp32.
+ *  - Results are run-to-run bit-identical: no floating-point atomics are used.
+ */
+#ifndef K3_H
+#define K3_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+    K3_OK = 0,
+    K3_E_BADARG = -1,      /* null pointer, negative size, unknown dtype */
+    K3_E_SHAPE = -2,       /* descriptors disagree, odd dimension given to pooling */
+    K3_E_UNSUPPORTED = -3, /* dtype / channel combination has no kernel */
+    K3_E_WORKSPACE = -4,   /* workspace or packed buffer too small */
+    K3_E_OOM = -5,         /* device budget or handle table exhausted */
+    K3_E_NOT_PINNED = -6,  /* host pointer is not page-locked */
+    K3_E_STATE = -7,       /* illegal swap-state transition */
+    K3_E_HIP = -8          /* a HIP call failed; see k3_last_hip_error() */
+};
+
+enum { K3_BF16 = 1, K3_F32 = 2 };
+
+/* Shape and element type of a dense NDHWC tensor. */
+typedef struct k3_tensor {
+    int64_t n, d, h, w, c;
+    int32_t dtype;    /* K3_BF16 or K3_F32 */
+    int32_t reserved; /* must be 0 */
+} k3_tensor;
+
+const char *k3_status_string(int status);
+int k3_last_hip_error(void);
+/* Library ABI version (major * 100 + minor). */
+int k3_version(void);
+
+/* ------------------------------------------------------------------ 3x3x3 convolution
+ * The 3x3x3 convolutional layer of the encoder and decoder (section 4.1), stride 1,
+ * zero padding 1 (cross-correlation):
+ *   y[n,d,h,w,co] = act(bias[co] + sum_{kd,kh,kw,ci} x[n,d+kd-1,h+kh-1,w+kw-1,ci] * W[kd,kh,kw,ci,co])
+ *
+ * bf16 tensors whose channel counts are multiples of 32 run on the MFMA implicit-GEMM
+ * kernels and need the weights in a packed device buffer made by k3_conv3d_pack_weights;
+ * every other case (fp32, or small / odd channel counts) runs on direct kernels that
+ * read the canonical weights.  k3_conv3d_packed_bytes reports 0 for the latter.
+ */
+
+/* Bytes needed for the packed form of a C_in -> C_out weight tensor (0: not needed). */
+int k3_conv3d_packed_bytes(int64_t cin, int64_t cout, int dtype, size_t *bytes);
+
+/* Builds the packed forms (forward and backward-data operand order) of canonical
+ * weights w (dev) into packed (dev, caller-owned, packed_bytes long).  Must be
+ * called again whenever w changes.  A no-op returning K3_OK when no packed form exists. */
+int k3_conv3d_pack_weights(const void *w, int64_t cin, int64_t cout, int dtype,
+                           void *packed, size_t packed_bytes, void *stream);
+
+/* Forward pass with fused bias and optional ReLU.  The input may be given as two
+ * tensors of equal n,d,h,w that are concatenated along channels, [x | x2] (the skip
+ * connection of a decoder level); pass x2d = x2 = NULL for one input.  w is
+ * [3][3][3][C_in][C_out] with C_in = x.c + x2.c; bias may be NULL (zero).  packed may
+ * be NULL only when k3_conv3d_packed_bytes reports 0.  All pointers dev. */
+int k3_conv3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2,
+                  const void *w, const void *packed, const float *bias, int relu,
+                  const k3_tensor *yd, void *y, void *stream);
+
+/* Backward-data pass: with g = dy where y_mask > 0 else 0 (g = dy when y_mask is NULL),
+ *   dx[n,d,h,w,ci] = sum_{kd,kh,kw,co} g[n,d-kd+1,h-kh+1,w-kw+1,co] * W[kd,kh,kw,ci,co].
+ * y_mask is the stored forward output of the same layer (same shape and dtype as dy).
+ * The result may be split along channels into two tensors [dx | dx2] (pass NULLs for
+ * one output). */
+int k3_conv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *y_mask,
+                       const void *w, const void *packed,
+                       const k3_tensor *dxd, void *dx, const k3_tensor *dx2d, void *dx2,
+                       void *stream);
+
+/* Workspace bytes k3_conv3d_bwd_weight needs for these shapes (split-K partial sums). */
+int k3_conv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor *x2d,
+                                         const k3_tensor *dyd, size_t *bytes);
+
+/* Backward-weight pass, with g as above and x = [x | x2]:
+ *   dW[kd,kh,kw,ci,co] = sum_{n,d,h,w} x[n,d+kd-1,h+kh-1,w+kw-1,ci] * g[n,d,h,w,co]
+ *   db[co]            = sum_{n,d,h,w} g[n,d,h,w,co]            (skipped when db is NULL)
+ * dW and db are fp32 dev buffers that are overwritten.  The voxel sum is split into
+ * slabs whose partial results go to ws (dev) and are then added in a fixed order. */
+int k3_conv3d_bwd_weight(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2,
+                         const k3_tensor *dyd, const void *dy, const void *y_mask,
+                         float *dW, float *db, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------ 2x2x2 max pooling
+ * The 2x2x2 max-pooling layer that follows the encoder convolutions (section 4.1):
+ *   y[n,d,h,w,c] = max_{i,j,k in {0,1}} x[n,2d+i,2h+j,2w+k,c].
+ * x.d, x.h, x.w must be even (K3_E_SHAPE otherwise). */
+int k3_pool3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *yd, void *y, void *stream);
+
+/* Backward: dx is zero except at the first maximum of each window (order i, j, k),
+ * which receives that window's dy.  The arg-max is recomputed from x.  When add is not
+ * NULL (same shape as dx) it is added element-wise: dx = route(dy) + add (the skip
+ * connection's gradient joining the pooled path). */
+int k3_pool3d_bwd(const k3_tensor *xd, const void *x, const k3_tensor *dyd, const void *dy,
+                  const void *add, void *dx, void *stream);
+
+/* ------------------------------------------------------------------ 2x2x2 stride-2 transposed convolution
+ * The decoder's up-sampling layer (section 4.1) in its learned form:
+ *   y[n,2d+i,2h+j,2w+k,co] = bias[co] + sum_ci x[n,d,h,w,ci] * W[i,j,k,ci,co]
+ * w is the canonical [2][2][2][C_in][C_out] tensor in the activation dtype (dev). */
+int k3_upconv3d_fwd(const k3_tensor *xd, const void *x, const void *w, const float *bias,
+                    const k3_tensor *yd, void *y, void *stream);
+/* dx[n,d,h,w,ci] = sum_{i,j,k,co} dy[n,2d+i,2h+j,2w+k,co] * W[i,j,k,ci,co] */
+int k3_upconv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *w,
+                         const k3_tensor *dxd, void *dx, void *stream);
+int k3_upconv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor *dyd, size_t *bytes);
+/* dW[i,j,k,ci,co] = sum_{n,d,h,w} x[n,d,h,w,ci] * dy[n,2d+i,2h+j,2w+k,co]; db[co] = sum dy. */
+int k3_upconv3d_bwd_weight(const k3_tensor *xd, const void *x, const k3_tensor *dyd, const void *dy,
+                           float *dW, float *db, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------ 1x1x1 head + softmax cross-entropy
+ * The per-voxel likelihood of each of K = 3 classes (section 4.1), forward and
+ * backward in one pass over the activations:
+ *   z[v,k] = bh[k] + sum_c a[v,c] * Wh[c,k];  p = softmax_k(z);
+ *   loss = -(1/V) sum_v log p[v, label_v];    dz = (p - onehot(label)) / V;
+ *   da = dz * Wh^T;  dWh = a^T * dz;  dbh = sum_v dz.
+ * a: dev, ad->dtype; wh [C][3], bh [3]: fp32 dev; labels: uint8 dev, one per voxel;
+ * loss: one fp32 (dev); da: dev, same shape and dtype as a; dWh [C][3], dbh [3]: fp32
+ * dev; logits: optional fp32 [V][3] dev (NULL to skip).  ws holds per-workgroup
+ * partial sums. */
+int k3_head_workspace_bytes(const k3_tensor *ad, size_t *bytes);
+int k3_head_softmax_ce_fwd_bwd(const k3_tensor *ad, const void *a, const float *wh, const float *bh,
+                               const uint8_t *labels, float *loss, void *da, float *dWh, float *dbh,
+                               float *logits, void *ws, size_t ws_bytes, void *stream);
+
+/* ------------------------------------------------------------------ LMS swap engine
+ * Tensor swapping between device and host memory so that only the tensors a training
+ * step currently needs stay on the GPU (section 2.2): a finished forward activation
+ * is copied to page-locked host memory on a dedicated copy stream and its device block
+ * can be reused; before its backward consumer runs it is copied back.
+ *
+ * A handle walks RESIDENT -> OUT_IN_FLIGHT -> ON_HOST -> IN_IN_FLIGHT -> RESIDENT; calls
+ * that do not fit the current state return K3_E_STATE.  The context owns two copy
+ * streams (device-to-host, host-to-device) and its events.  Host buffers are owned by
+ * the caller, must be page-locked (K3_E_NOT_PINNED otherwise) and must stay valid
+ * until the handle is released.  Calls on one context must come from one thread. */
+typedef struct k3_lms k3_lms;
+
+/* device_budget_bytes: cap on the bytes of device blocks accounted through
+ * k3_lms_account_alloc / _free (0 = unlimited). */
+int k3_lms_create(uint64_t device_budget_bytes, k3_lms **ctx);
+int k3_lms_destroy(k3_lms *ctx);
+
+/* Page-locked host memory helpers (hipHostMalloc / hipHostFree). */
+int k3_lms_host_alloc(size_t bytes, void **host_ptr);
+int k3_lms_host_free(void *host_ptr);
+
+/* Device-budget accounting for blocks the caller allocates: _alloc fails with
+ * K3_E_OOM (and accounts nothing) when the budget would be exceeded. */
+int k3_lms_account_alloc(k3_lms *ctx, uint64_t bytes);
+int k3_lms_account_free(k3_lms *ctx, uint64_t bytes);
+
+/* Starts the device-to-host copy of bytes at dev_ptr into host_ptr.  The copy waits
+ * for everything enqueued so far on compute_stream (the producers and forward readers
+ * of the tensor).  Returns a new handle in OUT_IN_FLIGHT. */
+int k3_lms_swap_out(k3_lms *ctx, const void *dev_ptr, size_t bytes, void *host_ptr,
+                    void *compute_stream, int *handle);
+/* 1 in *done once the swap-out copy has finished (handle moves to ON_HOST), else 0. */
+int k3_lms_swap_out_done(k3_lms *ctx, int handle, int *done);
+/* Makes `stream` wait for the swap-out copy, so that work enqueued on it afterwards
+ * may overwrite or free the device block; the handle moves to ON_HOST. */
+int k3_lms_release_after(k3_lms *ctx, int handle, void *stream);
+/* Starts the host-to-device copy of the tensor into dev_ptr (a block of at least the
+ * swapped size).  The copy waits for work already enqueued on consumer_stream (earlier
+ * users of that block), and consumer_stream is made to wait for the copy, so kernels
+ * enqueued on it afterwards see the data.  Handle: ON_HOST -> IN_IN_FLIGHT. */
+int k3_lms_prefetch_in(k3_lms *ctx, int handle, void *dev_ptr, void *consumer_stream);
+/* Makes `stream` wait for the prefetch copy of `handle` (for consumers on other streams). */
+int k3_lms_wait_in(k3_lms *ctx, int handle, void *stream);
+/* Drops the handle (any state but a copy still in flight is waited for first). */
+int k3_lms_release(k3_lms *ctx, int handle);
+/* Blocks the host until both copy streams are idle. */
+int k3_lms_sync(k3_lms *ctx);
+
+typedef struct k3_lms_stats {
+    uint64_t bytes_out, bytes_in;           /* bytes copied in each direction */
+    uint64_t n_out, n_in;                   /* copies started */
+    uint64_t device_bytes, device_peak;     /* accounted device bytes now / high-water mark */
+    uint64_t live_handles;
+} k3_lms_stats;
+int k3_lms_get_stats(k3_lms *ctx, k3_lms_stats *out);
+int k3_lms_handle_state(k3_lms *ctx, int handle, int *state);
+
+enum { K3_LMS_RESIDENT = 0, K3_LMS_OUT_IN_FLIGHT = 1, K3_LMS_ON_HOST = 2, K3_LMS_IN_IN_FLIGHT = 3 };
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* K3_H */

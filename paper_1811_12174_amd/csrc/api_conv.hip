@@ -1,0 +1,130 @@
+// C-ABI entry points for the 3x3x3 convolution passes: argument validation and dispatch
+// between the MFMA implicit-GEMM kernels and the direct kernels.
+#include "common.h"
+#include "conv_internal.h"
+
+namespace k3 {
+static thread_local int g_last_hip_error = 0;
+void set_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
+}  // namespace k3
+
+using namespace k3;
+
+extern "C" {
+
+int k3_version(void) { return 100; }
+int k3_last_hip_error(void) { return g_last_hip_error; }
+
+const char *k3_status_string(int s)
+{
+    switch (s) {
+    case K3_OK: return "ok";
+    case K3_E_BADARG: return "bad argument";
+    case K3_E_SHAPE: return "shape mismatch";
+    case K3_E_UNSUPPORTED: return "unsupported dtype or channel count";
+    case K3_E_WORKSPACE: return "workspace too small";
+    case K3_E_OOM: return "device budget or table exhausted";
+    case K3_E_NOT_PINNED: return "host pointer is not page-locked";
+    case K3_E_STATE: return "illegal swap-state transition";
+    case K3_E_HIP: return "HIP error";
+    default: return "unknown status";
+    }
+}
+
+int k3_conv3d_packed_bytes(int64_t cin, int64_t cout, int dtype, size_t *bytes)
+{
+    if (!bytes || cin <= 0 || cout <= 0 || (dtype != K3_BF16 && dtype != K3_F32)) return K3_E_BADARG;
+    // the packed form does not depend on how C_in is split over two sources
+    *bytes = (dtype == K3_BF16 && cin % 32 == 0 && cout % 32 == 0) ? conv_packed_bytes(cin, cout) : 0;
+    return K3_OK;
+}
+
+int k3_conv3d_pack_weights(const void *w, int64_t cin, int64_t cout, int dtype, void *packed, size_t packed_bytes,
+                           void *stream)
+{
+    size_t need = 0;
+    int rc = k3_conv3d_packed_bytes(cin, cout, dtype, &need);
+    if (rc != K3_OK) return rc;
+    if (need == 0) return K3_OK;
+    if (!w || !packed) return K3_E_BADARG;
+    if (packed_bytes < need) return K3_E_WORKSPACE;
+    return conv_pack_weights(w, cin, cout, packed, (hipStream_t)stream);
+}
+
+// Validates a (two-source) input / output descriptor set and fills the common fields.
+static int fill_args(ConvArgs &a, const k3_tensor *xd, const k3_tensor *x2d, const void *x2, const k3_tensor *yd)
+{
+    if (!desc_ok(xd) || !desc_ok(yd)) return K3_E_BADARG;
+    if ((x2d == nullptr) != (x2 == nullptr)) return K3_E_BADARG;
+    if (x2d && !desc_ok(x2d)) return K3_E_BADARG;
+    if (!same_space(xd, yd) || xd->dtype != yd->dtype) return K3_E_SHAPE;
+    if (x2d && (!same_space(xd, x2d) || x2d->dtype != xd->dtype)) return K3_E_SHAPE;
+    if (xd->d > 0x3fffffff || xd->h > 0x3fffffff || xd->w > 0x3fffffff || xd->n > 0x3fffffff) return K3_E_UNSUPPORTED;
+    a.dtype = xd->dtype;
+    a.N = xd->n; a.D = xd->d; a.H = xd->h; a.W = xd->w;
+    a.c1 = xd->c;
+    a.c2 = x2d ? x2d->c : 0;
+    a.cout = yd->c;
+    return K3_OK;
+}
+
+int k3_conv3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2, const void *w,
+                  const void *packed, const float *bias, int relu, const k3_tensor *yd, void *y, void *stream)
+{
+    ConvArgs a;
+    int rc = fill_args(a, xd, x2d, x2, yd);
+    if (rc != K3_OK) return rc;
+    if (!x || !w || !y) return K3_E_BADARG;
+    a.x = x; a.x2 = x2; a.w = w; a.packed = packed; a.bias = bias; a.relu = relu ? 1 : 0; a.y = y;
+    if (mfma_ok(a.dtype, a.c1, a.c2, a.cout)) {
+        if (!packed) return K3_E_BADARG;
+        return conv_fwd_mfma(a, (hipStream_t)stream);
+    }
+    return conv_fwd_direct(a, (hipStream_t)stream);
+}
+
+int k3_conv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *y_mask, const void *w, const void *packed,
+                       const k3_tensor *dxd, void *dx, const k3_tensor *dx2d, void *dx2, void *stream)
+{
+    ConvArgs a;
+    int rc = fill_args(a, dxd, dx2d, dx2, dyd);
+    if (rc != K3_OK) return rc;
+    if (!dy || !w || !dx) return K3_E_BADARG;
+    a.dy = dy; a.ymask = y_mask; a.w = w; a.packed = packed; a.dx = dx; a.dx2 = dx2;
+    if (mfma_ok(a.dtype, a.c1, a.c2, a.cout)) {
+        if (!packed) return K3_E_BADARG;
+        return conv_dgrad_mfma(a, (hipStream_t)stream);
+    }
+    return conv_dgrad_direct(a, (hipStream_t)stream);
+}
+
+int k3_conv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor *x2d, const k3_tensor *dyd, size_t *bytes)
+{
+    if (!desc_ok(xd) || !desc_ok(dyd) || !bytes || (x2d && !desc_ok(x2d))) return K3_E_BADARG;
+    if (!same_space(xd, dyd) || (x2d && !same_space(xd, x2d))) return K3_E_SHAPE;
+    int64_t c1 = xd->c, c2 = x2d ? x2d->c : 0;
+    if (mfma_ok(xd->dtype, c1, c2, dyd->c))
+        *bytes = conv_wgrad_mfma_ws_bytes(xd->n, xd->d, xd->h, xd->w, c1 + c2, dyd->c);
+    else
+        *bytes = conv_wgrad_direct_ws_bytes(voxels(xd), c1 + c2, dyd->c);
+    return K3_OK;
+}
+
+int k3_conv3d_bwd_weight(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2,
+                         const k3_tensor *dyd, const void *dy, const void *y_mask, float *dW, float *db, void *ws,
+                         size_t ws_bytes, void *stream)
+{
+    ConvArgs a;
+    int rc = fill_args(a, xd, x2d, x2, dyd);
+    if (rc != K3_OK) return rc;
+    if (!x || !dy || !dW || !ws) return K3_E_BADARG;
+    size_t need = 0;
+    rc = k3_conv3d_bwd_weight_workspace_bytes(xd, x2d, dyd, &need);
+    if (rc != K3_OK) return rc;
+    if (ws_bytes < need) return K3_E_WORKSPACE;
+    a.x = x; a.x2 = x2; a.dy = dy; a.ymask = y_mask;
+    if (mfma_ok(a.dtype, a.c1, a.c2, a.cout)) return conv_wgrad_mfma(a, dW, db, (float *)ws, (hipStream_t)stream);
+    return conv_wgrad_direct(a, dW, db, (float *)ws, (hipStream_t)stream);
+}
+
+}  // extern "C"

@@ -1,0 +1,65 @@
+// Shared host/device helpers for the k3 kernels (gfx950 only).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+#include "k3.h"
+
+typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8;
+typedef __attribute__((ext_vector_type(4))) __bf16 bf16x4;
+typedef __attribute__((ext_vector_type(16))) float f32x16;
+typedef __attribute__((ext_vector_type(4))) float f32x4;
+typedef __attribute__((ext_vector_type(4))) short s16x4;
+typedef unsigned short bf16_t;  // raw bf16 bit pattern in memory
+
+namespace k3 {
+
+void set_hip_error(hipError_t e);
+
+#define K3_HIP(expr)                                   \
+    do {                                               \
+        hipError_t e__ = (expr);                       \
+        if (e__ != hipSuccess) {                       \
+            k3::set_hip_error(e__);                    \
+            return K3_E_HIP;                           \
+        }                                              \
+    } while (0)
+
+#define K3_LAUNCH_CHECK() K3_HIP(hipGetLastError())
+
+static inline bool desc_ok(const k3_tensor *t)
+{
+    return t && t->n > 0 && t->d > 0 && t->h > 0 && t->w > 0 && t->c > 0 &&
+           (t->dtype == K3_BF16 || t->dtype == K3_F32) && t->reserved == 0;
+}
+static inline bool same_space(const k3_tensor *a, const k3_tensor *b)
+{
+    return a->n == b->n && a->d == b->d && a->h == b->h && a->w == b->w;
+}
+static inline int64_t voxels(const k3_tensor *t) { return t->n * t->d * t->h * t->w; }
+static inline size_t esize(int dtype) { return dtype == K3_BF16 ? 2 : 4; }
+
+// bf16 <-> fp32 (round to nearest even; inputs are finite in this library's use)
+__device__ __forceinline__ float bf2f(bf16_t b) { return __uint_as_float(((uint32_t)b) << 16); }
+__device__ __forceinline__ bf16_t f2bf(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (bf16_t)((u >> 16) | 0x40);  // NaN stays NaN
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (bf16_t)(u >> 16);
+}
+__device__ __forceinline__ uint32_t pack2bf(float lo, float hi)
+{
+    return (uint32_t)f2bf(lo) | ((uint32_t)f2bf(hi) << 16);
+}
+
+template <typename T> struct elem;
+template <> struct elem<float> {
+    static __device__ __forceinline__ float ld(const float *p) { return *p; }
+    static __device__ __forceinline__ void st(float *p, float v) { *p = v; }
+};
+template <> struct elem<bf16_t> {
+    static __device__ __forceinline__ float ld(const bf16_t *p) { return bf2f(*p); }
+    static __device__ __forceinline__ void st(bf16_t *p, float v) { *p = f2bf(v); }
+};
+
+}  // namespace k3

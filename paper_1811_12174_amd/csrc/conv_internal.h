@@ -1,0 +1,46 @@
+// Internal argument bundle and launcher declarations shared by the conv3d sources.
+#pragma once
+#include "common.h"
+
+namespace k3 {
+
+struct ConvArgs {
+    int dtype = 0;
+    int64_t N = 0, D = 0, H = 0, W = 0;
+    int64_t c1 = 0, c2 = 0;   // input channels of the first / second source (or destination)
+    int64_t cout = 0;
+    // forward / weight gradient inputs
+    const void *x = nullptr, *x2 = nullptr;
+    // canonical and packed weights
+    const void *w = nullptr, *packed = nullptr;
+    const float *bias = nullptr;
+    int relu = 0;
+    void *y = nullptr;
+    // backward inputs / outputs
+    const void *dy = nullptr, *ymask = nullptr;
+    void *dx = nullptr, *dx2 = nullptr;
+    int64_t V() const { return N * D * H * W; }
+};
+
+// true when the bf16 MFMA implicit-GEMM kernels cover this channel configuration
+static inline bool mfma_ok(int dtype, int64_t c1, int64_t c2, int64_t cout)
+{
+    return dtype == K3_BF16 && c1 % 32 == 0 && c2 % 32 == 0 && cout % 32 == 0;
+}
+
+int conv_fwd_direct(const ConvArgs &a, hipStream_t st);
+int conv_dgrad_direct(const ConvArgs &a, hipStream_t st);
+int conv_wgrad_direct(const ConvArgs &a, float *dW, float *db, float *ws, hipStream_t st);
+size_t conv_wgrad_direct_ws_bytes(int64_t V, int64_t cin, int64_t cout);
+
+size_t conv_packed_bytes(int64_t cin, int64_t cout);
+int conv_pack_weights(const void *w, int64_t cin, int64_t cout, void *packed, hipStream_t st);
+int conv_fwd_mfma(const ConvArgs &a, hipStream_t st);
+int conv_dgrad_mfma(const ConvArgs &a, hipStream_t st);
+int conv_wgrad_mfma(const ConvArgs &a, float *dW, float *db, float *ws, hipStream_t st);
+size_t conv_wgrad_mfma_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout);
+
+int launch_reduce_partials(const float *ws, float *dW, float *db, int64_t countW, int64_t count, int nsplit,
+                           hipStream_t st);
+
+}  // namespace k3

@@ -1,0 +1,178 @@
+"""GPU parity of the 3x3x3 convolution passes against the fp64 oracle, through the C-ABI."""
+import numpy as np
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+# (N, D, H, W, c1, c2, cout, dtype): spans direct and MFMA paths, several tiles, ragged tails
+FWD_CASES = [
+    (1, 16, 16, 16, 4, 0, 8, "f32"),       # workload config 1
+    (2, 5, 6, 7, 3, 2, 5, "f32"),          # odd sizes, two sources, direct
+    (1, 9, 10, 11, 1, 0, 32, "bf16"),      # single-channel first layer (direct, bf16)
+    (1, 16, 16, 16, 32, 0, 32, "bf16"),    # MFMA, MB=1, 8 tiles
+    (1, 12, 20, 9, 32, 0, 64, "bf16"),     # MFMA, MB=2, ragged tiles
+    (2, 8, 8, 16, 64, 0, 32, "bf16"),      # several K chunks
+    (1, 10, 8, 8, 32, 32, 32, "bf16"),     # two sources (decoder conv1)
+    (1, 4, 4, 4, 128, 0, 128, "bf16"),     # volume smaller than a tile, 2 channel groups
+    (1, 2, 2, 2, 64, 64, 64, "bf16"),      # bottleneck-like
+]
+
+
+def _mk(case, seed0):
+    N, D, H, W, c1, c2, co, dt = case
+    x = synth.activations(seed0, (N, D, H, W, c1), dt)
+    x2 = synth.activations(seed0 + 1, (N, D, H, W, c2), dt) if c2 else None
+    w = synth.conv_weights(seed0 + 2, c1 + c2, co, dt)
+    b = (synth.normal(synth.SEED, seed0 + 3, (co,), np.float64) * 0.5).astype(np.float32)
+    return x, x2, w, b
+
+
+@pytest.mark.parametrize("case", FWD_CASES, ids=lambda c: "x".join(map(str, c)))
+@pytest.mark.parametrize("relu", [0, 1])
+def test_conv_fwd(orc, case, relu):
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, to_f64, empty, rel_l2, packed_for, TOL
+    N, D, H, W, c1, c2, co, dt = case
+    x, x2, w, b = _mk(case, 10)
+    xd, wd, bd = to_dev(x, dt), to_dev(w, dt), torch.from_numpy(b).cuda()
+    x2d = to_dev(x2, dt) if c2 else None
+    y = empty((N, D, H, W, co), dt)
+    y.fill_(float("nan"))
+    k3.conv3d_fwd(xd, wd, packed_for(wd), bd, relu, y, x2=x2d)
+    torch.cuda.synchronize()
+    xin = x if not c2 else np.concatenate([x, x2], axis=-1)
+    ref = orc.conv3d_fwd(xin.astype(np.float64), w.astype(np.float64), b.astype(np.float64), relu=bool(relu))
+    got = to_f64(y)
+    assert np.isfinite(got).all()
+    err = rel_l2(got, ref)
+    assert err < TOL[dt], err
+    if dt == "bf16":
+        # one bf16 rounding of an fp32 accumulation: anything above 4e-3 means a structural bug
+        assert err < 4e-3, err
+        assert rel_l2(got, orc.round_bf16(ref)) < 2e-3
+
+
+@pytest.mark.parametrize("case", FWD_CASES, ids=lambda c: "x".join(map(str, c)))
+@pytest.mark.parametrize("masked", [0, 1])
+def test_conv_bwd_data(orc, case, masked):
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, to_f64, empty, rel_l2, packed_for, TOL
+    N, D, H, W, c1, c2, co, dt = case
+    _, _, w, _ = _mk(case, 20)
+    dy = synth.activations(24, (N, D, H, W, co), dt)
+    ym = synth.activations(25, (N, D, H, W, co), dt)
+    ym[ym < 0.3] = 0.0       # plenty of exact zeros and negatives, like a stored ReLU output
+    wd, dyd, ymd = to_dev(w, dt), to_dev(dy, dt), to_dev(ym, dt)
+    dx = empty((N, D, H, W, c1), dt)
+    dx2 = empty((N, D, H, W, c2), dt) if c2 else None
+    k3.conv3d_bwd_data(dyd, ymd if masked else None, wd, packed_for(wd), dx, dx2=dx2)
+    torch.cuda.synchronize()
+    g = dy.astype(np.float64)
+    if masked:
+        g = orc.relu_bwd(g, ym.astype(np.float64))
+    ref = orc.conv3d_bwd_data(g, w.astype(np.float64))
+    got = to_f64(dx) if not c2 else np.concatenate([to_f64(dx), to_f64(dx2)], axis=-1)
+    err = rel_l2(got, ref)
+    assert err < TOL[dt], err
+    if dt == "bf16":
+        assert err < 4e-3, err
+
+
+@pytest.mark.parametrize("case", FWD_CASES, ids=lambda c: "x".join(map(str, c)))
+@pytest.mark.parametrize("masked", [0, 1])
+def test_conv_bwd_weight(orc, case, masked):
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, to_f64, empty, rel_l2, TOL
+    N, D, H, W, c1, c2, co, dt = case
+    x, x2, _, _ = _mk(case, 30)
+    dy = synth.activations(34, (N, D, H, W, co), dt)
+    ym = synth.activations(35, (N, D, H, W, co), dt)
+    ym[ym < 0.3] = 0.0
+    xd, dyd, ymd = to_dev(x, dt), to_dev(dy, dt), to_dev(ym, dt)
+    x2d = to_dev(x2, dt) if c2 else None
+    dW = torch.full((3, 3, 3, c1 + c2, co), float("nan"), device="cuda")
+    db = torch.full((co,), float("nan"), device="cuda")
+    ws = torch.empty(max(1, k3.conv3d_bwd_weight_workspace_bytes(xd, dyd, x2=x2d)), device="cuda", dtype=torch.uint8)
+    k3.conv3d_bwd_weight(xd, dyd, ymd if masked else None, dW, db, ws, x2=x2d)
+    torch.cuda.synchronize()
+    g = dy.astype(np.float64)
+    if masked:
+        g = orc.relu_bwd(g, ym.astype(np.float64))
+    xin = x if not c2 else np.concatenate([x, x2], axis=-1)
+    rW, rb = orc.conv3d_bwd_weight(xin.astype(np.float64), g)
+    # fp32 accumulation of exact products: far inside either tolerance
+    assert rel_l2(to_f64(dW), rW) < 1e-5
+    assert rel_l2(to_f64(db), rb) < 1e-5
+    # run-to-run identical
+    dW2 = torch.empty_like(dW)
+    k3.conv3d_bwd_weight(xd, dyd, ymd if masked else None, dW2, db, ws, x2=x2d)
+    torch.cuda.synchronize()
+    assert torch.equal(dW, dW2)
+
+
+def test_identity_kernel_is_bit_exact_bf16():
+    """Centre-tap identity weights reproduce the bf16 input bit for bit (MFMA path)."""
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, empty, packed_for
+    C = 32
+    x = to_dev(synth.activations(40, (1, 9, 8, 10, C), "bf16"), "bf16")
+    w = np.zeros((3, 3, 3, C, C), dtype=np.float32)
+    w[1, 1, 1] = np.eye(C)
+    wd = to_dev(w, "bf16")
+    y = empty(x.shape, "bf16")
+    k3.conv3d_fwd(x, wd, packed_for(wd), None, 0, y)
+    torch.cuda.synchronize()
+    assert torch.equal(x.view(torch.int16), y.view(torch.int16))
+
+
+def test_shift_kernels_bf16_mfma():
+    """One-hot kernels at each tap shift the input exactly, zero filled at every face."""
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, to_f64, empty, packed_for
+    C = 32
+    xs = synth.activations(41, (1, 9, 10, 11, C), "bf16")
+    x = to_dev(xs, "bf16")
+    for tap in (0, 2, 6, 8, 13, 18, 20, 24, 26, 4, 10, 22):
+        kd, kh, kw = tap // 9, (tap // 3) % 3, tap % 3
+        w = np.zeros((3, 3, 3, C, C), dtype=np.float32)
+        w[kd, kh, kw] = np.eye(C)
+        wd = to_dev(w, "bf16")
+        y = empty(x.shape, "bf16")
+        k3.conv3d_fwd(x, wd, packed_for(wd), None, 0, y)
+        torch.cuda.synchronize()
+        exp = np.zeros_like(xs)
+        D, H, W = xs.shape[1:4]
+
+        def rng_(s, n):
+            return slice(max(0, -s), n - max(0, s)), slice(max(0, s), n - max(0, -s))
+        (od, id_), (oh, ih), (ow, iw) = rng_(kd - 1, D), rng_(kh - 1, H), rng_(kw - 1, W)
+        exp[:, od, oh, ow] = xs[:, id_, ih, iw]
+        assert np.array_equal(to_f64(y), exp.astype(np.float64)), tap
+
+
+def test_error_codes():
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import empty
+    x = empty((1, 4, 4, 4, 32), "bf16")
+    y = empty((1, 4, 4, 5, 32), "bf16")
+    w = empty((3, 3, 3, 32, 32), "bf16")
+    with pytest.raises(k3.K3Error) as e:
+        k3.conv3d_fwd(x, w, None, None, 0, y)
+    assert e.value.status == k3.E_SHAPE
+    y = empty((1, 4, 4, 4, 32), "bf16")
+    with pytest.raises(k3.K3Error) as e:
+        k3.conv3d_fwd(x, w, None, None, 0, y)      # MFMA shape without packed weights
+    assert e.value.status == k3.E_BADARG
+    dW = torch.empty((3, 3, 3, 32, 32), device="cuda")
+    ws = torch.empty(16, device="cuda", dtype=torch.uint8)
+    with pytest.raises(k3.K3Error) as e:
+        k3.conv3d_bwd_weight(x, y, None, dW, None, ws)
+    assert e.value.status == k3.E_WORKSPACE
