@@ -129,14 +129,21 @@ int k3_pool3d_bwd(const k3_tensor *xd, const void *x, const k3_tensor *dyd, cons
 /* ------------------------------------------------------------------ 2x2x2 stride-2 transposed convolution
  * The decoder's up-sampling layer (section 4.1) in its learned form:
  *   y[n,2d+i,2h+j,2w+k,co] = bias[co] + sum_ci x[n,d,h,w,ci] * W[i,j,k,ci,co]
- * w is the canonical [2][2][2][C_in][C_out] tensor in the activation dtype (dev). */
-int k3_upconv3d_fwd(const k3_tensor *xd, const void *x, const void *w, const float *bias,
-                    const k3_tensor *yd, void *y, void *stream);
+ * w is the canonical [2][2][2][C_in][C_out] tensor in the activation dtype (dev).  As for
+ * the 3x3x3 convolution, bf16 tensors with channel counts that are multiples of 32 run on
+ * MFMA kernels and need a packed copy of the weights (k3_upconv3d_packed_bytes reports 0
+ * otherwise, and packed may then be NULL). */
+int k3_upconv3d_packed_bytes(int64_t cin, int64_t cout, int dtype, size_t *bytes);
+int k3_upconv3d_pack_weights(const void *w, int64_t cin, int64_t cout, int dtype,
+                             void *packed, size_t packed_bytes, void *stream);
+int k3_upconv3d_fwd(const k3_tensor *xd, const void *x, const void *w, const void *packed,
+                    const float *bias, const k3_tensor *yd, void *y, void *stream);
 /* dx[n,d,h,w,ci] = sum_{i,j,k,co} dy[n,2d+i,2h+j,2w+k,co] * W[i,j,k,ci,co] */
-int k3_upconv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *w,
+int k3_upconv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *w, const void *packed,
                          const k3_tensor *dxd, void *dx, void *stream);
 int k3_upconv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor *dyd, size_t *bytes);
-/* dW[i,j,k,ci,co] = sum_{n,d,h,w} x[n,d,h,w,ci] * dy[n,2d+i,2h+j,2w+k,co]; db[co] = sum dy. */
+/* dW[i,j,k,ci,co] = sum_{n,d,h,w} x[n,d,h,w,ci] * dy[n,2d+i,2h+j,2w+k,co]; db[co] = sum dy
+ * (db may be NULL).  dW, db: fp32 dev, overwritten; ws: dev workspace for partial sums. */
 int k3_upconv3d_bwd_weight(const k3_tensor *xd, const void *x, const k3_tensor *dyd, const void *dy,
                            float *dW, float *db, void *ws, size_t ws_bytes, void *stream);
 

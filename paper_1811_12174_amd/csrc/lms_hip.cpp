@@ -1,0 +1,157 @@
+// HIP backend of the swap engine and the k3_lms_* C-ABI entry points.  Copies run on two
+// dedicated non-blocking streams at the default priority (one per direction, so both DMA
+// directions can be busy at once) and are fenced with timing-disabled events.
+#include <new>
+
+#include "common.h"
+#include "lms_engine.h"
+
+namespace {
+
+struct HipBackend : k3lms::Backend {
+    int last = 0;
+    int chk(hipError_t e)
+    {
+        if (e != hipSuccess) {
+            last = (int)e;
+            k3::set_hip_error(e);
+            return 1;
+        }
+        return 0;
+    }
+    int stream_create(k3lms::stream_t *s) override
+    {
+        hipStream_t st;
+        if (chk(hipStreamCreateWithFlags(&st, hipStreamNonBlocking))) return 1;
+        *s = st;
+        return 0;
+    }
+    int stream_destroy(k3lms::stream_t s) override { return chk(hipStreamDestroy((hipStream_t)s)); }
+    int stream_sync(k3lms::stream_t s) override { return chk(hipStreamSynchronize((hipStream_t)s)); }
+    int event_create(k3lms::event_t *e) override
+    {
+        hipEvent_t ev;
+        if (chk(hipEventCreateWithFlags(&ev, hipEventDisableTiming))) return 1;
+        *e = ev;
+        return 0;
+    }
+    int event_destroy(k3lms::event_t e) override { return chk(hipEventDestroy((hipEvent_t)e)); }
+    int event_record(k3lms::event_t e, k3lms::stream_t s) override { return chk(hipEventRecord((hipEvent_t)e, (hipStream_t)s)); }
+    int stream_wait_event(k3lms::stream_t s, k3lms::event_t e) override
+    {
+        return chk(hipStreamWaitEvent((hipStream_t)s, (hipEvent_t)e, 0));
+    }
+    int event_query(k3lms::event_t e, bool *done) override
+    {
+        hipError_t r = hipEventQuery((hipEvent_t)e);
+        if (r == hipSuccess) { *done = true; return 0; }
+        if (r == hipErrorNotReady) { *done = false; (void)hipGetLastError(); return 0; }
+        return chk(r);
+    }
+    int event_sync(k3lms::event_t e) override { return chk(hipEventSynchronize((hipEvent_t)e)); }
+    int copy_d2h(void *host, const void *dev, size_t bytes, k3lms::stream_t s) override
+    {
+        return chk(hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, (hipStream_t)s));
+    }
+    int copy_h2d(void *dev, const void *host, size_t bytes, k3lms::stream_t s) override
+    {
+        return chk(hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, (hipStream_t)s));
+    }
+    bool is_pinned(const void *host, size_t bytes) override
+    {
+        hipPointerAttribute_t at;
+        hipError_t r = hipPointerGetAttributes(&at, host);
+        if (r != hipSuccess) { (void)hipGetLastError(); return false; }
+        if (at.type != hipMemoryTypeHost) return false;
+        // the last byte must belong to a page-locked allocation too
+        r = hipPointerGetAttributes(&at, (const char *)host + bytes - 1);
+        if (r != hipSuccess) { (void)hipGetLastError(); return false; }
+        return at.type == hipMemoryTypeHost;
+    }
+};
+
+int map_status(int s)
+{
+    switch (s) {
+    case k3lms::OK: return K3_OK;
+    case k3lms::E_BADARG: return K3_E_BADARG;
+    case k3lms::E_OOM: return K3_E_OOM;
+    case k3lms::E_NOT_PINNED: return K3_E_NOT_PINNED;
+    case k3lms::E_STATE: return K3_E_STATE;
+    default: return K3_E_HIP;
+    }
+}
+
+}  // namespace
+
+struct k3_lms {
+    HipBackend be;
+    k3lms::Engine eng;
+    explicit k3_lms(uint64_t budget) : eng(&be, budget) {}
+};
+
+extern "C" {
+
+int k3_lms_create(uint64_t device_budget_bytes, k3_lms **ctx)
+{
+    if (!ctx) return K3_E_BADARG;
+    k3_lms *c = new (std::nothrow) k3_lms(device_budget_bytes);
+    if (!c) return K3_E_OOM;
+    int rc = c->eng.init();
+    if (rc) {
+        delete c;
+        return map_status(rc);
+    }
+    *ctx = c;
+    return K3_OK;
+}
+
+int k3_lms_destroy(k3_lms *ctx)
+{
+    if (!ctx) return K3_E_BADARG;
+    delete ctx;
+    return K3_OK;
+}
+
+int k3_lms_host_alloc(size_t bytes, void **host_ptr)
+{
+    if (!host_ptr || bytes == 0) return K3_E_BADARG;
+    K3_HIP(hipHostMalloc(host_ptr, bytes, hipHostMallocDefault));
+    return K3_OK;
+}
+
+int k3_lms_host_free(void *host_ptr)
+{
+    if (!host_ptr) return K3_E_BADARG;
+    K3_HIP(hipHostFree(host_ptr));
+    return K3_OK;
+}
+
+int k3_lms_account_alloc(k3_lms *ctx, uint64_t bytes) { return ctx ? map_status(ctx->eng.account_alloc(bytes)) : K3_E_BADARG; }
+int k3_lms_account_free(k3_lms *ctx, uint64_t bytes) { return ctx ? map_status(ctx->eng.account_free(bytes)) : K3_E_BADARG; }
+
+int k3_lms_swap_out(k3_lms *ctx, const void *dev_ptr, size_t bytes, void *host_ptr, void *compute_stream, int *handle)
+{
+    return ctx ? map_status(ctx->eng.swap_out(dev_ptr, bytes, host_ptr, compute_stream, handle)) : K3_E_BADARG;
+}
+int k3_lms_swap_out_done(k3_lms *ctx, int handle, int *done) { return ctx ? map_status(ctx->eng.swap_out_done(handle, done)) : K3_E_BADARG; }
+int k3_lms_release_after(k3_lms *ctx, int handle, void *stream) { return ctx ? map_status(ctx->eng.release_after(handle, stream)) : K3_E_BADARG; }
+int k3_lms_prefetch_in(k3_lms *ctx, int handle, void *dev_ptr, void *consumer_stream)
+{
+    return ctx ? map_status(ctx->eng.prefetch_in(handle, dev_ptr, consumer_stream)) : K3_E_BADARG;
+}
+int k3_lms_wait_in(k3_lms *ctx, int handle, void *stream) { return ctx ? map_status(ctx->eng.wait_in(handle, stream)) : K3_E_BADARG; }
+int k3_lms_release(k3_lms *ctx, int handle) { return ctx ? map_status(ctx->eng.release(handle)) : K3_E_BADARG; }
+int k3_lms_sync(k3_lms *ctx) { return ctx ? map_status(ctx->eng.sync()) : K3_E_BADARG; }
+int k3_lms_handle_state(k3_lms *ctx, int handle, int *state) { return ctx ? map_status(ctx->eng.handle_state(handle, state)) : K3_E_BADARG; }
+
+int k3_lms_get_stats(k3_lms *ctx, k3_lms_stats *out)
+{
+    if (!ctx || !out) return K3_E_BADARG;
+    const k3lms::Stats &s = ctx->eng.stats();
+    out->bytes_out = s.bytes_out; out->bytes_in = s.bytes_in; out->n_out = s.n_out; out->n_in = s.n_in;
+    out->device_bytes = s.device_bytes; out->device_peak = s.device_peak; out->live_handles = s.live_handles;
+    return K3_OK;
+}
+
+}  // extern "C"

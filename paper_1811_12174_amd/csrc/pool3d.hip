@@ -1,0 +1,166 @@
+// 2x2x2 stride-2 max pooling, forward and backward, for gfx950.  Pure streaming kernels:
+// one thread handles VEC consecutive channels of one output window (16-byte loads when
+// the channel count allows), so every byte of x / y / dx is touched exactly once.
+#include "common.h"
+
+namespace k3 {
+
+template <typename T, int VEC> struct vec_io;
+template <> struct vec_io<bf16_t, 8> {
+    static __device__ __forceinline__ void ld(const bf16_t *p, float *v)
+    {
+        uint4 u = *reinterpret_cast<const uint4 *>(p);
+        uint32_t w[4] = {u.x, u.y, u.z, u.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            v[2 * i] = __uint_as_float(w[i] << 16);
+            v[2 * i + 1] = __uint_as_float(w[i] & 0xffff0000u);
+        }
+    }
+    static __device__ __forceinline__ void st(bf16_t *p, const float *v)
+    {
+        uint4 u = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
+        *reinterpret_cast<uint4 *>(p) = u;
+    }
+};
+template <> struct vec_io<float, 4> {
+    static __device__ __forceinline__ void ld(const float *p, float *v)
+    {
+        float4 u = *reinterpret_cast<const float4 *>(p);
+        v[0] = u.x; v[1] = u.y; v[2] = u.z; v[3] = u.w;
+    }
+    static __device__ __forceinline__ void st(float *p, const float *v)
+    {
+        *reinterpret_cast<float4 *>(p) = make_float4(v[0], v[1], v[2], v[3]);
+    }
+};
+template <typename T> struct vec_io<T, 1> {
+    static __device__ __forceinline__ void ld(const T *p, float *v) { v[0] = elem<T>::ld(p); }
+    static __device__ __forceinline__ void st(T *p, const float *v) { elem<T>::st(p, v[0]); }
+};
+
+// D, H, W are the OUTPUT sizes; the input is (2D, 2H, 2W).
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void pool_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int64_t total,
+                                                      int D, int H, int W, int C)
+{
+    int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= total) return;
+    int cv = C / VEC;
+    int c = (int)(gid % cv) * VEC;
+    int64_t o = gid / cv;
+    int w = (int)(o % W);
+    int h = (int)((o / W) % H);
+    int d = (int)((o / ((int64_t)W * H)) % D);
+    int64_t n = o / ((int64_t)W * H * D);
+    float m[VEC], v[VEC];
+    bool have = false;
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j)
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                int64_t u = ((n * 2 * D + 2 * d + i) * 2 * H + 2 * h + j) * (2 * (int64_t)W) + 2 * w + k;
+                vec_io<T, VEC>::ld(x + u * C + c, v);
+#pragma unroll
+                for (int e = 0; e < VEC; ++e) m[e] = (!have || v[e] > m[e]) ? v[e] : m[e];
+                have = true;
+            }
+    vec_io<T, VEC>::st(y + o * C + c, m);
+}
+
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void pool_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy,
+                                                      const T *__restrict__ add, T *__restrict__ dx, int64_t total,
+                                                      int D, int H, int W, int C)
+{
+    int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= total) return;
+    int cv = C / VEC;
+    int c = (int)(gid % cv) * VEC;
+    int64_t o = gid / cv;
+    int w = (int)(o % W);
+    int h = (int)((o / W) % H);
+    int d = (int)((o / ((int64_t)W * H)) % D);
+    int64_t n = o / ((int64_t)W * H * D);
+    float m[VEC], v[VEC], g[VEC], a[VEC], r[VEC];
+    int arg[VEC];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        int64_t u = ((n * 2 * D + 2 * d + (p >> 2)) * 2 * H + 2 * h + ((p >> 1) & 1)) * (2 * (int64_t)W) + 2 * w + (p & 1);
+        vec_io<T, VEC>::ld(x + u * C + c, v);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            if (p == 0 || v[e] > m[e]) { m[e] = v[e]; arg[e] = p; }  // strict >: the first maximum wins
+    }
+    vec_io<T, VEC>::ld(dy + o * C + c, g);
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        int64_t u = ((n * 2 * D + 2 * d + (p >> 2)) * 2 * H + 2 * h + ((p >> 1) & 1)) * (2 * (int64_t)W) + 2 * w + (p & 1);
+        if (add) vec_io<T, VEC>::ld(add + u * C + c, a);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) r[e] = (arg[e] == p ? g[e] : 0.f) + (add ? a[e] : 0.f);
+        vec_io<T, VEC>::st(dx + u * C + c, r);
+    }
+}
+
+template <typename T, int VEC>
+static int pool_launch(bool bwd, const void *x, const void *dy, const void *add, void *out, int64_t N, int64_t D,
+                       int64_t H, int64_t W, int64_t C, hipStream_t st)
+{
+    int64_t total = N * D * H * W * (C / VEC);
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+    if (!bwd)
+        pool_fwd_kernel<T, VEC><<<dim3((unsigned)blocks), 256, 0, st>>>((const T *)x, (T *)out, total, (int)D, (int)H,
+                                                                        (int)W, (int)C);
+    else
+        pool_bwd_kernel<T, VEC><<<dim3((unsigned)blocks), 256, 0, st>>>((const T *)x, (const T *)dy, (const T *)add,
+                                                                        (T *)out, total, (int)D, (int)H, (int)W, (int)C);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
+static int pool_dispatch(bool bwd, int dtype, const void *x, const void *dy, const void *add, void *out, int64_t N,
+                         int64_t D, int64_t H, int64_t W, int64_t C, hipStream_t st)
+{
+    if (dtype == K3_BF16) {
+        if (C % 8 == 0) return pool_launch<bf16_t, 8>(bwd, x, dy, add, out, N, D, H, W, C, st);
+        return pool_launch<bf16_t, 1>(bwd, x, dy, add, out, N, D, H, W, C, st);
+    }
+    if (C % 4 == 0) return pool_launch<float, 4>(bwd, x, dy, add, out, N, D, H, W, C, st);
+    return pool_launch<float, 1>(bwd, x, dy, add, out, N, D, H, W, C, st);
+}
+
+static int pool_check(const k3_tensor *xd, const k3_tensor *yd)
+{
+    if (!desc_ok(xd) || !desc_ok(yd)) return K3_E_BADARG;
+    if (xd->d % 2 || xd->h % 2 || xd->w % 2) return K3_E_SHAPE;
+    if (yd->n != xd->n || yd->d * 2 != xd->d || yd->h * 2 != xd->h || yd->w * 2 != xd->w || yd->c != xd->c ||
+        yd->dtype != xd->dtype)
+        return K3_E_SHAPE;
+    if (xd->d > 0x3fffffff || xd->h > 0x3fffffff || xd->w > 0x3fffffff || xd->c > 0x3fffffff) return K3_E_UNSUPPORTED;
+    return K3_OK;
+}
+
+}  // namespace k3
+
+using namespace k3;
+
+extern "C" int k3_pool3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *yd, void *y, void *stream)
+{
+    int rc = pool_check(xd, yd);
+    if (rc != K3_OK) return rc;
+    if (!x || !y) return K3_E_BADARG;
+    return pool_dispatch(false, xd->dtype, x, nullptr, nullptr, y, yd->n, yd->d, yd->h, yd->w, yd->c, (hipStream_t)stream);
+}
+
+extern "C" int k3_pool3d_bwd(const k3_tensor *xd, const void *x, const k3_tensor *dyd, const void *dy, const void *add,
+                             void *dx, void *stream)
+{
+    int rc = pool_check(xd, dyd);
+    if (rc != K3_OK) return rc;
+    if (!x || !dy || !dx) return K3_E_BADARG;
+    return pool_dispatch(true, xd->dtype, x, dy, add, dx, dyd->n, dyd->d, dyd->h, dyd->w, dyd->c, (hipStream_t)stream);
+}

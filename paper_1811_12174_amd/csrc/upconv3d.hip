@@ -1,0 +1,555 @@
+// 2x2x2 stride-2 transposed convolution (decoder up-sampling), forward, backward-data and
+// backward-weight, for gfx950.
+//
+// Every output voxel (2d+i, 2h+j, 2w+k) receives exactly one tap, so the forward pass is
+// eight independent 1x1x1 GEMMs that share their input, and backward-data is one GEMM with
+// contraction over (tap, C_out).  On the MFMA path (bf16, channels multiples of 32) the
+// weights are the A operand (rows = produced channels, permuted so that a lane owns 16
+// consecutive channels) and the activations the B operand, read straight from global
+// memory: a lane needs 8 consecutive channels of one voxel, which is a 16-byte load.
+// Backward-weight contracts over voxels and uses transposing LDS reads like the 3x3x3
+// weight-gradient kernel.  Other dtypes / channel counts use direct kernels.
+#include "common.h"
+#include "conv_internal.h"
+
+namespace k3 {
+
+__host__ __device__ static inline int up_row_to_channel(int r) { return ((r >> 2) & 1) * 16 + (r >> 3) * 4 + (r & 3); }
+
+static inline bool up_mfma_ok(int dtype, int64_t cin, int64_t cout)
+{
+    return dtype == K3_BF16 && cin % 32 == 0 && cout % 32 == 0;
+}
+
+// ------------------------------------------------------------------ packing
+// fwd[tap][cob][kc][lane][j] = W[tap][kc*16 + (lane/32)*8 + j][cob*32 + r2c(lane%32)]
+// bwd[cib][tap][kc][lane][j] = W[tap][cib*32 + r2c(lane%32)][kc*16 + (lane/32)*8 + j]
+__global__ __launch_bounds__(256) void up_pack_kernel(const bf16_t *__restrict__ w, bf16_t *__restrict__ packed,
+                                                     int cin, int cout)
+{
+    int64_t per = (int64_t)8 * cin * cout;
+    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= 2 * per) return;
+    bool bwd = i >= per;
+    int64_t r = bwd ? i - per : i;
+    int j = (int)(r & 7), lane = (int)((r >> 3) & 63);
+    int64_t q = r >> 9;
+    bf16_t v;
+    if (!bwd) {
+        int nkc = cin / 16, ncob = cout / 32;
+        int kc = (int)(q % nkc);
+        q /= nkc;
+        int cob = (int)(q % ncob);
+        int tap = (int)(q / ncob);
+        v = w[((int64_t)tap * cin + kc * 16 + (lane >> 5) * 8 + j) * cout + cob * 32 + up_row_to_channel(lane & 31)];
+    } else {
+        int nkc = cout / 16;
+        int kc = (int)(q % nkc);
+        q /= nkc;
+        int tap = (int)(q % 8);
+        int cib = (int)(q / 8);
+        v = w[((int64_t)tap * cin + cib * 32 + up_row_to_channel(lane & 31)) * cout + kc * 16 + (lane >> 5) * 8 + j];
+    }
+    packed[i] = v;
+}
+
+// ------------------------------------------------------------------ MFMA forward
+// wave = 32 consecutive input voxels x one 32-channel output block x 8 taps
+__global__ __launch_bounds__(256) void up_fwd_mfma_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ packed,
+                                                         const float *__restrict__ bias, bf16_t *__restrict__ y,
+                                                         int64_t V, int D, int H, int W, int cin, int cout)
+{
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int hb = lane >> 5, vl = lane & 31;
+    const int64_t nb = (int64_t)blockIdx.x * 4 + wv;
+    const int cob = blockIdx.y, ncob = cout / 32, nkc = cin / 16;
+    const int64_t v = nb * 32 + vl;
+    const bool live = v < V;
+    f32x16 acc[8];
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[t][i] = 0.f;
+    const uint4 *xp = reinterpret_cast<const uint4 *>(x + (live ? v : 0) * cin + hb * 8);
+    const uint4 *ap = reinterpret_cast<const uint4 *>(packed) + lane;
+    for (int kc = 0; kc < nkc; ++kc) {
+        uint4 braw = live ? xp[kc * 2] : make_uint4(0, 0, 0, 0);
+        bf16x8 b = __builtin_bit_cast(bf16x8, braw);
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            uint4 araw = ap[(((int64_t)t * ncob + cob) * nkc + kc) * 64];
+            acc[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, araw), b, acc[t], 0, 0, 0);
+        }
+    }
+    if (!live) return;
+    int w = (int)(v % W);
+    int h = (int)((v / W) % H);
+    int d = (int)((v / ((int64_t)W * H)) % D);
+    int64_t n = v / ((int64_t)W * H * D);
+    const int co0 = cob * 32 + hb * 16;
+    float bv[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) bv[i] = bias ? bias[co0 + i] : 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t) {
+        int64_t o = ((n * 2 * D + 2 * d + (t >> 2)) * 2 * H + 2 * h + ((t >> 1) & 1)) * (2 * (int64_t)W) + 2 * w + (t & 1);
+        float r[16];
+#pragma unroll
+        for (int i = 0; i < 16; ++i) r[i] = acc[t][i] + bv[i];
+        uint4 *dst = reinterpret_cast<uint4 *>(y + o * cout + co0);
+        dst[0] = make_uint4(pack2bf(r[0], r[1]), pack2bf(r[2], r[3]), pack2bf(r[4], r[5]), pack2bf(r[6], r[7]));
+        dst[1] = make_uint4(pack2bf(r[8], r[9]), pack2bf(r[10], r[11]), pack2bf(r[12], r[13]), pack2bf(r[14], r[15]));
+    }
+}
+
+// ------------------------------------------------------------------ MFMA backward-data
+// wave = 32 consecutive input voxels x MB 32-channel blocks of dx; contraction over (tap, C_out)
+template <int MB>
+__global__ __launch_bounds__(256) void up_dgrad_mfma_kernel(const bf16_t *__restrict__ dy,
+                                                           const bf16_t *__restrict__ packed, bf16_t *__restrict__ dx,
+                                                           int64_t V, int D, int H, int W, int cin, int cout)
+{
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int hb = lane >> 5, vl = lane & 31;
+    const int64_t nb = (int64_t)blockIdx.x * 4 + wv;
+    const int cib0 = blockIdx.y * MB, nkc = cout / 16;
+    const int64_t v = nb * 32 + vl;
+    const bool live = v < V;
+    const int64_t vv = live ? v : 0;
+    int w = (int)(vv % W);
+    int h = (int)((vv / W) % H);
+    int d = (int)((vv / ((int64_t)W * H)) % D);
+    int64_t n = vv / ((int64_t)W * H * D);
+    f32x16 acc[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[m][i] = 0.f;
+    const uint4 *ap = reinterpret_cast<const uint4 *>(packed) + lane;
+    for (int t = 0; t < 8; ++t) {
+        int64_t o = ((n * 2 * D + 2 * d + (t >> 2)) * 2 * H + 2 * h + ((t >> 1) & 1)) * (2 * (int64_t)W) + 2 * w + (t & 1);
+        const uint4 *gp = reinterpret_cast<const uint4 *>(dy + o * cout + hb * 8);
+        for (int kc = 0; kc < nkc; ++kc) {
+            uint4 braw = live ? gp[kc * 2] : make_uint4(0, 0, 0, 0);
+            bf16x8 b = __builtin_bit_cast(bf16x8, braw);
+#pragma unroll
+            for (int m = 0; m < MB; ++m) {
+                uint4 araw = ap[(((int64_t)(cib0 + m) * 8 + t) * nkc + kc) * 64];
+                acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, araw), b, acc[m], 0, 0, 0);
+            }
+        }
+    }
+    if (!live) return;
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        uint4 *dst = reinterpret_cast<uint4 *>(dx + v * cin + (cib0 + m) * 32 + hb * 16);
+        dst[0] = make_uint4(pack2bf(acc[m][0], acc[m][1]), pack2bf(acc[m][2], acc[m][3]), pack2bf(acc[m][4], acc[m][5]),
+                            pack2bf(acc[m][6], acc[m][7]));
+        dst[1] = make_uint4(pack2bf(acc[m][8], acc[m][9]), pack2bf(acc[m][10], acc[m][11]),
+                            pack2bf(acc[m][12], acc[m][13]), pack2bf(acc[m][14], acc[m][15]));
+    }
+}
+
+// ------------------------------------------------------------------ MFMA backward-weight
+// Workgroup: one 32-channel block of x, one 32-channel block of dy, a strided set of
+// 4x4x8 input-voxel tiles (8x8x16 output voxels).  Wave wv owns taps (i,j) = (wv/2, wv%2),
+// k = 0,1.  K-step s covers input voxels (d = s/2, h = 2*(s%2) + lane half, w = 0..7).
+namespace uw {
+constexpr int TD = 4, TH = 4, TW = 8;
+constexpr int NVOX = TD * TH * TW;            // 128 input voxels
+constexpr int XS_BYTES = NVOX * 64;           // 8 KB
+constexpr int GS_BYTES = NVOX * 8 * 64;       // 64 KB: [2TD][2TH][2TW][32 ch]
+constexpr int LDS_BYTES = XS_BYTES + GS_BYTES + 4 * 32 * 4;
+}  // namespace uw
+
+__device__ __forceinline__ bf16x8 up_tr_pair(const unsigned char *base, int off0, int off1)
+{
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(base + off0));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(base + off1));
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+__global__ __launch_bounds__(256) void up_wgrad_mfma_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy,
+                                                           float *__restrict__ ws, int64_t per_split, int N, int D,
+                                                           int H, int W, int cin, int cout, int ntd, int nth, int ntw,
+                                                           int64_t ntiles, int nsplit)
+{
+    using namespace uw;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    unsigned char *xs = smem;
+    unsigned char *gs = smem + XS_BYTES;
+    float *dbs = reinterpret_cast<float *>(smem + XS_BYTES + GS_BYTES);
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int hb = lane >> 5, blk = lane >> 4, j = lane & 15;
+    const int cib = blockIdx.y, cob = blockIdx.z;
+    const int ti = wv >> 1, tj = wv & 1;
+    const int lane_x = (hb * TW + (j >> 2)) * 64 + (blk & 1) * 32 + (j & 3) * 8;
+    // dy tile voxel (2d+ti, 2h+tj, 2w+k), h = 2*(s%2)+hb, w = 4r + j/4
+    const int lane_g = (((ti * 2 * TH) + 2 * hb + tj) * (2 * TW) + 2 * (j >> 2)) * 64 + (blk & 1) * 32 + (j & 3) * 8;
+    f32x16 acc[2], accb;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) acc[0][i] = acc[1][i] = accb[i] = 0.f;
+    bf16x8 ones;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
+
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += nsplit) {
+        int64_t q = tile;
+        const int twi = (int)(q % ntw);
+        q /= ntw;
+        const int thi = (int)(q % nth);
+        q /= nth;
+        const int tdi = (int)(q % ntd);
+        const int n = (int)(q / ntd);
+        const int d0 = tdi * TD, h0 = thi * TH, w0 = twi * TW;
+        __syncthreads();
+        for (int i = tid; i < NVOX * 4; i += 256) {
+            int vox = i >> 2, part = i & 3;
+            int lw = vox % TW, lh = (vox / TW) % TH, ld = vox / (TW * TH);
+            int gd = d0 + ld, gh = h0 + lh, gw = w0 + lw;
+            uint4 val = make_uint4(0, 0, 0, 0);
+            if (gd < D && gh < H && gw < W)
+                val = *reinterpret_cast<const uint4 *>(x + ((((int64_t)n * D + gd) * H + gh) * W + gw) * cin + cib * 32 + part * 8);
+            *reinterpret_cast<uint4 *>(xs + vox * 64 + part * 16) = val;
+        }
+        for (int i = tid; i < NVOX * 8 * 4; i += 256) {
+            int vox = i >> 2, part = i & 3;
+            int lw = vox % (2 * TW), lh = (vox / (2 * TW)) % (2 * TH), ld = vox / (4 * TW * TH);
+            int gd = 2 * d0 + ld, gh = 2 * h0 + lh, gw = 2 * w0 + lw;
+            uint4 val = make_uint4(0, 0, 0, 0);
+            if (gd < 2 * D && gh < 2 * H && gw < 2 * W)
+                val = *reinterpret_cast<const uint4 *>(dy + ((((int64_t)n * 2 * D + gd) * 2 * H + gh) * 2 * W + gw) * cout + cob * 32 + part * 8);
+            *reinterpret_cast<uint4 *>(gs + vox * 64 + part * 16) = val;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int s = 0; s < NVOX / 16; ++s) {
+            const int sx = (((s >> 1) * TH + 2 * (s & 1)) * TW) * 64;
+            const int sg = (((2 * (s >> 1)) * (2 * TH) + 4 * (s & 1)) * (2 * TW)) * 64;
+            bf16x8 ax = up_tr_pair(xs, lane_x + sx, lane_x + sx + 4 * 64);
+#pragma unroll
+            for (int k = 0; k < 2; ++k) {
+                bf16x8 bg = up_tr_pair(gs, lane_g + sg + k * 64, lane_g + sg + k * 64 + 8 * 64);
+                acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax, bg, acc[k], 0, 0, 0);
+                accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, bg, accb, 0, 0, 0);
+            }
+        }
+    }
+    float *out = ws + (int64_t)blockIdx.x * per_split;
+    const int co = cob * 32 + (lane & 31);
+#pragma unroll
+    for (int k = 0; k < 2; ++k) {
+        const int tap = (ti * 2 + tj) * 2 + k;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            int ci = cib * 32 + (i >> 2) * 8 + hb * 4 + (i & 3);
+            out[((int64_t)tap * cin + ci) * cout + co] = acc[k][i];
+        }
+    }
+    if (cib == 0) {  // bias gradient: add the four waves' tap sums in a fixed order
+        if (hb == 0) dbs[wv * 32 + lane] = accb[0];
+        __syncthreads();
+        if (tid < 32) out[(int64_t)8 * cin * cout + cob * 32 + tid] = ((dbs[tid] + dbs[32 + tid]) + dbs[64 + tid]) + dbs[96 + tid];
+    }
+}
+
+// ------------------------------------------------------------------ direct kernels
+template <typename T>
+__global__ __launch_bounds__(256) void up_fwd_direct_kernel(const T *__restrict__ x, const T *__restrict__ w,
+                                                           const float *__restrict__ bias, T *__restrict__ y,
+                                                           int64_t total, int D, int H, int W, int cin, int cout)
+{
+    int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;  // over output elements; D,H,W are input sizes
+    if (gid >= total) return;
+    int co = (int)(gid % cout);
+    int64_t o = gid / cout;
+    int ow = (int)(o % (2 * W));
+    int oh = (int)((o / (2 * W)) % (2 * H));
+    int od = (int)((o / ((int64_t)4 * W * H)) % (2 * D));
+    int64_t n = o / ((int64_t)8 * W * H * D);
+    int tap = ((od & 1) * 2 + (oh & 1)) * 2 + (ow & 1);
+    int64_t v = ((n * D + (od >> 1)) * H + (oh >> 1)) * (int64_t)W + (ow >> 1);
+    float acc = bias ? bias[co] : 0.f;
+    const T *xp = x + v * cin;
+    const T *wp = w + (int64_t)tap * cin * cout + co;
+    for (int ci = 0; ci < cin; ++ci) acc += elem<T>::ld(xp + ci) * elem<T>::ld(wp + (int64_t)ci * cout);
+    elem<T>::st(y + gid, acc);
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void up_dgrad_direct_kernel(const T *__restrict__ dy, const T *__restrict__ w,
+                                                             T *__restrict__ dx, int64_t total, int D, int H, int W,
+                                                             int cin, int cout)
+{
+    int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= total) return;
+    int ci = (int)(gid % cin);
+    int64_t v = gid / cin;
+    int ww = (int)(v % W);
+    int hh = (int)((v / W) % H);
+    int dd = (int)((v / ((int64_t)W * H)) % D);
+    int64_t n = v / ((int64_t)W * H * D);
+    float acc = 0.f;
+    for (int t = 0; t < 8; ++t) {
+        int64_t o = ((n * 2 * D + 2 * dd + (t >> 2)) * 2 * H + 2 * hh + ((t >> 1) & 1)) * (2 * (int64_t)W) + 2 * ww + (t & 1);
+        const T *gp = dy + o * cout;
+        const T *wp = w + ((int64_t)t * cin + ci) * cout;
+        for (int co = 0; co < cout; ++co) acc += elem<T>::ld(gp + co) * elem<T>::ld(wp + co);
+    }
+    elem<T>::st(dx + gid, acc);
+}
+
+constexpr int UW_CIB = 8;
+// block (split, ci-block, co-block): thread owns channel co and every (256/CB)-th input voxel
+template <typename T>
+__global__ __launch_bounds__(256) void up_wgrad_direct_kernel(const T *__restrict__ x, const T *__restrict__ dy,
+                                                             float *__restrict__ ws, int64_t V, int D, int H, int W,
+                                                             int cin, int cout, int CB, int64_t slab, int64_t per_split)
+{
+    __shared__ float red[256];
+    int tid = threadIdx.x;
+    int nvs = 256 / CB;
+    int cl = tid % CB, vs = tid / CB;
+    int co = blockIdx.z * CB + cl;
+    bool active = (vs < nvs) && (co < cout);
+    int ci0 = blockIdx.y * UW_CIB;
+    int64_t v0 = (int64_t)blockIdx.x * slab;
+    int64_t v1 = v0 + slab < V ? v0 + slab : V;
+    float acc[8][UW_CIB];
+    float accb = 0.f;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int c = 0; c < UW_CIB; ++c) acc[t][c] = 0.f;
+    if (active) {
+        for (int64_t v = v0 + vs; v < v1; v += nvs) {
+            int ww = (int)(v % W);
+            int hh = (int)((v / W) % H);
+            int dd = (int)((v / ((int64_t)W * H)) % D);
+            int64_t n = v / ((int64_t)W * H * D);
+            float xv[UW_CIB];
+#pragma unroll
+            for (int c = 0; c < UW_CIB; ++c) xv[c] = (ci0 + c < cin) ? elem<T>::ld(x + v * cin + ci0 + c) : 0.f;
+#pragma unroll
+            for (int t = 0; t < 8; ++t) {
+                int64_t o = ((n * 2 * D + 2 * dd + (t >> 2)) * 2 * H + 2 * hh + ((t >> 1) & 1)) * (2 * (int64_t)W) + 2 * ww + (t & 1);
+                float g = elem<T>::ld(dy + o * cout + co);
+                accb += g;
+#pragma unroll
+                for (int c = 0; c < UW_CIB; ++c) acc[t][c] += xv[c] * g;
+            }
+        }
+    }
+    float *out = ws + (int64_t)blockIdx.x * per_split;
+#pragma unroll
+    for (int t = 0; t < 8; ++t)
+#pragma unroll
+        for (int c = 0; c < UW_CIB; ++c) {
+            red[tid] = acc[t][c];
+            __syncthreads();
+            if (active && vs == 0 && ci0 + c < cin) {
+                float s = 0.f;
+                for (int k = 0; k < nvs; ++k) s += red[k * CB + cl];
+                out[((int64_t)t * cin + ci0 + c) * cout + co] = s;
+            }
+            __syncthreads();
+        }
+    if (blockIdx.y == 0) {
+        red[tid] = accb;
+        __syncthreads();
+        if (active && vs == 0) {
+            float s = 0.f;
+            for (int k = 0; k < nvs; ++k) s += red[k * CB + cl];
+            out[(int64_t)8 * cin * cout + co] = s;
+        }
+    }
+}
+
+static int64_t up_direct_nsplit(int64_t V)
+{
+    int64_t s = V / 256;
+    return s < 1 ? 1 : (s > 1024 ? 1024 : s);
+}
+
+static void up_wgrad_plan(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout, int64_t *ntiles,
+                          int *nsplit)
+{
+    *ntiles = N * ((D + uw::TD - 1) / uw::TD) * ((H + uw::TH - 1) / uw::TH) * ((W + uw::TW - 1) / uw::TW);
+    int64_t yz = (cin / 32) * (cout / 32);
+    int64_t s = 1024 / yz;
+    if (s < 1) s = 1;
+    if (s > *ntiles) s = *ntiles;
+    *nsplit = (int)s;
+}
+
+}  // namespace k3
+
+using namespace k3;
+
+extern "C" {
+
+int k3_upconv3d_packed_bytes(int64_t cin, int64_t cout, int dtype, size_t *bytes)
+{
+    if (!bytes || cin <= 0 || cout <= 0 || (dtype != K3_BF16 && dtype != K3_F32)) return K3_E_BADARG;
+    *bytes = up_mfma_ok(dtype, cin, cout) ? (size_t)2 * 8 * cin * cout * sizeof(bf16_t) : 0;
+    return K3_OK;
+}
+
+int k3_upconv3d_pack_weights(const void *w, int64_t cin, int64_t cout, int dtype, void *packed, size_t packed_bytes,
+                             void *stream)
+{
+    size_t need = 0;
+    int rc = k3_upconv3d_packed_bytes(cin, cout, dtype, &need);
+    if (rc != K3_OK) return rc;
+    if (need == 0) return K3_OK;
+    if (!w || !packed) return K3_E_BADARG;
+    if (packed_bytes < need) return K3_E_WORKSPACE;
+    int64_t total = 2 * 8 * cin * cout;
+    up_pack_kernel<<<dim3((unsigned)((total + 255) / 256)), 256, 0, (hipStream_t)stream>>>((const bf16_t *)w, (bf16_t *)packed,
+                                                                                         (int)cin, (int)cout);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
+static int up_check(const k3_tensor *xd, const k3_tensor *yd)
+{
+    if (!desc_ok(xd) || !desc_ok(yd)) return K3_E_BADARG;
+    if (yd->n != xd->n || yd->d != 2 * xd->d || yd->h != 2 * xd->h || yd->w != 2 * xd->w || yd->dtype != xd->dtype)
+        return K3_E_SHAPE;
+    if (yd->d > 0x3fffffff || yd->h > 0x3fffffff || yd->w > 0x3fffffff || xd->c > 0x3fffffff || yd->c > 0x3fffffff)
+        return K3_E_UNSUPPORTED;
+    return K3_OK;
+}
+
+int k3_upconv3d_fwd(const k3_tensor *xd, const void *x, const void *w, const void *packed, const float *bias,
+                    const k3_tensor *yd, void *y, void *stream)
+{
+    int rc = up_check(xd, yd);
+    if (rc != K3_OK) return rc;
+    if (!x || !w || !y) return K3_E_BADARG;
+    hipStream_t st = (hipStream_t)stream;
+    int64_t V = voxels(xd);
+    int cin = (int)xd->c, cout = (int)yd->c;
+    if (up_mfma_ok(xd->dtype, cin, cout)) {
+        if (!packed) return K3_E_BADARG;
+        int64_t blocks = (V + 127) / 128;
+        if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+        up_fwd_mfma_kernel<<<dim3((unsigned)blocks, (unsigned)(cout / 32)), 256, 0, st>>>(
+            (const bf16_t *)x, (const bf16_t *)packed, bias, (bf16_t *)y, V, (int)xd->d, (int)xd->h, (int)xd->w, cin, cout);
+        K3_LAUNCH_CHECK();
+        return K3_OK;
+    }
+    int64_t total = V * 8 * cout;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+    if (xd->dtype == K3_F32)
+        up_fwd_direct_kernel<float><<<dim3((unsigned)blocks), 256, 0, st>>>((const float *)x, (const float *)w, bias, (float *)y,
+                                                                            total, (int)xd->d, (int)xd->h, (int)xd->w, cin, cout);
+    else
+        up_fwd_direct_kernel<bf16_t><<<dim3((unsigned)blocks), 256, 0, st>>>((const bf16_t *)x, (const bf16_t *)w, bias,
+                                                                             (bf16_t *)y, total, (int)xd->d, (int)xd->h,
+                                                                             (int)xd->w, cin, cout);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
+int k3_upconv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *w, const void *packed, const k3_tensor *dxd,
+                         void *dx, void *stream)
+{
+    int rc = up_check(dxd, dyd);
+    if (rc != K3_OK) return rc;
+    if (!dy || !w || !dx) return K3_E_BADARG;
+    hipStream_t st = (hipStream_t)stream;
+    int64_t V = voxels(dxd);
+    int cin = (int)dxd->c, cout = (int)dyd->c;
+    int D = (int)dxd->d, H = (int)dxd->h, W = (int)dxd->w;
+    if (up_mfma_ok(dxd->dtype, cin, cout)) {
+        if (!packed) return K3_E_BADARG;
+        const bf16_t *pb = (const bf16_t *)packed + (int64_t)8 * cin * cout;
+        int64_t blocks = (V + 127) / 128;
+        if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+        int nb = cin / 32;
+        if (nb % 4 == 0)
+            up_dgrad_mfma_kernel<4><<<dim3((unsigned)blocks, (unsigned)(nb / 4)), 256, 0, st>>>((const bf16_t *)dy, pb, (bf16_t *)dx, V, D, H, W, cin, cout);
+        else if (nb % 2 == 0)
+            up_dgrad_mfma_kernel<2><<<dim3((unsigned)blocks, (unsigned)(nb / 2)), 256, 0, st>>>((const bf16_t *)dy, pb, (bf16_t *)dx, V, D, H, W, cin, cout);
+        else
+            up_dgrad_mfma_kernel<1><<<dim3((unsigned)blocks, (unsigned)nb), 256, 0, st>>>((const bf16_t *)dy, pb, (bf16_t *)dx, V, D, H, W, cin, cout);
+        K3_LAUNCH_CHECK();
+        return K3_OK;
+    }
+    int64_t total = V * cin;
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+    if (dxd->dtype == K3_F32)
+        up_dgrad_direct_kernel<float><<<dim3((unsigned)blocks), 256, 0, st>>>((const float *)dy, (const float *)w, (float *)dx, total, D, H, W, cin, cout);
+    else
+        up_dgrad_direct_kernel<bf16_t><<<dim3((unsigned)blocks), 256, 0, st>>>((const bf16_t *)dy, (const bf16_t *)w, (bf16_t *)dx, total, D, H, W, cin, cout);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
+int k3_upconv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor *dyd, size_t *bytes)
+{
+    int rc = up_check(xd, dyd);
+    if (rc != K3_OK) return rc;
+    if (!bytes) return K3_E_BADARG;
+    int64_t cin = xd->c, cout = dyd->c;
+    int64_t per = 8 * cin * cout + cout;
+    if (up_mfma_ok(xd->dtype, cin, cout)) {
+        int64_t ntiles;
+        int nsplit;
+        up_wgrad_plan(xd->n, xd->d, xd->h, xd->w, cin, cout, &ntiles, &nsplit);
+        *bytes = (size_t)nsplit * per * sizeof(float);
+    } else {
+        *bytes = (size_t)up_direct_nsplit(voxels(xd)) * per * sizeof(float);
+    }
+    return K3_OK;
+}
+
+int k3_upconv3d_bwd_weight(const k3_tensor *xd, const void *x, const k3_tensor *dyd, const void *dy, float *dW, float *db,
+                           void *ws, size_t ws_bytes, void *stream)
+{
+    size_t need = 0;
+    int rc = k3_upconv3d_bwd_weight_workspace_bytes(xd, dyd, &need);
+    if (rc != K3_OK) return rc;
+    if (!x || !dy || !dW || !ws) return K3_E_BADARG;
+    if (ws_bytes < need) return K3_E_WORKSPACE;
+    hipStream_t st = (hipStream_t)stream;
+    int64_t V = voxels(xd);
+    int cin = (int)xd->c, cout = (int)dyd->c;
+    int D = (int)xd->d, H = (int)xd->h, W = (int)xd->w;
+    int64_t per = (int64_t)8 * cin * cout + cout;
+    if (up_mfma_ok(xd->dtype, cin, cout)) {
+        int64_t ntiles;
+        int nsplit;
+        up_wgrad_plan(xd->n, D, H, W, cin, cout, &ntiles, &nsplit);
+        static bool attr_done = false;
+        if (!attr_done) {
+            K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&up_wgrad_mfma_kernel),
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, uw::LDS_BYTES));
+            attr_done = true;
+        }
+        up_wgrad_mfma_kernel<<<dim3((unsigned)nsplit, (unsigned)(cin / 32), (unsigned)(cout / 32)), 256, uw::LDS_BYTES, st>>>(
+            (const bf16_t *)x, (const bf16_t *)dy, (float *)ws, per, (int)xd->n, D, H, W, cin, cout,
+            (D + uw::TD - 1) / uw::TD, (H + uw::TH - 1) / uw::TH, (W + uw::TW - 1) / uw::TW, ntiles, nsplit);
+        K3_LAUNCH_CHECK();
+        return launch_reduce_partials((const float *)ws, dW, db, (int64_t)8 * cin * cout, per, nsplit, st);
+    }
+    int64_t nsplit = up_direct_nsplit(V);
+    int64_t slab = (V + nsplit - 1) / nsplit;
+    int CB = cout < 256 ? cout : 256;
+    dim3 grid((unsigned)nsplit, (unsigned)((cin + UW_CIB - 1) / UW_CIB), (unsigned)((cout + CB - 1) / CB));
+    if (grid.y > 65535 || grid.z > 65535) return K3_E_UNSUPPORTED;
+    if (xd->dtype == K3_F32)
+        up_wgrad_direct_kernel<float><<<grid, 256, 0, st>>>((const float *)x, (const float *)dy, (float *)ws, V, D, H, W, cin, cout, CB, slab, per);
+    else
+        up_wgrad_direct_kernel<bf16_t><<<grid, 256, 0, st>>>((const bf16_t *)x, (const bf16_t *)dy, (float *)ws, V, D, H, W, cin, cout, CB, slab, per);
+    K3_LAUNCH_CHECK();
+    return launch_reduce_partials((const float *)ws, dW, db, (int64_t)8 * cin * cout, per, (int)nsplit, st);
+}
+
+}  // extern "C"

@@ -146,12 +146,28 @@ def pool3d_bwd(x, dy, add, dx):
 
 
 # ------------------------------------------------------------------ transposed convolution
-def upconv3d_fwd(x, w, bias, y):
-    _check(lib().k3_upconv3d_fwd(_d(x), _p(x), _p(w), _p(bias), _d(y), _p(y), _stream()), "k3_upconv3d_fwd")
+def upconv3d_packed_bytes(cin, cout, dtype):
+    out = ctypes.c_size_t(0)
+    _check(lib().k3_upconv3d_packed_bytes(ctypes.c_int64(cin), ctypes.c_int64(cout), ctypes.c_int(dtype),
+                                          ctypes.byref(out)), "k3_upconv3d_packed_bytes")
+    return out.value
 
 
-def upconv3d_bwd_data(dy, w, dx):
-    _check(lib().k3_upconv3d_bwd_data(_d(dy), _p(dy), _p(w), _d(dx), _p(dx), _stream()), "k3_upconv3d_bwd_data")
+def upconv3d_pack_weights(w, packed):
+    cin, cout = w.shape[3], w.shape[4]
+    nbytes = 0 if packed is None else packed.numel() * packed.element_size()
+    _check(lib().k3_upconv3d_pack_weights(_p(w), ctypes.c_int64(cin), ctypes.c_int64(cout),
+                                          ctypes.c_int(_dtype_code(w)), _p(packed), ctypes.c_size_t(nbytes), _stream()),
+           "k3_upconv3d_pack_weights")
+
+
+def upconv3d_fwd(x, w, packed, bias, y):
+    _check(lib().k3_upconv3d_fwd(_d(x), _p(x), _p(w), _p(packed), _p(bias), _d(y), _p(y), _stream()), "k3_upconv3d_fwd")
+
+
+def upconv3d_bwd_data(dy, w, packed, dx):
+    _check(lib().k3_upconv3d_bwd_data(_d(dy), _p(dy), _p(w), _p(packed), _d(dx), _p(dx), _stream()),
+           "k3_upconv3d_bwd_data")
 
 
 def upconv3d_bwd_weight_workspace_bytes(x, dy):
