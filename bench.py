@@ -1,0 +1,290 @@
+#!/usr/bin/env python3
+"""Benchmark of the k3 hot path on one MI355X.
+
+Default workload ("cfg2"): the 3-D U-Net encoder block -- two 3x3x3 conv + ReLU layers
+(32 -> 32 channels) and a 2x2x2 max-pool on a 1 x 64^3 volume, bf16 with fp32
+accumulation, forward + backward (both weight gradients, both data gradients, pool
+backward).  A step is one pass of that block; the step is captured in a HIP graph so the
+~10 kernel launches are not bound by host launch latency.  The headline value is the
+exact (in-bounds) convolution FLOPs of the step divided by the step time.
+
+Other workloads: "unet128" (full 4-level U-Net, base 32, 1 x 128^3, no swapping) and
+"unet256" (base 64, 2 x 256^3, every encoder activation swapped to pinned host memory and
+prefetched back); they report voxels/s, swap bandwidth and overlap in the "unet" object.
+
+Prints ONE JSON line on stdout.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+MFMA_BF16_PEAK_TFLOPS = 2516.6   # 256 CU x 4096 FLOP/clk x 2.4 GHz, dense
+HBM_PEAK_GBS = 8000.0
+
+
+def conv_flops(n, d, h, w, cin, cout):
+    """Exact multiply-add FLOPs of one 3x3x3 pass: taps that fall into the zero padding are not counted."""
+    return 2.0 * n * cin * cout * (3 * d - 2) * (3 * h - 2) * (3 * w - 2)
+
+
+def time_calls(fn, iters, warm=3):
+    """Average duration (ms) of fn() over `iters` back-to-back calls, HIP events on the launch stream."""
+    import torch
+    for _ in range(warm):
+        fn()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    e0.record()
+    for _ in range(iters):
+        fn()
+    e1.record()
+    e1.synchronize()
+    return e0.elapsed_time(e1) / iters
+
+
+# ----------------------------------------------------------------------------- cfg2
+def bench_cfg2(args):
+    import numpy as np
+    import torch
+    import synth
+    from paper_1811_12174_amd import k3
+
+    N, S, C = 1, 64, 32
+    bf = torch.bfloat16
+
+    def dev(a):
+        return torch.from_numpy(a).cuda().to(bf).contiguous()
+
+    x = dev(synth.activations(1, (N, S, S, S, C), "bf16"))
+    w1 = dev(synth.conv_weights(2, C, C, "bf16"))
+    w2 = dev(synth.conv_weights(3, C, C, "bf16"))
+    b1 = torch.zeros(C, device="cuda")
+    b2 = torch.zeros(C, device="cuda")
+    dyp = dev(synth.activations(4, (N, S // 2, S // 2, S // 2, C), "bf16"))
+    pk1 = torch.empty(k3.conv3d_packed_bytes(C, C, k3.BF16), device="cuda", dtype=torch.uint8)
+    pk2 = torch.empty_like(pk1)
+    k3.conv3d_pack_weights(w1, pk1)
+    k3.conv3d_pack_weights(w2, pk2)
+    a1, a2, da2, da1, dx = (torch.empty_like(x) for _ in range(5))
+    p = torch.empty_like(dyp)
+    dW1, dW2 = torch.empty((3, 3, 3, C, C), device="cuda"), torch.empty((3, 3, 3, C, C), device="cuda")
+    db1, db2 = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
+    ws = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(x, a1), device="cuda", dtype=torch.uint8)
+
+    def step():
+        k3.conv3d_fwd(x, w1, pk1, b1, 1, a1)
+        k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2)
+        k3.pool3d_fwd(a2, p)
+        k3.pool3d_bwd(a2, dyp, None, da2)
+        k3.conv3d_bwd_weight(a1, da2, a2, dW2, db2, ws)
+        k3.conv3d_bwd_data(da2, a2, w2, pk2, da1)
+        k3.conv3d_bwd_weight(x, da1, a1, dW1, db1, ws)
+        k3.conv3d_bwd_data(da1, a1, w1, pk1, dx)
+
+    for _ in range(3):
+        step()
+    torch.cuda.synchronize()
+    run = step
+    graph = None
+    if not args.no_graph:
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph):
+            step()
+        run = graph.replay
+    for _ in range(args.warmup):
+        run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        run()
+    torch.cuda.synchronize()
+    ms = (time.perf_counter() - t0) * 1e3 / args.steps
+
+    f1 = conv_flops(N, S, S, S, C, C)
+    step_flops = 6 * f1
+    value = step_flops / (ms * 1e-3) / 1e12
+
+    # per-call timings (events on the launch stream), same launch configuration as the step
+    it = max(20, args.steps // 4)
+    kern = {
+        "conv3d_fwd": time_calls(lambda: k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2), it),
+        "conv3d_bwd_data": time_calls(lambda: k3.conv3d_bwd_data(da2, a2, w2, pk2, da1), it),
+        "conv3d_bwd_weight": time_calls(lambda: k3.conv3d_bwd_weight(a1, da2, a2, dW2, db2, ws), it),
+        "pool3d_fwd": time_calls(lambda: k3.pool3d_fwd(a2, p), it),
+        "pool3d_bwd": time_calls(lambda: k3.pool3d_bwd(a2, dyp, None, da2), it),
+    }
+
+    def mix():   # the implicit-GEMM kernel as the step launches it: 2 forward + 2 backward-data passes
+        k3.conv3d_fwd(x, w1, pk1, b1, 1, a1)
+        k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2)
+        k3.conv3d_bwd_data(da2, a2, w2, pk2, da1)
+        k3.conv3d_bwd_data(da1, a1, w1, pk1, dx)
+    mfma_ms = time_calls(mix, it) / 4.0
+    share = {"conv_mfma_kernel": 4 * mfma_ms, "conv_wgrad_mfma_kernel": 2 * kern["conv3d_bwd_weight"]}
+    dominant = max(share, key=share.get)
+    dom_ms = mfma_ms if dominant == "conv_mfma_kernel" else kern["conv3d_bwd_weight"]
+    achieved = f1 / (dom_ms * 1e-3) / 1e12
+    roofline = {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
+                "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
+                "flops_per_launch": f1, "avg_launch_ms": round(dom_ms, 5), "traffic": load_traffic(dominant, "cfg2")}
+    out = {
+        "metric": "3D conv fwd+bwd TFLOP/s", "value": round(value, 2), "unit": "TFLOP/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True,
+        "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+        "config": {"workload": "cfg2: encoder block, 2x(conv3x3x3 32->32 + ReLU) + 2x2x2 max-pool, N=1, 64^3, fwd+bwd",
+                   "hip_graph": graph is not None, "conv_passes_per_step": 6, "flops_per_step": step_flops},
+        "pct_mfma_peak": round(100 * value / MFMA_BF16_PEAK_TFLOPS, 2),
+        "voxels_per_s": round(N * S ** 3 / (ms * 1e-3), 1),
+        "roofline": roofline,
+        "call_ms": {k: round(v, 5) for k, v in kern.items()},
+        "call_tflops": {k: round(f1 / (kern[k] * 1e-3) / 1e12, 2) for k in ("conv3d_fwd", "conv3d_bwd_data", "conv3d_bwd_weight")},
+    }
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline_cfg2(step_flops)
+    return out
+
+
+def cpu_baseline_cfg2(step_flops):
+    """The oracle, as it stands, on the same block (one full forward + backward), timed on the host cores."""
+    import numpy as np
+    import oracle
+    import synth
+    oracle.build(force=False)
+    N, S, C = 1, 64, 32
+    x = synth.activations(1, (N, S, S, S, C), "bf16").astype(np.float64)
+    w1 = synth.conv_weights(2, C, C, "bf16").astype(np.float64)
+    w2 = synth.conv_weights(3, C, C, "bf16").astype(np.float64)
+    dyp = synth.activations(4, (N, S // 2, S // 2, S // 2, C), "bf16").astype(np.float64)
+    t0 = time.perf_counter()
+    a1 = oracle.conv3d_fwd(x, w1, None, relu=True)
+    a2 = oracle.conv3d_fwd(a1, w2, None, relu=True)
+    oracle.pool3d_fwd(a2)
+    g2 = oracle.relu_bwd(oracle.pool3d_bwd(a2, dyp), a2)
+    oracle.conv3d_bwd_weight(a1, g2)
+    g1 = oracle.relu_bwd(oracle.conv3d_bwd_data(g2, w2), a1)
+    oracle.conv3d_bwd_weight(x, g1)
+    oracle.conv3d_bwd_data(g1, w1)
+    dt = time.perf_counter() - t0
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {"value": round(step_flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+            "seconds": round(dt, 2), "sample": "one full cfg2 step (6 conv passes + pool fwd/bwd) in fp64 direct loops"}
+
+
+def load_traffic(kernel, workload):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE); null when not recorded."""
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            t = json.load(f)
+        return t.get(workload, {}).get(kernel)
+    except (OSError, ValueError):
+        return None
+
+
+# ----------------------------------------------------------------------------- U-Net steps
+def unet_flops(base, levels, n, size):
+    """Exact conv FLOPs of one forward + backward U-Net step (3x3x3 layers only; no dgrad for the first layer)."""
+    import synth
+    total = 0.0
+    res = {}
+    for name, kind, ci, co in synth.unet_plan(base, 1, levels, 3):
+        if kind != "conv":
+            continue
+        l = int(name[3])
+        s = size // 2 ** l
+        f = conv_flops(n, s, s, s, ci, co)
+        total += f * (2 if name == "enc0.conv1" else 3)
+    return total
+
+
+def bench_unet(args, base, size, n, swap, label):
+    import numpy as np
+    import torch
+    import synth
+    from paper_1811_12174_amd import k3
+    from paper_1811_12174_amd.unet import UNet3D
+    params = synth.unet_params(base=base, levels=4, dtype="bf16")
+    x = torch.from_numpy(synth.volume_field(7, n, size, dtype="bf16")).cuda().to(torch.bfloat16)
+    lab = torch.from_numpy(synth.ellipsoid_labels(8, n, size)).cuda()
+    net = UNet3D(params, base=base, levels=4)
+    steps, warm = max(1, args.unet_steps), 2
+
+    def run(sw):
+        for _ in range(warm):
+            net.step(x, lab, swap=sw)
+        torch.cuda.synchronize()
+        before = dict(net.last_stats) if sw else {}
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            net.step(x, lab, swap=sw)
+        torch.cuda.synchronize()
+        if sw:
+            k3.lms_sync(net.lms)
+        dt = (time.perf_counter() - t0) / steps
+        moved = (net.last_stats["bytes_out"] - before["bytes_out"]) / steps if sw else 0
+        return dt, moved
+
+    t_noswap, _ = run(False)
+    fl = unet_flops(base, 4, n, size)
+    V = n * size ** 3
+    res = {"workload": label, "steps": steps, "ms_per_step_no_swap": round(t_noswap * 1e3, 3),
+           "voxels_per_s_no_swap": round(V / t_noswap, 1), "conv_tflops_no_swap": round(fl / t_noswap / 1e12, 2),
+           "pct_mfma_peak_no_swap": round(100 * fl / t_noswap / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2),
+           "peak_mem_gb": round(torch.cuda.max_memory_allocated() / 1e9, 2)}
+    if swap:
+        t_swap, moved = run(True)
+        res.update({"ms_per_step_swap": round(t_swap * 1e3, 3), "voxels_per_s_swap": round(V / t_swap, 1),
+                    "swap_overhead_pct": round(100 * (t_swap / t_noswap - 1), 2),
+                    "swap_bytes_per_direction_per_step": int(moved),
+                    "copy_seconds_at_link_peak": round(moved / 57e9, 4)})
+    net.close()
+    return res
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=300)
+    ap.add_argument("--warmup", type=int, default=30)
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "unet128", "unet256"])
+    ap.add_argument("--unet-steps", type=int, default=3)
+    ap.add_argument("--with-unet", action="store_true", help="also time the full U-Net steps (cfg3, and cfg4 with swapping)")
+    ap.add_argument("--no-graph", action="store_true")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (the paper's multi-GPU all-reduce is out of scope); use --gpus 1",
+              file=sys.stderr)
+        sys.exit(2)
+    import torch
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the k3 kernels have no CPU fallback", file=sys.stderr)
+        sys.exit(1)
+    from paper_1811_12174_amd import k3
+    k3.lib()
+    if args.workload == "cfg2":
+        out = bench_cfg2(args)
+        if args.with_unet:
+            out["unet"] = [bench_unet(args, 32, 128, 1, False, "cfg3: U-Net base 32, 1 x 128^3, no swapping"),
+                           bench_unet(args, 64, 256, 2, True, "cfg4: U-Net base 64, 2 x 256^3, encoder activations swapped")]
+    else:
+        if args.workload == "unet128":
+            u = bench_unet(args, 32, 128, 1, False, "cfg3: U-Net base 32, 1 x 128^3, no swapping")
+        else:
+            u = bench_unet(args, 64, 256, 2, True, "cfg4: U-Net base 64, 2 x 256^3, encoder activations swapped")
+        key = "voxels_per_s_swap" if "voxels_per_s_swap" in u else "voxels_per_s_no_swap"
+        ms = u.get("ms_per_step_swap", u["ms_per_step_no_swap"])
+        out = {"metric": "U-Net step voxels/s", "value": u[key], "unit": "voxels/s", "n_gpus": 1, "steps": u["steps"],
+               "warmup": 2, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+               "dtype": "bf16", "data": "synthetic", "config": {"workload": u["workload"]}, "unet": u}
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()
