@@ -80,6 +80,7 @@ int k3_conv3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *x2d, cons
         if (!packed) return K3_E_BADARG;
         return conv_fwd_mfma(a, (hipStream_t)stream);
     }
+    if (conv_first_ok(a.dtype, a.c1, a.c2, a.cout)) return conv_first_fwd(a, (hipStream_t)stream);
     return conv_fwd_direct(a, (hipStream_t)stream);
 }
 
@@ -105,6 +106,8 @@ int k3_conv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor *x
     int64_t c1 = xd->c, c2 = x2d ? x2d->c : 0;
     if (mfma_ok(xd->dtype, c1, c2, dyd->c))
         *bytes = conv_wgrad_mfma_ws_bytes(xd->n, xd->d, xd->h, xd->w, c1 + c2, dyd->c);
+    else if (conv_first_ok(xd->dtype, c1, c2, dyd->c))
+        *bytes = conv_first_wgrad_ws_bytes(xd->n, xd->d, xd->h, xd->w, dyd->c);
     else
         *bytes = conv_wgrad_direct_ws_bytes(voxels(xd), c1 + c2, dyd->c);
     return K3_OK;
@@ -124,6 +127,7 @@ int k3_conv3d_bwd_weight(const k3_tensor *xd, const void *x, const k3_tensor *x2
     if (ws_bytes < need) return K3_E_WORKSPACE;
     a.x = x; a.x2 = x2; a.dy = dy; a.ymask = y_mask;
     if (mfma_ok(a.dtype, a.c1, a.c2, a.cout)) return conv_wgrad_mfma(a, dW, db, (float *)ws, (hipStream_t)stream);
+    if (conv_first_ok(a.dtype, a.c1, a.c2, a.cout)) return conv_first_wgrad(a, dW, db, (float *)ws, (hipStream_t)stream);
     return conv_wgrad_direct(a, dW, db, (float *)ws, (hipStream_t)stream);
 }
 

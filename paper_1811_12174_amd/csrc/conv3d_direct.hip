@@ -167,24 +167,39 @@ __global__ __launch_bounds__(256) void conv_wgrad_direct_kernel(
     }
 }
 
-// out[i] = sum_s ws[s*count + i] in increasing s (fixed order); the first countW
-// entries go to dW, the remaining ones (bias gradient) to db when it is not null.
+// out[i] = sum_s ws[s*count + i] in a fixed order: a block owns 64 entries; its 4 thread groups
+// add the splits g, g+4, g+8, ... in increasing order and the four group sums are then combined
+// as ((g0+g1)+g2)+g3.  The first countW entries go to dW, the remaining ones (bias gradient)
+// to db when it is not null.
 __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__restrict__ ws, float *__restrict__ dW,
                                                              float *__restrict__ db, int64_t countW, int64_t count,
                                                              int nsplit)
 {
-    int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= count) return;
-    float s = 0.f;
-    for (int k = 0; k < nsplit; ++k) s += ws[(int64_t)k * count + i];
-    if (i < countW) dW[i] = s;
-    else if (db) db[i - countW] = s;
+    __shared__ float part[4][64];
+    const int e = threadIdx.x & 63, g = threadIdx.x >> 6;
+    const int64_t i = (int64_t)blockIdx.x * 64 + e;
+    float s0 = 0.f, s1 = 0.f;
+    if (i < count) {
+        int k = g;
+        for (; k + 4 < nsplit; k += 8) {   // two independent chains, merged below in a fixed order
+            s0 += ws[(int64_t)k * count + i];
+            s1 += ws[(int64_t)(k + 4) * count + i];
+        }
+        if (k < nsplit) s0 += ws[(int64_t)k * count + i];
+    }
+    part[g][e] = s0 + s1;
+    __syncthreads();
+    if (g == 0 && i < count) {
+        float s = ((part[0][e] + part[1][e]) + part[2][e]) + part[3][e];
+        if (i < countW) dW[i] = s;
+        else if (db) db[i - countW] = s;
+    }
 }
 
 int launch_reduce_partials(const float *ws, float *dW, float *db, int64_t countW, int64_t count, int nsplit,
                            hipStream_t st)
 {
-    int64_t blocks = (count + 255) / 256;
+    int64_t blocks = (count + 63) / 64;
     reduce_partials_kernel<<<dim3((unsigned)blocks), 256, 0, st>>>(ws, dW, db, countW, count, nsplit);
     K3_LAUNCH_CHECK();
     return K3_OK;

@@ -83,8 +83,14 @@ struct TileCfg {
     static constexpr int CK = 16;
     static constexpr int HD = TD + 2, HH = TH + 2, HW = TW + 2;
     static constexpr int NHALO = HD * HH * HW;
-    static constexpr int XS_STRIDE = CK * 2 + 16;  // bytes per voxel row, padded against bank conflicts
-    static constexpr int XS_BYTES = NHALO * XS_STRIDE;
+    // LDS tile: 32 bytes per voxel (16 channels), rows of HW voxels padded by one 16-byte slot.
+    // A ds_read_b128 serves 16 lanes per cycle = two 8-voxel rows of a patch; voxels of one row
+    // land on the even 16-byte slots and, thanks to the odd row pitch, the next row on the odd
+    // ones, so the 16 lanes cover all 64 banks exactly once.
+    static constexpr int XS_VOX = CK * 2;
+    static constexpr int XS_ROW = HW * XS_VOX + 16;
+    static constexpr int XS_PLANE = HH * XS_ROW;
+    static constexpr int XS_BYTES = HD * XS_PLANE;
     static constexpr int WS_BYTES = TAPS * MB * 1024;
     static constexpr int LDS_BYTES = XS_BYTES + WS_BYTES;
     static constexpr int PW = TW / 8, PH = TH / 4;  // 4x8 (h x w) voxel patches per plane
@@ -136,13 +142,13 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 #pragma unroll
             for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
 
-    // LDS voxel index (tap 0,0,0 corner) of this lane's voxel in each of the wave's patches
+    // LDS byte offset (tap 0,0,0 corner, this lane's channel half) of the lane's voxel in each patch
     int vbase[C::NBW];
 #pragma unroll
     for (int a = 0; a < C::NBW; ++a) {
         int nb = wv * C::NBW + a;
         int bw = nb % C::PW, bh = (nb / C::PW) % C::PH, bd = nb / (C::PW * C::PH);
-        vbase[a] = (bd * C::HH + bh * 4 + (vl >> 3)) * C::HW + bw * 8 + (vl & 7);
+        vbase[a] = bd * C::XS_PLANE + (bh * 4 + (vl >> 3)) * C::XS_ROW + (bw * 8 + (vl & 7)) * C::XS_VOX + hb * 16;
     }
 
     for (int c = 0; c < nkc; ++c) {
@@ -169,7 +175,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
                     val.w = mask_pair(val.w, m.w);
                 }
             }
-            *reinterpret_cast<uint4 *>(xs + vox * C::XS_STRIDE + half * 16) = val;
+            *reinterpret_cast<uint4 *>(xs + ld * C::XS_PLANE + lh * C::XS_ROW + lw * C::XS_VOX + half * 16) = val;
         }
         for (int g = 0; g < 27 / C::TAPS; ++g) {
             if (g > 0) __syncthreads();  // previous tap group consumed
@@ -181,17 +187,17 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
                 *reinterpret_cast<uint4 *>(wsm + ((tl * C::MB + mb) * 64 + ln) * 16) = *s;
             }
             __syncthreads();
-            const int goff = (C::TAPS == 27) ? 0 : g * (C::TAPS / 9) * C::HH * C::HW;
+            const int goff = (C::TAPS == 27) ? 0 : g * (C::TAPS / 9) * C::XS_PLANE;
 #pragma unroll
             for (int tl = 0; tl < C::TAPS; ++tl) {
-                const int toff = ((tl / 9) * C::HH + (tl / 3) % 3) * C::HW + tl % 3;
+                const int toff = (tl / 9) * C::XS_PLANE + ((tl / 3) % 3) * C::XS_ROW + (tl % 3) * C::XS_VOX;
                 bf16x8 a[C::MB];
 #pragma unroll
                 for (int mb = 0; mb < C::MB; ++mb)
                     a[mb] = *reinterpret_cast<const bf16x8 *>(wsm + ((tl * C::MB + mb) * 64 + lane) * 16);
 #pragma unroll
                 for (int nb = 0; nb < C::NBW; ++nb) {
-                    bf16x8 b = *reinterpret_cast<const bf16x8 *>(xs + (vbase[nb] + goff + toff) * C::XS_STRIDE + hb * 16);
+                    bf16x8 b = *reinterpret_cast<const bf16x8 *>(xs + vbase[nb] + goff + toff);
 #pragma unroll
                     for (int mb = 0; mb < C::MB; ++mb)
                         acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a[mb], b, acc[nb][mb], 0, 0, 0);

@@ -179,10 +179,12 @@ static void wgrad_plan(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, 
 {
     *cobn = (cout % 64 == 0) ? 2 : 1;
     *ntiles = N * ((D + wg::TD - 1) / wg::TD) * ((H + wg::TH - 1) / wg::TH) * ((W + wg::TW - 1) / wg::TW);
+    // about two resident workgroups per CU in total, and at least four tiles per workgroup so the
+    // partial-sum traffic stays small next to the tensor reads
     int64_t yz = (cin / 32) * (cout / (32 * *cobn));
-    int64_t s = 1024 / yz;
+    int64_t s = 512 / yz;
+    if (s > *ntiles / 4) s = *ntiles / 4;
     if (s < 1) s = 1;
-    if (s > *ntiles) s = *ntiles;
     *nsplit = (int)s;
 }
 

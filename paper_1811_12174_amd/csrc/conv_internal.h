@@ -40,6 +40,11 @@ int conv_dgrad_mfma(const ConvArgs &a, hipStream_t st);
 int conv_wgrad_mfma(const ConvArgs &a, float *dW, float *db, float *ws, hipStream_t st);
 size_t conv_wgrad_mfma_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout);
 
+bool conv_first_ok(int dtype, int64_t c1, int64_t c2, int64_t cout);
+int conv_first_fwd(const ConvArgs &a, hipStream_t st);
+int conv_first_wgrad(const ConvArgs &a, float *dW, float *db, float *ws, hipStream_t st);
+size_t conv_first_wgrad_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cout);
+
 int launch_reduce_partials(const float *ws, float *dW, float *db, int64_t countW, int64_t count, int nsplit,
                            hipStream_t st);
 
