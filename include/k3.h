@@ -94,11 +94,14 @@ int k3_conv3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *x2d, cons
  *   dx[n,d,h,w,ci] = sum_{kd,kh,kw,co} g[n,d-kd+1,h-kh+1,w-kw+1,co] * W[kd,kh,kw,ci,co].
  * y_mask is the stored forward output of the same layer (same shape and dtype as dy).
  * The result may be split along channels into two tensors [dx | dx2] (pass NULLs for
- * one output). */
+ * one output).  When dx_mask is not NULL (same shape and dtype as dx) the first output is
+ * zeroed where dx_mask <= 0: dx is the gradient of a stored ReLU output, and applying that
+ * layer's mask here, once, lets its backward passes run with y_mask = NULL (their fastest
+ * path: a masked input cannot be copied asynchronously into LDS). */
 int k3_conv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *y_mask,
                        const void *w, const void *packed,
                        const k3_tensor *dxd, void *dx, const k3_tensor *dx2d, void *dx2,
-                       void *stream);
+                       const void *dx_mask, void *stream);
 
 /* Workspace bytes k3_conv3d_bwd_weight needs for these shapes (split-K partial sums). */
 int k3_conv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor *x2d,

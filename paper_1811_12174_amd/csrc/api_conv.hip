@@ -85,13 +85,14 @@ int k3_conv3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *x2d, cons
 }
 
 int k3_conv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *y_mask, const void *w, const void *packed,
-                       const k3_tensor *dxd, void *dx, const k3_tensor *dx2d, void *dx2, void *stream)
+                       const k3_tensor *dxd, void *dx, const k3_tensor *dx2d, void *dx2, const void *dx_mask,
+                       void *stream)
 {
     ConvArgs a;
     int rc = fill_args(a, dxd, dx2d, dx2, dyd);
     if (rc != K3_OK) return rc;
     if (!dy || !w || !dx) return K3_E_BADARG;
-    a.dy = dy; a.ymask = y_mask; a.w = w; a.packed = packed; a.dx = dx; a.dx2 = dx2;
+    a.dy = dy; a.ymask = y_mask; a.w = w; a.packed = packed; a.dx = dx; a.dx2 = dx2; a.omask = dx_mask;
     if (mfma_ok(a.dtype, a.c1, a.c2, a.cout)) {
         if (!packed) return K3_E_BADARG;
         return conv_dgrad_mfma(a, (hipStream_t)stream);

@@ -51,7 +51,8 @@ __global__ __launch_bounds__(256) void conv_fwd_direct_kernel(
 template <typename T>
 __global__ __launch_bounds__(256) void conv_dgrad_direct_kernel(
     const T *__restrict__ dy, const T *__restrict__ ymask, const T *__restrict__ w,
-    T *__restrict__ dx, T *__restrict__ dx2, int c1, int c2, int64_t N, int D, int H, int W, int cout)
+    T *__restrict__ dx, T *__restrict__ dx2, const T *__restrict__ omask, int c1, int c2, int64_t N, int D, int H, int W,
+    int cout)
 {
     int cin = c1 + c2;
     int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
@@ -85,8 +86,12 @@ __global__ __launch_bounds__(256) void conv_dgrad_direct_kernel(
             }
         }
     }
-    if (ci < c1) elem<T>::st(dx + v * c1 + ci, acc);
-    else elem<T>::st(dx2 + v * c2 + (ci - c1), acc);
+    if (ci < c1) {
+        if (omask && !(elem<T>::ld(omask + v * c1 + ci) > 0.f)) acc = 0.f;
+        elem<T>::st(dx + v * c1 + ci, acc);
+    } else {
+        elem<T>::st(dx2 + v * c2 + (ci - c1), acc);
+    }
 }
 
 // Weight gradient: block (split s, ci-block b, co-block z) sums its voxel slab.
@@ -242,7 +247,7 @@ static int dgrad_direct_t(const ConvArgs &a, hipStream_t st)
     int64_t blocks = (total + 255) / 256;
     if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
     conv_dgrad_direct_kernel<T><<<dim3((unsigned)blocks), 256, 0, st>>>(
-        (const T *)a.dy, (const T *)a.ymask, (const T *)a.w, (T *)a.dx, (T *)a.dx2, (int)a.c1, (int)a.c2, a.N,
+        (const T *)a.dy, (const T *)a.ymask, (const T *)a.w, (T *)a.dx, (T *)a.dx2, (const T *)a.omask, (int)a.c1, (int)a.c2, a.N,
         (int)a.D, (int)a.H, (int)a.W, (int)a.cout);
     K3_LAUNCH_CHECK();
     return K3_OK;

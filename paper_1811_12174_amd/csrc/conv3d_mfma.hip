@@ -13,6 +13,8 @@
 // group of weight taps in LDS; each wave multiplies its 32-voxel patches by all taps.
 // Backward-data is the same kernel run on dy with the taps mirrored and the channel roles
 // swapped (done once, when the weights are packed).
+#include <type_traits>
+
 #include "common.h"
 #include "conv_internal.h"
 
@@ -70,6 +72,7 @@ struct MfmaParams {
     const float *bias;
     int relu;
     bf16_t *dst1, *dst2;
+    const bf16_t *omask;               // optional: dst1 is zeroed where omask (same shape) is <= 0
     int cd1, cd2;                      // output channels per destination
     int N, D, H, W;
     int ntd, nth, ntw;                 // tiles per axis
@@ -223,13 +226,327 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
                 float t = acc[nb][mb][i] + (p.bias ? p.bias[co0 + i] : 0.f);
                 v[i] = (p.relu && !(t > 0.f)) ? 0.f : t;
             }
-            bf16_t *dst = co0 < p.cd1 ? p.dst1 + vox * p.cd1 + co0 : p.dst2 + vox * p.cd2 + (co0 - p.cd1);
             uint4 o0 = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
             uint4 o1 = make_uint4(pack2bf(v[8], v[9]), pack2bf(v[10], v[11]), pack2bf(v[12], v[13]), pack2bf(v[14], v[15]));
-            reinterpret_cast<uint4 *>(dst)[0] = o0;
-            reinterpret_cast<uint4 *>(dst)[1] = o1;
+            const bool d1 = co0 < p.cd1;
+            const int64_t eo = d1 ? vox * p.cd1 + co0 : vox * p.cd2 + (co0 - p.cd1);
+            if (d1 && p.omask) {
+                const uint4 *mp = reinterpret_cast<const uint4 *>(p.omask + eo);
+                uint4 m0 = mp[0], m1 = mp[1];
+                o0.x = mask_pair(o0.x, m0.x); o0.y = mask_pair(o0.y, m0.y); o0.z = mask_pair(o0.z, m0.z); o0.w = mask_pair(o0.w, m0.w);
+                o1.x = mask_pair(o1.x, m1.x); o1.y = mask_pair(o1.y, m1.y); o1.z = mask_pair(o1.z, m1.z); o1.w = mask_pair(o1.w, m1.w);
+            }
+            uint4 *dst = reinterpret_cast<uint4 *>((d1 ? p.dst1 : p.dst2) + eo);
+            dst[0] = o0;
+            dst[1] = o1;
         }
     }
+}
+
+// ---------------------------------------------------------------------------- pipelined kernel
+// Same GEMM mapping as conv_mfma_kernel, organised for one workgroup per CU: a larger tile, so
+// each wave keeps NBW x MB accumulator blocks (fewer LDS bytes per MFMA), and asynchronous
+// staging.  A stage is (16-channel chunk c, tap plane kd): 9 taps.  While the waves multiply
+// stage s out of LDS, the data of stage s+1 -- the next tap plane of packed weights and one
+// third of the next chunk's halo tile -- is in flight from global memory straight into the
+// other LDS buffers (global_load_lds_dwordx4: lane l of a wave writes 16 bytes to LDS slot
+// base + l, from any global address; no registers are staged).  One vmcnt wait and one
+// barrier per stage.  Voxels outside the volume and the row-padding slots read a 16-byte
+// block of zeros instead.  This kernel takes no input-side ReLU mask (the asynchronous copy
+// cannot apply one); backward passes feed it gradients that were masked by their producer.
+__device__ uint4 g_zero_block[4];   // zero-initialised; source of every out-of-volume halo item
+
+template <int TD_, int TH_, int TW_, int MB_>
+struct PipeCfg {
+    static constexpr int TD = TD_, TH = TH_, TW = TW_, MB = MB_;
+    static constexpr int HD = TD + 2, HH = TH + 2, HW = TW + 2;
+    static constexpr int ROWSLOTS = HW * 2 + 1;               // 16-byte slots per halo row (32 B per voxel + 1 pad)
+    static constexpr int XS_ROW = ROWSLOTS * 16;              // odd number of slots: see TileCfg
+    static constexpr int XS_PLANE = HH * XS_ROW;
+    static constexpr int NSLOT = HD * HH * ROWSLOTS;
+    static constexpr int XGROUPS = (NSLOT + 63) / 64;         // 64-slot (1 KB) copy groups per chunk
+    static constexpr int XS_BYTES = XGROUPS * 1024;
+    static constexpr int XG_STAGE = (XGROUPS + 2) / 3;        // groups copied per stage
+    static constexpr int XG_WAVE = (XG_STAGE + 3) / 4;        // per wave and stage
+    static constexpr int WFRAGS = 9 * MB;                     // 1 KB weight fragments per stage
+    static constexpr int WF_WAVE = (WFRAGS + 3) / 4;
+    static constexpr int WS_BYTES = WFRAGS * 1024;
+    static constexpr int LDS_BYTES = 2 * XS_BYTES + 2 * WS_BYTES;
+    static constexpr int PW = TW / 8, PH = TH / 4;
+    static constexpr int NBLK = TD * PH * PW;
+    static constexpr int NBW = NBLK / 4;
+    static_assert(TW % 8 == 0 && TH % 4 == 0 && NBLK % 4 == 0, "tile must split into 4x8 patches over 4 waves");
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+    static_assert(3 * XG_WAVE <= 32, "validity bits are kept in one 32-bit mask");
+};
+
+// Asynchronous 16-byte-per-lane copy global -> LDS (64 consecutive slots starting at lds_base).
+__device__ __forceinline__ void dma16(unsigned lds_base, const void *gptr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+
+// One tile of work: output block origin, output-channel group and the halo validity bits.
+struct PipeTile {
+    int n, d0, h0, w0, mb0;
+    int64_t origin;     // linear voxel index of (n, d0, h0, w0)
+    unsigned vmask;     // bit idx: the lane's halo slot idx lies inside the volume
+    bool valid;
+};
+
+template <class C>
+__global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hb = lane >> 5, vl = lane & 31;
+    const int nkc = (p.c1 + p.c2) / 16;
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const unsigned char *zero = reinterpret_cast<const unsigned char *>(g_zero_block);
+
+    // ---- tile-independent description of the halo slots this lane copies in each stage part
+    int voxoff[3 * C::XG_WAVE];        // voxel offset of the slot from the tile origin
+    int coords[3 * C::XG_WAVE];        // halo coordinates of the slot, packed ld | lh << 8 | lw << 16
+    unsigned smask = 0, hmask = 0;     // slot is a real (voxel, half) item / holds the upper 8 channels
+#pragma unroll
+    for (int g = 0; g < 3; ++g)
+#pragma unroll
+        for (int k = 0; k < C::XG_WAVE; ++k) {
+            const int idx = g * C::XG_WAVE + k;
+            const int G = g * C::XG_STAGE + k * 4 + wv;
+            const int slot = G * 64 + lane;
+            const int r = slot / C::ROWSLOTS, pos = slot - r * C::ROWSLOTS;
+            const int ld = r / C::HH, lh = r - ld * C::HH, lw = pos >> 1;
+            const bool ok = G < C::XGROUPS && slot < C::NSLOT && pos < C::ROWSLOTS - 1;
+            voxoff[idx] = ((ld - 1) * p.H + (lh - 1)) * p.W + (lw - 1);
+            coords[idx] = ld | (lh << 8) | (lw << 16);
+            smask |= (ok ? 1u : 0u) << idx;
+            hmask |= (unsigned)(pos & 1) << idx;
+        }
+
+    // Persistent workgroups: virtual block vb = blockIdx.x + j * gridDim.x (gridDim.x is a multiple
+    // of 8, so a workgroup stays on its XCD).  The logical tile order is cut into 8 contiguous
+    // runs, one per XCD, so halo-sharing neighbours and the channel groups of a tile share an L2.
+    auto decode = [&](int64_t vb) {
+        PipeTile t;
+        const int64_t logical = (vb & 7) * p.per_xcd + (vb >> 3);
+        t.valid = (vb >> 3) < p.per_xcd && logical < p.total;
+        int64_t tile = t.valid ? logical : 0;
+        const int cg = (int)(tile % p.ncg);
+        tile /= p.ncg;
+        const int twi = (int)(tile % p.ntw);
+        tile /= p.ntw;
+        const int thi = (int)(tile % p.nth);
+        tile /= p.nth;
+        const int tdi = (int)(tile % p.ntd);
+        t.n = (int)(tile / p.ntd);
+        t.d0 = tdi * C::TD; t.h0 = thi * C::TH; t.w0 = twi * C::TW;
+        t.mb0 = cg * C::MB;
+        t.origin = (((int64_t)t.n * p.D + t.d0) * p.H + t.h0) * p.W + t.w0;
+        // a halo coordinate l is inside the volume iff 0 <= t0 + l - 1 < size, i.e. lo <= l < hi
+        const int dlo = 1 - t.d0, dhi = p.D + 1 - t.d0, hlo = 1 - t.h0, hhi = p.H + 1 - t.h0;
+        const int wlo = 1 - t.w0, whi = p.W + 1 - t.w0;
+        unsigned vm = 0;
+#pragma unroll
+        for (int idx = 0; idx < 3 * C::XG_WAVE; ++idx) {
+            const int ld = coords[idx] & 255, lh = (coords[idx] >> 8) & 255, lw = coords[idx] >> 16;
+            const bool in = ld >= dlo && ld < dhi && lh >= hlo && lh < hhi && lw >= wlo && lw < whi;
+            vm |= (in ? 1u : 0u) << idx;
+        }
+        t.vmask = vm & smask;
+        return t;
+    };
+
+    // copies part g of chunk c of tile t into x buffer `buf`
+    auto copy_x = [&](const PipeTile &t, int c, int buf, auto gtag) {
+        constexpr int g = decltype(gtag)::value;
+        const int ch0 = c * 16;
+        const bool first = ch0 < p.c1;
+        const bf16_t *src = first ? p.src1 : p.src2;
+        const int Csrc = first ? p.c1 : p.c2;
+        const int chs = first ? ch0 : ch0 - p.c1;
+        const unsigned char *base = reinterpret_cast<const unsigned char *>(src + t.origin * Csrc + chs);
+        const int strideB = Csrc * 2;
+        const unsigned xb = lds0 + buf * C::XS_BYTES;
+#pragma unroll
+        for (int k = 0; k < C::XG_WAVE; ++k) {
+            const int idx = g * C::XG_WAVE + k;
+            const int G = g * C::XG_STAGE + k * 4 + wv;
+            if (k * 4 + wv < C::XG_STAGE && G < C::XGROUPS) {
+                const unsigned char *ptr = base + (int64_t)voxoff[idx] * strideB + ((hmask >> idx) & 1) * 16;
+                if (!((t.vmask >> idx) & 1)) ptr = zero;
+                dma16(xb + G * 1024, ptr);
+            }
+        }
+    };
+    // copies the packed weights of stage (c, g) of tile t into weight buffer `buf`
+    auto copy_w = [&](const PipeTile &t, int c, int g, int buf) {
+        const unsigned wb = lds0 + 2 * C::XS_BYTES + buf * C::WS_BYTES;
+#pragma unroll
+        for (int k = 0; k < C::WF_WAVE; ++k) {
+            const int f = k * 4 + wv;   // fragment (tap tl, block mb) of this stage
+            if (f < C::WFRAGS) {
+                const int tl = f / C::MB, mb = f - tl * C::MB;
+                const uint4 *ptr = reinterpret_cast<const uint4 *>(p.packed) +
+                                   ((((int64_t)(t.mb0 + mb) * 27 + g * 9 + tl) * nkc + c) * 64 + lane);
+                dma16(wb + f * 1024, ptr);
+            }
+        }
+    };
+
+    int vbase[C::NBW];
+#pragma unroll
+    for (int a = 0; a < C::NBW; ++a) {
+        int nb = wv * C::NBW + a;
+        int bw = nb % C::PW, bh = (nb / C::PW) % C::PH, bd = nb / (C::PW * C::PH);
+        vbase[a] = bd * C::XS_PLANE + (bh * 4 + (vl >> 3)) * C::XS_ROW + (bw * 8 + (vl & 7)) * 32 + hb * 16;
+    }
+
+    PipeTile cur = decode(blockIdx.x);
+    if (!cur.valid) return;
+    int64_t vb_next = (int64_t)blockIdx.x + gridDim.x;
+    PipeTile nxt = decode(vb_next);
+
+    // ---- prologue: chunk 0 of the first tile and the weights of its stage (0, 0)
+    copy_x(cur, 0, 0, std::integral_constant<int, 0>());
+    copy_x(cur, 0, 0, std::integral_constant<int, 1>());
+    copy_x(cur, 0, 0, std::integral_constant<int, 2>());
+    copy_w(cur, 0, 0, 0);
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+
+    int xpar = 0, wpar = 0;   // LDS buffers holding the current chunk / the current stage's weights
+    while (true) {
+    f32x16 acc[C::NBW][C::MB];   // per-tile accumulators (not carried from tile to tile)
+#pragma unroll
+    for (int a = 0; a < C::NBW; ++a)
+#pragma unroll
+        for (int b = 0; b < C::MB; ++b)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
+    auto stage = [&](int c, auto gtag) {
+        constexpr int g = decltype(gtag)::value;
+        // the data of the next stage (possibly the first stage of the next tile) starts moving now
+        const bool more = c + 1 < nkc;
+        if (g < 2) copy_w(cur, c, g + 1, wpar ^ 1);
+        else if (more) copy_w(cur, c + 1, 0, wpar ^ 1);
+        else if (nxt.valid) copy_w(nxt, 0, 0, wpar ^ 1);
+        if (more) copy_x(cur, c + 1, xpar ^ 1, gtag);
+        else if (nxt.valid) copy_x(nxt, 0, xpar ^ 1, gtag);
+        const unsigned char *xs = smem + xpar * C::XS_BYTES + g * C::XS_PLANE;
+        const unsigned char *wsm = smem + 2 * C::XS_BYTES + wpar * C::WS_BYTES + lane * 16;
+        // Software pipeline over the 9 x NBW (tap, patch) items of the stage: the activation
+        // fragment of item i+PD and the weight fragments of the next tap are requested from LDS
+        // before the MFMAs of item i issue, so LDS latency hides behind matrix work even with a
+        // single wave per SIMD.  sched_barrier keeps the compiler from undoing the order.
+        constexpr int NI = 9 * C::NBW, PD = 3;
+        bf16x8 bq[4], aq[2][C::MB];
+        auto ldb = [&](int i) {
+            const int tl = i / C::NBW, nb = i % C::NBW;
+            return *reinterpret_cast<const bf16x8 *>(xs + vbase[nb] + (tl / 3) * C::XS_ROW + (tl % 3) * 32);
+        };
+#pragma unroll
+        for (int mb = 0; mb < C::MB; ++mb) aq[0][mb] = *reinterpret_cast<const bf16x8 *>(wsm + mb * 1024);
+#pragma unroll
+        for (int i = 0; i < PD; ++i) bq[i] = ldb(i);
+#pragma unroll
+        for (int i = 0; i < NI; ++i) {
+            const int tl = i / C::NBW, nb = i % C::NBW;
+            if (i + PD < NI) bq[(i + PD) & 3] = ldb(i + PD);
+            if (nb == 0 && tl + 1 < 9) {
+#pragma unroll
+                for (int mb = 0; mb < C::MB; ++mb)
+                    aq[(tl + 1) & 1][mb] = *reinterpret_cast<const bf16x8 *>(wsm + ((tl + 1) * C::MB + mb) * 1024);
+            }
+#pragma unroll
+            for (int mb = 0; mb < C::MB; ++mb)
+                acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[tl & 1][mb], bq[i & 3], acc[nb][mb], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+        wpar ^= 1;
+    };
+
+        for (int c = 0; c < nkc; ++c) {
+            stage(c, std::integral_constant<int, 0>());
+            stage(c, std::integral_constant<int, 1>());
+            stage(c, std::integral_constant<int, 2>());
+            xpar ^= 1;
+        }
+        // ---- epilogue of the tile: bias, ReLU, optional output mask, round to bf16, 32 contiguous
+        // bytes per lane; the stores drain while the next tile is being multiplied
+        float bv[C::MB][16];
+#pragma unroll
+        for (int mb = 0; mb < C::MB; ++mb)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) bv[mb][i] = p.bias ? p.bias[(cur.mb0 + mb) * 32 + hb * 16 + i] : 0.f;
+#pragma unroll
+        for (int nb = 0; nb < C::NBW; ++nb) {
+            int blk = wv * C::NBW + nb;
+            int bw = blk % C::PW, bh = (blk / C::PW) % C::PH, bd = blk / (C::PW * C::PH);
+            int gd = cur.d0 + bd, gh = cur.h0 + bh * 4 + (vl >> 3), gw = cur.w0 + bw * 8 + (vl & 7);
+            const bool inb = gd < p.D && gh < p.H && gw < p.W;   // no early exit: keeps the epilogue one block
+            int64_t vox = inb ? (((int64_t)cur.n * p.D + gd) * p.H + gh) * p.W + gw : cur.origin;
+#pragma unroll
+            for (int mb = 0; mb < C::MB; ++mb) {
+                // keep this block in accumulator registers until here: without the pin the compiler
+                // copies every block to VGPRs right after the last MFMA and spills
+                asm volatile("" : "+a"(acc[nb][mb]));
+                int co0 = (cur.mb0 + mb) * 32 + hb * 16;
+                float v[16];
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    float t = acc[nb][mb][i] + bv[mb][i];
+                    v[i] = (p.relu && !(t > 0.f)) ? 0.f : t;
+                }
+                uint4 o0 = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
+                uint4 o1 = make_uint4(pack2bf(v[8], v[9]), pack2bf(v[10], v[11]), pack2bf(v[12], v[13]), pack2bf(v[14], v[15]));
+                const bool d1 = co0 < p.cd1;
+                const int64_t eo = d1 ? vox * p.cd1 + co0 : vox * p.cd2 + (co0 - p.cd1);
+                if (d1 && p.omask) {
+                    const uint4 *mp = reinterpret_cast<const uint4 *>(p.omask + eo);
+                    uint4 m0 = mp[0], m1 = mp[1];
+                    o0.x = mask_pair(o0.x, m0.x); o0.y = mask_pair(o0.y, m0.y); o0.z = mask_pair(o0.z, m0.z); o0.w = mask_pair(o0.w, m0.w);
+                    o1.x = mask_pair(o1.x, m1.x); o1.y = mask_pair(o1.y, m1.y); o1.z = mask_pair(o1.z, m1.z); o1.w = mask_pair(o1.w, m1.w);
+                }
+                uint4 *dst = reinterpret_cast<uint4 *>((d1 ? p.dst1 : p.dst2) + eo);
+                if (inb) {
+                    dst[0] = o0;
+                    dst[1] = o1;
+                }
+                __builtin_amdgcn_sched_barrier(0);   // one accumulator block at a time: keeps registers low
+            }
+        }
+        if (!nxt.valid) break;
+        cur = nxt;
+        vb_next += gridDim.x;
+        nxt = decode(vb_next);
+    }
+}
+
+template <class C>
+static int launch_pipe(MfmaParams p, int64_t mblocks, hipStream_t st)
+{
+    p.ntd = (p.D + C::TD - 1) / C::TD;
+    p.nth = (p.H + C::TH - 1) / C::TH;
+    p.ntw = (p.W + C::TW - 1) / C::TW;
+    p.ncg = (int)(mblocks / C::MB);
+    p.total = (int64_t)p.N * p.ntd * p.nth * p.ntw * p.ncg;
+    p.per_xcd = (p.total + 7) / 8;
+    if (p.per_xcd * 8 > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+    static bool attr_done = false;
+    if (!attr_done) {
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+        attr_done = true;
+    }
+    // persistent workgroups, one per CU (fewer when there is less work); a multiple of 8
+    int64_t grid = p.per_xcd * 8 < 256 ? p.per_xcd * 8 : 256;
+    conv_mfma_pipe_kernel<C><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
 }
 
 template <class C>
@@ -256,6 +573,17 @@ static int launch_cfg(MfmaParams p, int64_t mblocks, hipStream_t st)
 static int launch_mfma(MfmaParams p, int64_t mchannels, hipStream_t st)
 {
     int64_t mblocks = mchannels / 32;
+    // Large problems: the pipelined one-workgroup-per-CU kernel on 8x8x16 tiles, when that still
+    // gives every CU work; small volumes keep the 8x8x8 tiles (more, smaller workgroups).
+    {
+        typedef PipeCfg<8, 8, 16, 2> P2;
+        typedef PipeCfg<8, 8, 16, 1> P1;
+        int64_t tiles = (int64_t)p.N * ((p.D + 7) / 8) * ((p.H + 7) / 8) * ((p.W + 15) / 16);
+        // the halo tile's voxel offsets are kept in 32 bits
+        const bool fits = (int64_t)10 * p.H * p.W < 0x7fffffffLL;
+        if (!p.mask && fits && mblocks % 2 == 0 && tiles * (mblocks / 2) >= 256) return launch_pipe<P2>(p, mblocks, st);
+        if (!p.mask && fits && mblocks % 2 == 1 && tiles * mblocks >= 256) return launch_pipe<P1>(p, mblocks, st);
+    }
     if (mblocks % 2 == 0) return launch_cfg<TileCfg<8, 8, 8, 2, 9>>(p, mblocks, st);
     return launch_cfg<TileCfg<8, 8, 8, 1, 27>>(p, mblocks, st);
 }
@@ -293,6 +621,7 @@ int conv_dgrad_mfma(const ConvArgs &a, hipStream_t st)
     p.relu = 0;
     p.dst1 = (bf16_t *)a.dx;
     p.dst2 = (bf16_t *)a.dx2;
+    p.omask = (const bf16_t *)a.omask;
     p.cd1 = (int)a.c1;
     p.cd2 = (int)a.c2;
     p.N = (int)a.N; p.D = (int)a.D; p.H = (int)a.H; p.W = (int)a.W;

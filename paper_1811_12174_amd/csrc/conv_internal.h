@@ -19,6 +19,7 @@ struct ConvArgs {
     // backward inputs / outputs
     const void *dy = nullptr, *ymask = nullptr;
     void *dx = nullptr, *dx2 = nullptr;
+    const void *omask = nullptr;   // optional mask applied to dx (first destination) by the producer
     int64_t V() const { return N * D * H * W; }
 };
 

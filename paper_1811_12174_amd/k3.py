@@ -118,9 +118,9 @@ def conv3d_fwd(x, w, packed, bias, relu, y, x2=None):
                                _d(y), _p(y), _stream()), "k3_conv3d_fwd")
 
 
-def conv3d_bwd_data(dy, y_mask, w, packed, dx, dx2=None):
+def conv3d_bwd_data(dy, y_mask, w, packed, dx, dx2=None, dx_mask=None):
     _check(lib().k3_conv3d_bwd_data(_d(dy), _p(dy), _p(y_mask), _p(w), _p(packed), _d(dx), _p(dx), _d(dx2), _p(dx2),
-                                    _stream()), "k3_conv3d_bwd_data")
+                                    _p(dx_mask), _stream()), "k3_conv3d_bwd_data")
 
 
 def conv3d_bwd_weight_workspace_bytes(x, dy, x2=None):

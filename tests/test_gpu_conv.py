@@ -58,8 +58,9 @@ def test_conv_fwd(orc, case, relu):
 
 
 @pytest.mark.parametrize("case", FWD_CASES, ids=lambda c: "x".join(map(str, c)))
-@pytest.mark.parametrize("masked", [0, 1])
+@pytest.mark.parametrize("masked", [0, 1, 2])
 def test_conv_bwd_data(orc, case, masked):
+    """masked = 1: ReLU mask on the incoming gradient; 2: mask applied to the produced gradient."""
     import torch
     from paper_1811_12174_amd import k3
     from gpu_util import to_dev, to_f64, empty, rel_l2, packed_for, TOL
@@ -71,12 +72,18 @@ def test_conv_bwd_data(orc, case, masked):
     wd, dyd, ymd = to_dev(w, dt), to_dev(dy, dt), to_dev(ym, dt)
     dx = empty((N, D, H, W, c1), dt)
     dx2 = empty((N, D, H, W, c2), dt) if c2 else None
-    k3.conv3d_bwd_data(dyd, ymd if masked else None, wd, packed_for(wd), dx, dx2=dx2)
+    om = synth.activations(26, (N, D, H, W, c1), dt)
+    om[om < 0.2] = 0.0
+    omd = to_dev(om, dt)
+    k3.conv3d_bwd_data(dyd, ymd if masked == 1 else None, wd, packed_for(wd), dx, dx2=dx2,
+                       dx_mask=omd if masked == 2 else None)
     torch.cuda.synchronize()
     g = dy.astype(np.float64)
-    if masked:
+    if masked == 1:
         g = orc.relu_bwd(g, ym.astype(np.float64))
     ref = orc.conv3d_bwd_data(g, w.astype(np.float64))
+    if masked == 2:
+        ref[..., :c1] = orc.relu_bwd(ref[..., :c1], om.astype(np.float64))
     got = to_f64(dx) if not c2 else np.concatenate([to_f64(dx), to_f64(dx2)], axis=-1)
     err = rel_l2(got, ref)
     assert err < TOL[dt], err
