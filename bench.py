@@ -81,11 +81,14 @@ def bench_cfg2(args):
         k3.conv3d_fwd(x, w1, pk1, b1, 1, a1)
         k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2)
         k3.pool3d_fwd(a2, p)
-        k3.pool3d_bwd(a2, dyp, None, da2)
-        k3.conv3d_bwd_weight(a1, da2, a2, dW2, db2, ws)
-        k3.conv3d_bwd_data(da2, a2, w2, pk2, da1)
-        k3.conv3d_bwd_weight(x, da1, a1, dW1, db1, ws)
-        k3.conv3d_bwd_data(da1, a1, w1, pk1, dx)
+        # each producer of an activation gradient applies the ReLU mask of the tensor it
+        # differentiates (pool backward: a2; conv2 backward-data: a1), so the conv backward
+        # passes read no mask
+        k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True)
+        k3.conv3d_bwd_weight(a1, da2, None, dW2, db2, ws)
+        k3.conv3d_bwd_data(da2, None, w2, pk2, da1, dx_mask=a1)
+        k3.conv3d_bwd_weight(x, da1, None, dW1, db1, ws)
+        k3.conv3d_bwd_data(da1, None, w1, pk1, dx)
 
     for _ in range(3):
         step()
@@ -114,17 +117,17 @@ def bench_cfg2(args):
     it = max(20, args.steps // 4)
     kern = {
         "conv3d_fwd": time_calls(lambda: k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2), it),
-        "conv3d_bwd_data": time_calls(lambda: k3.conv3d_bwd_data(da2, a2, w2, pk2, da1), it),
-        "conv3d_bwd_weight": time_calls(lambda: k3.conv3d_bwd_weight(a1, da2, a2, dW2, db2, ws), it),
+        "conv3d_bwd_data": time_calls(lambda: k3.conv3d_bwd_data(da2, None, w2, pk2, da1, dx_mask=a1), it),
+        "conv3d_bwd_weight": time_calls(lambda: k3.conv3d_bwd_weight(a1, da2, None, dW2, db2, ws), it),
         "pool3d_fwd": time_calls(lambda: k3.pool3d_fwd(a2, p), it),
-        "pool3d_bwd": time_calls(lambda: k3.pool3d_bwd(a2, dyp, None, da2), it),
+        "pool3d_bwd": time_calls(lambda: k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True), it),
     }
 
     def mix():   # the implicit-GEMM kernel as the step launches it: 2 forward + 2 backward-data passes
         k3.conv3d_fwd(x, w1, pk1, b1, 1, a1)
         k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2)
-        k3.conv3d_bwd_data(da2, a2, w2, pk2, da1)
-        k3.conv3d_bwd_data(da1, a1, w1, pk1, dx)
+        k3.conv3d_bwd_data(da2, None, w2, pk2, da1, dx_mask=a1)
+        k3.conv3d_bwd_data(da1, None, w1, pk1, dx)
     mfma_ms = time_calls(mix, it) / 4.0
     share = {"conv_mfma_kernel": 4 * mfma_ms, "conv_wgrad_mfma_kernel": 2 * kern["conv3d_bwd_weight"]}
     dominant = max(share, key=share.get)

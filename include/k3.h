@@ -125,9 +125,11 @@ int k3_pool3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *yd, void 
 /* Backward: dx is zero except at the first maximum of each window (order i, j, k),
  * which receives that window's dy.  The arg-max is recomputed from x.  When add is not
  * NULL (same shape as dx) it is added element-wise: dx = route(dy) + add (the skip
- * connection's gradient joining the pooled path). */
+ * connection's gradient joining the pooled path).  When relu_mask is non-zero the result
+ * is then zeroed where x <= 0: x is a stored ReLU output, and applying its mask here lets
+ * that layer's backward passes run without one (see k3_conv3d_bwd_data, dx_mask). */
 int k3_pool3d_bwd(const k3_tensor *xd, const void *x, const k3_tensor *dyd, const void *dy,
-                  const void *add, void *dx, void *stream);
+                  const void *add, int relu_mask, void *dx, void *stream);
 
 /* ------------------------------------------------------------------ 2x2x2 stride-2 transposed convolution
  * The decoder's up-sampling layer (section 4.1) in its learned form:
@@ -141,9 +143,11 @@ int k3_upconv3d_pack_weights(const void *w, int64_t cin, int64_t cout, int dtype
                              void *packed, size_t packed_bytes, void *stream);
 int k3_upconv3d_fwd(const k3_tensor *xd, const void *x, const void *w, const void *packed,
                     const float *bias, const k3_tensor *yd, void *y, void *stream);
-/* dx[n,d,h,w,ci] = sum_{i,j,k,co} dy[n,2d+i,2h+j,2w+k,co] * W[i,j,k,ci,co] */
+/* dx[n,d,h,w,ci] = sum_{i,j,k,co} dy[n,2d+i,2h+j,2w+k,co] * W[i,j,k,ci,co]; when dx_mask is
+ * not NULL (same shape and dtype as dx) dx is zeroed where dx_mask <= 0 (the ReLU mask of
+ * the layer that produced the transposed conv's input, applied by the producer). */
 int k3_upconv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *w, const void *packed,
-                         const k3_tensor *dxd, void *dx, void *stream);
+                         const k3_tensor *dxd, void *dx, const void *dx_mask, void *stream);
 int k3_upconv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor *dyd, size_t *bytes);
 /* dW[i,j,k,ci,co] = sum_{n,d,h,w} x[n,d,h,w,ci] * dy[n,2d+i,2h+j,2w+k,co]; db[co] = sum dy
  * (db may be NULL).  dW, db: fp32 dev, overwritten; ws: dev workspace for partial sums. */
@@ -158,12 +162,14 @@ int k3_upconv3d_bwd_weight(const k3_tensor *xd, const void *x, const k3_tensor *
  *   da = dz * Wh^T;  dWh = a^T * dz;  dbh = sum_v dz.
  * a: dev, ad->dtype; wh [C][3], bh [3]: fp32 dev; labels: uint8 dev, one per voxel;
  * loss: one fp32 (dev); da: dev, same shape and dtype as a; dWh [C][3], dbh [3]: fp32
- * dev; logits: optional fp32 [V][3] dev (NULL to skip).  ws holds per-workgroup
- * partial sums. */
+ * dev; logits: optional fp32 [V][3] dev (NULL to skip).  When relu_mask is non-zero da is
+ * zeroed where a <= 0 (a is a stored ReLU output; see k3_conv3d_bwd_data, dx_mask).  ws
+ * holds per-workgroup partial sums. */
 int k3_head_workspace_bytes(const k3_tensor *ad, size_t *bytes);
 int k3_head_softmax_ce_fwd_bwd(const k3_tensor *ad, const void *a, const float *wh, const float *bh,
-                               const uint8_t *labels, float *loss, void *da, float *dWh, float *dbh,
-                               float *logits, void *ws, size_t ws_bytes, void *stream);
+                               const uint8_t *labels, float *loss, void *da, int relu_mask,
+                               float *dWh, float *dbh, float *logits, void *ws, size_t ws_bytes,
+                               void *stream);
 
 /* ------------------------------------------------------------------ LMS swap engine
  * Tensor swapping between device and host memory so that only the tensors a training

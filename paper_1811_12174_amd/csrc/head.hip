@@ -19,7 +19,7 @@ template <typename T>
 __global__ __launch_bounds__(256) void head_kernel(const T *__restrict__ a, const float *__restrict__ wh,
                                                   const float *__restrict__ bh, const uint8_t *__restrict__ labels,
                                                   T *__restrict__ da, float *__restrict__ logits,
-                                                  float *__restrict__ partial, int64_t V, int C, float invV)
+                                                  float *__restrict__ partial, int64_t V, int C, float invV, int relu_mask)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int rowb = C * (int)sizeof(T) + 4;  // padded row: consecutive voxels start in consecutive banks
@@ -74,8 +74,11 @@ __global__ __launch_bounds__(256) void head_kernel(const T *__restrict__ a, cons
             db0 += d0; db1 += d1; db2 += d2;
             dzs[tid * 4 + 0] = d0; dzs[tid * 4 + 1] = d1; dzs[tid * 4 + 2] = d2;
             T *drow = reinterpret_cast<T *>(ds + tid * rowb);
-            for (int c = 0; c < C; ++c)
-                elem<T>::st(drow + c, d0 * wh[c * 3 + 0] + d1 * wh[c * 3 + 1] + d2 * wh[c * 3 + 2]);
+            for (int c = 0; c < C; ++c) {
+                float gv = d0 * wh[c * 3 + 0] + d1 * wh[c * 3 + 1] + d2 * wh[c * 3 + 2];
+                if (relu_mask && !(elem<T>::ld(row + c) > 0.f)) gv = 0.f;
+                elem<T>::st(drow + c, gv);
+            }
         }
         __syncthreads();
         {   // coalesced store of the da rows
@@ -152,8 +155,8 @@ extern "C" int k3_head_workspace_bytes(const k3_tensor *ad, size_t *bytes)
 }
 
 extern "C" int k3_head_softmax_ce_fwd_bwd(const k3_tensor *ad, const void *a, const float *wh, const float *bh,
-                                          const uint8_t *labels, float *loss, void *da, float *dWh, float *dbh,
-                                          float *logits, void *ws, size_t ws_bytes, void *stream)
+                                          const uint8_t *labels, float *loss, void *da, int relu_mask, float *dWh,
+                                          float *dbh, float *logits, void *ws, size_t ws_bytes, void *stream)
 {
     size_t need = 0;
     int rc = k3_head_workspace_bytes(ad, &need);
@@ -172,11 +175,11 @@ extern "C" int k3_head_softmax_ce_fwd_bwd(const k3_tensor *ad, const void *a, co
     if (ad->dtype == K3_BF16) {
         K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&head_kernel<bf16_t>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        head_kernel<bf16_t><<<nb, 256, lds, st>>>((const bf16_t *)a, wh, bh, labels, (bf16_t *)da, logits, (float *)ws, V, C, invV);
+        head_kernel<bf16_t><<<nb, 256, lds, st>>>((const bf16_t *)a, wh, bh, labels, (bf16_t *)da, logits, (float *)ws, V, C, invV, relu_mask ? 1 : 0);
     } else {
         K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&head_kernel<float>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        head_kernel<float><<<nb, 256, lds, st>>>((const float *)a, wh, bh, labels, (float *)da, logits, (float *)ws, V, C, invV);
+        head_kernel<float><<<nb, 256, lds, st>>>((const float *)a, wh, bh, labels, (float *)da, logits, (float *)ws, V, C, invV, relu_mask ? 1 : 0);
     }
     K3_LAUNCH_CHECK();
     head_reduce_kernel<<<1, 256, 0, st>>>((const float *)ws, nb, C, invV, dWh, dbh, loss);

@@ -72,8 +72,8 @@ __global__ __launch_bounds__(256) void pool_fwd_kernel(const T *__restrict__ x, 
 
 template <typename T, int VEC>
 __global__ __launch_bounds__(256) void pool_bwd_kernel(const T *__restrict__ x, const T *__restrict__ dy,
-                                                      const T *__restrict__ add, T *__restrict__ dx, int64_t total,
-                                                      int D, int H, int W, int C)
+                                                      const T *__restrict__ add, int relu_mask, T *__restrict__ dx,
+                                                      int64_t total, int D, int H, int W, int C)
 {
     int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (gid >= total) return;
@@ -86,13 +86,18 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const T *__restrict__ x, 
     int64_t n = o / ((int64_t)W * H * D);
     float m[VEC], v[VEC], g[VEC], a[VEC], r[VEC];
     int arg[VEC];
+    unsigned pos[VEC];   // bit p: window element p is > 0 (the ReLU mask of x)
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) pos[e] = 0;
 #pragma unroll
     for (int p = 0; p < 8; ++p) {
         int64_t u = ((n * 2 * D + 2 * d + (p >> 2)) * 2 * H + 2 * h + ((p >> 1) & 1)) * (2 * (int64_t)W) + 2 * w + (p & 1);
         vec_io<T, VEC>::ld(x + u * C + c, v);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e)
+        for (int e = 0; e < VEC; ++e) {
             if (p == 0 || v[e] > m[e]) { m[e] = v[e]; arg[e] = p; }  // strict >: the first maximum wins
+            pos[e] |= (v[e] > 0.f ? 1u : 0u) << p;
+        }
     }
     vec_io<T, VEC>::ld(dy + o * C + c, g);
 #pragma unroll
@@ -100,13 +105,16 @@ __global__ __launch_bounds__(256) void pool_bwd_kernel(const T *__restrict__ x, 
         int64_t u = ((n * 2 * D + 2 * d + (p >> 2)) * 2 * H + 2 * h + ((p >> 1) & 1)) * (2 * (int64_t)W) + 2 * w + (p & 1);
         if (add) vec_io<T, VEC>::ld(add + u * C + c, a);
 #pragma unroll
-        for (int e = 0; e < VEC; ++e) r[e] = (arg[e] == p ? g[e] : 0.f) + (add ? a[e] : 0.f);
+        for (int e = 0; e < VEC; ++e) {
+            r[e] = (arg[e] == p ? g[e] : 0.f) + (add ? a[e] : 0.f);
+            if (relu_mask && !((pos[e] >> p) & 1)) r[e] = 0.f;
+        }
         vec_io<T, VEC>::st(dx + u * C + c, r);
     }
 }
 
 template <typename T, int VEC>
-static int pool_launch(bool bwd, const void *x, const void *dy, const void *add, void *out, int64_t N, int64_t D,
+static int pool_launch(bool bwd, const void *x, const void *dy, const void *add, int relu_mask, void *out, int64_t N, int64_t D,
                        int64_t H, int64_t W, int64_t C, hipStream_t st)
 {
     int64_t total = N * D * H * W * (C / VEC);
@@ -116,21 +124,21 @@ static int pool_launch(bool bwd, const void *x, const void *dy, const void *add,
         pool_fwd_kernel<T, VEC><<<dim3((unsigned)blocks), 256, 0, st>>>((const T *)x, (T *)out, total, (int)D, (int)H,
                                                                         (int)W, (int)C);
     else
-        pool_bwd_kernel<T, VEC><<<dim3((unsigned)blocks), 256, 0, st>>>((const T *)x, (const T *)dy, (const T *)add,
+        pool_bwd_kernel<T, VEC><<<dim3((unsigned)blocks), 256, 0, st>>>((const T *)x, (const T *)dy, (const T *)add, relu_mask,
                                                                         (T *)out, total, (int)D, (int)H, (int)W, (int)C);
     K3_LAUNCH_CHECK();
     return K3_OK;
 }
 
-static int pool_dispatch(bool bwd, int dtype, const void *x, const void *dy, const void *add, void *out, int64_t N,
+static int pool_dispatch(bool bwd, int dtype, const void *x, const void *dy, const void *add, int relu_mask, void *out, int64_t N,
                          int64_t D, int64_t H, int64_t W, int64_t C, hipStream_t st)
 {
     if (dtype == K3_BF16) {
-        if (C % 8 == 0) return pool_launch<bf16_t, 8>(bwd, x, dy, add, out, N, D, H, W, C, st);
-        return pool_launch<bf16_t, 1>(bwd, x, dy, add, out, N, D, H, W, C, st);
+        if (C % 8 == 0) return pool_launch<bf16_t, 8>(bwd, x, dy, add, relu_mask, out, N, D, H, W, C, st);
+        return pool_launch<bf16_t, 1>(bwd, x, dy, add, relu_mask, out, N, D, H, W, C, st);
     }
-    if (C % 4 == 0) return pool_launch<float, 4>(bwd, x, dy, add, out, N, D, H, W, C, st);
-    return pool_launch<float, 1>(bwd, x, dy, add, out, N, D, H, W, C, st);
+    if (C % 4 == 0) return pool_launch<float, 4>(bwd, x, dy, add, relu_mask, out, N, D, H, W, C, st);
+    return pool_launch<float, 1>(bwd, x, dy, add, relu_mask, out, N, D, H, W, C, st);
 }
 
 static int pool_check(const k3_tensor *xd, const k3_tensor *yd)
@@ -153,14 +161,14 @@ extern "C" int k3_pool3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor
     int rc = pool_check(xd, yd);
     if (rc != K3_OK) return rc;
     if (!x || !y) return K3_E_BADARG;
-    return pool_dispatch(false, xd->dtype, x, nullptr, nullptr, y, yd->n, yd->d, yd->h, yd->w, yd->c, (hipStream_t)stream);
+    return pool_dispatch(false, xd->dtype, x, nullptr, nullptr, 0, y, yd->n, yd->d, yd->h, yd->w, yd->c, (hipStream_t)stream);
 }
 
 extern "C" int k3_pool3d_bwd(const k3_tensor *xd, const void *x, const k3_tensor *dyd, const void *dy, const void *add,
-                             void *dx, void *stream)
+                             int relu_mask, void *dx, void *stream)
 {
     int rc = pool_check(xd, dyd);
     if (rc != K3_OK) return rc;
     if (!x || !dy || !dx) return K3_E_BADARG;
-    return pool_dispatch(true, xd->dtype, x, dy, add, dx, dyd->n, dyd->d, dyd->h, dyd->w, dyd->c, (hipStream_t)stream);
+    return pool_dispatch(true, xd->dtype, x, dy, add, relu_mask ? 1 : 0, dx, dyd->n, dyd->d, dyd->h, dyd->w, dyd->c, (hipStream_t)stream);
 }

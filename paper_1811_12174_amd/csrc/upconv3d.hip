@@ -102,12 +102,21 @@ __global__ __launch_bounds__(256) void up_fwd_mfma_kernel(const bf16_t *__restri
     }
 }
 
+__device__ __forceinline__ uint32_t up_mask_pair(uint32_t v, uint32_t m)
+{
+    // keep each bf16 half of v where the matching half of m is > 0 (sign clear and nonzero)
+    uint32_t lo = ((m & 0x8000u) == 0 && (m & 0x7fffu) != 0) ? 0x0000ffffu : 0u;
+    uint32_t hi = ((m & 0x80000000u) == 0 && (m & 0x7fff0000u) != 0) ? 0xffff0000u : 0u;
+    return v & (lo | hi);
+}
+
 // ------------------------------------------------------------------ MFMA backward-data
 // wave = 32 consecutive input voxels x MB 32-channel blocks of dx; contraction over (tap, C_out)
 template <int MB>
 __global__ __launch_bounds__(256) void up_dgrad_mfma_kernel(const bf16_t *__restrict__ dy,
                                                            const bf16_t *__restrict__ packed, bf16_t *__restrict__ dx,
-                                                           int64_t V, int D, int H, int W, int cin, int cout)
+                                                           const bf16_t *__restrict__ omask, int64_t V, int D, int H,
+                                                           int W, int cin, int cout)
 {
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int hb = lane >> 5, vl = lane & 31;
@@ -142,11 +151,20 @@ __global__ __launch_bounds__(256) void up_dgrad_mfma_kernel(const bf16_t *__rest
     if (!live) return;
 #pragma unroll
     for (int m = 0; m < MB; ++m) {
-        uint4 *dst = reinterpret_cast<uint4 *>(dx + v * cin + (cib0 + m) * 32 + hb * 16);
-        dst[0] = make_uint4(pack2bf(acc[m][0], acc[m][1]), pack2bf(acc[m][2], acc[m][3]), pack2bf(acc[m][4], acc[m][5]),
-                            pack2bf(acc[m][6], acc[m][7]));
-        dst[1] = make_uint4(pack2bf(acc[m][8], acc[m][9]), pack2bf(acc[m][10], acc[m][11]),
-                            pack2bf(acc[m][12], acc[m][13]), pack2bf(acc[m][14], acc[m][15]));
+        const int64_t eo = v * cin + (cib0 + m) * 32 + hb * 16;
+        uint4 o0 = make_uint4(pack2bf(acc[m][0], acc[m][1]), pack2bf(acc[m][2], acc[m][3]), pack2bf(acc[m][4], acc[m][5]),
+                              pack2bf(acc[m][6], acc[m][7]));
+        uint4 o1 = make_uint4(pack2bf(acc[m][8], acc[m][9]), pack2bf(acc[m][10], acc[m][11]),
+                              pack2bf(acc[m][12], acc[m][13]), pack2bf(acc[m][14], acc[m][15]));
+        if (omask) {
+            const uint4 *mp = reinterpret_cast<const uint4 *>(omask + eo);
+            uint4 m0 = mp[0], m1 = mp[1];
+            o0.x = up_mask_pair(o0.x, m0.x); o0.y = up_mask_pair(o0.y, m0.y); o0.z = up_mask_pair(o0.z, m0.z); o0.w = up_mask_pair(o0.w, m0.w);
+            o1.x = up_mask_pair(o1.x, m1.x); o1.y = up_mask_pair(o1.y, m1.y); o1.z = up_mask_pair(o1.z, m1.z); o1.w = up_mask_pair(o1.w, m1.w);
+        }
+        uint4 *dst = reinterpret_cast<uint4 *>(dx + eo);
+        dst[0] = o0;
+        dst[1] = o1;
     }
 }
 
@@ -281,8 +299,8 @@ __global__ __launch_bounds__(256) void up_fwd_direct_kernel(const T *__restrict_
 
 template <typename T>
 __global__ __launch_bounds__(256) void up_dgrad_direct_kernel(const T *__restrict__ dy, const T *__restrict__ w,
-                                                             T *__restrict__ dx, int64_t total, int D, int H, int W,
-                                                             int cin, int cout)
+                                                             T *__restrict__ dx, const T *__restrict__ omask,
+                                                             int64_t total, int D, int H, int W, int cin, int cout)
 {
     int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (gid >= total) return;
@@ -299,6 +317,7 @@ __global__ __launch_bounds__(256) void up_dgrad_direct_kernel(const T *__restric
         const T *wp = w + ((int64_t)t * cin + ci) * cout;
         for (int co = 0; co < cout; ++co) acc += elem<T>::ld(gp + co) * elem<T>::ld(wp + co);
     }
+    if (omask && !(elem<T>::ld(omask + gid) > 0.f)) acc = 0.f;
     elem<T>::st(dx + gid, acc);
 }
 
@@ -457,7 +476,7 @@ int k3_upconv3d_fwd(const k3_tensor *xd, const void *x, const void *w, const voi
 }
 
 int k3_upconv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *w, const void *packed, const k3_tensor *dxd,
-                         void *dx, void *stream)
+                         void *dx, const void *dx_mask, void *stream)
 {
     int rc = up_check(dxd, dyd);
     if (rc != K3_OK) return rc;
@@ -473,11 +492,11 @@ int k3_upconv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *w, co
         if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
         int nb = cin / 32;
         if (nb % 4 == 0)
-            up_dgrad_mfma_kernel<4><<<dim3((unsigned)blocks, (unsigned)(nb / 4)), 256, 0, st>>>((const bf16_t *)dy, pb, (bf16_t *)dx, V, D, H, W, cin, cout);
+            up_dgrad_mfma_kernel<4><<<dim3((unsigned)blocks, (unsigned)(nb / 4)), 256, 0, st>>>((const bf16_t *)dy, pb, (bf16_t *)dx, (const bf16_t *)dx_mask, V, D, H, W, cin, cout);
         else if (nb % 2 == 0)
-            up_dgrad_mfma_kernel<2><<<dim3((unsigned)blocks, (unsigned)(nb / 2)), 256, 0, st>>>((const bf16_t *)dy, pb, (bf16_t *)dx, V, D, H, W, cin, cout);
+            up_dgrad_mfma_kernel<2><<<dim3((unsigned)blocks, (unsigned)(nb / 2)), 256, 0, st>>>((const bf16_t *)dy, pb, (bf16_t *)dx, (const bf16_t *)dx_mask, V, D, H, W, cin, cout);
         else
-            up_dgrad_mfma_kernel<1><<<dim3((unsigned)blocks, (unsigned)nb), 256, 0, st>>>((const bf16_t *)dy, pb, (bf16_t *)dx, V, D, H, W, cin, cout);
+            up_dgrad_mfma_kernel<1><<<dim3((unsigned)blocks, (unsigned)nb), 256, 0, st>>>((const bf16_t *)dy, pb, (bf16_t *)dx, (const bf16_t *)dx_mask, V, D, H, W, cin, cout);
         K3_LAUNCH_CHECK();
         return K3_OK;
     }
@@ -485,9 +504,9 @@ int k3_upconv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *w, co
     int64_t blocks = (total + 255) / 256;
     if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
     if (dxd->dtype == K3_F32)
-        up_dgrad_direct_kernel<float><<<dim3((unsigned)blocks), 256, 0, st>>>((const float *)dy, (const float *)w, (float *)dx, total, D, H, W, cin, cout);
+        up_dgrad_direct_kernel<float><<<dim3((unsigned)blocks), 256, 0, st>>>((const float *)dy, (const float *)w, (float *)dx, (const float *)dx_mask, total, D, H, W, cin, cout);
     else
-        up_dgrad_direct_kernel<bf16_t><<<dim3((unsigned)blocks), 256, 0, st>>>((const bf16_t *)dy, (const bf16_t *)w, (bf16_t *)dx, total, D, H, W, cin, cout);
+        up_dgrad_direct_kernel<bf16_t><<<dim3((unsigned)blocks), 256, 0, st>>>((const bf16_t *)dy, (const bf16_t *)w, (bf16_t *)dx, (const bf16_t *)dx_mask, total, D, H, W, cin, cout);
     K3_LAUNCH_CHECK();
     return K3_OK;
 }

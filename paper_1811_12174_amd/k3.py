@@ -141,8 +141,9 @@ def pool3d_fwd(x, y):
     _check(lib().k3_pool3d_fwd(_d(x), _p(x), _d(y), _p(y), _stream()), "k3_pool3d_fwd")
 
 
-def pool3d_bwd(x, dy, add, dx):
-    _check(lib().k3_pool3d_bwd(_d(x), _p(x), _d(dy), _p(dy), _p(add), _p(dx), _stream()), "k3_pool3d_bwd")
+def pool3d_bwd(x, dy, add, dx, relu_mask=False):
+    _check(lib().k3_pool3d_bwd(_d(x), _p(x), _d(dy), _p(dy), _p(add), ctypes.c_int(int(relu_mask)), _p(dx), _stream()),
+           "k3_pool3d_bwd")
 
 
 # ------------------------------------------------------------------ transposed convolution
@@ -165,8 +166,8 @@ def upconv3d_fwd(x, w, packed, bias, y):
     _check(lib().k3_upconv3d_fwd(_d(x), _p(x), _p(w), _p(packed), _p(bias), _d(y), _p(y), _stream()), "k3_upconv3d_fwd")
 
 
-def upconv3d_bwd_data(dy, w, packed, dx):
-    _check(lib().k3_upconv3d_bwd_data(_d(dy), _p(dy), _p(w), _p(packed), _d(dx), _p(dx), _stream()),
+def upconv3d_bwd_data(dy, w, packed, dx, dx_mask=None):
+    _check(lib().k3_upconv3d_bwd_data(_d(dy), _p(dy), _p(w), _p(packed), _d(dx), _p(dx), _p(dx_mask), _stream()),
            "k3_upconv3d_bwd_data")
 
 
@@ -190,8 +191,9 @@ def head_workspace_bytes(a):
     return out.value
 
 
-def head_softmax_ce_fwd_bwd(a, wh, bh, labels, loss, da, dWh, dbh, logits, ws):
-    _check(lib().k3_head_softmax_ce_fwd_bwd(_d(a), _p(a), _p(wh), _p(bh), _p(labels), _p(loss), _p(da), _p(dWh),
+def head_softmax_ce_fwd_bwd(a, wh, bh, labels, loss, da, dWh, dbh, logits, ws, relu_mask=False):
+    _check(lib().k3_head_softmax_ce_fwd_bwd(_d(a), _p(a), _p(wh), _p(bh), _p(labels), _p(loss), _p(da),
+                                            ctypes.c_int(int(relu_mask)), _p(dWh),
                                             _p(dbh), _p(logits), _p(ws),
                                             ctypes.c_size_t(ws.numel() * ws.element_size()), _stream()),
            "k3_head_softmax_ce_fwd_bwd")

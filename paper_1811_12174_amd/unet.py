@@ -101,15 +101,20 @@ class UNet3D:
         k3.conv3d_fwd(x, self.w[name], self.pk[name], self.b[name], relu, y, x2=x2)
         return y
 
-    def _conv_bwd(self, name, x, x2, dy, ymask, need_dx=True):
-        """Weight / bias gradients of layer `name`, and dx (split like the inputs)."""
-        ws = self._workspace(k3.conv3d_bwd_weight_workspace_bytes(x, dy, x2=x2))
-        k3.conv3d_bwd_weight(x, dy, ymask, self.gw[name], self.gb[name], ws, x2=x2)
+    def _conv_bwd(self, name, x, x2, g, need_dx=True, dx_mask=None):
+        """Weight / bias gradients of layer `name`, and dx (split like the inputs).
+
+        g is the gradient of the layer's pre-activation: every producer of an activation
+        gradient (head, pool backward, transposed-conv backward, conv backward-data) applies
+        the ReLU mask of the tensor it differentiates, so no mask is read here.  dx_mask is
+        the stored ReLU output that the first input x is (None when x is not a ReLU output)."""
+        ws = self._workspace(k3.conv3d_bwd_weight_workspace_bytes(x, g, x2=x2))
+        k3.conv3d_bwd_weight(x, g, None, self.gw[name], self.gb[name], ws, x2=x2)
         if not need_dx:
             return None, None
         dx = torch.empty_like(x)
         dx2 = torch.empty_like(x2) if x2 is not None else None
-        k3.conv3d_bwd_data(dy, ymask, self.w[name], self.pk[name], dx, dx2=dx2)
+        k3.conv3d_bwd_data(g, None, self.w[name], self.pk[name], dx, dx2=dx2, dx_mask=dx_mask)
         return dx, dx2
 
     # ------------------------------------------------------------------ swapping
@@ -245,7 +250,7 @@ class UNet3D:
             d = torch.empty_like(cur)
             ws = self._workspace(k3.head_workspace_bytes(cur))
             k3.head_softmax_ce_fwd_bwd(cur, self.w["head"], self.b["head"], labels, self.loss, d,
-                                       self.gw["head"], self.gb["head"], None, ws)
+                                       self.gw["head"], self.gb["head"], None, ws, relu_mask=True)
             del cur
             # ---------------- backward: stage list, with prefetches issued `prefetch_distance` stages ahead
             stages = [("dec", l) for l in range(0, L - 1)] + [("enc", l) for l in range(L - 1, -1, -1)]
@@ -268,16 +273,17 @@ class UNet3D:
                     a2, a1 = self._slots[f"da2_{l}"].t, self._slots[f"da1_{l}"].t
                     up, below = self._slots[f"dup{l}"].t, self._slots[f"dbelow{l}"].t
                     skip = self._get(f"a2_{l}")
-                    d1, _ = self._conv_bwd(f"dec{l}.conv2", a1, None, d, a2)
+                    # d already carries the ReLU mask of a2 (applied by its producer)
+                    d1, _ = self._conv_bwd(f"dec{l}.conv2", a1, None, d, dx_mask=a1)
                     del d
-                    dskip, dup = self._conv_bwd(f"dec{l}.conv1", skip, up, d1, a1)
+                    dskip, dup = self._conv_bwd(f"dec{l}.conv1", skip, up, d1)
                     del d1
                     skip_grad[l] = dskip
                     name = f"dec{l}.up"
                     ws = self._workspace(k3.upconv3d_bwd_weight_workspace_bytes(below, dup))
                     k3.upconv3d_bwd_weight(below, dup, self.gw[name], self.gb[name], ws)
                     d = torch.empty_like(below)
-                    k3.upconv3d_bwd_data(dup, self.w[name], self.pk[name], d)
+                    k3.upconv3d_bwd_data(dup, self.w[name], self.pk[name], d, dx_mask=below)
                     del dup, dskip, a2, a1, up, below, skip
                     for nm in (f"da2_{l}", f"da1_{l}", f"dup{l}", f"dbelow{l}"):
                         self._slots[nm].t = None
@@ -285,14 +291,14 @@ class UNet3D:
                     a2 = self._get(f"a2_{l}")
                     if l < L - 1:
                         dd = torch.empty_like(a2)
-                        k3.pool3d_bwd(a2, d, skip_grad.pop(l), dd)
+                        k3.pool3d_bwd(a2, d, skip_grad.pop(l), dd, relu_mask=True)
                         d = dd
                         del dd
                     a1 = self._get(f"a1_{l}")
-                    d1, _ = self._conv_bwd(f"enc{l}.conv2", a1, None, d, a2)
+                    d1, _ = self._conv_bwd(f"enc{l}.conv2", a1, None, d, dx_mask=a1)
                     del d
                     inp = self._get(f"in{l}")
-                    d, _ = self._conv_bwd(f"enc{l}.conv1", inp, None, d1, a1, need_dx=(l > 0))
+                    d, _ = self._conv_bwd(f"enc{l}.conv1", inp, None, d1, need_dx=(l > 0))
                     del d1, a1, a2, inp
                     for nm in (f"a2_{l}", f"a1_{l}", f"in{l}"):
                         self._drop(nm)

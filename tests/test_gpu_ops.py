@@ -29,16 +29,20 @@ def test_pool_fwd_bwd_exact(orc, shape, dt):
     k3.pool3d_bwd(xd, dyd, None, dx)
     dx2 = empty(shape, dt)
     k3.pool3d_bwd(xd, dyd, addd, dx2)
+    dx3 = empty(shape, dt)
+    k3.pool3d_bwd(xd, dyd, addd, dx3, relu_mask=True)
     torch.cuda.synchronize()
     assert np.array_equal(to_f64(y), orc.pool3d_fwd(x.astype(np.float64)))
     ref = orc.pool3d_bwd(x.astype(np.float64), dy.astype(np.float64))
     assert np.array_equal(to_f64(dx), ref)
     ref2 = ref + add.astype(np.float64)
+    ref3 = orc.relu_bwd(ref2, x.astype(np.float64))     # producer-side ReLU mask of x
     if dt == "bf16":
-        ref2 = orc.round_bf16(ref2)
-        assert np.array_equal(to_f64(dx2), ref2)
+        assert np.array_equal(to_f64(dx2), orc.round_bf16(ref2))
+        assert np.array_equal(to_f64(dx3), orc.round_bf16(ref3))
     else:
         np.testing.assert_allclose(to_f64(dx2), ref2, rtol=1e-6, atol=1e-7)
+        np.testing.assert_allclose(to_f64(dx3), ref3, rtol=1e-6, atol=1e-7)
 
 
 def test_pool_odd_dim_is_rejected():
@@ -83,6 +87,10 @@ def test_upconv_all_passes(orc, sp, ci, co, dt):
     dx = empty((N, D, H, W, ci), dt)
     dx.fill_(float("nan"))
     k3.upconv3d_bwd_data(dyd, wd, pk, dx)
+    om = synth.activations(64, (N, D, H, W, ci), dt)
+    om[om < 0.2] = 0.0
+    dxm = empty((N, D, H, W, ci), dt)
+    k3.upconv3d_bwd_data(dyd, wd, pk, dxm, dx_mask=to_dev(om, dt))
     dW = torch.full((2, 2, 2, ci, co), float("nan"), device="cuda")
     db = torch.full((co,), float("nan"), device="cuda")
     ws = torch.empty(max(1, k3.upconv3d_bwd_weight_workspace_bytes(xd, dyd)), device="cuda", dtype=torch.uint8)
@@ -91,8 +99,12 @@ def test_upconv_all_passes(orc, sp, ci, co, dt):
     x64, w64, dy64 = x.astype(np.float64), w.astype(np.float64), dy.astype(np.float64)
     e = rel_l2(to_f64(y), orc.upconv3d_fwd(x64, w64, b.astype(np.float64)))
     assert e < TOL[dt] and (dt != "bf16" or e < 4e-3), e
-    e = rel_l2(to_f64(dx), orc.upconv3d_bwd_data(dy64, w64))
+    rdx = orc.upconv3d_bwd_data(dy64, w64)
+    e = rel_l2(to_f64(dx), rdx)
     assert e < TOL[dt] and (dt != "bf16" or e < 4e-3), e
+    e = rel_l2(to_f64(dxm), orc.relu_bwd(rdx, om.astype(np.float64)))
+    assert e < TOL[dt] and (dt != "bf16" or e < 4e-3), e
+    assert np.all(to_f64(dxm)[om <= 0] == 0)
     rW, rb = orc.upconv3d_bwd_weight(x64, dy64)
     assert rel_l2(to_f64(dW), rW) < 1e-5
     assert rel_l2(to_f64(db), rb) < 1e-5
@@ -120,11 +132,14 @@ def test_head(orc, sp, C, dt):
     logits = torch.full((N * D * H * W, 3), float("nan"), device="cuda")
     ws = torch.empty(k3.head_workspace_bytes(ad), device="cuda", dtype=torch.uint8)
     k3.head_softmax_ce_fwd_bwd(ad, whd, bhd, labd, loss, da, dW, db, logits, ws)
+    dam = empty(a.shape, dt)
+    k3.head_softmax_ce_fwd_bwd(ad, whd, bhd, labd, loss, dam, dW, db, logits, ws, relu_mask=True)
     torch.cuda.synchronize()
     ref = orc.head_softmax_ce(a.astype(np.float64), wh.astype(np.float64), bh.astype(np.float64), lab)
     assert abs(loss.item() - ref["loss"]) < 1e-5 * abs(ref["loss"])
     assert rel_l2(to_f64(logits), ref["logits"].reshape(-1, 3)) < 1e-5
     assert rel_l2(to_f64(da), ref["da"]) < TOL[dt]
+    assert rel_l2(to_f64(dam), orc.relu_bwd(ref["da"], a.astype(np.float64))) < TOL[dt]
     assert rel_l2(to_f64(dW), ref["dW"]) < 1e-4      # fp32 exp/log + fp32 sums of mixed-sign terms
     assert np.abs(to_f64(db) - ref["db"]).max() < 1e-5 * max(1e-3, np.abs(ref["db"]).max()) + 1e-7
 
