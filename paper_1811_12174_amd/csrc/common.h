@@ -50,6 +50,15 @@ __device__ __forceinline__ uint32_t pack2bf(float lo, float hi)
 }
 __device__ __forceinline__ bf16_t f2bf(float f) { return (bf16_t)(pack2bf(f, 0.f) & 0xffffu); }
 
+// Asynchronous copy global -> LDS, 16 bytes per lane (global_load_lds_dwordx4): lane l of the
+// wave writes the 16 bytes at its own global address gptr to LDS byte address lds_base + 16*l
+// (lds_base is wave-uniform).  Completion is tracked by vmcnt; the compiler does not see the
+// LDS write, so the caller waits (s_waitcnt vmcnt) and synchronises before reading the data.
+__device__ __forceinline__ void dma16(unsigned lds_base, const void *gptr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
+}
+
 template <typename T> struct elem;
 template <> struct elem<float> {
     static __device__ __forceinline__ float ld(const float *p) { return *p; }

@@ -254,7 +254,7 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 // barrier per stage.  Voxels outside the volume and the row-padding slots read a 16-byte
 // block of zeros instead.  This kernel takes no input-side ReLU mask (the asynchronous copy
 // cannot apply one); backward passes feed it gradients that were masked by their producer.
-__device__ uint4 g_zero_block[4];   // zero-initialised; source of every out-of-volume halo item
+static __device__ uint4 g_zero_block[4];   // zero-initialised; source of every out-of-volume halo item
 
 template <int TD_, int TH_, int TW_, int MB_>
 struct PipeCfg {
@@ -279,12 +279,6 @@ struct PipeCfg {
     static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
     static_assert(3 * XG_WAVE <= 32, "validity bits are kept in one 32-bit mask");
 };
-
-// Asynchronous 16-byte-per-lane copy global -> LDS (64 consecutive slots starting at lds_base).
-__device__ __forceinline__ void dma16(unsigned lds_base, const void *gptr)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
-}
 
 // One tile of work: output block origin, output-channel group and the halo validity bits.
 struct PipeTile {
