@@ -193,7 +193,10 @@ size_t conv_wgrad_mfma_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int6
     int cobn, nsplit;
     int64_t ntiles;
     wgrad_plan(N, D, H, W, cin, cout, &cobn, &ntiles, &nsplit);
-    return (size_t)nsplit * (size_t)(27 * cin * cout + cout) * sizeof(float);
+    // either kernel may run (the pipelined one takes no ReLU mask): size for both
+    size_t need = (size_t)nsplit * (size_t)(27 * cin * cout + cout) * sizeof(float);
+    size_t pipe = conv_wgrad_pipe_ok(N, D, H, W, cin, cout) ? conv_wgrad_pipe_ws_bytes(N, D, H, W, cin, cout) : 0;
+    return need > pipe ? need : pipe;
 }
 
 template <int COBN>
@@ -215,6 +218,7 @@ int conv_wgrad_mfma(const ConvArgs &a, float *dW, float *db, float *ws, hipStrea
 {
     WgradParams p{};
     int64_t cin = a.c1 + a.c2;
+    if (!a.ymask && conv_wgrad_pipe_ok(a.N, a.D, a.H, a.W, cin, a.cout)) return conv_wgrad_pipe(a, dW, db, ws, st);
     int cobn;
     wgrad_plan(a.N, a.D, a.H, a.W, cin, a.cout, &cobn, &p.ntiles, &p.nsplit);
     p.x1 = (const bf16_t *)a.x;

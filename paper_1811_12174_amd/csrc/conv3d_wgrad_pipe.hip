@@ -1,0 +1,360 @@
+// Pipelined bf16 MFMA kernel for the 3x3x3 convolution backward-weight pass on gfx950.
+//
+// Same GEMM as conv3d_wgrad.hip, dW[tap][ci][co] = sum_v X[v + off_tap][ci] * G[v][co] with the
+// contraction over voxels and the MFMA operands produced by the transposing LDS read, but
+// organised as one persistent workgroup per CU that marches along the depth axis:
+//
+//  * A workgroup owns a 32-channel block of x, 32*COBN channels of g and a contiguous range
+//    of (column, plane) pairs, a column being a 16x16 (h, w) patch of one sample.  One stage
+//    multiplies one plane: 256 voxels = 16 K-steps.  The x planes d-1, d, d+1 (18x18 voxels
+//    with the in-plane halo) sit in a ring of four LDS buffers, so every x plane is fetched
+//    once per column and serves the three depth taps; g planes alternate between two buffers.
+//  * While a stage is multiplied, the next x plane and the next g plane move from global
+//    memory straight into the free LDS buffers (asynchronous 16-byte-per-lane copies); one
+//    vmcnt wait and one barrier per stage.  Voxels outside the volume read a block of zeros.
+//  * The four waves split the 27 taps (7, 7, 7, 6); the spare slot of the last wave
+//    multiplies g by ones, which yields the bias gradient.  Inside a stage the operand
+//    fragments of K-step s+1 are requested from LDS between the MFMAs of K-step s.
+//  * Each workgroup writes one partial sum per (split, tap, ci, co); the partials are added
+//    in a fixed order by reduce_partials_kernel (no atomics: run-to-run identical).
+//
+// The kernel takes no ReLU mask: backward passes that need one hand over a gradient already
+// masked by its producer, or use the kernel in conv3d_wgrad.hip.
+#include "common.h"
+#include "conv_internal.h"
+
+namespace k3 {
+
+namespace wp {
+constexpr int TH = 16, TW = 16, HH = TH + 2, HW = TW + 2;
+constexpr int XP_SLOTS = HH * HW * 4;              // 16-byte slots of one x plane (32 channels per voxel)
+constexpr int XP_GROUPS = (XP_SLOTS + 63) / 64;    // 1 KB copy groups
+constexpr int XP_BYTES = XP_GROUPS * 1024;
+constexpr int XK = (XP_GROUPS + 3) / 4;            // copy groups per wave and x plane
+constexpr int NXB = 4;                             // ring of x plane buffers
+constexpr int GP_BYTES1 = TH * TW * 64;            // one 32-channel block of a g plane
+constexpr int lds_bytes(int cobn) { return NXB * XP_BYTES + 2 * cobn * GP_BYTES1; }
+}  // namespace wp
+
+struct WgradPipeParams {
+    const bf16_t *x1, *x2;
+    int c1, c2;
+    const bf16_t *dy;
+    int cout;
+    float *ws;
+    int64_t per_split;   // floats per split: 27*cin*cout + cout
+    int N, D, H, W;
+    int nth, ntw;        // columns per sample along h and w
+    int64_t P;           // planes in total: columns * D
+    int S;               // splits of the plane range
+    int ncib, ncog;      // 32-channel blocks of x, groups of 32*COBN channels of g
+    int64_t total, per_xcd;
+};
+
+static __device__ uint4 g_wzero[4];   // zero-initialised: source of every out-of-volume item
+
+__device__ __forceinline__ bf16x8 wp_tr_pair(const unsigned char *base, int off)
+{
+    typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+    s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(base + off));
+    s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(base + off + 4 * 64));
+    typedef __attribute__((ext_vector_type(8))) short s16x8;
+    s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// One stage: the 16 K-steps of one plane.  K-step s covers rows 2*(s/2) + hb and columns
+// 8*(s%2) .. +7 of the 16x16 patch; xa[t] / ga are the lane's LDS byte offsets of the tap-t x
+// fragment and of the g fragment for K-step 0.  last (wave-uniform): the seventh slot is the
+// ones product (its x fragment is still read, from a valid address, and dropped).
+template <int COBN>
+__device__ __forceinline__ void wp_stage(f32x16 (&acc)[7][COBN], const unsigned char *smem, const int (&xa)[7], int ga,
+                                         bf16x8 ones, bool last)
+{
+    using namespace wp;
+    constexpr int NF = COBN + 7;        // fragments per K-step
+    constexpr int NM = 7 * COBN;        // MFMAs per K-step
+    bf16x8 fr[2][COBN + 7];
+    auto load = [&](int s, int f) -> bf16x8 {
+        const int r2 = 2 * (s >> 1), q = 8 * (s & 1);
+        if (f < COBN) return wp_tr_pair(smem, ga + f * GP_BYTES1 + (r2 * TW + q) * 64);
+        return wp_tr_pair(smem, xa[f - COBN] + (r2 * HW + q) * 64);
+    };
+#pragma unroll
+    for (int f = 0; f < NF; ++f) fr[0][f] = load(0, f);
+#pragma unroll
+    for (int s = 0; s < 16; ++s) {
+#pragma unroll
+        for (int m = 0; m < NM; ++m) {
+            if (s + 1 < 16) {
+#pragma unroll
+                for (int f = m * NF / NM; f < (m + 1) * NF / NM; ++f) fr[(s + 1) & 1][f] = load(s + 1, f);
+            }
+            const int t = m / COBN, c = m % COBN;
+            const bf16x8 a = (t == 6 && last) ? ones : fr[s & 1][COBN + t];
+            acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, fr[s & 1][c], acc[t][c], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+}
+
+template <int COBN>
+__global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams p)
+{
+    using namespace wp;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hb = lane >> 5, g16 = (lane >> 4) & 1, j = lane & 15;
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const unsigned char *zero = reinterpret_cast<const unsigned char *>(g_wzero);
+    // LDS map: the two g buffers first, then the ring of x planes.  (Measured: with the x ring
+    // first and the g buffers behind it the same kernel ran 2.8x slower for COBN = 2.)
+    constexpr int GOFF = 0;
+    constexpr int XOFF = 2 * COBN * GP_BYTES1;
+    constexpr int GBUF = COBN * GP_BYTES1;
+    constexpr int GK = COBN * 4;              // g copy groups per wave and plane
+
+    // XCD-aware order: consecutive block ids go round-robin to the 8 XCDs, so the logical order
+    // is cut into 8 contiguous runs; the workgroups of one split (same voxels, different channel
+    // blocks) are neighbours in the logical order and share an L2.
+    const int64_t logical = (int64_t)(blockIdx.x & 7) * p.per_xcd + (blockIdx.x >> 3);
+    if ((int64_t)(blockIdx.x >> 3) >= p.per_xcd || logical >= p.total) return;
+    const int yz = p.ncib * p.ncog;
+    const int split = (int)(logical / yz);
+    const int r = (int)(logical - (int64_t)split * yz);
+    const int cib = r % p.ncib, cob0 = (r / p.ncib) * COBN;
+    const int cin = p.c1 + p.c2;
+    const bool first = cib * 32 < p.c1;
+    const bf16_t *xsrc = first ? p.x1 : p.x2;
+    const int Cx = first ? p.c1 : p.c2;
+    const int chx = first ? cib * 32 : cib * 32 - p.c1;
+
+    // ---- per-lane description of the copy items (tile independent)
+    int xoff[XK], xco[XK];     // byte offset from the column origin / halo coords lh | lw << 8
+    unsigned xsl = 0;          // slot holds a voxel of the 18x18 plane
+#pragma unroll
+    for (int k = 0; k < XK; ++k) {
+        const int slot = (wv + 4 * k) * 64 + lane;
+        const int vox = slot >> 2, part = slot & 3;
+        const int lh = vox / HW, lw = vox - lh * HW;
+        xoff[k] = ((lh - 1) * p.W + (lw - 1)) * Cx * 2 + part * 16;
+        xco[k] = lh | (lw << 8);
+        xsl |= ((wv + 4 * k < XP_GROUPS && vox < HH * HW) ? 1u : 0u) << k;
+    }
+    int goff[GK], gco[GK];
+#pragma unroll
+    for (int k = 0; k < GK; ++k) {
+        const int slot = (wv + 4 * k) * 64 + lane;
+        const int cb = slot / (TH * TW * 4), rem = slot - cb * (TH * TW * 4);
+        const int vox = rem >> 2, part = rem & 3;
+        const int lh = vox / TW, lw = vox - lh * TW;
+        goff[k] = (lh * p.W + lw) * p.cout * 2 + ((cob0 + cb) * 32) * 2 + part * 16;
+        gco[k] = lh | (lw << 8);
+    }
+
+    // ---- lane-constant parts of the transposing-read addresses and the wave's taps
+    const int lane_x = (hb * HW + (j >> 2)) * 64 + g16 * 32 + (j & 3) * 8;
+    const int lane_g = GOFF + (hb * TW + (j >> 2)) * 64 + g16 * 32 + (j & 3) * 8;
+    int tapoff[7], tapkd[7];
+#pragma unroll
+    for (int t = 0; t < 7; ++t) {
+        int tap = wv * 7 + t;
+        if (tap > 26) tap = 26;   // slot of the ones product: address unused
+        tapkd[t] = tap / 9;
+        tapoff[t] = lane_x + (((tap / 3) % 3) * HW + tap % 3) * 64;
+    }
+
+    f32x16 acc[7][COBN];
+#pragma unroll
+    for (int t = 0; t < 7; ++t)
+#pragma unroll
+        for (int c = 0; c < COBN; ++c)
+#pragma unroll
+            for (int i = 0; i < 16; ++i) acc[t][c][i] = 0.f;
+    bf16x8 ones;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
+
+    // ---- this split's plane range, walked column by column
+    int64_t pl = (int64_t)split * p.P / p.S;
+    const int64_t pl_end = (int64_t)(split + 1) * p.P / p.S;
+    while (pl < pl_end) {
+        const int64_t col = pl / p.D;
+        const int dlo = (int)(pl - col * p.D);
+        int64_t run_end = (col + 1) * p.D;
+        if (run_end > pl_end) run_end = pl_end;
+        const int dhi = dlo + (int)(run_end - pl);
+        pl = run_end;
+        const int twi = (int)(col % p.ntw);
+        const int thi = (int)((col / p.ntw) % p.nth);
+        const int n = (int)(col / ((int64_t)p.ntw * p.nth));
+        const int h0 = thi * TH, w0 = twi * TW;
+
+        unsigned xvm = 0, gvm = 0;   // item lies inside the volume (in-plane test)
+#pragma unroll
+        for (int k = 0; k < XK; ++k) {
+            const int gh = h0 + (xco[k] & 255) - 1, gw = w0 + (xco[k] >> 8) - 1;
+            xvm |= ((gh >= 0 && gh < p.H && gw >= 0 && gw < p.W) ? 1u : 0u) << k;
+        }
+        xvm &= xsl;
+#pragma unroll
+        for (int k = 0; k < GK; ++k) {
+            const int gh = h0 + (gco[k] & 255), gw = w0 + (gco[k] >> 8);
+            gvm |= ((gh < p.H && gw < p.W) ? 1u : 0u) << k;
+        }
+        // element index of voxel (n, 0, h0, w0); planes are p.H * p.W voxels apart
+        const int64_t vox0 = (((int64_t)n * p.D) * p.H + h0) * p.W + w0;
+        const int64_t plane = (int64_t)p.H * p.W;
+
+        auto issue_x = [&](int d, int buf) {
+            const bool din = d >= 0 && d < p.D;
+            const unsigned char *base = reinterpret_cast<const unsigned char *>(xsrc + (vox0 + d * plane) * Cx + chx);
+#pragma unroll
+            for (int k = 0; k < XK; ++k) {
+                if (wv + 4 * k < XP_GROUPS) {
+                    const unsigned char *ptr = (din && ((xvm >> k) & 1)) ? base + xoff[k] : zero;
+                    dma16(lds0 + XOFF + buf * XP_BYTES + (wv + 4 * k) * 1024, ptr);
+                }
+            }
+        };
+        auto issue_g = [&](int d, int buf) {
+            const unsigned char *base = reinterpret_cast<const unsigned char *>(p.dy + (vox0 + d * plane) * p.cout);
+#pragma unroll
+            for (int k = 0; k < GK; ++k) {
+                const unsigned char *ptr = ((gvm >> k) & 1) ? base + goff[k] : zero;
+                dma16(lds0 + GOFF + buf * GBUF + (wv + 4 * k) * 1024, ptr);
+            }
+        };
+
+        // prologue of the run: planes dlo-1, dlo, dlo+1 of x and plane dlo of g.  The barrier
+        // also closes the previous run (every wave is done reading the buffers).
+        __syncthreads();
+        issue_x(dlo - 1, 0);
+        issue_x(dlo, 1);
+        issue_x(dlo + 1, 2);
+        issue_g(dlo, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();
+
+        for (int d = dlo; d < dhi; ++d) {
+            const int i = d - dlo;
+            if (d + 1 < dhi) {
+                issue_x(d + 2, (i + 3) & 3);
+                issue_g(d + 1, (i + 1) & 1);
+            }
+            int xa[7];
+#pragma unroll
+            for (int t = 0; t < 7; ++t) xa[t] = XOFF + ((i + tapkd[t]) & 3) * XP_BYTES + tapoff[t];
+            const int ga = lane_g + (i & 1) * GBUF;
+            wp_stage<COBN>(acc, smem, xa, ga, ones, wv == 3);
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+        }
+    }
+
+    float *out = p.ws + (int64_t)split * p.per_split;
+#pragma unroll
+    for (int t = 0; t < 7; ++t) {
+        const int tap = wv * 7 + t;
+#pragma unroll
+        for (int c = 0; c < COBN; ++c) {
+            const int co = (cob0 + c) * 32 + (lane & 31);
+            if (tap <= 26) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) {
+                    int ci = cib * 32 + (i >> 2) * 8 + hb * 4 + (i & 3);
+                    out[((int64_t)tap * cin + ci) * p.cout + co] = acc[t][c][i];
+                }
+            } else if (cib == 0 && hb == 0) {
+                out[(int64_t)27 * cin * p.cout + co] = acc[t][c][0];   // row 0 of ones^T * g
+            }
+        }
+    }
+}
+
+static int wp_num_cus()
+{
+    static int n = 0;
+    if (n == 0) {
+        int dev = 0, v = 0;
+        if (hipGetDevice(&dev) == hipSuccess &&
+            hipDeviceGetAttribute(&v, hipDeviceAttributeMultiprocessorCount, dev) == hipSuccess && v > 0)
+            n = v;
+        else
+            n = 256;
+    }
+    return n;
+}
+
+static void wp_plan(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout, int *cobn, int64_t *P,
+                    int *S)
+{
+    *cobn = (cout % 64 == 0) ? 2 : 1;
+    *P = N * ((H + wp::TH - 1) / wp::TH) * ((W + wp::TW - 1) / wp::TW) * D;
+    const int64_t yz = (cin / 32) * (cout / (32 * *cobn));
+    int64_t s = wp_num_cus() / yz;   // one workgroup per CU in total
+    if (s > *P) s = *P;
+    if (s < 1) s = 1;
+    *S = (int)s;
+}
+
+bool conv_wgrad_pipe_ok(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout)
+{
+    // byte offsets inside one plane are kept in 32 bits
+    const int64_t c = cin > cout ? cin : cout;
+    return (int64_t)(wp::HH + 1) * W * c * 2 < 0x7fffffffLL && H * W * c * 2 < 0x7fffffffLL;
+}
+
+size_t conv_wgrad_pipe_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout)
+{
+    int cobn, S;
+    int64_t P;
+    wp_plan(N, D, H, W, cin, cout, &cobn, &P, &S);
+    return (size_t)S * (size_t)(27 * cin * cout + cout) * sizeof(float);
+}
+
+template <int COBN>
+static int launch_wgrad_pipe(const WgradPipeParams &p, hipStream_t st)
+{
+    constexpr int lds = wp::lds_bytes(COBN);
+    static_assert(lds <= 160 * 1024, "LDS budget");
+    static bool attr_done = false;
+    if (!attr_done) {
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_wgrad_pipe_kernel<COBN>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        attr_done = true;
+    }
+    conv_wgrad_pipe_kernel<COBN><<<dim3((unsigned)(p.per_xcd * 8)), 256, lds, st>>>(p);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
+int conv_wgrad_pipe(const ConvArgs &a, float *dW, float *db, float *ws, hipStream_t st)
+{
+    WgradPipeParams p{};
+    const int64_t cin = a.c1 + a.c2;
+    int cobn;
+    wp_plan(a.N, a.D, a.H, a.W, cin, a.cout, &cobn, &p.P, &p.S);
+    p.x1 = (const bf16_t *)a.x;
+    p.x2 = (const bf16_t *)a.x2;
+    p.c1 = (int)a.c1;
+    p.c2 = (int)a.c2;
+    p.dy = (const bf16_t *)a.dy;
+    p.cout = (int)a.cout;
+    p.ws = ws;
+    p.per_split = 27 * cin * a.cout + a.cout;
+    p.N = (int)a.N; p.D = (int)a.D; p.H = (int)a.H; p.W = (int)a.W;
+    p.nth = (int)((a.H + wp::TH - 1) / wp::TH);
+    p.ntw = (int)((a.W + wp::TW - 1) / wp::TW);
+    p.ncib = (int)(cin / 32);
+    p.ncog = (int)(a.cout / (32 * cobn));
+    p.total = (int64_t)p.S * p.ncib * p.ncog;
+    p.per_xcd = (p.total + 7) / 8;
+    if (p.per_xcd * 8 > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+    int rc = cobn == 2 ? launch_wgrad_pipe<2>(p, st) : launch_wgrad_pipe<1>(p, st);
+    if (rc != K3_OK) return rc;
+    return launch_reduce_partials(ws, dW, db, 27 * cin * a.cout, p.per_split, p.S, st);
+}
+
+}  // namespace k3

@@ -19,6 +19,9 @@ FWD_CASES = [
     (1, 10, 8, 8, 32, 32, 32, "bf16"),     # two sources (decoder conv1)
     (1, 4, 4, 4, 128, 0, 128, "bf16"),     # volume smaller than a tile, 2 channel groups
     (1, 2, 2, 2, 64, 64, 64, "bf16"),      # bottleneck-like
+    (1, 7, 20, 35, 32, 0, 64, "bf16"),     # several 16x16 columns with ragged edges, odd depth
+    (2, 3, 17, 16, 64, 32, 32, "bf16"),    # two sources, one row past a column, two samples
+    (1, 40, 16, 18, 32, 0, 32, "bf16"),    # long depth run
 ]
 
 
