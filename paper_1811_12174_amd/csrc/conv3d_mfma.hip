@@ -271,7 +271,9 @@ struct PipeCfg {
     static constexpr int WFRAGS = 9 * MB;                     // 1 KB weight fragments per stage
     static constexpr int WF_WAVE = (WFRAGS + 3) / 4;
     static constexpr int WS_BYTES = WFRAGS * 1024;
-    static constexpr int LDS_BYTES = 2 * XS_BYTES + 2 * WS_BYTES;
+    static constexpr int BIAS_OFF = 2 * XS_BYTES + 2 * WS_BYTES;   // fp32 bias of every output channel
+    static constexpr int BIAS_MAX = 1024;
+    static constexpr int LDS_BYTES = BIAS_OFF + BIAS_MAX * 4;
     static constexpr int PW = TW / 8, PH = TH / 4;
     static constexpr int NBLK = TD * PH * PW;
     static constexpr int NBW = NBLK / 4;
@@ -288,7 +290,7 @@ struct PipeTile {
     bool valid;
 };
 
-template <class C>
+template <class C, bool OMASK>
 __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -300,7 +302,6 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
     const unsigned char *zero = reinterpret_cast<const unsigned char *>(g_zero_block);
 
     // ---- tile-independent description of the halo slots this lane copies in each stage part
-    int voxoff[3 * C::XG_WAVE];        // voxel offset of the slot from the tile origin
     int coords[3 * C::XG_WAVE];        // halo coordinates of the slot, packed ld | lh << 8 | lw << 16
     unsigned smask = 0, hmask = 0;     // slot is a real (voxel, half) item / holds the upper 8 channels
 #pragma unroll
@@ -313,7 +314,6 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             const int r = slot / C::ROWSLOTS, pos = slot - r * C::ROWSLOTS;
             const int ld = r / C::HH, lh = r - ld * C::HH, lw = pos >> 1;
             const bool ok = G < C::XGROUPS && slot < C::NSLOT && pos < C::ROWSLOTS - 1;
-            voxoff[idx] = ((ld - 1) * p.H + (lh - 1)) * p.W + (lw - 1);
             coords[idx] = ld | (lh << 8) | (lw << 16);
             smask |= (ok ? 1u : 0u) << idx;
             hmask |= (unsigned)(pos & 1) << idx;
@@ -344,7 +344,9 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
         unsigned vm = 0;
 #pragma unroll
         for (int idx = 0; idx < 3 * C::XG_WAVE; ++idx) {
-            const int ld = coords[idx] & 255, lh = (coords[idx] >> 8) & 255, lw = coords[idx] >> 16;
+            int cw = coords[idx];
+            asm volatile("" : "+v"(cw));
+            const int ld = cw & 255, lh = (cw >> 8) & 255, lw = cw >> 16;
             const bool in = ld >= dlo && ld < dhi && lh >= hlo && lh < hhi && lw >= wlo && lw < whi;
             vm |= (in ? 1u : 0u) << idx;
         }
@@ -352,49 +354,78 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
         return t;
     };
 
-    // copies part g of chunk c of tile t into x buffer `buf`
-    auto copy_x = [&](const PipeTile &t, int c, int buf, auto gtag) {
-        constexpr int g = decltype(gtag)::value;
+    // Source of one stage's asynchronous copies (all wave-uniform): the weight fragments of the
+    // next stage and one third of the next chunk's halo tile.
+    struct StageSrc {
+        const unsigned char *wbase;   // packed weights of (first output block, first tap, chunk) of the stage
+        const unsigned char *xbase;   // channel chs of the tile's origin voxel
+        int strideB;                  // bytes per voxel of the x source
+        unsigned vmask;               // halo validity bits of the tile
+        unsigned wlds, xlds;          // LDS byte addresses of the destination buffers
+        bool wok, xok;
+    };
+    auto w_src = [&](StageSrc &s, const PipeTile &t, int c, int g, int buf) {
+        s.wbase = reinterpret_cast<const unsigned char *>(p.packed) + ((((int64_t)t.mb0 * 27 + g * 9) * nkc + c) * 1024);
+        s.wlds = lds0 + 2 * C::XS_BYTES + buf * C::WS_BYTES;
+        s.wok = true;
+    };
+    auto x_src = [&](StageSrc &s, const PipeTile &t, int c, int buf) {
         const int ch0 = c * 16;
         const bool first = ch0 < p.c1;
         const bf16_t *src = first ? p.src1 : p.src2;
         const int Csrc = first ? p.c1 : p.c2;
         const int chs = first ? ch0 : ch0 - p.c1;
-        const unsigned char *base = reinterpret_cast<const unsigned char *>(src + t.origin * Csrc + chs);
-        const int strideB = Csrc * 2;
-        const unsigned xb = lds0 + buf * C::XS_BYTES;
-#pragma unroll
-        for (int k = 0; k < C::XG_WAVE; ++k) {
+        s.xbase = reinterpret_cast<const unsigned char *>(src + t.origin * Csrc + chs);
+        s.strideB = Csrc * 2;
+        s.vmask = t.vmask;
+        s.xlds = lds0 + buf * C::XS_BYTES;
+        s.xok = true;
+    };
+    // copy operation j of a stage: first the weight fragments, then the halo groups of part g
+    constexpr int NOPS = C::WF_WAVE + C::XG_WAVE;
+    auto issue_op = [&](const StageSrc &s, int j, auto gtag) __attribute__((always_inline)) {
+        constexpr int g = decltype(gtag)::value;
+        if (j < C::WF_WAVE) {
+            const int f = j * 4 + wv;   // fragment (tap tl, block mb) of the stage
+            if (s.wok && f < C::WFRAGS) {
+                const int tl = f / C::MB, mb = f - tl * C::MB;
+                dma16(s.wlds + f * 1024, s.wbase + ((int64_t)(mb * 27 + tl) * nkc) * 1024 + lane * 16);
+            }
+        } else {
+            const int k = j - C::WF_WAVE;
             const int idx = g * C::XG_WAVE + k;
             const int G = g * C::XG_STAGE + k * 4 + wv;
-            if (k * 4 + wv < C::XG_STAGE && G < C::XGROUPS) {
-                const unsigned char *ptr = base + (int64_t)voxoff[idx] * strideB + ((hmask >> idx) & 1) * 16;
-                if (!((t.vmask >> idx) & 1)) ptr = zero;
-                dma16(xb + G * 1024, ptr);
-            }
-        }
-    };
-    // copies the packed weights of stage (c, g) of tile t into weight buffer `buf`
-    auto copy_w = [&](const PipeTile &t, int c, int g, int buf) {
-        const unsigned wb = lds0 + 2 * C::XS_BYTES + buf * C::WS_BYTES;
-#pragma unroll
-        for (int k = 0; k < C::WF_WAVE; ++k) {
-            const int f = k * 4 + wv;   // fragment (tap tl, block mb) of this stage
-            if (f < C::WFRAGS) {
-                const int tl = f / C::MB, mb = f - tl * C::MB;
-                const uint4 *ptr = reinterpret_cast<const uint4 *>(p.packed) +
-                                   ((((int64_t)(t.mb0 + mb) * 27 + g * 9 + tl) * nkc + c) * 64 + lane);
-                dma16(wb + f * 1024, ptr);
+            if (s.xok && k * 4 + wv < C::XG_STAGE && G < C::XGROUPS) {
+                // unpacked here, per copy: the opaque move keeps the compiler from hoisting the
+                // unpacked values of all slots out of the loops (they would occupy ~60 registers)
+                int cw = coords[idx];
+                asm volatile("" : "+v"(cw));
+                const int ld = cw & 255, lh = (cw >> 8) & 255, lw = cw >> 16;
+                const int voxoff = ((ld - 1) * p.H + (lh - 1)) * p.W + (lw - 1);   // from the tile origin
+                const unsigned char *ptr = s.xbase + (int64_t)voxoff * s.strideB + ((hmask >> idx) & 1) * 16;
+                if (!((s.vmask >> idx) & 1)) ptr = zero;
+                dma16(s.xlds + G * 1024, ptr);
             }
         }
     };
 
-    int vbase[C::NBW];
-#pragma unroll
-    for (int a = 0; a < C::NBW; ++a) {
-        int nb = wv * C::NBW + a;
-        int bw = nb % C::PW, bh = (nb / C::PW) % C::PH, bd = nb / (C::PW * C::PH);
-        vbase[a] = bd * C::XS_PLANE + (bh * 4 + (vl >> 3)) * C::XS_ROW + (bw * 8 + (vl & 7)) * 32 + hb * 16;
+    // LDS byte offset of the lane's voxel (tap 0,0,0 corner, the lane's channel half) in patch 0 of
+    // the wave; patch a of the wave lies PatchOff::lds(a) bytes further (a compile-time constant,
+    // because the wave's NBW patches are whole depth planes of PW * PH patches)
+    static_assert(C::NBW % (C::PW * C::PH) == 0, "a wave owns whole planes of patches");
+    constexpr int PPL = C::PW * C::PH, WPL = C::NBW / PPL;   // patches per plane, planes per wave
+    const int lrow = vl >> 3, lcol = vl & 7;
+    const int vb0 = wv * WPL * C::XS_PLANE + lrow * C::XS_ROW + lcol * 32 + hb * 16;
+    auto patch_lds = [](int a) __attribute__((always_inline)) {
+        return (a / PPL) * C::XS_PLANE + (((a % PPL) / C::PW) * 4) * C::XS_ROW + ((a % PPL) % C::PW) * 8 * 32;
+    };
+    // voxel offset of the lane's voxel inside a patch from the patch's first voxel
+    const int lvox = lrow * p.W + lcol;
+    // the bias vector lives in LDS for the whole kernel (zeros when there is none)
+    {
+        float *bl = reinterpret_cast<float *>(smem + C::BIAS_OFF);
+        const int nco = p.cd1 + p.cd2;
+        for (int i = tid; i < nco; i += 256) bl[i] = p.bias ? p.bias[i] : 0.f;
     }
 
     PipeTile cur = decode(blockIdx.x);
@@ -403,116 +434,180 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
     PipeTile nxt = decode(vb_next);
 
     // ---- prologue: chunk 0 of the first tile and the weights of its stage (0, 0)
-    copy_x(cur, 0, 0, std::integral_constant<int, 0>());
-    copy_x(cur, 0, 0, std::integral_constant<int, 1>());
-    copy_x(cur, 0, 0, std::integral_constant<int, 2>());
-    copy_w(cur, 0, 0, 0);
+    {
+        StageSrc s0{};
+        w_src(s0, cur, 0, 0, 0);
+        x_src(s0, cur, 0, 0);
+#pragma unroll
+        for (int j = 0; j < NOPS; ++j) {
+            issue_op(s0, j, std::integral_constant<int, 0>());
+            if (j >= C::WF_WAVE) {
+                issue_op(s0, j, std::integral_constant<int, 1>());
+                issue_op(s0, j, std::integral_constant<int, 2>());
+            }
+        }
+    }
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
     int xpar = 0, wpar = 0;   // LDS buffers holding the current chunk / the current stage's weights
+    const float relu_floor = p.relu ? 0.f : -__builtin_inff();
     while (true) {
-    f32x16 acc[C::NBW][C::MB];   // per-tile accumulators (not carried from tile to tile)
+        // per-tile accumulators (not carried from tile to tile), started at the bias
+        f32x16 acc[C::NBW][C::MB];
+        {
+            const f32x4 *bl = reinterpret_cast<const f32x4 *>(smem + C::BIAS_OFF) + (cur.mb0 * 32 + hb * 16) / 4;
 #pragma unroll
-    for (int a = 0; a < C::NBW; ++a)
+            for (int b = 0; b < C::MB; ++b) {
+                f32x4 q[4];
 #pragma unroll
-        for (int b = 0; b < C::MB; ++b)
+                for (int i = 0; i < 4; ++i) q[i] = bl[b * 8 + i];
 #pragma unroll
-            for (int i = 0; i < 16; ++i) acc[a][b][i] = 0.f;
-    auto stage = [&](int c, auto gtag) {
-        constexpr int g = decltype(gtag)::value;
-        // the data of the next stage (possibly the first stage of the next tile) starts moving now
-        const bool more = c + 1 < nkc;
-        if (g < 2) copy_w(cur, c, g + 1, wpar ^ 1);
-        else if (more) copy_w(cur, c + 1, 0, wpar ^ 1);
-        else if (nxt.valid) copy_w(nxt, 0, 0, wpar ^ 1);
-        if (more) copy_x(cur, c + 1, xpar ^ 1, gtag);
-        else if (nxt.valid) copy_x(nxt, 0, xpar ^ 1, gtag);
-        const unsigned char *xs = smem + xpar * C::XS_BYTES + g * C::XS_PLANE;
-        const unsigned char *wsm = smem + 2 * C::XS_BYTES + wpar * C::WS_BYTES + lane * 16;
-        // Software pipeline over the 9 x NBW (tap, patch) items of the stage: the activation
-        // fragment of item i+PD and the weight fragments of the next tap are requested from LDS
-        // before the MFMAs of item i issue, so LDS latency hides behind matrix work even with a
-        // single wave per SIMD.  sched_barrier keeps the compiler from undoing the order.
-        constexpr int NI = 9 * C::NBW, PD = 3;
-        bf16x8 bq[4], aq[2][C::MB];
-        auto ldb = [&](int i) {
-            const int tl = i / C::NBW, nb = i % C::NBW;
-            return *reinterpret_cast<const bf16x8 *>(xs + vbase[nb] + (tl / 3) * C::XS_ROW + (tl % 3) * 32);
-        };
+                for (int a = 0; a < C::NBW; ++a) {
 #pragma unroll
-        for (int mb = 0; mb < C::MB; ++mb) aq[0][mb] = *reinterpret_cast<const bf16x8 *>(wsm + mb * 1024);
-#pragma unroll
-        for (int i = 0; i < PD; ++i) bq[i] = ldb(i);
-#pragma unroll
-        for (int i = 0; i < NI; ++i) {
-            const int tl = i / C::NBW, nb = i % C::NBW;
-            if (i + PD < NI) bq[(i + PD) & 3] = ldb(i + PD);
-            if (nb == 0 && tl + 1 < 9) {
-#pragma unroll
-                for (int mb = 0; mb < C::MB; ++mb)
-                    aq[(tl + 1) & 1][mb] = *reinterpret_cast<const bf16x8 *>(wsm + ((tl + 1) * C::MB + mb) * 1024);
-            }
-#pragma unroll
-            for (int mb = 0; mb < C::MB; ++mb)
-                acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[tl & 1][mb], bq[i & 3], acc[nb][mb], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-        __syncthreads();
-        wpar ^= 1;
-    };
-
-        for (int c = 0; c < nkc; ++c) {
-            stage(c, std::integral_constant<int, 0>());
-            stage(c, std::integral_constant<int, 1>());
-            stage(c, std::integral_constant<int, 2>());
-            xpar ^= 1;
-        }
-        // ---- epilogue of the tile: bias, ReLU, optional output mask, round to bf16, 32 contiguous
-        // bytes per lane; the stores drain while the next tile is being multiplied
-        float bv[C::MB][16];
-#pragma unroll
-        for (int mb = 0; mb < C::MB; ++mb)
-#pragma unroll
-            for (int i = 0; i < 16; ++i) bv[mb][i] = p.bias ? p.bias[(cur.mb0 + mb) * 32 + hb * 16 + i] : 0.f;
-#pragma unroll
-        for (int nb = 0; nb < C::NBW; ++nb) {
-            int blk = wv * C::NBW + nb;
-            int bw = blk % C::PW, bh = (blk / C::PW) % C::PH, bd = blk / (C::PW * C::PH);
-            int gd = cur.d0 + bd, gh = cur.h0 + bh * 4 + (vl >> 3), gw = cur.w0 + bw * 8 + (vl & 7);
-            const bool inb = gd < p.D && gh < p.H && gw < p.W;   // no early exit: keeps the epilogue one block
-            int64_t vox = inb ? (((int64_t)cur.n * p.D + gd) * p.H + gh) * p.W + gw : cur.origin;
-#pragma unroll
-            for (int mb = 0; mb < C::MB; ++mb) {
-                // keep this block in accumulator registers until here: without the pin the compiler
-                // copies every block to VGPRs right after the last MFMA and spills
-                asm volatile("" : "+a"(acc[nb][mb]));
-                int co0 = (cur.mb0 + mb) * 32 + hb * 16;
-                float v[16];
-#pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    float t = acc[nb][mb][i] + bv[mb][i];
-                    v[i] = (p.relu && !(t > 0.f)) ? 0.f : t;
+                    for (int i = 0; i < 16; ++i) acc[a][b][i] = q[i >> 2][i & 3];
+                    asm volatile("" : "+a"(acc[a][b]));   // straight into accumulator registers
                 }
-                uint4 o0 = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
-                uint4 o1 = make_uint4(pack2bf(v[8], v[9]), pack2bf(v[10], v[11]), pack2bf(v[12], v[13]), pack2bf(v[14], v[15]));
-                const bool d1 = co0 < p.cd1;
-                const int64_t eo = d1 ? vox * p.cd1 + co0 : vox * p.cd2 + (co0 - p.cd1);
-                if (d1 && p.omask) {
-                    const uint4 *mp = reinterpret_cast<const uint4 *>(p.omask + eo);
+            }
+        }
+        const int dlim = p.D - cur.d0, hlim = p.H - cur.h0, wlim = p.W - cur.w0;
+
+        // Finishes one accumulator block: bias, ReLU, optional output mask, round to bf16, store
+        // 32 contiguous bytes per lane.
+        auto emit = [&](int nb, int mb) __attribute__((always_inline)) {
+            const int bw = (nb % PPL) % C::PW, bh = (nb % PPL) / C::PW, bd = wv * WPL + nb / PPL;
+            const bool inb = bd < dlim && bh * 4 + lrow < hlim && bw * 8 + lcol < wlim;
+            const int pvox = (bd * p.H + bh * 4) * p.W + bw * 8 + lvox;
+            const int co0 = (cur.mb0 + mb) * 32;   // wave-uniform; the lane's 16 channels start at co0 + hb * 16
+            // keep the block in accumulator registers until here: without the pin the compiler
+            // copies blocks to VGPRs right after their last MFMA and spills
+            asm volatile("" : "+a"(acc[nb][mb]));
+            float v[16];
+#pragma unroll
+            for (int i = 0; i < 16; ++i) v[i] = fmaxf(acc[nb][mb][i], relu_floor);
+            uint4 o0 = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
+            uint4 o1 = make_uint4(pack2bf(v[8], v[9]), pack2bf(v[10], v[11]), pack2bf(v[12], v[13]), pack2bf(v[14], v[15]));
+            const bool d1 = co0 < p.cd1;
+            const int cd = d1 ? p.cd1 : p.cd2;
+            // wave-uniform 64-bit part + per-lane 32-bit element offset (fits: checked at launch)
+            const int64_t ubase = cur.origin * cd + (d1 ? co0 : co0 - p.cd1);
+            const int loff = pvox * cd + hb * 16;
+            if constexpr (OMASK) {
+                if (d1) {
+                    const uint4 *mp = reinterpret_cast<const uint4 *>(p.omask + ubase + (inb ? loff : hb * 16));
                     uint4 m0 = mp[0], m1 = mp[1];
                     o0.x = mask_pair(o0.x, m0.x); o0.y = mask_pair(o0.y, m0.y); o0.z = mask_pair(o0.z, m0.z); o0.w = mask_pair(o0.w, m0.w);
                     o1.x = mask_pair(o1.x, m1.x); o1.y = mask_pair(o1.y, m1.y); o1.z = mask_pair(o1.z, m1.z); o1.w = mask_pair(o1.w, m1.w);
                 }
-                uint4 *dst = reinterpret_cast<uint4 *>((d1 ? p.dst1 : p.dst2) + eo);
-                if (inb) {
-                    dst[0] = o0;
-                    dst[1] = o1;
-                }
-                __builtin_amdgcn_sched_barrier(0);   // one accumulator block at a time: keeps registers low
             }
+            // buffer stores relative to the tile's first voxel: lanes outside the volume get an
+            // offset beyond the range of the descriptor, which the hardware drops (no branch)
+            bf16_t *dbase = (d1 ? p.dst1 : p.dst2) + ubase;
+            __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(dbase, 0, 0x7ffffff0, 0x00020000);
+            const int boff = inb ? loff * 2 : -1;
+            typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+            __builtin_amdgcn_raw_buffer_store_b128(u32x4{o0.x, o0.y, o0.z, o0.w}, rsrc, boff, 0, 0);
+            __builtin_amdgcn_raw_buffer_store_b128(u32x4{o1.x, o1.y, o1.z, o1.w}, rsrc, boff, 16, 0);
+        };
+
+        // One stage = 9 taps of one depth plane of one 16-channel chunk.  FINAL marks the last
+        // stage of the tile.
+        auto stage = [&](int c, auto gtag, auto finaltag) __attribute__((always_inline)) {
+            constexpr int g = decltype(gtag)::value;
+            constexpr bool FINAL = decltype(finaltag)::value;
+            // the data of the next stage (possibly the first stage of the next tile) starts moving
+            // now; its copies are issued one at a time between the matrix instructions below
+            const bool more = c + 1 < nkc;
+            StageSrc ss{};
+            if (g < 2) w_src(ss, cur, c, g + 1, wpar ^ 1);
+            else if (more) w_src(ss, cur, c + 1, 0, wpar ^ 1);
+            else if (nxt.valid) w_src(ss, nxt, 0, 0, wpar ^ 1);
+            if (more) x_src(ss, cur, c + 1, xpar ^ 1);
+            else if (nxt.valid) x_src(ss, nxt, 0, xpar ^ 1);
+            const unsigned char *xs = smem + xpar * C::XS_BYTES + g * C::XS_PLANE;
+            const unsigned char *wsm = smem + 2 * C::XS_BYTES + wpar * C::WS_BYTES + lane * 16;
+            // Software pipeline over the 9 x NBW (tap, patch) items of the stage: the fragments of
+            // item i+PD are requested from LDS before the MFMAs of item i issue, so LDS latency hides
+            // behind matrix work even with a single wave per SIMD.  sched_barrier keeps the compiler
+            // from undoing the order.
+            constexpr int NI = 9 * C::NBW, PD = 3;
+            constexpr int SP = C::MB == 1 ? 3 : 2;   // items between two copy operations
+            static_assert(NOPS * SP <= NI, "copy operations must fit into the stage");
+            auto ldb = [&](int tl, int nb) __attribute__((always_inline)) {
+                return *reinterpret_cast<const bf16x8 *>(xs + vb0 + patch_lds(nb) + (tl / 3) * C::XS_ROW + (tl % 3) * 32);
+            };
+            auto lda = [&](int tl, int mb) __attribute__((always_inline)) { return *reinterpret_cast<const bf16x8 *>(wsm + (tl * C::MB + mb) * 1024); };
+            if constexpr (!FINAL) {
+                // tap-major order: the weight fragments of a tap serve all NBW patches
+                bf16x8 bq[4], aq[2][C::MB];
+#pragma unroll
+                for (int mb = 0; mb < C::MB; ++mb) aq[0][mb] = lda(0, mb);
+#pragma unroll
+                for (int i = 0; i < PD; ++i) bq[i] = ldb(i / C::NBW, i % C::NBW);
+#pragma unroll
+                for (int i = 0; i < NI; ++i) {
+                    const int tl = i / C::NBW, nb = i % C::NBW;
+                    if (i + PD < NI) bq[(i + PD) & 3] = ldb((i + PD) / C::NBW, (i + PD) % C::NBW);
+                    if (nb == 0 && tl + 1 < 9) {
+#pragma unroll
+                        for (int mb = 0; mb < C::MB; ++mb) aq[(tl + 1) & 1][mb] = lda(tl + 1, mb);
+                    }
+#pragma unroll
+                    for (int mb = 0; mb < C::MB; ++mb)
+                        acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[tl & 1][mb], bq[i & 3], acc[nb][mb], 0, 0, 0);
+                    if (i % SP == 0 && i / SP < NOPS) issue_op(ss, i / SP, gtag);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            } else {
+                // patch-major order: a patch is complete after its 9 taps, and its blocks are
+                // converted and stored between the matrix instructions of the next patch (the
+                // weight fragments are re-read per patch; this is one stage in 3 * nkc)
+                constexpr int PF = 2, RF = PF + 1;   // read-ahead and ring size of this stage
+                bf16x8 bq[RF], aq[RF][C::MB];
+#pragma unroll
+                for (int i = 0; i < PF; ++i) {
+                    bq[i] = ldb(i % 9, i / 9);
+#pragma unroll
+                    for (int mb = 0; mb < C::MB; ++mb) aq[i][mb] = lda(i % 9, mb);
+                }
+#pragma unroll
+                for (int i = 0; i < NI; ++i) {
+                    const int nb = i / 9, tl = i % 9;
+                    if (i + PF < NI) {
+                        bq[(i + PF) % RF] = ldb((i + PF) % 9, (i + PF) / 9);
+#pragma unroll
+                        for (int mb = 0; mb < C::MB; ++mb) aq[(i + PF) % RF][mb] = lda((i + PF) % 9, mb);
+                    }
+#pragma unroll
+                    for (int mb = 0; mb < C::MB; ++mb)
+                        acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[i % RF][mb], bq[i % RF], acc[nb][mb], 0, 0, 0);
+                    if (i % SP == 0 && i / SP < NOPS) issue_op(ss, i / SP, gtag);
+                    // blocks of the previous patch: one after taps 2 and 5 of this patch
+                    if (nb > 0 && tl == 2) emit(nb - 1, 0);
+                    if (nb > 0 && tl == 5 && C::MB > 1) emit(nb - 1, C::MB - 1);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+#pragma unroll
+                for (int mb = 0; mb < C::MB; ++mb) {
+                    emit(C::NBW - 1, mb);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+            }
+            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            __syncthreads();
+            wpar ^= 1;
+        };
+
+        for (int c = 0; c + 1 < nkc; ++c) {
+            stage(c, std::integral_constant<int, 0>(), std::false_type());
+            stage(c, std::integral_constant<int, 1>(), std::false_type());
+            stage(c, std::integral_constant<int, 2>(), std::false_type());
+            xpar ^= 1;
         }
+        stage(nkc - 1, std::integral_constant<int, 0>(), std::false_type());
+        stage(nkc - 1, std::integral_constant<int, 1>(), std::false_type());
+        stage(nkc - 1, std::integral_constant<int, 2>(), std::true_type());
+        xpar ^= 1;
         if (!nxt.valid) break;
         cur = nxt;
         vb_next += gridDim.x;
@@ -532,13 +627,16 @@ static int launch_pipe(MfmaParams p, int64_t mblocks, hipStream_t st)
     if (p.per_xcd * 8 > 0x7fffffffLL) return K3_E_UNSUPPORTED;
     static bool attr_done = false;
     if (!attr_done) {
-        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C>),
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
         attr_done = true;
     }
     // persistent workgroups, one per CU (fewer when there is less work); a multiple of 8
     int64_t grid = p.per_xcd * 8 < 256 ? p.per_xcd * 8 : 256;
-    conv_mfma_pipe_kernel<C><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    if (p.omask) conv_mfma_pipe_kernel<C, true><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    else conv_mfma_pipe_kernel<C, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
     K3_LAUNCH_CHECK();
     return K3_OK;
 }
@@ -574,7 +672,8 @@ static int launch_mfma(MfmaParams p, int64_t mchannels, hipStream_t st)
         typedef PipeCfg<8, 8, 16, 1> P1;
         int64_t tiles = (int64_t)p.N * ((p.D + 7) / 8) * ((p.H + 7) / 8) * ((p.W + 15) / 16);
         // the halo tile's voxel offsets are kept in 32 bits
-        const bool fits = (int64_t)10 * p.H * p.W < 0x7fffffffLL;
+        const int cmax = p.cd1 > p.cd2 ? p.cd1 : p.cd2;
+        const bool fits = (int64_t)10 * p.H * p.W * (cmax > 1 ? cmax : 1) < 0x7fffffffLL && p.cd1 + p.cd2 <= 1024;
         if (!p.mask && fits && mblocks % 2 == 0 && tiles * (mblocks / 2) >= 256) return launch_pipe<P2>(p, mblocks, st);
         if (!p.mask && fits && mblocks % 2 == 1 && tiles * mblocks >= 256) return launch_pipe<P1>(p, mblocks, st);
     }
