@@ -273,7 +273,8 @@ struct PipeCfg {
     static constexpr int WS_BYTES = WFRAGS * 1024;
     static constexpr int BIAS_OFF = 2 * XS_BYTES + 2 * WS_BYTES;   // fp32 bias of every output channel
     static constexpr int BIAS_MAX = 1024;
-    static constexpr int LDS_BYTES = BIAS_OFF + BIAS_MAX * 4;
+    static constexpr int DUMP_OFF = BIAS_OFF + BIAS_MAX * 4;       // 1 KB target of the padding copies
+    static constexpr int LDS_BYTES = DUMP_OFF + 1024;
     static constexpr int PW = TW / 8, PH = TH / 4;
     static constexpr int NBLK = TD * PH * PW;
     static constexpr int NBW = NBLK / 4;
@@ -383,29 +384,32 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
     };
     // copy operation j of a stage: first the weight fragments, then the halo groups of part g
     constexpr int NOPS = C::WF_WAVE + C::XG_WAVE;
+    // Every wave issues exactly NOPS copies per stage, so that the number of copies still in
+    // flight at a stage end is known at compile time (s_waitcnt takes an immediate): a slot that
+    // has nothing to copy moves the zero block into a dump area of LDS.
     auto issue_op = [&](const StageSrc &s, int j, auto gtag) __attribute__((always_inline)) {
         constexpr int g = decltype(gtag)::value;
+        const unsigned dump = lds0 + C::DUMP_OFF;
         if (j < C::WF_WAVE) {
             const int f = j * 4 + wv;   // fragment (tap tl, block mb) of the stage
-            if (s.wok && f < C::WFRAGS) {
-                const int tl = f / C::MB, mb = f - tl * C::MB;
-                dma16(s.wlds + f * 1024, s.wbase + ((int64_t)(mb * 27 + tl) * nkc) * 1024 + lane * 16);
-            }
+            const bool ok = s.wok && f < C::WFRAGS;
+            const int tl = f / C::MB, mb = f - tl * C::MB;
+            const unsigned char *ptr = ok ? s.wbase + ((int64_t)(mb * 27 + tl) * nkc) * 1024 + lane * 16 : zero;
+            dma16(ok ? s.wlds + f * 1024 : dump, ptr);
         } else {
             const int k = j - C::WF_WAVE;
             const int idx = g * C::XG_WAVE + k;
             const int G = g * C::XG_STAGE + k * 4 + wv;
-            if (s.xok && k * 4 + wv < C::XG_STAGE && G < C::XGROUPS) {
-                // unpacked here, per copy: the opaque move keeps the compiler from hoisting the
-                // unpacked values of all slots out of the loops (they would occupy ~60 registers)
-                int cw = coords[idx];
-                asm volatile("" : "+v"(cw));
-                const int ld = cw & 255, lh = (cw >> 8) & 255, lw = cw >> 16;
-                const int voxoff = ((ld - 1) * p.H + (lh - 1)) * p.W + (lw - 1);   // from the tile origin
-                const unsigned char *ptr = s.xbase + (int64_t)voxoff * s.strideB + ((hmask >> idx) & 1) * 16;
-                if (!((s.vmask >> idx) & 1)) ptr = zero;
-                dma16(s.xlds + G * 1024, ptr);
-            }
+            const bool ok = s.xok && k * 4 + wv < C::XG_STAGE && G < C::XGROUPS;
+            // unpacked here, per copy: the opaque move keeps the compiler from hoisting the
+            // unpacked values of all slots out of the loops (they would occupy ~60 registers)
+            int cw = coords[idx];
+            asm volatile("" : "+v"(cw));
+            const int ld = cw & 255, lh = (cw >> 8) & 255, lw = cw >> 16;
+            const int voxoff = ((ld - 1) * p.H + (lh - 1)) * p.W + (lw - 1);   // from the tile origin
+            const unsigned char *ptr = s.xbase + (int64_t)voxoff * s.strideB + ((hmask >> idx) & 1) * 16;
+            if (!ok || !((s.vmask >> idx) & 1)) ptr = zero;
+            dma16(ok ? s.xlds + G * 1024 : dump, ptr);
         }
     };
 
@@ -436,6 +440,7 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
     // ---- prologue: chunk 0 of the first tile and the weights of its stage (0, 0)
     {
         StageSrc s0{};
+        s0.wbase = s0.xbase = zero;
         w_src(s0, cur, 0, 0, 0);
         x_src(s0, cur, 0, 0);
 #pragma unroll
@@ -519,6 +524,7 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             // now; its copies are issued one at a time between the matrix instructions below
             const bool more = c + 1 < nkc;
             StageSrc ss{};
+            ss.wbase = ss.xbase = zero;
             if (g < 2) w_src(ss, cur, c, g + 1, wpar ^ 1);
             else if (more) w_src(ss, cur, c + 1, 0, wpar ^ 1);
             else if (nxt.valid) w_src(ss, nxt, 0, 0, wpar ^ 1);
@@ -593,7 +599,11 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            // The next stage needs its weights, issued first in this stage; the halo thirds issued
+            // after them are not read before the next chunk starts, so after the first two stages
+            // of a chunk they may stay in flight (copies complete in issue order).
+            if constexpr (g < 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::XG_WAVE) : "memory");
+            else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
             wpar ^= 1;
         };
