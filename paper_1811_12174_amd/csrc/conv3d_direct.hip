@@ -201,9 +201,54 @@ __global__ __launch_bounds__(256) void reduce_partials_kernel(const float *__res
     }
 }
 
+// Same sum for 16-byte aligned buffers whose element counts are multiples of 4: a thread adds
+// float4 quads, 16 quads x 16 groups of splits per block, groups merged in a fixed order.
+__global__ __launch_bounds__(256) void reduce_partials_vec4_kernel(const float4 *__restrict__ ws, float4 *__restrict__ dW,
+                                                                  float4 *__restrict__ db, int64_t quadsW, int64_t quads,
+                                                                  int nsplit)
+{
+    __shared__ float4 part[16][16];
+    const int e = threadIdx.x & 15, g = threadIdx.x >> 4;
+    const int64_t i = (int64_t)blockIdx.x * 16 + e;
+    float4 s0 = make_float4(0.f, 0.f, 0.f, 0.f), s1 = s0;
+    if (i < quads) {
+        int k = g;
+        for (; k + 16 < nsplit; k += 32) {   // two independent chains
+            const float4 a = ws[(int64_t)k * quads + i], b = ws[(int64_t)(k + 16) * quads + i];
+            s0.x += a.x; s0.y += a.y; s0.z += a.z; s0.w += a.w;
+            s1.x += b.x; s1.y += b.y; s1.z += b.z; s1.w += b.w;
+        }
+        if (k < nsplit) {
+            const float4 a = ws[(int64_t)k * quads + i];
+            s0.x += a.x; s0.y += a.y; s0.z += a.z; s0.w += a.w;
+        }
+    }
+    part[g][e] = make_float4(s0.x + s1.x, s0.y + s1.y, s0.z + s1.z, s0.w + s1.w);
+    __syncthreads();
+    if (g == 0 && i < quads) {
+        float4 s = part[0][e];
+#pragma unroll
+        for (int q = 1; q < 16; ++q) {
+            const float4 a = part[q][e];
+            s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+        }
+        if (i < quadsW) dW[i] = s;
+        else if (db) db[i - quadsW] = s;
+    }
+}
+
 int launch_reduce_partials(const float *ws, float *dW, float *db, int64_t countW, int64_t count, int nsplit,
                            hipStream_t st)
 {
+    const bool vec = count % 4 == 0 && countW % 4 == 0 && ((uintptr_t)ws & 15) == 0 && ((uintptr_t)dW & 15) == 0 &&
+                     ((uintptr_t)db & 15) == 0;
+    if (vec) {
+        const int64_t quads = count / 4;
+        reduce_partials_vec4_kernel<<<dim3((unsigned)((quads + 15) / 16)), 256, 0, st>>>(
+            (const float4 *)ws, (float4 *)dW, (float4 *)db, countW / 4, quads, nsplit);
+        K3_LAUNCH_CHECK();
+        return K3_OK;
+    }
     int64_t blocks = (count + 63) / 64;
     reduce_partials_kernel<<<dim3((unsigned)blocks), 256, 0, st>>>(ws, dW, db, countW, count, nsplit);
     K3_LAUNCH_CHECK();

@@ -9,7 +9,7 @@
 //    multiplies one plane: 256 voxels = 16 K-steps.  The x planes d-1, d, d+1 (18x18 voxels
 //    with the in-plane halo) sit in a ring of four LDS buffers, so every x plane is fetched
 //    once per column and serves the three depth taps; g planes alternate between two buffers.
-//  * While a stage is multiplied, the next x plane and the next g plane move from global
+//  * While a stage is multiplied, x and g planes one or two stages ahead move from global
 //    memory straight into the free LDS buffers (asynchronous 16-byte-per-lane copies); one
 //    vmcnt wait and one barrier per stage.  Voxels outside the volume read a block of zeros.
 //  * The four waves split the 27 taps (7, 7, 7, 6); the spare slot of the last wave
@@ -30,10 +30,14 @@ constexpr int TH = 16, TW = 16, HH = TH + 2, HW = TW + 2;
 constexpr int XP_SLOTS = HH * HW * 4;              // 16-byte slots of one x plane (32 channels per voxel)
 constexpr int XP_GROUPS = (XP_SLOTS + 63) / 64;    // 1 KB copy groups
 constexpr int XP_BYTES = XP_GROUPS * 1024;
-constexpr int XK = (XP_GROUPS + 3) / 4;            // copy groups per wave and x plane
-constexpr int NXB = 4;                             // ring of x plane buffers
+constexpr int XK = (XP_GROUPS + 3) / 4;            // copies per wave and x plane
 constexpr int GP_BYTES1 = TH * TW * 64;            // one 32-channel block of a g plane
-constexpr int lds_bytes(int cobn) { return NXB * XP_BYTES + 2 * cobn * GP_BYTES1; }
+// PF = how many planes ahead of the multiplied one the copies run.  The x ring holds the three
+// planes in use plus PF incoming ones, the g ring the one in use plus PF incoming ones.
+constexpr int nxb(int pf) { return 3 + pf; }
+constexpr int ngb(int pf) { return 1 + pf; }
+constexpr int dump_off(int cobn, int pf) { return ngb(pf) * cobn * GP_BYTES1 + nxb(pf) * XP_BYTES; }
+constexpr int lds_bytes(int cobn, int pf) { return dump_off(cobn, pf) + 1024; }
 }  // namespace wp
 
 struct WgradPipeParams {
@@ -45,10 +49,11 @@ struct WgradPipeParams {
     int64_t per_split;   // floats per split: 27*cin*cout + cout
     int N, D, H, W;
     int nth, ntw;        // columns per sample along h and w
-    int64_t P;           // planes in total: columns * D
-    int S;               // splits of the plane range
+    int P;               // planes in total: columns * D
+    int S;               // splits of the plane range: split s owns planes [s*pbase + min(s, prem), ...)
+    int pbase, prem;     // P / S and P % S
     int ncib, ncog;      // 32-channel blocks of x, groups of 32*COBN channels of g
-    int64_t total, per_xcd;
+    int total, per_xcd;
 };
 
 static __device__ uint4 g_wzero[4];   // zero-initialised: source of every out-of-volume item
@@ -75,7 +80,7 @@ __device__ __forceinline__ void wp_stage(f32x16 (&acc)[7][COBN], const unsigned 
     constexpr int NF = COBN + 7;        // fragments per K-step
     constexpr int NM = 7 * COBN;        // MFMAs per K-step
     bf16x8 fr[2][COBN + 7];
-    auto load = [&](int s, int f) -> bf16x8 {
+    auto load = [&](int s, int f) __attribute__((always_inline)) -> bf16x8 {
         const int r2 = 2 * (s >> 1), q = 8 * (s & 1);
         if (f < COBN) return wp_tr_pair(smem, ga + f * GP_BYTES1 + (r2 * TW + q) * 64);
         return wp_tr_pair(smem, xa[f - COBN] + (r2 * HW + q) * 64);
@@ -98,7 +103,7 @@ __device__ __forceinline__ void wp_stage(f32x16 (&acc)[7][COBN], const unsigned 
     }
 }
 
-template <int COBN>
+template <int COBN, int PF>
 __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams p)
 {
     using namespace wp;
@@ -108,21 +113,25 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
     const int hb = lane >> 5, g16 = (lane >> 4) & 1, j = lane & 15;
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
     const unsigned char *zero = reinterpret_cast<const unsigned char *>(g_wzero);
-    // LDS map: the two g buffers first, then the ring of x planes.  (Measured: with the x ring
-    // first and the g buffers behind it the same kernel ran 2.8x slower for COBN = 2.)
-    constexpr int GOFF = 0;
-    constexpr int XOFF = 2 * COBN * GP_BYTES1;
+    constexpr int NXB = nxb(PF), NGB = ngb(PF);
+    // LDS map: the g ring first, then the ring of x planes, then the dump area of the padding
+    // copies.  (Measured: with the x ring first and the g buffers behind it the same kernel ran
+    // 2.8x slower for COBN = 2.)
     constexpr int GBUF = COBN * GP_BYTES1;
-    constexpr int GK = COBN * 4;              // g copy groups per wave and plane
+    constexpr int GOFF = 0;
+    constexpr int XOFF = NGB * GBUF;
+    constexpr int GK = COBN * 4;              // g copies per wave and plane
+    constexpr int OPS = XK + GK;              // copies per wave and stage (always exactly this many)
+    const unsigned dump = lds0 + dump_off(COBN, PF);
 
     // XCD-aware order: consecutive block ids go round-robin to the 8 XCDs, so the logical order
     // is cut into 8 contiguous runs; the workgroups of one split (same voxels, different channel
     // blocks) are neighbours in the logical order and share an L2.
-    const int64_t logical = (int64_t)(blockIdx.x & 7) * p.per_xcd + (blockIdx.x >> 3);
-    if ((int64_t)(blockIdx.x >> 3) >= p.per_xcd || logical >= p.total) return;
-    const int yz = p.ncib * p.ncog;
+    const unsigned logical = (blockIdx.x & 7u) * (unsigned)p.per_xcd + (blockIdx.x >> 3);
+    if ((blockIdx.x >> 3) >= (unsigned)p.per_xcd || logical >= (unsigned)p.total) return;
+    const unsigned yz = (unsigned)(p.ncib * p.ncog);
     const int split = (int)(logical / yz);
-    const int r = (int)(logical - (int64_t)split * yz);
+    const int r = (int)(logical - (unsigned)split * yz);
     const int cib = r % p.ncib, cob0 = (r / p.ncib) * COBN;
     const int cin = p.c1 + p.c2;
     const bool first = cib * 32 < p.c1;
@@ -154,7 +163,7 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
     }
 
     // ---- lane-constant parts of the transposing-read addresses and the wave's taps
-    const int lane_x = (hb * HW + (j >> 2)) * 64 + g16 * 32 + (j & 3) * 8;
+    const int lane_x = XOFF + (hb * HW + (j >> 2)) * 64 + g16 * 32 + (j & 3) * 8;
     const int lane_g = GOFF + (hb * TW + (j >> 2)) * 64 + g16 * 32 + (j & 3) * 8;
     int tapoff[7], tapkd[7];
 #pragma unroll
@@ -177,18 +186,19 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
     for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
 
     // ---- this split's plane range, walked column by column
-    int64_t pl = (int64_t)split * p.P / p.S;
-    const int64_t pl_end = (int64_t)(split + 1) * p.P / p.S;
+    int pl = split * p.pbase + (split < p.prem ? split : p.prem);
+    const int pl_end = pl + p.pbase + (split < p.prem ? 1 : 0);
     while (pl < pl_end) {
-        const int64_t col = pl / p.D;
-        const int dlo = (int)(pl - col * p.D);
-        int64_t run_end = (col + 1) * p.D;
+        const int col = (int)((unsigned)pl / (unsigned)p.D);
+        const int dlo = pl - col * p.D;
+        int run_end = (col + 1) * p.D;
         if (run_end > pl_end) run_end = pl_end;
-        const int dhi = dlo + (int)(run_end - pl);
+        const int n_run = run_end - pl;   // planes of this run
         pl = run_end;
-        const int twi = (int)(col % p.ntw);
-        const int thi = (int)((col / p.ntw) % p.nth);
-        const int n = (int)(col / ((int64_t)p.ntw * p.nth));
+        const int twi = (int)((unsigned)col % (unsigned)p.ntw);
+        const int q1 = (int)((unsigned)col / (unsigned)p.ntw);
+        const int thi = (int)((unsigned)q1 % (unsigned)p.nth);
+        const int n = (int)((unsigned)q1 / (unsigned)p.nth);
         const int h0 = thi * TH, w0 = twi * TW;
 
         unsigned xvm = 0, gvm = 0;   // item lies inside the volume (in-plane test)
@@ -207,49 +217,67 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
         const int64_t vox0 = (((int64_t)n * p.D) * p.H + h0) * p.W + w0;
         const int64_t plane = (int64_t)p.H * p.W;
 
-        auto issue_x = [&](int d, int buf) {
-            const bool din = d >= 0 && d < p.D;
+        // x plane with run index q (plane dlo - 1 + q) -> ring buffer buf; `on` false: padding copies
+        auto issue_x = [&](int q, int buf, bool on) __attribute__((always_inline)) {
+            const int d = dlo - 1 + q;
+            const bool din = on && d >= 0 && d < p.D;
             const unsigned char *base = reinterpret_cast<const unsigned char *>(xsrc + (vox0 + d * plane) * Cx + chx);
 #pragma unroll
             for (int k = 0; k < XK; ++k) {
-                if (wv + 4 * k < XP_GROUPS) {
-                    const unsigned char *ptr = (din && ((xvm >> k) & 1)) ? base + xoff[k] : zero;
-                    dma16(lds0 + XOFF + buf * XP_BYTES + (wv + 4 * k) * 1024, ptr);
-                }
+                const bool grp = on && wv + 4 * k < XP_GROUPS;
+                const unsigned char *ptr = (din && ((xvm >> k) & 1)) ? base + xoff[k] : zero;
+                dma16(grp ? lds0 + XOFF + buf * XP_BYTES + (wv + 4 * k) * 1024 : dump, ptr);
             }
         };
-        auto issue_g = [&](int d, int buf) {
-            const unsigned char *base = reinterpret_cast<const unsigned char *>(p.dy + (vox0 + d * plane) * p.cout);
+        // g plane with run index i (plane dlo + i)
+        auto issue_g = [&](int i, int buf, bool on) __attribute__((always_inline)) {
+            const unsigned char *base = reinterpret_cast<const unsigned char *>(p.dy + (vox0 + (dlo + i) * plane) * p.cout);
 #pragma unroll
             for (int k = 0; k < GK; ++k) {
-                const unsigned char *ptr = ((gvm >> k) & 1) ? base + goff[k] : zero;
-                dma16(lds0 + GOFF + buf * GBUF + (wv + 4 * k) * 1024, ptr);
+                const unsigned char *ptr = (on && ((gvm >> k) & 1)) ? base + goff[k] : zero;
+                dma16(on ? lds0 + GOFF + buf * GBUF + (wv + 4 * k) * 1024 : dump, ptr);
             }
         };
 
-        // prologue of the run: planes dlo-1, dlo, dlo+1 of x and plane dlo of g.  The barrier
-        // also closes the previous run (every wave is done reading the buffers).
+        // Prologue of the run: what stage 0 reads (x planes 0..2, g plane 0), then the planes the
+        // first PF - 1 stages would have fetched.  The barrier also closes the previous run.
+        // Stage i reads x planes i..i+2 and g plane i, and fetches x plane i+2+PF and g plane
+        // i+PF when stage i+PF exists; at its end only the copies of the last PF-1 stages may
+        // still be in flight (copies complete in issue order).
         __syncthreads();
-        issue_x(dlo - 1, 0);
-        issue_x(dlo, 1);
-        issue_x(dlo + 1, 2);
-        issue_g(dlo, 0);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        issue_x(0, 0, true);
+        issue_x(1, 1, true);
+        issue_x(2, 2, true);
+        issue_g(0, 0, true);
+#pragma unroll
+        for (int e = 1; e < PF; ++e) {
+            issue_x(2 + e, 2 + e, e < n_run);
+            issue_g(e, e, e < n_run);
+        }
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PF - 1) * OPS) : "memory");
         __syncthreads();
 
-        for (int d = dlo; d < dhi; ++d) {
-            const int i = d - dlo;
-            if (d + 1 < dhi) {
-                issue_x(d + 2, (i + 3) & 3);
-                issue_g(d + 1, (i + 1) & 1);
+        int xb = 0, gb = 0;   // ring buffers of x plane i and g plane i
+        for (int i = 0; i < n_run; ++i) {
+            {
+                int xn = xb + 2 + PF; if (xn >= NXB) xn -= NXB; if (xn >= NXB) xn -= NXB;
+                int gn = gb + PF; if (gn >= NGB) gn -= NGB;
+                const bool on = i + PF < n_run;
+                issue_x(i + 2 + PF, xn, on);
+                issue_g(i + PF, gn, on);
             }
             int xa[7];
 #pragma unroll
-            for (int t = 0; t < 7; ++t) xa[t] = XOFF + ((i + tapkd[t]) & 3) * XP_BYTES + tapoff[t];
-            const int ga = lane_g + (i & 1) * GBUF;
+            for (int t = 0; t < 7; ++t) {
+                int bsel = xb + tapkd[t]; if (bsel >= NXB) bsel -= NXB;
+                xa[t] = bsel * XP_BYTES + tapoff[t];
+            }
+            const int ga = lane_g + gb * GBUF;
             wp_stage<COBN>(acc, smem, xa, ga, ones, wv == 3);
-            asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PF - 1) * OPS) : "memory");
             __syncthreads();
+            if (++xb == NXB) xb = 0;
+            if (++gb == NGB) gb = 0;
         }
     }
 
@@ -261,11 +289,10 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
         for (int c = 0; c < COBN; ++c) {
             const int co = (cob0 + c) * 32 + (lane & 31);
             if (tap <= 26) {
+                // rows ci = cib*32 + (i/4)*8 + hb*4 + i%4 of this tap's [cin][cout] block
+                float *o = out + ((int64_t)tap * cin + cib * 32 + hb * 4) * p.cout + co;
 #pragma unroll
-                for (int i = 0; i < 16; ++i) {
-                    int ci = cib * 32 + (i >> 2) * 8 + hb * 4 + (i & 3);
-                    out[((int64_t)tap * cin + ci) * p.cout + co] = acc[t][c][i];
-                }
+                for (int i = 0; i < 16; ++i) o[((i >> 2) * 8 + (i & 3)) * p.cout] = acc[t][c][i];
             } else if (cib == 0 && hb == 0) {
                 out[(int64_t)27 * cin * p.cout + co] = acc[t][c][0];   // row 0 of ones^T * g
             }
@@ -287,6 +314,8 @@ static int wp_num_cus()
     return n;
 }
 
+static constexpr int wp_pf(int cobn) { return cobn == 1 ? 2 : 1; }   // deeper read-ahead where a stage is short
+
 static void wp_plan(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout, int *cobn, int64_t *P,
                     int *S)
 {
@@ -301,9 +330,11 @@ static void wp_plan(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int
 
 bool conv_wgrad_pipe_ok(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout)
 {
-    // byte offsets inside one plane are kept in 32 bits
+    // byte offsets inside one plane and the plane / workgroup counts are kept in 32 bits
     const int64_t c = cin > cout ? cin : cout;
-    return (int64_t)(wp::HH + 1) * W * c * 2 < 0x7fffffffLL && H * W * c * 2 < 0x7fffffffLL;
+    const int64_t P = N * ((H + wp::TH - 1) / wp::TH) * ((W + wp::TW - 1) / wp::TW) * D;
+    return (int64_t)(wp::HH + 1) * W * c * 2 < 0x7fffffffLL && H * W * c * 2 < 0x7fffffffLL && P < 0x3fffffffLL &&
+           (cin / 32) * (cout / 32) < 0x100000LL;
 }
 
 size_t conv_wgrad_pipe_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout)
@@ -317,15 +348,16 @@ size_t conv_wgrad_pipe_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int6
 template <int COBN>
 static int launch_wgrad_pipe(const WgradPipeParams &p, hipStream_t st)
 {
-    constexpr int lds = wp::lds_bytes(COBN);
+    constexpr int PF = wp_pf(COBN);
+    constexpr int lds = wp::lds_bytes(COBN, PF);
     static_assert(lds <= 160 * 1024, "LDS budget");
     static bool attr_done = false;
     if (!attr_done) {
-        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_wgrad_pipe_kernel<COBN>),
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_wgrad_pipe_kernel<COBN, PF>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         attr_done = true;
     }
-    conv_wgrad_pipe_kernel<COBN><<<dim3((unsigned)(p.per_xcd * 8)), 256, lds, st>>>(p);
+    conv_wgrad_pipe_kernel<COBN, PF><<<dim3((unsigned)(p.per_xcd * 8)), 256, lds, st>>>(p);
     K3_LAUNCH_CHECK();
     return K3_OK;
 }
@@ -335,7 +367,11 @@ int conv_wgrad_pipe(const ConvArgs &a, float *dW, float *db, float *ws, hipStrea
     WgradPipeParams p{};
     const int64_t cin = a.c1 + a.c2;
     int cobn;
-    wp_plan(a.N, a.D, a.H, a.W, cin, a.cout, &cobn, &p.P, &p.S);
+    int64_t P;
+    wp_plan(a.N, a.D, a.H, a.W, cin, a.cout, &cobn, &P, &p.S);
+    p.P = (int)P;
+    p.pbase = p.P / p.S;
+    p.prem = p.P % p.S;
     p.x1 = (const bf16_t *)a.x;
     p.x2 = (const bf16_t *)a.x2;
     p.c1 = (int)a.c1;
@@ -349,9 +385,10 @@ int conv_wgrad_pipe(const ConvArgs &a, float *dW, float *db, float *ws, hipStrea
     p.ntw = (int)((a.W + wp::TW - 1) / wp::TW);
     p.ncib = (int)(cin / 32);
     p.ncog = (int)(a.cout / (32 * cobn));
-    p.total = (int64_t)p.S * p.ncib * p.ncog;
+    const int64_t total = (int64_t)p.S * p.ncib * p.ncog;
+    if (total > 0x3fffffffLL) return K3_E_UNSUPPORTED;
+    p.total = (int)total;
     p.per_xcd = (p.total + 7) / 8;
-    if (p.per_xcd * 8 > 0x7fffffffLL) return K3_E_UNSUPPORTED;
     int rc = cobn == 2 ? launch_wgrad_pipe<2>(p, st) : launch_wgrad_pipe<1>(p, st);
     if (rc != K3_OK) return rc;
     return launch_reduce_partials(ws, dW, db, 27 * cin * a.cout, p.per_split, p.S, st);
