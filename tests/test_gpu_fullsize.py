@@ -1,0 +1,192 @@
+"""GPU parity at the sizes and in the launch configuration the benchmark times.
+
+The small cases of test_gpu_conv.py run the small-volume kernels; volumes with at least one
+tile per compute unit take the persistent pipelined kernels, which these tests cover: the
+whole encoder block of workload config 2 (1 x 64^3, 32 -> 32) exactly as bench.py issues it,
+and U-Net-sized layers (64 and 128 channels, two sources / two destinations, ragged tiles).
+The oracle evaluates sampled output voxels (all channels) and sampled weight-gradient entries
+(full voxel sum) one by one; the samples include every corner, points on faces and edges, and
+points on both sides of tile borders.
+"""
+import numpy as np
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+def sample_points(N, D, H, W, count, seed):
+    """Voxel coordinates: the 8 corners of each sample, border and tile-border points, random fill."""
+    rng = np.random.default_rng(seed)
+    pts = []
+    for n in range(N):
+        for d in (0, D - 1):
+            for h in (0, H - 1):
+                for w in (0, W - 1):
+                    pts.append((n, d, h, w))
+    special = {  # coordinates next to tile borders of every kernel (tiles of 4, 8 and 16 voxels)
+        "d": [v for v in (0, 1, 3, 4, 5, 6, 7, 8, 9, 15, 16, D // 2, D - 2, D - 1) if 0 <= v < D],
+        "h": [v for v in (0, 1, 7, 8, 9, 15, 16, 17, H // 2, H - 2, H - 1) if 0 <= v < H],
+        "w": [v for v in (0, 1, 7, 8, 15, 16, 17, 31, 32, W // 2, W - 2, W - 1) if 0 <= v < W],
+    }
+    for _ in range(count // 2):
+        pts.append((int(rng.integers(N)), int(rng.choice(special["d"])), int(rng.choice(special["h"])),
+                    int(rng.choice(special["w"]))))
+    while len(pts) < count:
+        pts.append((int(rng.integers(N)), int(rng.integers(D)), int(rng.integers(H)), int(rng.integers(W))))
+    return np.array(pts, dtype=np.int64)
+
+
+def gather(t, pts):
+    """device tensor [N,D,H,W,C] -> float64 numpy [npts, C] at the sampled voxels."""
+    import torch
+    idx = torch.from_numpy(pts).cuda()
+    return t[idx[:, 0], idx[:, 1], idx[:, 2], idx[:, 3]].to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def host64(t):
+    import torch
+    return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
+
+
+def flip_transpose(w):
+    """Weights of the correlation that backward-data is: taps mirrored, channel roles swapped.
+    (The oracle's own backward-data is pinned to this by the adjoint identity in the CPU tests.)"""
+    return np.ascontiguousarray(w[::-1, ::-1, ::-1].transpose(0, 1, 2, 4, 3))
+
+
+def rel(got, ref):
+    return np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
+
+
+def wgrad_entries(cin, cout, count, seed):
+    rng = np.random.default_rng(seed)
+    ent = [(t, int(rng.integers(cin)), int(rng.integers(cout))) for t in range(27)]   # every tap once
+    while len(ent) < count:
+        ent.append((int(rng.integers(27)), int(rng.integers(cin)), int(rng.integers(cout))))
+    return np.array(ent, dtype=np.int64)
+
+
+def test_cfg2_block_as_benchmarked(orc):
+    """The encoder block of workload config 2, call for call as bench.py runs it."""
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev
+    N, S, C = 1, 64, 32
+    bf = torch.bfloat16
+    xh = synth.activations(1, (N, S, S, S, C), "bf16")
+    w1h, w2h = synth.conv_weights(2, C, C, "bf16"), synth.conv_weights(3, C, C, "bf16")
+    b1h = (synth.normal(synth.SEED, 5, (C,), np.float64) * 0.1).astype(np.float32)
+    b2h = (synth.normal(synth.SEED, 6, (C,), np.float64) * 0.1).astype(np.float32)
+    dyph = synth.activations(4, (N, S // 2, S // 2, S // 2, C), "bf16")
+    x, w1, w2, dyp = to_dev(xh, "bf16"), to_dev(w1h, "bf16"), to_dev(w2h, "bf16"), to_dev(dyph, "bf16")
+    b1, b2 = torch.from_numpy(b1h).cuda(), torch.from_numpy(b2h).cuda()
+    pk1 = torch.empty(k3.conv3d_packed_bytes(C, C, k3.BF16), device="cuda", dtype=torch.uint8)
+    pk2 = torch.empty_like(pk1)
+    k3.conv3d_pack_weights(w1, pk1)
+    k3.conv3d_pack_weights(w2, pk2)
+    a1, a2, da2, da1, dx = (torch.full_like(x, float("nan")) for _ in range(5))
+    p = torch.empty_like(dyp)
+    dW1, dW2 = torch.empty((3, 3, 3, C, C), device="cuda"), torch.empty((3, 3, 3, C, C), device="cuda")
+    db1, db2 = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
+    ws = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(x, a1), device="cuda", dtype=torch.uint8)
+    k3.conv3d_fwd(x, w1, pk1, b1, 1, a1)
+    k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2)
+    k3.pool3d_fwd(a2, p)
+    k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True)
+    k3.conv3d_bwd_weight(a1, da2, None, dW2, db2, ws)
+    k3.conv3d_bwd_data(da2, None, w2, pk2, da1, dx_mask=a1)
+    k3.conv3d_bwd_weight(x, da1, None, dW1, db1, ws)
+    k3.conv3d_bwd_data(da1, None, w1, pk1, dx)
+    torch.cuda.synchronize()
+    for t in (a1, a2, da2, da1, dx):
+        assert torch.isfinite(t.float()).all()
+
+    pts = sample_points(N, S, S, S, 3000, 11)
+    X, W1, W2 = xh.astype(np.float64), w1h.astype(np.float64), w2h.astype(np.float64)
+    A1, A2, DA2, DA1 = host64(a1), host64(a2), host64(da2), host64(da1)
+    # forward convs on the GPU's own inputs: one bf16 rounding of an fp32 sum
+    e = rel(gather(a1, pts), orc.conv3d_fwd_points(X, W1, b1h.astype(np.float64), True, pts))
+    assert e < 4e-3, e
+    e = rel(gather(a2, pts), orc.conv3d_fwd_points(A1, W2, b2h.astype(np.float64), True, pts))
+    assert e < 4e-3, e
+    # pool forward and pool backward with the ReLU mask of a2: compare-only, exact
+    assert np.array_equal(host64(p), orc.pool3d_fwd(A2))
+    assert np.array_equal(DA2, orc.relu_bwd(orc.pool3d_bwd(A2, dyph.astype(np.float64)), A2))
+    # backward-data of conv2, masked by a1 at the producer
+    ref = orc.conv3d_fwd_points(DA2, flip_transpose(W2), None, False, pts) * (gather(a1, pts) > 0)
+    e = rel(gather(da1, pts), ref)
+    assert e < 4e-3, e
+    ref = orc.conv3d_fwd_points(DA1, flip_transpose(W1), None, False, pts)
+    e = rel(gather(dx, pts), ref)
+    assert e < 4e-3, e
+    # weight gradients: sampled entries with the full voxel sum, bias gradients in full
+    ent = wgrad_entries(C, C, 160, 12)
+    got2 = host64(dW2).reshape(27, C, C)[ent[:, 0], ent[:, 1], ent[:, 2]]
+    assert rel(got2, orc.conv3d_bwd_weight_entries(A1, DA2, ent)) < 1e-5
+    got1 = host64(dW1).reshape(27, C, C)[ent[:, 0], ent[:, 1], ent[:, 2]]
+    assert rel(got1, orc.conv3d_bwd_weight_entries(X, DA1, ent)) < 1e-5
+    assert rel(host64(db2), DA2.reshape(-1, C).sum(axis=0)) < 1e-5
+    assert rel(host64(db1), DA1.reshape(-1, C).sum(axis=0)) < 1e-5
+
+
+# (N, D, H, W, c1, c2, cout): U-Net layer shapes, several tiles per compute unit, ragged edges
+BIG_CASES = [
+    (1, 64, 72, 140, 64, 0, 64),     # encoder conv2 (two output blocks per workgroup), ragged in w
+    (2, 44, 64, 64, 64, 64, 64),     # decoder conv1: two sources / two destinations, ragged depth
+    (1, 64, 64, 64, 128, 0, 128),    # deeper level: four channel blocks, two channel groups
+    (1, 66, 70, 72, 64, 0, 32),      # one output block per workgroup, ragged everywhere
+]
+
+
+@pytest.mark.parametrize("case", BIG_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_unet_sized_layers_sampled(orc, case):
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, packed_for
+    N, D, H, W, c1, c2, co = case
+    cin = c1 + c2
+    xh = synth.activations(50, (N, D, H, W, c1), "bf16")
+    x2h = synth.activations(51, (N, D, H, W, c2), "bf16") if c2 else None
+    wh = synth.conv_weights(52, cin, co, "bf16")
+    bh = (synth.normal(synth.SEED, 53, (co,), np.float64) * 0.3).astype(np.float32)
+    gh = synth.activations(54, (N, D, H, W, co), "bf16")
+    mh = synth.activations(55, (N, D, H, W, c1), "bf16")
+    mh[mh < 0.2] = 0.0
+    x, wd, g, m = to_dev(xh, "bf16"), to_dev(wh, "bf16"), to_dev(gh, "bf16"), to_dev(mh, "bf16")
+    x2 = to_dev(x2h, "bf16") if c2 else None
+    b = torch.from_numpy(bh).cuda()
+    pk = packed_for(wd)
+    pts = sample_points(N, D, H, W, 1500, 21)
+    X = xh.astype(np.float64) if not c2 else np.concatenate([xh, x2h], axis=-1).astype(np.float64)
+    Wt, G = wh.astype(np.float64), gh.astype(np.float64)
+
+    y = torch.full((N, D, H, W, co), float("nan"), device="cuda", dtype=torch.bfloat16)
+    k3.conv3d_fwd(x, wd, pk, b, 1, y, x2=x2)
+    torch.cuda.synchronize()
+    assert torch.isfinite(y.float()).all()
+    e = rel(gather(y, pts), orc.conv3d_fwd_points(X, Wt, bh.astype(np.float64), True, pts))
+    assert e < 4e-3, e
+
+    dx = torch.full((N, D, H, W, c1), float("nan"), device="cuda", dtype=torch.bfloat16)
+    dx2 = torch.full((N, D, H, W, c2), float("nan"), device="cuda", dtype=torch.bfloat16) if c2 else None
+    k3.conv3d_bwd_data(g, None, wd, pk, dx, dx2=dx2, dx_mask=m)
+    torch.cuda.synchronize()
+    ref = orc.conv3d_fwd_points(G, flip_transpose(Wt), None, False, pts)
+    ref[:, :c1] *= gather(m, pts) > 0
+    got = gather(dx, pts) if not c2 else np.concatenate([gather(dx, pts), gather(dx2, pts)], axis=1)
+    assert np.isfinite(got).all()
+    e = rel(got, ref)
+    assert e < 4e-3, e
+
+    dW = torch.full((3, 3, 3, cin, co), float("nan"), device="cuda")
+    db = torch.full((co,), float("nan"), device="cuda")
+    ws = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(x, g, x2=x2), device="cuda", dtype=torch.uint8)
+    k3.conv3d_bwd_weight(x, g, None, dW, db, ws, x2=x2)
+    torch.cuda.synchronize()
+    assert torch.isfinite(dW).all()
+    ent = wgrad_entries(cin, co, 60, 22)
+    got = host64(dW).reshape(27, cin, co)[ent[:, 0], ent[:, 1], ent[:, 2]]
+    assert rel(got, orc.conv3d_bwd_weight_entries(X, G, ent)) < 1e-5
+    assert rel(host64(db), G.reshape(-1, co).sum(axis=0)) < 1e-5
