@@ -129,9 +129,11 @@ def bench_cfg2(args):
         k3.conv3d_bwd_data(da2, None, w2, pk2, da1, dx_mask=a1)
         k3.conv3d_bwd_data(da1, None, w1, pk1, dx)
     mfma_ms = time_calls(mix, it) / 4.0
-    share = {"conv_mfma_kernel": 4 * mfma_ms, "conv_wgrad_mfma_kernel": 2 * kern["conv3d_bwd_weight"]}
+    # (the weight-gradient call is two launches: the MFMA kernel and the small split-K reduction)
+    wgrad_ms = kern["conv3d_bwd_weight"]
+    share = {"conv_mfma_pipe_kernel": 4 * mfma_ms, "conv_wgrad_pipe_kernel": 2 * wgrad_ms}
     dominant = max(share, key=share.get)
-    dom_ms = mfma_ms if dominant == "conv_mfma_kernel" else kern["conv3d_bwd_weight"]
+    dom_ms = mfma_ms if dominant == "conv_mfma_pipe_kernel" else wgrad_ms
     achieved = f1 / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),
@@ -180,14 +182,93 @@ def cpu_baseline_cfg2(step_flops):
 
 
 def load_traffic(kernel, workload):
-    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE); null when not recorded."""
+    """HBM bytes per launch (fetched + written) measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE and
+    scaled by the same counters on a copy kernel of known size; null when not recorded."""
     path = os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as f:
             t = json.load(f)
-        return t.get(workload, {}).get(kernel)
+        rec = t.get(workload, {}).get(kernel)
+        return None if rec is None else rec.get("bytes_per_launch")
     except (OSError, ValueError):
         return None
+
+
+# ----------------------------------------------------------------------------- HBM traffic counters
+def pmc_pass(args):
+    """Workload for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: a device copy of known size (the
+    calibration of the counter) followed by a few launches of every cfg2 call."""
+    import torch
+    import synth
+    from paper_1811_12174_amd import k3
+    N, S, C = 1, 64, 32
+    bf = torch.bfloat16
+    src = torch.ones(64 << 20, device="cuda", dtype=torch.float32)   # 256 MiB read + 256 MiB written
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        torch.add(src, 1.0, out=dst)   # a plain elementwise kernel: reads 256 MiB, writes 256 MiB
+    x = torch.from_numpy(synth.activations(1, (N, S, S, S, C), "bf16")).cuda().to(bf)
+    w = torch.from_numpy(synth.conv_weights(2, C, C, "bf16")).cuda().to(bf)
+    dyp = torch.from_numpy(synth.activations(4, (N, S // 2, S // 2, S // 2, C), "bf16")).cuda().to(bf)
+    b = torch.zeros(C, device="cuda")
+    pk = torch.empty(k3.conv3d_packed_bytes(C, C, k3.BF16), device="cuda", dtype=torch.uint8)
+    k3.conv3d_pack_weights(w, pk)
+    a1, a2, da2, da1 = (torch.empty_like(x) for _ in range(4))
+    p = torch.empty_like(dyp)
+    dW, db = torch.empty((3, 3, 3, C, C), device="cuda"), torch.empty(C, device="cuda")
+    ws = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(x, a1), device="cuda", dtype=torch.uint8)
+    for _ in range(3):
+        k3.conv3d_fwd(x, w, pk, b, 1, a1)
+        k3.conv3d_fwd(a1, w, pk, b, 1, a2)
+        k3.pool3d_fwd(a2, p)
+        k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True)
+        k3.conv3d_bwd_weight(a1, da2, None, dW, db, ws)
+        k3.conv3d_bwd_data(da2, None, w, pk, da1, dx_mask=a1)
+    torch.cuda.synchronize()
+    print(json.dumps({"pmc_pass": "done", "copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4}))
+
+
+def pmc_parse(fetch_csv, write_csv):
+    """Turns the two counter_collection.csv files of the pmc passes into profiles/traffic.json."""
+    import csv
+    import collections
+
+    def per_kernel(path, counter):
+        acc, cnt = collections.defaultdict(float), collections.Counter()
+        with open(path) as f:
+            for r in csv.DictReader(f):
+                if r["Counter_Name"] != counter:
+                    continue
+                acc[r["Kernel_Name"]] += float(r["Counter_Value"])
+                cnt[r["Kernel_Name"]] += 1
+        return {k: acc[k] / cnt[k] for k in acc}
+
+    fetch, write = per_kernel(fetch_csv, "FETCH_SIZE"), per_kernel(write_csv, "WRITE_SIZE")
+    copy = sorted((k for k in fetch if "elementwise" in k), key=lambda k: -fetch[k])[:1]   # the 256 MiB one
+    if not copy:
+        raise SystemExit("no copy kernel found in the counter files")
+    known = float(64 << 20) * 4
+    f_scale = known / (fetch[copy[0]] * 1024.0)    # counters are in KiB per dispatch
+    w_scale = known / (write[copy[0]] * 1024.0)
+    out = {"_calibration": {"copy_kernel": copy[0], "known_bytes_each_way": known,
+                            "fetch_counter_kib": fetch[copy[0]], "write_counter_kib": write[copy[0]],
+                            "fetch_scale": f_scale, "write_scale": w_scale}, "cfg2": {}}
+    for k in fetch:
+        if "k3::" not in k:
+            continue
+        short = k.split("k3::")[1].split("<")[0].split("(")[0]
+        fb, wb = fetch[k] * 1024.0 * f_scale, write.get(k, 0.0) * 1024.0 * w_scale
+        rec = out["cfg2"].setdefault(short, {"variants": {}})
+        rec["variants"][k] = {"fetch_bytes": round(fb), "write_bytes": round(wb)}
+    for short, rec in out["cfg2"].items():
+        v = list(rec["variants"].values())
+        rec["fetch_bytes"] = round(sum(x["fetch_bytes"] for x in v) / len(v))
+        rec["write_bytes"] = round(sum(x["write_bytes"] for x in v) / len(v))
+        rec["bytes_per_launch"] = rec["fetch_bytes"] + rec["write_bytes"]
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    with open(path, "w") as f:
+        json.dump(out, f, indent=1, sort_keys=True)
+    print("wrote", path)
 
 
 # ----------------------------------------------------------------------------- U-Net steps
@@ -260,7 +341,13 @@ def main():
     ap.add_argument("--with-unet", action="store_true", help="also time the full U-Net steps (cfg3, and cfg4 with swapping)")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-pass", action="store_true", help="run the short workload the HBM-traffic counters are collected on")
+    ap.add_argument("--pmc-parse", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
+                    help="write profiles/traffic.json from the counter files of two --pmc-pass runs")
     args = ap.parse_args()
+    if args.pmc_parse:
+        pmc_parse(*args.pmc_parse)
+        return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the paper's multi-GPU all-reduce is out of scope); use --gpus 1",
               file=sys.stderr)
@@ -271,6 +358,9 @@ def main():
         sys.exit(1)
     from paper_1811_12174_amd import k3
     k3.lib()
+    if args.pmc_pass:
+        pmc_pass(args)
+        return
     if args.workload == "cfg2":
         out = bench_cfg2(args)
         if args.with_unet:
