@@ -123,6 +123,128 @@ __global__ __launch_bounds__(256) void head_kernel(const T *__restrict__ a, cons
     }
 }
 
+// Streaming variant for bf16 activations whose channel count is a multiple of 16 (the U-Net
+// levels): LPV = C / 16 neighbouring lanes share a voxel, 16 channels (32 bytes) each, so a wave
+// reads and writes whole contiguous 2 KB runs and nothing goes through LDS.  The lanes of a
+// voxel add their partial logits with xor-shuffles, every lane then forms the softmax terms,
+// its 16 values of da, and its share of dWh in 48 register accumulators.  Workgroup partials
+// are merged in a fixed order.
+template <int LPV>
+__global__ __launch_bounds__(256) void head_stream_kernel(const bf16_t *__restrict__ a, const float *__restrict__ wh,
+                                                         const float *__restrict__ bh,
+                                                         const uint8_t *__restrict__ labels, bf16_t *__restrict__ da,
+                                                         float *__restrict__ logits, float *__restrict__ partial,
+                                                         int64_t V, float invV, int relu_mask)
+{
+    constexpr int C = 16 * LPV;
+    constexpr int VPB = 256 / LPV;   // voxels per workgroup and step
+    __shared__ float red[256 * 49];
+    const int tid = threadIdx.x, sub = tid % LPV;
+    float w0[16], w1[16], w2[16], g0[16], g1[16], g2[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        w0[i] = wh[(sub * 16 + i) * 3 + 0];
+        w1[i] = wh[(sub * 16 + i) * 3 + 1];
+        w2[i] = wh[(sub * 16 + i) * 3 + 2];
+        g0[i] = g1[i] = g2[i] = 0.f;
+    }
+    const float b0 = bh ? bh[0] : 0.f, b1 = bh ? bh[1] : 0.f, b2 = bh ? bh[2] : 0.f;
+    float lossacc = 0.f, db0 = 0.f, db1 = 0.f, db2 = 0.f;
+    const int64_t nstep = (V + VPB - 1) / VPB;
+    for (int64_t st = blockIdx.x; st < nstep; st += gridDim.x) {
+        const int64_t v = st * VPB + tid / LPV;
+        const bool on = v < V;
+        const int64_t vv = on ? v : V - 1;
+        const uint4 *src = reinterpret_cast<const uint4 *>(a + vv * C + sub * 16);
+        const uint4 r0 = src[0], r1 = src[1];
+        const uint32_t raw[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+        float av[16];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            av[2 * i] = __uint_as_float(raw[i] << 16);
+            av[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
+        }
+        float z0 = 0.f, z1 = 0.f, z2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            z0 += av[i] * w0[i];
+            z1 += av[i] * w1[i];
+            z2 += av[i] * w2[i];
+        }
+#pragma unroll
+        for (int m = 1; m < LPV; m <<= 1) {   // fixed pairing: the same sum in every lane of the voxel
+            z0 += __shfl_xor(z0, m);
+            z1 += __shfl_xor(z1, m);
+            z2 += __shfl_xor(z2, m);
+        }
+        z0 += b0; z1 += b1; z2 += b2;
+        const int lab = labels[vv];
+        const float mx = fmaxf(z0, fmaxf(z1, z2));
+        const float e0 = expf(z0 - mx), e1 = expf(z1 - mx), e2 = expf(z2 - mx);
+        const float den = e0 + e1 + e2, inv = 1.f / den;
+        const float zl = lab == 0 ? z0 : (lab == 1 ? z1 : z2);
+        float d0 = (e0 * inv - (lab == 0 ? 1.f : 0.f)) * invV;
+        float d1 = (e1 * inv - (lab == 1 ? 1.f : 0.f)) * invV;
+        float d2 = (e2 * inv - (lab == 2 ? 1.f : 0.f)) * invV;
+        if (!on) d0 = d1 = d2 = 0.f;
+        if (on && sub == 0) {
+            lossacc += (mx - zl) + logf(den);
+            db0 += d0; db1 += d1; db2 += d2;
+            if (logits) {
+                float *lp = logits + v * 3;
+                lp[0] = z0; lp[1] = z1; lp[2] = z2;
+            }
+        }
+        uint32_t o[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            float x0 = d0 * w0[2 * i] + d1 * w1[2 * i] + d2 * w2[2 * i];
+            float x1 = d0 * w0[2 * i + 1] + d1 * w1[2 * i + 1] + d2 * w2[2 * i + 1];
+            if (relu_mask && !(av[2 * i] > 0.f)) x0 = 0.f;
+            if (relu_mask && !(av[2 * i + 1] > 0.f)) x1 = 0.f;
+            o[i] = pack2bf(x0, x1);
+        }
+        if (on) {
+            uint4 *dst = reinterpret_cast<uint4 *>(da + v * C + sub * 16);
+            dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
+            dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
+        }
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            g0[i] += av[i] * d0;
+            g1[i] += av[i] * d1;
+            g2[i] += av[i] * d2;
+        }
+    }
+    // workgroup partials [C*3 dWh][3 dbh][1 loss]: thread values to LDS, then fixed-order column sums
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        red[tid * 49 + i * 3 + 0] = g0[i];
+        red[tid * 49 + i * 3 + 1] = g1[i];
+        red[tid * 49 + i * 3 + 2] = g2[i];
+    }
+    red[tid * 49 + 48] = 0.f;
+    __syncthreads();
+    float *out = partial + (int64_t)blockIdx.x * (C * 3 + 4);
+    for (int e = tid; e < C * 3; e += 256) {
+        const int c = e / 3, k = e - c * 3, sb = c / 16, i = c - sb * 16;
+        float s = 0.f;
+        for (int t = sb; t < 256; t += LPV) s += red[t * 49 + i * 3 + k];
+        out[e] = s;
+    }
+    const float sc[4] = {db0, db1, db2, lossacc};
+    for (int k = 0; k < 4; ++k) {
+        __syncthreads();
+        red[tid] = sc[k];
+        __syncthreads();
+        if (tid == 0) {
+            float s = 0.f;
+            for (int t = 0; t < 256; ++t) s += red[t];
+            out[C * 3 + k] = s;
+        }
+    }
+}
+
 __global__ __launch_bounds__(256) void head_reduce_kernel(const float *__restrict__ partial, int nblocks, int C,
                                                          float invV, float *__restrict__ dWh, float *__restrict__ dbh,
                                                          float *__restrict__ loss)
@@ -172,7 +294,19 @@ extern "C" int k3_head_softmax_ce_fwd_bwd(const k3_tensor *ad, const void *a, co
     size_t es = esize(ad->dtype);
     size_t lds = 2 * (size_t)HB * (C * es + 4) + HB * 4 * sizeof(float) + 256 * sizeof(float);
     if (lds > 160 * 1024) return K3_E_UNSUPPORTED;
-    if (ad->dtype == K3_BF16) {
+    if (ad->dtype == K3_BF16 && (C == 16 || C == 32 || C == 64 || C == 128 || C == 256)) {
+        const bf16_t *ap = (const bf16_t *)a;
+        bf16_t *dp = (bf16_t *)da;
+        float *pw = (float *)ws;
+        const int rm = relu_mask ? 1 : 0;
+        switch (C / 16) {
+        case 1: head_stream_kernel<1><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm); break;
+        case 2: head_stream_kernel<2><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm); break;
+        case 4: head_stream_kernel<4><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm); break;
+        case 8: head_stream_kernel<8><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm); break;
+        default: head_stream_kernel<16><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm); break;
+        }
+    } else if (ad->dtype == K3_BF16) {
         K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&head_kernel<bf16_t>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
         head_kernel<bf16_t><<<nb, 256, lds, st>>>((const bf16_t *)a, wh, bh, labels, (bf16_t *)da, logits, (float *)ws, V, C, invV, relu_mask ? 1 : 0);

@@ -112,7 +112,8 @@ def test_upconv_all_passes(orc, sp, ci, co, dt):
 
 # ------------------------------------------------------------------ head
 @pytest.mark.parametrize("sp,C,dt", [((1, 8, 8, 8), 32, "bf16"), ((2, 5, 7, 9), 64, "bf16"), ((1, 4, 4, 4), 8, "f32"),
-                                     ((1, 3, 3, 3), 2, "bf16"), ((1, 16, 16, 17), 32, "bf16")])
+                                     ((1, 3, 3, 3), 2, "bf16"), ((1, 16, 16, 17), 32, "bf16"), ((1, 7, 9, 11), 16, "bf16"),
+                                     ((2, 6, 5, 9), 128, "bf16"), ((1, 33, 30, 31), 64, "bf16")])
 def test_head(orc, sp, C, dt):
     import torch
     from paper_1811_12174_amd import k3
