@@ -102,6 +102,118 @@ __global__ __launch_bounds__(256) void up_fwd_mfma_kernel(const bf16_t *__restri
     }
 }
 
+// ------------------------------------------------------------------ MFMA forward, weights in LDS
+// The op is HBM-bound (it writes 8 output voxels per input voxel), so the kernel must not
+// spend its memory pipe on weights: a persistent workgroup copies the packed weights of its
+// COBG output blocks (8 taps x COBG x NKC fragments of 1 KB) into LDS once and then streams
+// blocks of 128 input voxels.  A wave holds the NKC B fragments of its 32 voxels in registers
+// (loaded with 16-byte accesses that together cover the voxels' contiguous rows) and, per
+// (tap, output block), runs NKC MFMAs against LDS-resident A fragments, adds the bias and
+// stores 32 bytes per lane.
+template <int NKC, int COBG>
+__global__ __launch_bounds__(256) void up_fwd_lds_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ packed,
+                                                        const float *__restrict__ bias, bf16_t *__restrict__ y,
+                                                        int64_t V, int D, int H, int W, int cout)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int cin = NKC * 16;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int hb = lane >> 5, vl = lane & 31;
+    const int cob0 = blockIdx.y * COBG, ncob = cout / 32;
+    {   // weights of this workgroup's output blocks: LDS [tap][cb][kc][lane] x 16 bytes
+        const uint4 *src = reinterpret_cast<const uint4 *>(packed);
+        uint4 *dst = reinterpret_cast<uint4 *>(smem);
+        for (int i = threadIdx.x; i < 8 * COBG * NKC * 64; i += 256) {
+            const int ln = i & 63, kc = (i >> 6) % NKC, cb = (i / (64 * NKC)) % COBG, t = i / (64 * NKC * COBG);
+            dst[i] = src[(((int64_t)t * ncob + cob0 + cb) * NKC + kc) * 64 + ln];
+        }
+    }
+    __syncthreads();
+    float bv[COBG][16];
+#pragma unroll
+    for (int cb = 0; cb < COBG; ++cb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) bv[cb][i] = bias ? bias[(cob0 + cb) * 32 + hb * 16 + i] : 0.f;
+    const int64_t nblk = (V + 127) / 128;
+    for (int64_t blk = blockIdx.x; blk < nblk; blk += gridDim.x) {
+        const int64_t v = blk * 128 + wv * 32 + vl;
+        const bool live = v < V;
+        const uint4 *xp = reinterpret_cast<const uint4 *>(x + (live ? v : 0) * cin + hb * 8);
+        bf16x8 b[NKC];
+#pragma unroll
+        for (int kc = 0; kc < NKC; ++kc) {
+            uint4 raw = xp[kc * 2];
+            if (!live) raw = make_uint4(0, 0, 0, 0);
+            b[kc] = __builtin_bit_cast(bf16x8, raw);
+        }
+        const int64_t vv = live ? v : 0;
+        const int w = (int)(vv % W);
+        const int h = (int)((vv / W) % H);
+        const int d = (int)((vv / ((int64_t)W * H)) % D);
+        const int64_t n = vv / ((int64_t)W * H * D);
+        const int64_t o0 = ((n * 2 * D + 2 * d) * 2 * H + 2 * h) * (2 * (int64_t)W) + 2 * w;   // output voxel of tap 0
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            const int64_t o = o0 + ((int64_t)(t >> 2) * 2 * H + ((t >> 1) & 1)) * (2 * (int64_t)W) + (t & 1);
+#pragma unroll
+            for (int cb = 0; cb < COBG; ++cb) {
+                f32x16 acc;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] = bv[cb][i];
+                const bf16x8 *ap = reinterpret_cast<const bf16x8 *>(smem) + ((t * COBG + cb) * NKC) * 64 + lane;
+#pragma unroll
+                for (int kc = 0; kc < NKC; ++kc) acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ap[kc * 64], b[kc], acc, 0, 0, 0);
+                if (live) {
+                    uint4 *dst = reinterpret_cast<uint4 *>(y + o * cout + (cob0 + cb) * 32 + hb * 16);
+                    dst[0] = make_uint4(pack2bf(acc[0], acc[1]), pack2bf(acc[2], acc[3]), pack2bf(acc[4], acc[5]),
+                                        pack2bf(acc[6], acc[7]));
+                    dst[1] = make_uint4(pack2bf(acc[8], acc[9]), pack2bf(acc[10], acc[11]), pack2bf(acc[12], acc[13]),
+                                        pack2bf(acc[14], acc[15]));
+                }
+            }
+        }
+    }
+}
+
+template <int NKC, int COBG>
+static int launch_up_fwd_lds(const bf16_t *x, const bf16_t *packed, const float *bias, bf16_t *y, int64_t V, int D, int H,
+                             int W, int cout, hipStream_t st)
+{
+    constexpr int lds = 8 * COBG * NKC * 1024;
+    static_assert(lds <= 160 * 1024, "LDS budget");
+    static bool attr_done = false;
+    if (!attr_done) {
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&up_fwd_lds_kernel<NKC, COBG>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        attr_done = true;
+    }
+    const int ncog = cout / 32 / COBG;
+    int64_t nblk = (V + 127) / 128;
+    int64_t gx = 512 / ncog;   // about two workgroups' worth of blocks per CU in total
+    if (gx < 1) gx = 1;
+    if (gx > nblk) gx = nblk;
+    up_fwd_lds_kernel<NKC, COBG><<<dim3((unsigned)gx, (unsigned)ncog), 256, lds, st>>>(x, packed, bias, y, V, D, H, W, cout);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
+// returns K3_E_UNSUPPORTED when the shape has no LDS-resident variant (the caller falls back)
+static int up_fwd_lds_dispatch(const bf16_t *x, const bf16_t *packed, const float *bias, bf16_t *y, int64_t V, int D, int H,
+                               int W, int cin, int cout, hipStream_t st)
+{
+    const bool two = (cout / 32) % 2 == 0;
+    switch (cin) {
+    case 32: return two ? launch_up_fwd_lds<2, 2>(x, packed, bias, y, V, D, H, W, cout, st)
+                        : launch_up_fwd_lds<2, 1>(x, packed, bias, y, V, D, H, W, cout, st);
+    case 64: return two ? launch_up_fwd_lds<4, 2>(x, packed, bias, y, V, D, H, W, cout, st)
+                        : launch_up_fwd_lds<4, 1>(x, packed, bias, y, V, D, H, W, cout, st);
+    case 128: return two ? launch_up_fwd_lds<8, 2>(x, packed, bias, y, V, D, H, W, cout, st)
+                         : launch_up_fwd_lds<8, 1>(x, packed, bias, y, V, D, H, W, cout, st);
+    case 256: return launch_up_fwd_lds<16, 1>(x, packed, bias, y, V, D, H, W, cout, st);
+    default: return K3_E_UNSUPPORTED;
+    }
+}
+
 __device__ __forceinline__ uint32_t up_mask_pair(uint32_t v, uint32_t m)
 {
     // keep each bf16 half of v where the matching half of m is > 0 (sign clear and nonzero)
@@ -456,6 +568,9 @@ int k3_upconv3d_fwd(const k3_tensor *xd, const void *x, const void *w, const voi
         if (!packed) return K3_E_BADARG;
         int64_t blocks = (V + 127) / 128;
         if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+        rc = up_fwd_lds_dispatch((const bf16_t *)x, (const bf16_t *)packed, bias, (bf16_t *)y, V, (int)xd->d, (int)xd->h,
+                                 (int)xd->w, cin, cout, st);
+        if (rc != K3_E_UNSUPPORTED) return rc;
         up_fwd_mfma_kernel<<<dim3((unsigned)blocks, (unsigned)(cout / 32)), 256, 0, st>>>(
             (const bf16_t *)x, (const bf16_t *)packed, bias, (bf16_t *)y, V, (int)xd->d, (int)xd->h, (int)xd->w, cin, cout);
         K3_LAUNCH_CHECK();

@@ -55,7 +55,8 @@ def test_pool_odd_dim_is_rejected():
 
 # ------------------------------------------------------------------ upconv
 UP_CASES = [((1, 3, 4, 5), 3, 5, "f32"), ((2, 2, 2, 2), 8, 4, "bf16"), ((1, 4, 4, 8), 64, 32, "bf16"),
-            ((2, 5, 3, 7), 32, 32, "bf16"), ((1, 6, 5, 9), 128, 64, "bf16"), ((1, 2, 2, 2), 256, 128, "bf16")]
+            ((2, 5, 3, 7), 32, 32, "bf16"), ((1, 6, 5, 9), 128, 64, "bf16"), ((1, 2, 2, 2), 256, 128, "bf16"),
+            ((1, 12, 10, 22), 64, 64, "bf16"), ((2, 9, 8, 8), 128, 32, "bf16"), ((1, 2, 2, 3), 512, 256, "bf16")]
 
 
 def _up_packed(w):
