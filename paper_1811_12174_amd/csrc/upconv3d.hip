@@ -281,16 +281,39 @@ __global__ __launch_bounds__(256) void up_dgrad_mfma_kernel(const bf16_t *__rest
 }
 
 // ------------------------------------------------------------------ MFMA backward-weight
-// Workgroup: one 32-channel block of x, one 32-channel block of dy, a strided set of
-// 4x4x8 input-voxel tiles (8x8x16 output voxels).  Wave wv owns taps (i,j) = (wv/2, wv%2),
-// k = 0,1.  K-step s covers input voxels (d = s/2, h = 2*(s%2) + lane half, w = 0..7).
+// dW[t][ci][co] = sum_v x[v][ci] * dy[2v + t][co]: the contraction runs over input voxels and
+// dy is the large tensor (8 voxels per input voxel), so the pass is HBM-bound and every byte
+// of dy should be fetched once.  A persistent workgroup owns CIBG 32-channel blocks of x and
+// COBG blocks of dy -- the whole weight gradient when C_in <= 128 and C_out <= 64 -- and a
+// contiguous range of 2x2x8 input-voxel tiles (4x4x16 output voxels).  Tiles move from global
+// memory into a ring of three LDS stages with asynchronous copies, two tiles ahead of the one
+// being multiplied.  Wave wv owns the taps (i, j) = (wv / 2, wv % 2), k = 0, 1, for all
+// channel blocks: 2 * CIBG * COBG accumulator blocks.  The operands (8 consecutive voxels of
+// one channel per lane) come from transposing LDS reads.  The bias gradient is summed on the
+// vector ALU from the dy fragments the wave reads anyway.  Partials per split are added in a
+// fixed order by reduce_partials_kernel.
 namespace uw {
-constexpr int TD = 4, TH = 4, TW = 8;
-constexpr int NVOX = TD * TH * TW;            // 128 input voxels
-constexpr int XS_BYTES = NVOX * 64;           // 8 KB
-constexpr int GS_BYTES = NVOX * 8 * 64;       // 64 KB: [2TD][2TH][2TW][32 ch]
-constexpr int LDS_BYTES = XS_BYTES + GS_BYTES + 4 * 32 * 4;
+constexpr int TD = 2, TH = 2, TW = 8;
+constexpr int NVOX = TD * TH * TW;            // 32 input voxels = 2 K-steps
+constexpr int XB = NVOX * 64;                 // one 32-channel block of the x tile
+constexpr int GB = NVOX * 8 * 64;             // one 32-channel block of the dy tile
+constexpr int NST = 3;                        // ring of stages: one in use, two incoming
+constexpr int xk(int cibg) { return (cibg * 2 + 3) / 4; }   // copies per wave: x groups (1 KB each)
+constexpr int gk(int cobg) { return cobg * 4; }             // dy groups
+constexpr int stage_bytes(int cibg, int cobg) { return cibg * XB + cobg * GB; }
+constexpr int lds_bytes(int cibg, int cobg) { return NST * stage_bytes(cibg, cobg) + 1024 + 4 * 64 * 4; }
 }  // namespace uw
+
+struct UpWgradParams {
+    const bf16_t *x, *dy;
+    float *ws;
+    int64_t per_split;
+    int N, D, H, W, cin, cout;
+    int ntd, nth, ntw;
+    int ntiles, nsplit, tbase, trem;   // split s owns tiles [s*tbase + min(s, trem), ...)
+};
+
+static __device__ uint4 g_uzero[4];   // zero-initialised: source of every out-of-volume item
 
 __device__ __forceinline__ bf16x8 up_tr_pair(const unsigned char *base, int off0, int off1)
 {
@@ -302,87 +325,165 @@ __device__ __forceinline__ bf16x8 up_tr_pair(const unsigned char *base, int off0
     return __builtin_bit_cast(bf16x8, v);
 }
 
-__global__ __launch_bounds__(256) void up_wgrad_mfma_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy,
-                                                           float *__restrict__ ws, int64_t per_split, int N, int D,
-                                                           int H, int W, int cin, int cout, int ntd, int nth, int ntw,
-                                                           int64_t ntiles, int nsplit)
+template <int CIBG, int COBG>
+__global__ __launch_bounds__(256, 1) void up_wgrad_pipe_kernel(UpWgradParams p)
 {
     using namespace uw;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
-    unsigned char *xs = smem;
-    unsigned char *gs = smem + XS_BYTES;
-    float *dbs = reinterpret_cast<float *>(smem + XS_BYTES + GS_BYTES);
-    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    const int hb = lane >> 5, blk = lane >> 4, j = lane & 15;
-    const int cib = blockIdx.y, cob = blockIdx.z;
+    constexpr int STB = stage_bytes(CIBG, COBG);
+    constexpr int XK = xk(CIBG), GK = gk(COBG), OPS = XK + GK;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hb = lane >> 5, g16 = (lane >> 4) & 1, j = lane & 15;
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const unsigned dump = lds0 + NST * STB;
+    float *dbs = reinterpret_cast<float *>(smem + NST * STB + 1024);   // [4 waves][COBG * 32]
+    const unsigned char *zero = reinterpret_cast<const unsigned char *>(g_uzero);
+    const int split = blockIdx.x, cig = blockIdx.y, cog = blockIdx.z;
     const int ti = wv >> 1, tj = wv & 1;
-    const int lane_x = (hb * TW + (j >> 2)) * 64 + (blk & 1) * 32 + (j & 3) * 8;
-    // dy tile voxel (2d+ti, 2h+tj, 2w+k), h = 2*(s%2)+hb, w = 4r + j/4
-    const int lane_g = (((ti * 2 * TH) + 2 * hb + tj) * (2 * TW) + 2 * (j >> 2)) * 64 + (blk & 1) * 32 + (j & 3) * 8;
-    f32x16 acc[2], accb;
-#pragma unroll
-    for (int i = 0; i < 16; ++i) acc[0][i] = acc[1][i] = accb[i] = 0.f;
-    bf16x8 ones;
-#pragma unroll
-    for (int i = 0; i < 8; ++i) ones[i] = (__bf16)1.0f;
+    const int D2 = 2 * p.D, H2 = 2 * p.H, W2 = 2 * p.W;
 
-    for (int64_t tile = blockIdx.x; tile < ntiles; tile += nsplit) {
-        int64_t q = tile;
-        const int twi = (int)(q % ntw);
-        q /= ntw;
-        const int thi = (int)(q % nth);
-        q /= nth;
-        const int tdi = (int)(q % ntd);
-        const int n = (int)(q / ntd);
-        const int d0 = tdi * TD, h0 = thi * TH, w0 = twi * TW;
-        __syncthreads();
-        for (int i = tid; i < NVOX * 4; i += 256) {
-            int vox = i >> 2, part = i & 3;
-            int lw = vox % TW, lh = (vox / TW) % TH, ld = vox / (TW * TH);
-            int gd = d0 + ld, gh = h0 + lh, gw = w0 + lw;
-            uint4 val = make_uint4(0, 0, 0, 0);
-            if (gd < D && gh < H && gw < W)
-                val = *reinterpret_cast<const uint4 *>(x + ((((int64_t)n * D + gd) * H + gh) * W + gw) * cin + cib * 32 + part * 8);
-            *reinterpret_cast<uint4 *>(xs + vox * 64 + part * 16) = val;
-        }
-        for (int i = tid; i < NVOX * 8 * 4; i += 256) {
-            int vox = i >> 2, part = i & 3;
-            int lw = vox % (2 * TW), lh = (vox / (2 * TW)) % (2 * TH), ld = vox / (4 * TW * TH);
-            int gd = 2 * d0 + ld, gh = 2 * h0 + lh, gw = 2 * w0 + lw;
-            uint4 val = make_uint4(0, 0, 0, 0);
-            if (gd < 2 * D && gh < 2 * H && gw < 2 * W)
-                val = *reinterpret_cast<const uint4 *>(dy + ((((int64_t)n * 2 * D + gd) * 2 * H + gh) * 2 * W + gw) * cout + cob * 32 + part * 8);
-            *reinterpret_cast<uint4 *>(gs + vox * 64 + part * 16) = val;
-        }
-        __syncthreads();
+    // ---- per-lane copy items.  x stage layout [cib][vox 32][32 ch], dy [cob][vox 256][32 ch]
+    int xoff[XK], xco[XK];
+    unsigned xsl = 0;
 #pragma unroll
-        for (int s = 0; s < NVOX / 16; ++s) {
-            const int sx = (((s >> 1) * TH + 2 * (s & 1)) * TW) * 64;
-            const int sg = (((2 * (s >> 1)) * (2 * TH) + 4 * (s & 1)) * (2 * TW)) * 64;
-            bf16x8 ax = up_tr_pair(xs, lane_x + sx, lane_x + sx + 4 * 64);
-#pragma unroll
-            for (int k = 0; k < 2; ++k) {
-                bf16x8 bg = up_tr_pair(gs, lane_g + sg + k * 64, lane_g + sg + k * 64 + 8 * 64);
-                acc[k] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax, bg, acc[k], 0, 0, 0);
-                accb = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, bg, accb, 0, 0, 0);
-            }
-        }
+    for (int k = 0; k < XK; ++k) {
+        const int slot = (wv + 4 * k) * 64 + lane;
+        const int cib = slot >> 7, vox = (slot >> 2) & 31, part = slot & 3;
+        const int ld = vox >> 4, lh = (vox >> 3) & 1, lw = vox & 7;
+        xoff[k] = ((ld * p.H + lh) * p.W + lw) * p.cin * 2 + ((cig * CIBG + cib) * 32) * 2 + part * 16;
+        xco[k] = ld | (lh << 8) | (lw << 16);
+        xsl |= ((wv + 4 * k < CIBG * 2) ? 1u : 0u) << k;
     }
-    float *out = ws + (int64_t)blockIdx.x * per_split;
-    const int co = cob * 32 + (lane & 31);
+    int goff[GK], gco[GK];
+#pragma unroll
+    for (int k = 0; k < GK; ++k) {
+        const int slot = (wv + 4 * k) * 64 + lane;
+        const int cob = slot >> 10, vox = (slot >> 2) & 255, part = slot & 3;
+        const int ld = vox >> 6, lh = (vox >> 4) & 3, lw = vox & 15;
+        goff[k] = ((ld * H2 + lh) * W2 + lw) * p.cout * 2 + ((cog * COBG + cob) * 32) * 2 + part * 16;
+        gco[k] = ld | (lh << 8) | (lw << 16);
+    }
+    // ---- lane-constant parts of the transposing-read addresses (K-step 0, first block)
+    const int lane_x = (hb * TW + (j >> 2)) * 64 + g16 * 32 + (j & 3) * 8;
+    const int lane_g = CIBG * XB + ((ti * 4 + 2 * hb + tj) * 16 + 2 * (j >> 2)) * 64 + g16 * 32 + (j & 3) * 8;
+
+    f32x16 acc[2][CIBG][COBG];
+#pragma unroll
+    for (int k = 0; k < 2; ++k)
+#pragma unroll
+        for (int a = 0; a < CIBG; ++a)
+#pragma unroll
+            for (int b = 0; b < COBG; ++b)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[k][a][b][i] = 0.f;
+    float dbacc[COBG];
+#pragma unroll
+    for (int b = 0; b < COBG; ++b) dbacc[b] = 0.f;
+
+    const int t0 = split * p.tbase + (split < p.trem ? split : p.trem);
+    const int nt = p.tbase + (split < p.trem ? 1 : 0);
+
+    auto issue = [&](int tile, int buf, bool on) __attribute__((always_inline)) {
+        unsigned q = (unsigned)(on ? tile : 0);
+        const int twi = (int)(q % (unsigned)p.ntw);
+        q /= (unsigned)p.ntw;
+        const int thi = (int)(q % (unsigned)p.nth);
+        q /= (unsigned)p.nth;
+        const int tdi = (int)(q % (unsigned)p.ntd);
+        const int n = (int)(q / (unsigned)p.ntd);
+        const int d0 = tdi * TD, h0 = thi * TH, w0 = twi * TW;
+        const unsigned char *xb = reinterpret_cast<const unsigned char *>(
+            p.x + ((((int64_t)n * p.D + d0) * p.H + h0) * p.W + w0) * p.cin);
+        const unsigned char *gb = reinterpret_cast<const unsigned char *>(
+            p.dy + ((((int64_t)n * D2 + 2 * d0) * H2 + 2 * h0) * W2 + 2 * w0) * p.cout);
+        const unsigned sb = lds0 + buf * STB;
+#pragma unroll
+        for (int k = 0; k < XK; ++k) {
+            const int ld = xco[k] & 255, lh = (xco[k] >> 8) & 255, lw = xco[k] >> 16;
+            const bool grp = on && ((xsl >> k) & 1);
+            const bool in = grp && d0 + ld < p.D && h0 + lh < p.H && w0 + lw < p.W;
+            dma16(grp ? sb + (wv + 4 * k) * 1024 : dump, in ? xb + xoff[k] : zero);
+        }
+#pragma unroll
+        for (int k = 0; k < GK; ++k) {
+            const int ld = gco[k] & 255, lh = (gco[k] >> 8) & 255, lw = gco[k] >> 16;
+            const bool in = on && 2 * d0 + ld < D2 && 2 * h0 + lh < H2 && 2 * w0 + lw < W2;
+            dma16(on ? sb + CIBG * XB + (wv + 4 * k) * 1024 : dump, in ? gb + goff[k] : zero);
+        }
+    };
+
+    // prologue: the first two tiles; afterwards stage i fetches tile i + 2
+    issue(t0, 0, nt > 0);
+    issue(t0 + 1, 1, nt > 1);
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(OPS) : "memory");
+    __syncthreads();
+    int buf = 0;
+    for (int i = 0; i < nt; ++i) {
+        {
+            int nb = buf + 2;
+            if (nb >= NST) nb -= NST;
+            issue(t0 + i + 2, nb, i + 2 < nt);
+        }
+        const unsigned char *st = smem + buf * STB;
+#pragma unroll
+        for (int s = 0; s < 2; ++s) {   // K-step s: input voxels (d = s, h = hb, w = 0..7)
+            bf16x8 ax[CIBG], bg[2][COBG];
+#pragma unroll
+            for (int a = 0; a < CIBG; ++a) {
+                const int o = a * XB + lane_x + s * (TH * TW * 64);
+                ax[a] = up_tr_pair(st, o, o + 4 * 64);
+            }
+#pragma unroll
+            for (int k = 0; k < 2; ++k)
+#pragma unroll
+                for (int b = 0; b < COBG; ++b) {
+                    const int o = b * GB + lane_g + s * (2 * 64 * 64) + k * 64;
+                    bg[k][b] = up_tr_pair(st, o, o + 8 * 64);
+                }
+#pragma unroll
+            for (int k = 0; k < 2; ++k)
+#pragma unroll
+                for (int b = 0; b < COBG; ++b) {
+#pragma unroll
+                    for (int a = 0; a < CIBG; ++a)
+                        acc[k][a][b] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax[a], bg[k][b], acc[k][a][b], 0, 0, 0);
+                    float sum = 0.f;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) sum += (float)bg[k][b][e];
+                    dbacc[b] += sum;
+                }
+        }
+        asm volatile("s_waitcnt vmcnt(%0)" ::"n"(OPS) : "memory");
+        __syncthreads();
+        if (++buf == NST) buf = 0;
+    }
+
+    float *out = p.ws + (int64_t)split * p.per_split;
 #pragma unroll
     for (int k = 0; k < 2; ++k) {
         const int tap = (ti * 2 + tj) * 2 + k;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-            int ci = cib * 32 + (i >> 2) * 8 + hb * 4 + (i & 3);
-            out[((int64_t)tap * cin + ci) * cout + co] = acc[k][i];
-        }
+        for (int a = 0; a < CIBG; ++a)
+#pragma unroll
+            for (int b = 0; b < COBG; ++b) {
+                const int co = (cog * COBG + b) * 32 + (lane & 31);
+                float *o = out + ((int64_t)tap * p.cin + (cig * CIBG + a) * 32 + hb * 4) * p.cout + co;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) o[((i >> 2) * 8 + (i & 3)) * p.cout] = acc[k][a][b][i];
+            }
     }
-    if (cib == 0) {  // bias gradient: add the four waves' tap sums in a fixed order
-        if (hb == 0) dbs[wv * 32 + lane] = accb[0];
+    if (cig == 0) {   // bias gradient: lane halves, then the four waves, in a fixed order
+#pragma unroll
+        for (int b = 0; b < COBG; ++b) {
+            const float other = __shfl_xor(dbacc[b], 32);
+            if (hb == 0) dbs[wv * (COBG * 32) + b * 32 + lane] = dbacc[b] + other;
+        }
         __syncthreads();
-        if (tid < 32) out[(int64_t)8 * cin * cout + cob * 32 + tid] = ((dbs[tid] + dbs[32 + tid]) + dbs[64 + tid]) + dbs[96 + tid];
+        if (tid < COBG * 32) {
+            const int n32 = COBG * 32;
+            out[(int64_t)8 * p.cin * p.cout + cog * n32 + tid] = ((dbs[tid] + dbs[n32 + tid]) + dbs[2 * n32 + tid]) + dbs[3 * n32 + tid];
+        }
     }
 }
 
@@ -506,14 +607,33 @@ static int64_t up_direct_nsplit(int64_t V)
 }
 
 static void up_wgrad_plan(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout, int64_t *ntiles,
-                          int *nsplit)
+                          int *nsplit, int *cibg, int *cobg)
 {
     *ntiles = N * ((D + uw::TD - 1) / uw::TD) * ((H + uw::TH - 1) / uw::TH) * ((W + uw::TW - 1) / uw::TW);
-    int64_t yz = (cin / 32) * (cout / 32);
-    int64_t s = 1024 / yz;
+    const int64_t nci = cin / 32, nco = cout / 32;
+    *cibg = nci % 4 == 0 ? 4 : (nci % 2 == 0 ? 2 : 1);
+    *cobg = nco % 2 == 0 ? 2 : 1;
+    int64_t yz = (nci / *cibg) * (nco / *cobg);
+    int64_t s = 256 / yz;   // one persistent workgroup per CU in total
     if (s < 1) s = 1;
     if (s > *ntiles) s = *ntiles;
     *nsplit = (int)s;
+}
+
+template <int CIBG, int COBG>
+static int launch_up_wgrad(const UpWgradParams &p, dim3 grid, hipStream_t st)
+{
+    constexpr int lds = uw::lds_bytes(CIBG, COBG);
+    static_assert(lds <= 160 * 1024, "LDS budget");
+    static bool attr_done = false;
+    if (!attr_done) {
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&up_wgrad_pipe_kernel<CIBG, COBG>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        attr_done = true;
+    }
+    up_wgrad_pipe_kernel<CIBG, COBG><<<grid, 256, lds, st>>>(p);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
 }
 
 }  // namespace k3
@@ -635,8 +755,8 @@ int k3_upconv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor 
     int64_t per = 8 * cin * cout + cout;
     if (up_mfma_ok(xd->dtype, cin, cout)) {
         int64_t ntiles;
-        int nsplit;
-        up_wgrad_plan(xd->n, xd->d, xd->h, xd->w, cin, cout, &ntiles, &nsplit);
+        int nsplit, cibg, cobg;
+        up_wgrad_plan(xd->n, xd->d, xd->h, xd->w, cin, cout, &ntiles, &nsplit, &cibg, &cobg);
         *bytes = (size_t)nsplit * per * sizeof(float);
     } else {
         *bytes = (size_t)up_direct_nsplit(voxels(xd)) * per * sizeof(float);
@@ -659,18 +779,25 @@ int k3_upconv3d_bwd_weight(const k3_tensor *xd, const void *x, const k3_tensor *
     int64_t per = (int64_t)8 * cin * cout + cout;
     if (up_mfma_ok(xd->dtype, cin, cout)) {
         int64_t ntiles;
-        int nsplit;
-        up_wgrad_plan(xd->n, D, H, W, cin, cout, &ntiles, &nsplit);
-        static bool attr_done = false;
-        if (!attr_done) {
-            K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&up_wgrad_mfma_kernel),
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, uw::LDS_BYTES));
-            attr_done = true;
-        }
-        up_wgrad_mfma_kernel<<<dim3((unsigned)nsplit, (unsigned)(cin / 32), (unsigned)(cout / 32)), 256, uw::LDS_BYTES, st>>>(
-            (const bf16_t *)x, (const bf16_t *)dy, (float *)ws, per, (int)xd->n, D, H, W, cin, cout,
-            (D + uw::TD - 1) / uw::TD, (H + uw::TH - 1) / uw::TH, (W + uw::TW - 1) / uw::TW, ntiles, nsplit);
-        K3_LAUNCH_CHECK();
+        int nsplit, cibg, cobg;
+        up_wgrad_plan(xd->n, D, H, W, cin, cout, &ntiles, &nsplit, &cibg, &cobg);
+        // 32-bit byte offsets inside a tile and 32-bit tile counts
+        if (ntiles > 0x3fffffffLL || (int64_t)4 * (2 * H) * (2 * W) * cout * 2 > 0x7fffffffLL ||
+            (int64_t)2 * H * W * cin * 2 > 0x7fffffffLL)
+            return K3_E_UNSUPPORTED;
+        UpWgradParams p{};
+        p.x = (const bf16_t *)x; p.dy = (const bf16_t *)dy; p.ws = (float *)ws; p.per_split = per;
+        p.N = (int)xd->n; p.D = D; p.H = H; p.W = W; p.cin = cin; p.cout = cout;
+        p.ntd = (D + uw::TD - 1) / uw::TD; p.nth = (H + uw::TH - 1) / uw::TH; p.ntw = (W + uw::TW - 1) / uw::TW;
+        p.ntiles = (int)ntiles; p.nsplit = nsplit; p.tbase = p.ntiles / nsplit; p.trem = p.ntiles % nsplit;
+        dim3 grid((unsigned)nsplit, (unsigned)(cin / 32 / cibg), (unsigned)(cout / 32 / cobg));
+        if (cibg == 4 && cobg == 2) rc = launch_up_wgrad<4, 2>(p, grid, st);
+        else if (cibg == 4) rc = launch_up_wgrad<4, 1>(p, grid, st);
+        else if (cibg == 2 && cobg == 2) rc = launch_up_wgrad<2, 2>(p, grid, st);
+        else if (cibg == 2) rc = launch_up_wgrad<2, 1>(p, grid, st);
+        else if (cobg == 2) rc = launch_up_wgrad<1, 2>(p, grid, st);
+        else rc = launch_up_wgrad<1, 1>(p, grid, st);
+        if (rc != K3_OK) return rc;
         return launch_reduce_partials((const float *)ws, dW, db, (int64_t)8 * cin * cout, per, nsplit, st);
     }
     int64_t nsplit = up_direct_nsplit(V);
