@@ -675,17 +675,22 @@ static int launch_cfg(MfmaParams p, int64_t mblocks, hipStream_t st)
 static int launch_mfma(MfmaParams p, int64_t mchannels, hipStream_t st)
 {
     int64_t mblocks = mchannels / 32;
-    // Large problems: the pipelined one-workgroup-per-CU kernel on 8x8x16 tiles, when that still
-    // gives every CU work; small volumes keep the 8x8x8 tiles (more, smaller workgroups).
+    // The pipelined one-workgroup-per-CU kernel: 8x8x16 tiles when they give every CU a tile,
+    // else 4x8x8 tiles (the deep, small-volume levels of the network), taking one output block
+    // per workgroup where two would leave CUs without work.
     {
-        typedef PipeCfg<8, 8, 16, 2> P2;
-        typedef PipeCfg<8, 8, 16, 1> P1;
-        int64_t tiles = (int64_t)p.N * ((p.D + 7) / 8) * ((p.H + 7) / 8) * ((p.W + 15) / 16);
-        // the halo tile's voxel offsets are kept in 32 bits
         const int cmax = p.cd1 > p.cd2 ? p.cd1 : p.cd2;
+        // the halo tile's voxel offsets and the per-lane output offsets are kept in 32 bits
         const bool fits = (int64_t)10 * p.H * p.W * (cmax > 1 ? cmax : 1) < 0x7fffffffLL && p.cd1 + p.cd2 <= 1024;
-        if (!p.mask && fits && mblocks % 2 == 0 && tiles * (mblocks / 2) >= 256) return launch_pipe<P2>(p, mblocks, st);
-        if (!p.mask && fits && mblocks % 2 == 1 && tiles * mblocks >= 256) return launch_pipe<P1>(p, mblocks, st);
+        if (!p.mask && fits) {
+            const int64_t big = (int64_t)p.N * ((p.D + 7) / 8) * ((p.H + 7) / 8) * ((p.W + 15) / 16);
+            const int64_t small = (int64_t)p.N * ((p.D + 3) / 4) * ((p.H + 7) / 8) * ((p.W + 7) / 8);
+            const bool even = mblocks % 2 == 0;
+            if (even && big * (mblocks / 2) >= 256) return launch_pipe<PipeCfg<8, 8, 16, 2>>(p, mblocks, st);
+            if (!even && big * mblocks >= 256) return launch_pipe<PipeCfg<8, 8, 16, 1>>(p, mblocks, st);
+            if (even && small * (mblocks / 2) >= 192) return launch_pipe<PipeCfg<4, 8, 8, 2>>(p, mblocks, st);
+            if (small * mblocks >= 48) return launch_pipe<PipeCfg<4, 8, 8, 1>>(p, mblocks, st);
+        }
     }
     if (mblocks % 2 == 0) return launch_cfg<TileCfg<8, 8, 8, 2, 9>>(p, mblocks, st);
     return launch_cfg<TileCfg<8, 8, 8, 1, 27>>(p, mblocks, st);

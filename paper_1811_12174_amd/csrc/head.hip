@@ -245,17 +245,27 @@ __global__ __launch_bounds__(256) void head_stream_kernel(const bf16_t *__restri
     }
 }
 
+// One block per output element (C*3 weight gradients, 3 bias gradients, the loss): its 256
+// threads add the workgroup partials in a fixed strided order, then a fixed tree.
 __global__ __launch_bounds__(256) void head_reduce_kernel(const float *__restrict__ partial, int nblocks, int C,
                                                          float invV, float *__restrict__ dWh, float *__restrict__ dbh,
                                                          float *__restrict__ loss)
 {
-    int cnt = C * 3 + 4;
-    for (int i = threadIdx.x; i < cnt; i += 256) {
-        float s = 0.f;
-        for (int b = 0; b < nblocks; ++b) s += partial[(int64_t)b * cnt + i];
-        if (i < C * 3) { if (dWh) dWh[i] = s; }
-        else if (i < C * 3 + 3) { if (dbh) dbh[i - C * 3] = s; }
-        else *loss = s * invV;
+    __shared__ float red[256];
+    const int cnt = C * 3 + 4, i = blockIdx.x, tid = threadIdx.x;
+    float s = 0.f;
+    for (int b = tid; b < nblocks; b += 256) s += partial[(int64_t)b * cnt + i];
+    red[tid] = s;
+    __syncthreads();
+    for (int h = 128; h > 0; h >>= 1) {
+        if (tid < h) red[tid] += red[tid + h];
+        __syncthreads();
+    }
+    if (tid == 0) {
+        const float r = red[0];
+        if (i < C * 3) { if (dWh) dWh[i] = r; }
+        else if (i < C * 3 + 3) { if (dbh) dbh[i - C * 3] = r; }
+        else *loss = r * invV;
     }
 }
 
@@ -316,7 +326,7 @@ extern "C" int k3_head_softmax_ce_fwd_bwd(const k3_tensor *ad, const void *a, co
         head_kernel<float><<<nb, 256, lds, st>>>((const float *)a, wh, bh, labels, (float *)da, logits, (float *)ws, V, C, invV, relu_mask ? 1 : 0);
     }
     K3_LAUNCH_CHECK();
-    head_reduce_kernel<<<1, 256, 0, st>>>((const float *)ws, nb, C, invV, dWh, dbh, loss);
+    head_reduce_kernel<<<C * 3 + 4, 256, 0, st>>>((const float *)ws, nb, C, invV, dWh, dbh, loss);
     K3_LAUNCH_CHECK();
     return K3_OK;
 }

@@ -137,6 +137,9 @@ BIG_CASES = [
     (2, 44, 64, 64, 64, 64, 64),     # decoder conv1: two sources / two destinations, ragged depth
     (1, 64, 64, 64, 128, 0, 128),    # deeper level: four channel blocks, two channel groups
     (1, 66, 70, 72, 64, 0, 32),      # one output block per workgroup, ragged everywhere
+    (1, 32, 32, 32, 128, 0, 128),    # deep level: 4x8x8 tiles, two output blocks per workgroup
+    (1, 16, 16, 16, 256, 0, 256),    # bottleneck: 4x8x8 tiles, one output block per workgroup
+    (1, 14, 20, 28, 64, 64, 128),    # 4x8x8 tiles, two sources / destinations, ragged
 ]
 
 
