@@ -327,15 +327,15 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
         PipeTile t;
         const int64_t logical = (vb & 7) * p.per_xcd + (vb >> 3);
         t.valid = (vb >> 3) < p.per_xcd && logical < p.total;
-        int64_t tile = t.valid ? logical : 0;
-        const int cg = (int)(tile % p.ncg);
-        tile /= p.ncg;
-        const int twi = (int)(tile % p.ntw);
-        tile /= p.ntw;
-        const int thi = (int)(tile % p.nth);
-        tile /= p.nth;
-        const int tdi = (int)(tile % p.ntd);
-        t.n = (int)(tile / p.ntd);
+        unsigned tile = t.valid ? (unsigned)logical : 0u;   // the tile count fits 31 bits (checked at launch)
+        const int cg = (int)(tile % (unsigned)p.ncg);
+        tile /= (unsigned)p.ncg;
+        const int twi = (int)(tile % (unsigned)p.ntw);
+        tile /= (unsigned)p.ntw;
+        const int thi = (int)(tile % (unsigned)p.nth);
+        tile /= (unsigned)p.nth;
+        const int tdi = (int)(tile % (unsigned)p.ntd);
+        t.n = (int)(tile / (unsigned)p.ntd);
         t.d0 = tdi * C::TD; t.h0 = thi * C::TH; t.w0 = twi * C::TW;
         t.mb0 = cg * C::MB;
         t.origin = (((int64_t)t.n * p.D + t.d0) * p.H + t.h0) * p.W + t.w0;
@@ -425,17 +425,9 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
     };
     // voxel offset of the lane's voxel inside a patch from the patch's first voxel
     const int lvox = lrow * p.W + lcol;
-    // the bias vector lives in LDS for the whole kernel (zeros when there is none)
-    {
-        float *bl = reinterpret_cast<float *>(smem + C::BIAS_OFF);
-        const int nco = p.cd1 + p.cd2;
-        for (int i = tid; i < nco; i += 256) bl[i] = p.bias ? p.bias[i] : 0.f;
-    }
-
     PipeTile cur = decode(blockIdx.x);
     if (!cur.valid) return;
     int64_t vb_next = (int64_t)blockIdx.x + gridDim.x;
-    PipeTile nxt = decode(vb_next);
 
     // ---- prologue: chunk 0 of the first tile and the weights of its stage (0, 0)
     {
@@ -452,6 +444,14 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             }
         }
     }
+    // while the first copies are in flight: the bias vector goes to LDS for the whole kernel
+    // (zeros when there is none), and the next tile is decoded
+    {
+        float *bl = reinterpret_cast<float *>(smem + C::BIAS_OFF);
+        const int nco = p.cd1 + p.cd2;
+        for (int i = tid; i < nco; i += 256) bl[i] = p.bias ? p.bias[i] : 0.f;
+    }
+    PipeTile nxt = decode(vb_next);
     asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __syncthreads();
 
@@ -616,7 +616,18 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
         }
         stage(nkc - 1, std::integral_constant<int, 0>(), std::false_type());
         stage(nkc - 1, std::integral_constant<int, 1>(), std::false_type());
-        stage(nkc - 1, std::integral_constant<int, 2>(), std::true_type());
+        if constexpr (!OMASK) {
+            stage(nkc - 1, std::integral_constant<int, 2>(), std::true_type());
+        } else {
+            // With an output mask the blocks are finished after the stage instead: their mask
+            // loads then wait for nothing but themselves (inside the stage every wait on a load
+            // would also wait for the copies in flight) and are all issued together.
+            stage(nkc - 1, std::integral_constant<int, 2>(), std::false_type());
+#pragma unroll
+            for (int nb = 0; nb < C::NBW; ++nb)
+#pragma unroll
+                for (int mb = 0; mb < C::MB; ++mb) emit(nb, mb);
+        }
         xpar ^= 1;
         if (!nxt.valid) break;
         cur = nxt;
