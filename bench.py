@@ -8,9 +8,11 @@ backward).  A step is one pass of that block; the step is captured in a HIP grap
 ~10 kernel launches are not bound by host launch latency.  The headline value is the
 exact (in-bounds) convolution FLOPs of the step divided by the step time.
 
-Other workloads: "unet128" (full 4-level U-Net, base 32, 1 x 128^3, no swapping) and
+Other workloads: "unet128" (full 4-level U-Net, base 32, 1 x 128^3, no swapping),
 "unet256" (base 64, 2 x 256^3, every encoder activation swapped to pinned host memory and
-prefetched back); they report voxels/s, swap bandwidth and overlap in the "unet" object.
+prefetched back) and "unet320" (base 64, 4 x 320^3); they report voxels/s and the swap
+traffic in the "unet" object.  With --budget-gb the U-Net step is also run under a
+device-memory limit, without swapping (expected to run out of memory) and with it.
 
 Prints ONE JSON line on stdout.
 """
@@ -287,7 +289,7 @@ def unet_flops(base, levels, n, size):
     return total
 
 
-def bench_unet(args, base, size, n, swap, label):
+def bench_unet(args, base, size, n, swap, label, budget_gb=0.0):
     import numpy as np
     import torch
     import synth
@@ -327,6 +329,43 @@ def bench_unet(args, base, size, n, swap, label):
                     "swap_overhead_pct": round(100 * (t_swap / t_noswap - 1), 2),
                     "swap_bytes_per_direction_per_step": int(moved),
                     "copy_seconds_at_link_peak": round(moved / 57e9, 4)})
+    if budget_gb:
+        # The situation the paper's LMS exists for: a device-memory limit below what the step
+        # needs without swapping.  The limit is enforced by the allocator for every allocation.
+        total = torch.cuda.get_device_properties(0).total_memory
+        res["device_budget_gb"] = budget_gb
+        net.reset()
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()
+        torch.cuda.set_per_process_memory_fraction(min(1.0, budget_gb * 1e9 / total))
+        try:
+            try:
+                net.step(x, lab, swap=False)
+                torch.cuda.synchronize()
+                res["no_swap_under_budget"] = "completed"
+            except torch.cuda.OutOfMemoryError:
+                res["no_swap_under_budget"] = "out of memory"
+            net.reset()
+            torch.cuda.synchronize()
+            torch.cuda.empty_cache()
+            try:
+                net.step(x, lab, swap=True)
+                torch.cuda.synchronize()
+                net.stall_count, net.stall_seconds = 0, 0.0
+                t0 = time.perf_counter()
+                for _ in range(steps):
+                    net.step(x, lab, swap=True)
+                torch.cuda.synchronize()
+                k3.lms_sync(net.lms)
+                dt = (time.perf_counter() - t0) / steps
+                res.update({"swap_under_budget": "completed", "ms_per_step_swap_under_budget": round(dt * 1e3, 3),
+                            "voxels_per_s_swap_under_budget": round(V / dt, 1),
+                            "allocations_that_waited_per_step": net.stall_count / steps,
+                            "wait_seconds_per_step": round(net.stall_seconds / steps, 4)})
+            except torch.cuda.OutOfMemoryError:
+                res["swap_under_budget"] = "out of memory"
+        finally:
+            torch.cuda.set_per_process_memory_fraction(1.0)
     net.close()
     return res
 
@@ -336,7 +375,9 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "unet128", "unet256"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "unet128", "unet256", "unet320"])
+    ap.add_argument("--budget-gb", type=float, default=0.0,
+                    help="U-Net workloads: also run under this device-memory limit, without and with swapping")
     ap.add_argument("--unet-steps", type=int, default=3)
     ap.add_argument("--with-unet", action="store_true", help="also time the full U-Net steps (cfg3, and cfg4 with swapping)")
     ap.add_argument("--no-graph", action="store_true")
@@ -369,8 +410,12 @@ def main():
     else:
         if args.workload == "unet128":
             u = bench_unet(args, 32, 128, 1, False, "cfg3: U-Net base 32, 1 x 128^3, no swapping")
+        elif args.workload == "unet256":
+            u = bench_unet(args, 64, 256, 2, True, "cfg4: U-Net base 64, 2 x 256^3, encoder activations swapped",
+                           budget_gb=args.budget_gb)
         else:
-            u = bench_unet(args, 64, 256, 2, True, "cfg4: U-Net base 64, 2 x 256^3, encoder activations swapped")
+            u = bench_unet(args, 64, 320, 4, True, "cfg5: U-Net base 64, 4 x 320^3, encoder activations swapped",
+                           budget_gb=args.budget_gb)
         key = "voxels_per_s_swap" if "voxels_per_s_swap" in u else "voxels_per_s_no_swap"
         ms = u.get("ms_per_step_swap", u["ms_per_step_no_swap"])
         out = {"metric": "U-Net step voxels/s", "value": u[key], "unit": "voxels/s", "n_gpus": 1, "steps": u["steps"],

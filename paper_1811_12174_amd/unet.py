@@ -14,7 +14,15 @@ device-to-host copy stream as soon as their last forward reader is enqueued, and
 back on the host-to-device stream ahead of their backward (or skip-connection) consumer.
 Device copies of swapped tensors are dropped lazily, when the copy is seen to be complete,
 so the compute stream never waits for an outgoing copy.
+
+Under a device-memory limit (the situation the paper's LMS exists for: the stored
+activations do not fit) an allocation that fails makes the harness wait for the oldest
+outgoing copy, drop that tensor's device copy and try again -- the step then runs at the
+pace of the host link instead of failing.  Without swapping the same limit ends the step
+with an out-of-memory error.
 """
+import time
+
 import torch
 
 from . import k3
@@ -61,6 +69,7 @@ class UNet3D:
         self.lms = None
         self.loss = torch.zeros(1, device=device, dtype=torch.float32)
         self.last_stats = {}
+        self.stall_count, self.stall_seconds = 0, 0.0   # allocations that had to wait for an outgoing copy
 
     # ------------------------------------------------------------------ parameters
     def repack(self):
@@ -92,9 +101,18 @@ class UNet3D:
             self._ws = torch.empty(max(nbytes, 1 << 20), device=self.dev, dtype=torch.uint8)
         return self._ws
 
+    def _empty(self, shape):
+        """Device tensor; when the allocator is out of memory, reclaim swapped-out tensors and retry."""
+        while True:
+            try:
+                return torch.empty(tuple(shape), device=self.dev, dtype=self.dtype)
+            except torch.cuda.OutOfMemoryError:
+                if not self._reclaim():
+                    raise
+
     def _new(self, like_shape, c):
         n, d, h, w, _ = like_shape
-        return torch.empty((n, d, h, w, c), device=self.dev, dtype=self.dtype)
+        return self._empty((n, d, h, w, c))
 
     def _conv(self, name, x, x2=None, relu=True):
         y = self._new(x.shape, self.w[name].shape[4])
@@ -112,8 +130,8 @@ class UNet3D:
         k3.conv3d_bwd_weight(x, g, None, self.gw[name], self.gb[name], ws, x2=x2)
         if not need_dx:
             return None, None
-        dx = torch.empty_like(x)
-        dx2 = torch.empty_like(x2) if x2 is not None else None
+        dx = self._empty(x.shape)
+        dx2 = self._empty(x2.shape) if x2 is not None else None
         k3.conv3d_bwd_data(g, None, self.w[name], self.pk[name], dx, dx2=dx2, dx_mask=dx_mask)
         return dx, dx2
 
@@ -145,13 +163,34 @@ class UNet3D:
                 s.out_pending = False
                 s.t = None
 
+    def _reclaim(self):
+        """Free device memory held by tensors that are on their way to the host: drop every copy
+        that has completed, else block on the oldest outgoing copy.  False when nothing can be freed."""
+        if self.lms is None:
+            return False
+        pending = [s for s in self._slots.values() if s.out_pending]
+        if not pending:
+            return False
+        self.stall_count += 1
+        t0 = time.perf_counter()
+        while True:
+            done = [s for s in pending if k3.lms_swap_out_done(self.lms, s.handle)]
+            if done:
+                break
+            time.sleep(0.0002)
+        for s in done:
+            s.out_pending = False
+            s.t = None
+        self.stall_seconds += time.perf_counter() - t0
+        return True
+
     def _prefetch(self, name):
         """Start bringing a swapped tensor back (no-op while it is still on the device)."""
         s = self._slots[name]
         if s.t is not None or self.lms is None:
             s.out_pending = False
             return
-        s.t = torch.empty(s.shape, device=self.dev, dtype=self.dtype)
+        s.t = self._empty(s.shape)
         k3.lms_prefetch_in(self.lms, s.handle, s.t.data_ptr())
 
     def _get(self, name):
@@ -165,6 +204,16 @@ class UNet3D:
         if s.handle is not None and self.lms is not None:
             k3.lms_release(self.lms, s.handle)
         s.handle, s.t, s.out_pending = None, None, False
+
+    def reset(self):
+        """Drop every stored activation and swap handle (after a step that ended in an error)."""
+        if self.lms is not None:
+            k3.lms_sync(self.lms)
+        for s in self._slots.values():
+            if s.handle is not None and self.lms is not None:
+                k3.lms_release(self.lms, s.handle)
+            s.handle, s.t, s.out_pending = None, None, False
+        self._ws = None
 
     def close(self):
         for s in self._slots.values():
@@ -207,8 +256,7 @@ class UNet3D:
                 else:
                     self._slot(f"a1_{l}").t = a1
                 if l < L - 1:
-                    pooled = torch.empty((a2.shape[0], a2.shape[1] // 2, a2.shape[2] // 2, a2.shape[3] // 2, a2.shape[4]),
-                                         device=self.dev, dtype=self.dtype)
+                    pooled = self._empty((a2.shape[0], a2.shape[1] // 2, a2.shape[2] // 2, a2.shape[3] // 2, a2.shape[4]))
                     k3.pool3d_fwd(a2, pooled)
                     self._swap_out(f"a2_{l}", a2)
                     nxt = pooled
@@ -230,8 +278,7 @@ class UNet3D:
                 if l >= 1:
                     self._prefetch(f"a2_{l - 1}")   # one level ahead of its skip-connection reader
                 name = f"dec{l}.up"
-                up = torch.empty((cur.shape[0], cur.shape[1] * 2, cur.shape[2] * 2, cur.shape[3] * 2, self.w[name].shape[4]),
-                                 device=self.dev, dtype=self.dtype)
+                up = self._empty((cur.shape[0], cur.shape[1] * 2, cur.shape[2] * 2, cur.shape[3] * 2, self.w[name].shape[4]))
                 k3.upconv3d_fwd(cur, self.w[name], self.pk[name], self.b[name], up)
                 skip = self._get(f"a2_{l}")
                 a1 = self._conv(f"dec{l}.conv1", skip, x2=up)
@@ -239,7 +286,9 @@ class UNet3D:
                 self._slot(f"dbelow{l}").t = cur
                 self._slot(f"dup{l}").t = up
                 self._slot(f"da1_{l}").t = a1
-                self._slot(f"da2_{l}").t = a2
+                # a2 is kept only as the input of the next transposed conv (slot dbelow) or of the
+                # head: its own backward needs the gradient mask only, which the producer of that
+                # gradient applies
                 if keep_acts:
                     acts[f"dec{l}.up"], acts[f"dec{l}.a1"], acts[f"dec{l}.a2"] = up, a1, a2
                 del up, a1, skip, cur
@@ -247,7 +296,7 @@ class UNet3D:
                 del a2
                 self._poll()
             # ---------------- head: loss and the gradient of the last activation
-            d = torch.empty_like(cur)
+            d = self._empty(cur.shape)
             ws = self._workspace(k3.head_workspace_bytes(cur))
             k3.head_softmax_ce_fwd_bwd(cur, self.w["head"], self.b["head"], labels, self.loss, d,
                                        self.gw["head"], self.gb["head"], None, ws, relu_mask=True)
@@ -270,27 +319,28 @@ class UNet3D:
                             issued.add(nm)
                 kind, l = stage
                 if kind == "dec":
-                    a2, a1 = self._slots[f"da2_{l}"].t, self._slots[f"da1_{l}"].t
+                    a1 = self._slots[f"da1_{l}"].t
                     up, below = self._slots[f"dup{l}"].t, self._slots[f"dbelow{l}"].t
                     skip = self._get(f"a2_{l}")
                     # d already carries the ReLU mask of a2 (applied by its producer)
                     d1, _ = self._conv_bwd(f"dec{l}.conv2", a1, None, d, dx_mask=a1)
-                    del d
+                    del d, a1
+                    self._slots[f"da1_{l}"].t = None   # not read again: free it before the next allocations
                     dskip, dup = self._conv_bwd(f"dec{l}.conv1", skip, up, d1)
                     del d1
                     skip_grad[l] = dskip
                     name = f"dec{l}.up"
                     ws = self._workspace(k3.upconv3d_bwd_weight_workspace_bytes(below, dup))
                     k3.upconv3d_bwd_weight(below, dup, self.gw[name], self.gb[name], ws)
-                    d = torch.empty_like(below)
+                    d = self._empty(below.shape)
                     k3.upconv3d_bwd_data(dup, self.w[name], self.pk[name], d, dx_mask=below)
-                    del dup, dskip, a2, a1, up, below, skip
-                    for nm in (f"da2_{l}", f"da1_{l}", f"dup{l}", f"dbelow{l}"):
+                    del dup, dskip, up, below, skip
+                    for nm in (f"da1_{l}", f"dup{l}", f"dbelow{l}"):
                         self._slots[nm].t = None
                 else:
                     a2 = self._get(f"a2_{l}")
                     if l < L - 1:
-                        dd = torch.empty_like(a2)
+                        dd = self._empty(a2.shape)
                         k3.pool3d_bwd(a2, d, skip_grad.pop(l), dd, relu_mask=True)
                         d = dd
                         del dd

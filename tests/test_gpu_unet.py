@@ -104,3 +104,62 @@ def test_swapping_is_bit_identical(base, levels, size):
     assert st["bytes_out"] == 2 * per_step_out, (st, per_step_out)
     assert st["live_handles"] == 0
     net.close()
+
+
+def test_step_under_a_device_memory_limit():
+    """The paper's LMS situation: with a device-memory limit below what the step needs without
+    swapping, the step without swapping runs out of memory, and the step with swapping completes
+    (allocations wait for outgoing copies) with exactly the same loss and gradients."""
+    import gc
+    import torch
+    from gpu_util import to_dev
+    base, levels, size = 32, 4, 128   # workload config 3: tensors large against the allocator's granularity
+    net, loss0, params, x, lab = _run(base, levels, size, 1, "bf16")
+    g0 = {k: v.clone() for k, v in net.grads().items()}
+    l0 = net.loss.clone()
+    xd, labd = to_dev(x, "bf16"), torch.from_numpy(lab).cuda()
+    net.reset()
+    gc.collect()
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    floor = torch.cuda.memory_allocated()
+    torch.cuda.reset_peak_memory_stats()
+    net.step(xd, labd, swap=False)
+    torch.cuda.synchronize()
+    peak = torch.cuda.max_memory_allocated()
+    total = torch.cuda.get_device_properties(0).total_memory
+    passed = None
+    try:
+        for factor in (0.97, 0.94, 0.91, 0.88):
+            limit = floor + factor * (peak - floor)
+            net.reset()
+            torch.cuda.synchronize()
+            torch.cuda.empty_cache()
+            torch.cuda.set_per_process_memory_fraction(limit / total)
+            try:
+                net.step(xd, labd, swap=False)
+                torch.cuda.synchronize()
+                print("step without swapping still fits at factor", factor)
+                continue                      # still fits without swapping: tighten the limit
+            except torch.cuda.OutOfMemoryError:
+                pass
+            net.reset()
+            torch.cuda.synchronize()
+            torch.cuda.empty_cache()
+            try:
+                for _ in range(2):
+                    net.step(xd, labd, swap=True)
+                    torch.cuda.synchronize()
+            except torch.cuda.OutOfMemoryError:
+                print("swapping step ran out of memory at factor", factor)
+                break                         # below the working set of the swapping step
+            passed = factor
+            break
+    finally:
+        torch.cuda.set_per_process_memory_fraction(1.0)
+    assert passed is not None, "no limit found under which only the swapping step completes"
+    assert torch.equal(net.loss, l0)
+    for k, v in net.grads().items():
+        assert torch.equal(v, g0[k]), k
+    assert net.stall_count > 0          # some allocation really had to wait for an outgoing copy
+    net.close()
