@@ -13,6 +13,8 @@
 
 namespace k3 {
 
+static __device__ uint4 g_fzero[4];   // zero-initialised: source of out-of-volume copy items
+
 namespace first {
 constexpr int TD = 4, TH = 8, TW = 16;            // output voxels per tile
 constexpr int HD = TD + 2, HH = TH + 2, HW = TW + 2;
@@ -163,6 +165,233 @@ __global__ __launch_bounds__(256) void conv_first_wgrad_kernel(const bf16_t *__r
     }
 }
 
+// ---------------------------------------------------------------------------- MFMA variants
+// For C_out a multiple of 32 both passes run on the matrix cores with the 27 taps as the
+// contraction (forward) or as the 32 output rows (backward-weight); the single-channel halo
+// tile sits in LDS as bf16 and the im2col operand of a lane is gathered from it with eight
+// 16-bit LDS reads.  The thread-per-channel kernels above need 27 LDS reads and 108 FMAs per
+// 4 outputs and are LDS-bound at ~1.5-1.9 TB/s; these stream at the HBM rate.
+namespace firstm {
+constexpr int TD = 4, TH = 8, TW = 16;
+constexpr int HD = TD + 2, HH = TH + 2, HW = TW + 2;
+constexpr int NHALO = HD * HH * HW;               // 1080 bf16 values
+constexpr int NVOX = TD * TH * TW;                // 512 = 16 patches of 2 rows x 16 columns
+__host__ __device__ constexpr int tapoff(int t) { return (((t / 9) * HH + (t / 3) % 3) * HW + t % 3) * 2; }   // bytes
+}  // namespace firstm
+
+__host__ __device__ static inline int first_row_to_channel(int r) { return ((r >> 2) & 1) * 16 + (r >> 3) * 4 + (r & 3); }
+
+__device__ __forceinline__ void stage_x_bf16(const bf16_t *__restrict__ x, bf16_t *xs, const FirstTile &t, int D, int H, int W)
+{
+    using namespace firstm;
+    for (int i = threadIdx.x; i < NHALO; i += 256) {
+        int lw = i % HW, lh = (i / HW) % HH, ld = i / (HW * HH);
+        int gd = t.d0 + ld - 1, gh = t.h0 + lh - 1, gw = t.w0 + lw - 1;
+        bf16_t v = 0;
+        if (gd >= 0 && gd < D && gh >= 0 && gh < H && gw >= 0 && gw < W) v = x[(((int64_t)t.n * D + gd) * H + gh) * W + gw];
+        xs[i] = v;
+    }
+}
+
+// eight halo values at byte offsets o0..o7 from p, packed as an MFMA operand
+template <int O0, int O1, int O2, int O3, int O4, int O5, int O6, int O7>
+__device__ __forceinline__ bf16x8 gather8(const unsigned char *p)
+{
+    typedef __attribute__((ext_vector_type(8))) unsigned short u16x8;
+    u16x8 v;
+    v[0] = *reinterpret_cast<const unsigned short *>(p + O0);
+    v[1] = *reinterpret_cast<const unsigned short *>(p + O1);
+    v[2] = *reinterpret_cast<const unsigned short *>(p + O2);
+    v[3] = *reinterpret_cast<const unsigned short *>(p + O3);
+    v[4] = *reinterpret_cast<const unsigned short *>(p + O4);
+    v[5] = *reinterpret_cast<const unsigned short *>(p + O5);
+    v[6] = *reinterpret_cast<const unsigned short *>(p + O6);
+    v[7] = *reinterpret_cast<const unsigned short *>(p + O7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+// Forward: D[co][voxel] = sum_tap W[tap][co] * x[voxel + tap]; K = 32 (27 taps + 5 zero rows) = 2 MFMAs
+// per 32 voxels and 32-channel block.  Persistent blocks walk the 4x8x16 tiles.
+template <int MB>
+__global__ __launch_bounds__(256) void conv_first_fwd_mfma_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
+                                                                 const float *__restrict__ bias, int relu,
+                                                                 bf16_t *__restrict__ y, int D, int H, int W, int ntd,
+                                                                 int nth, int ntw, int64_t ntiles)
+{
+    using namespace firstm;
+    constexpr int cout = 32 * MB;
+    __shared__ __attribute__((aligned(16))) bf16_t xs[2][NHALO + 8];
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int hb = lane >> 5, vl = lane & 31;
+    // A operand: weights, rows permuted so that a lane ends up with 16 consecutive channels
+    bf16x8 aw[MB][2];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int m = 0; m < 2; ++m) {
+            typedef __attribute__((ext_vector_type(8))) unsigned short u16x8;
+            u16x8 v;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int tap = m * 16 + hb * 8 + e;
+                v[e] = tap < 27 ? w[(int64_t)tap * cout + mb * 32 + first_row_to_channel(vl)] : (unsigned short)0;
+            }
+            aw[mb][m] = __builtin_bit_cast(bf16x8, v);
+        }
+    float bv[MB][16];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) bv[mb][i] = bias ? bias[mb * 32 + hb * 16 + i] : 0.f;
+    const float floor_ = relu ? 0.f : -__builtin_inff();
+    int buf = 0;
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x, buf ^= 1) {
+        const FirstTile t = first_tile(tile, ntd, nth, ntw);
+        stage_x_bf16(x, xs[buf], t, D, H, W);
+        __syncthreads();   // (the other buffer is still being read by slower waves: two buffers, one barrier)
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const int patch = wv * 4 + q;                 // 16 patches: depth plane patch / 4, rows 2 * (patch % 4) ..+1
+            const int ld = patch >> 2, lh = (patch & 3) * 2 + (vl >> 4), lw = vl & 15;
+            const unsigned char *p = reinterpret_cast<const unsigned char *>(xs[buf]) + ((ld * HH + lh) * HW + lw) * 2;
+            // taps 0-7 / 8-15 (first K chunk) and 16-23 / 24-26 (second), by lane half
+            const bf16x8 lo0 = gather8<tapoff(0), tapoff(1), tapoff(2), tapoff(3), tapoff(4), tapoff(5), tapoff(6), tapoff(7)>(p);
+            const bf16x8 hi0 = gather8<tapoff(8), tapoff(9), tapoff(10), tapoff(11), tapoff(12), tapoff(13), tapoff(14), tapoff(15)>(p);
+            const bf16x8 lo1 = gather8<tapoff(16), tapoff(17), tapoff(18), tapoff(19), tapoff(20), tapoff(21), tapoff(22), tapoff(23)>(p);
+            bf16x8 hi1 = gather8<tapoff(24), tapoff(25), tapoff(26), tapoff(26), tapoff(26), tapoff(26), tapoff(26), tapoff(26)>(p);
+#pragma unroll
+            for (int e = 3; e < 8; ++e) hi1[e] = (__bf16)0.f;   // rows 27-31 of the contraction do not exist
+            const bf16x8 b0 = hb ? hi0 : lo0, b1 = hb ? hi1 : lo1;
+            const int gd = t.d0 + ld, gh = t.h0 + lh, gw = t.w0 + lw;
+            const bool inb = gd < D && gh < H && gw < W;
+            const int64_t vox = (((int64_t)t.n * D + gd) * H + gh) * W + gw;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                f32x16 acc;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[i] = bv[mb][i];
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aw[mb][0], b0, acc, 0, 0, 0);
+                acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aw[mb][1], b1, acc, 0, 0, 0);
+                if (inb) {
+                    float v[16];
+#pragma unroll
+                    for (int i = 0; i < 16; ++i) v[i] = fmaxf(acc[i], floor_);
+                    uint4 *dst = reinterpret_cast<uint4 *>(y + vox * cout + mb * 32 + hb * 16);
+                    dst[0] = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
+                    dst[1] = make_uint4(pack2bf(v[8], v[9]), pack2bf(v[10], v[11]), pack2bf(v[12], v[13]), pack2bf(v[14], v[15]));
+                }
+            }
+        }
+    }
+}
+
+// Backward-weight: rows = taps (row 27 multiplies ones: the bias gradient), columns = channels,
+// contraction over voxels, 16 per MFMA (one row of the 16-wide tile).  dy tiles are copied
+// global -> LDS asynchronously, double buffered, as [block][voxel][32 channels]; the dy operand
+// comes from transposing LDS reads, the x operand from eight 16-bit reads of the halo tile.
+// The four waves split the 32 rows of a tile and add their accumulators through LDS in a
+// fixed order at the end; one partial per workgroup.
+template <int MB>
+__global__ __launch_bounds__(256) void conv_first_wgrad_mfma_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy,
+                                                                   float *__restrict__ ws, int64_t per_split, int D, int H,
+                                                                   int W, int ntd, int nth, int ntw, int64_t ntiles)
+{
+    using namespace firstm;
+    constexpr int cout = 32 * MB;
+    constexpr int GB = NVOX * 64;          // one 32-channel block of the dy tile
+    constexpr int GSTAGE = MB * GB;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2][GSTAGE] dy, then 2 x halo tiles, then 4 KB
+    bf16_t *xs0 = reinterpret_cast<bf16_t *>(smem + 2 * GSTAGE);
+    float *red = reinterpret_cast<float *>(smem + 2 * GSTAGE + 2 * (NHALO + 8) * 2);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hb = lane >> 5, r = lane & 31, g16 = (lane >> 4) & 1, j = lane & 15;
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
+    const unsigned char *zero = reinterpret_cast<const unsigned char *>(g_fzero);
+    // copy items of a dy tile: MB * 32 groups of 64 slots; wave wv copies groups wv, wv + 4, ...
+    constexpr int GK = MB * 8;
+    int goff[GK], gco[GK];
+#pragma unroll
+    for (int k = 0; k < GK; ++k) {
+        const int slot = (wv + 4 * k) * 64 + lane;
+        const int cb = slot >> 11, vox = (slot >> 2) & 511, part = slot & 3;
+        const int ld = vox >> 7, lh = (vox >> 4) & 7, lw = vox & 15;
+        goff[k] = ((ld * H + lh) * W + lw) * cout * 2 + cb * 64 + part * 16;
+        gco[k] = ld | (lh << 8) | (lw << 16);
+    }
+    auto issue_g = [&](int64_t tile, int buf) __attribute__((always_inline)) {
+        const FirstTile t = first_tile(tile, ntd, nth, ntw);
+        const unsigned char *gb = reinterpret_cast<const unsigned char *>(dy + ((((int64_t)t.n * D + t.d0) * H + t.h0) * W + t.w0) * cout);
+#pragma unroll
+        for (int k = 0; k < GK; ++k) {
+            const int ld = gco[k] & 255, lh = (gco[k] >> 8) & 255, lw = gco[k] >> 16;
+            const bool in = t.d0 + ld < D && t.h0 + lh < H && t.w0 + lw < W;
+            dma16(lds0 + buf * GSTAGE + (wv + 4 * k) * 1024, in ? gb + goff[k] : zero);
+        }
+    };
+    // this lane's row of the x operand: tap r (rows 27-31: address of tap 26, value replaced below)
+    const int tap = r < 27 ? r : 26;
+    const int xrow = tapoff(tap) + hb * 16;   // + 8 voxels for the upper lane half
+    const int lane_g = (hb * 8 + (j >> 2)) * 64 + g16 * 32 + (j & 3) * 8;
+    bf16x8 ones;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) ones[e] = (__bf16)1.0f;
+    bf16x8 zeros8;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) zeros8[e] = (__bf16)0.f;
+
+    f32x16 acc[MB];
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[mb][i] = 0.f;
+
+    int buf = 0;
+    if ((int64_t)blockIdx.x < ntiles) issue_g(blockIdx.x, 0);
+    for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x, buf ^= 1) {
+        const FirstTile t = first_tile(tile, ntd, nth, ntw);
+        bf16_t *xs = xs0 + buf * (NHALO + 8);
+        stage_x_bf16(x, xs, t, D, H, W);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+        __syncthreads();   // dy tile and halo tile of this stage are in LDS; the other buffers are free
+        if (tile + gridDim.x < ntiles) issue_g(tile + gridDim.x, buf ^ 1);
+        const unsigned char *gs = smem + buf * GSTAGE;
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int row = wv * 8 + q;            // K-step: depth plane row / 8, tile row row % 8, 16 voxels along w
+            const int ld = row >> 3, lh = row & 7;
+            const unsigned char *p = reinterpret_cast<const unsigned char *>(xs) + ((ld * HH + lh) * HW) * 2 + xrow;
+            bf16x8 ax = gather8<0, 2, 4, 6, 8, 10, 12, 14>(p);
+            if (r == 27) ax = ones;
+            if (r > 27) ax = zeros8;
+#pragma unroll
+            for (int mb = 0; mb < MB; ++mb) {
+                const int o = mb * GB + (row * 16) * 64 + lane_g;
+                typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+                s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(gs + o));
+                s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(gs + o + 4 * 64));
+                typedef __attribute__((ext_vector_type(8))) short s16x8;
+                s16x8 v = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax, __builtin_bit_cast(bf16x8, v), acc[mb], 0, 0, 0);
+            }
+        }
+    }
+    // add the four waves in wave order; acc[mb][i] is row (i/4)*8 + hb*4 + i%4, column mb*32 + lane%32
+    float *out = ws + (int64_t)blockIdx.x * per_split;
+    __syncthreads();
+#pragma unroll
+    for (int mb = 0; mb < MB; ++mb)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) {
+            const int row = (i >> 2) * 8 + hb * 4 + (i & 3);
+            __syncthreads();
+            if (row < 28) red[wv * 64 + lane] = acc[mb][i];
+            __syncthreads();
+            if (wv == 0 && row < 28)
+                out[(int64_t)row * cout + mb * 32 + (lane & 31)] = ((red[lane] + red[64 + lane]) + red[128 + lane]) + red[192 + lane];
+        }
+}
+
 bool conv_first_ok(int dtype, int64_t c1, int64_t c2, int64_t cout)
 {
     return dtype == K3_BF16 && c1 == 1 && c2 == 0 && cout % first::CPT == 0 && cout <= 256 &&
@@ -177,11 +406,28 @@ static int64_t first_tiles(const ConvArgs &a, int *ntd, int *nth, int *ntw)
     return a.N * *ntd * *nth * *ntw;
 }
 
+static bool first_mfma_ok(const ConvArgs &a)
+{
+    // 32-bit byte offsets inside a tile
+    return (a.cout == 32 || a.cout == 64) && (int64_t)(first::TD + 1) * a.H * a.W * a.cout * 2 < 0x7fffffffLL;
+}
+
 int conv_first_fwd(const ConvArgs &a, hipStream_t st)
 {
     int ntd, nth, ntw;
     int64_t ntiles = first_tiles(a, &ntd, &nth, &ntw);
     if (ntiles > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+    if (first_mfma_ok(a)) {
+        const unsigned grid = (unsigned)(ntiles < 2048 ? ntiles : 2048);
+        if (a.cout == 64)
+            conv_first_fwd_mfma_kernel<2><<<dim3(grid), 256, 0, st>>>((const bf16_t *)a.x, (const bf16_t *)a.w, a.bias, a.relu,
+                                                                     (bf16_t *)a.y, (int)a.D, (int)a.H, (int)a.W, ntd, nth, ntw, ntiles);
+        else
+            conv_first_fwd_mfma_kernel<1><<<dim3(grid), 256, 0, st>>>((const bf16_t *)a.x, (const bf16_t *)a.w, a.bias, a.relu,
+                                                                     (bf16_t *)a.y, (int)a.D, (int)a.H, (int)a.W, ntd, nth, ntw, ntiles);
+        K3_LAUNCH_CHECK();
+        return K3_OK;
+    }
     conv_first_fwd_kernel<<<dim3((unsigned)ntiles), 256, 0, st>>>((const bf16_t *)a.x, (const bf16_t *)a.w, a.bias, a.relu,
                                                                   (bf16_t *)a.y, (int)a.D, (int)a.H, (int)a.W, (int)a.cout,
                                                                   ntd, nth, ntw);
@@ -190,6 +436,25 @@ int conv_first_fwd(const ConvArgs &a, hipStream_t st)
 }
 
 static int64_t first_nsplit(int64_t ntiles) { return ntiles < 2048 ? ntiles : 2048; }
+static int64_t first_nsplit_mfma(int64_t ntiles) { return ntiles < 256 ? ntiles : 256; }   // one workgroup per CU
+
+template <int MB>
+static int launch_first_wgrad_mfma(const ConvArgs &a, float *ws, int64_t per, int ntd, int nth, int ntw, int64_t ntiles,
+                                   hipStream_t st)
+{
+    constexpr int lds = 2 * MB * firstm::NVOX * 64 + 2 * (firstm::NHALO + 8) * 2 + 256 * 4;
+    static_assert(lds <= 160 * 1024, "LDS budget");
+    static bool attr_done = false;
+    if (!attr_done) {
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_first_wgrad_mfma_kernel<MB>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        attr_done = true;
+    }
+    conv_first_wgrad_mfma_kernel<MB><<<dim3((unsigned)first_nsplit_mfma(ntiles)), 256, lds, st>>>(
+        (const bf16_t *)a.x, (const bf16_t *)a.dy, ws, per, (int)a.D, (int)a.H, (int)a.W, ntd, nth, ntw, ntiles);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
 
 size_t conv_first_wgrad_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cout)
 {
@@ -204,6 +469,12 @@ int conv_first_wgrad(const ConvArgs &a, float *dW, float *db, float *ws, hipStre
     int64_t ntiles = first_tiles(a, &ntd, &nth, &ntw);
     int64_t nsplit = first_nsplit(ntiles);
     int64_t per = 28 * a.cout;   // 27 tap rows + the bias row: canonical [27][1][cout] followed by db
+    if (first_mfma_ok(a) && !a.ymask) {
+        int rc = a.cout == 64 ? launch_first_wgrad_mfma<2>(a, ws, per, ntd, nth, ntw, ntiles, st)
+                              : launch_first_wgrad_mfma<1>(a, ws, per, ntd, nth, ntw, ntiles, st);
+        if (rc != K3_OK) return rc;
+        return launch_reduce_partials(ws, dW, db, 27 * a.cout, per, (int)first_nsplit_mfma(ntiles), st);
+    }
     conv_first_wgrad_kernel<<<dim3((unsigned)nsplit), 256, 0, st>>>((const bf16_t *)a.x, (const bf16_t *)a.dy,
                                                                     (const bf16_t *)a.ymask, ws, per, (int)a.D, (int)a.H,
                                                                     (int)a.W, (int)a.cout, ntd, nth, ntw, ntiles);

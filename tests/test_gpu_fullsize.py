@@ -140,6 +140,8 @@ BIG_CASES = [
     (1, 32, 32, 32, 128, 0, 128),    # deep level: 4x8x8 tiles, two output blocks per workgroup
     (1, 16, 16, 16, 256, 0, 256),    # bottleneck: 4x8x8 tiles, one output block per workgroup
     (1, 14, 20, 28, 64, 64, 128),    # 4x8x8 tiles, two sources / destinations, ragged
+    (1, 40, 36, 50, 1, 0, 64),       # single-channel first layer (MFMA im2col kernels), ragged tiles
+    (2, 20, 24, 48, 1, 0, 32),       # first layer, two samples, one output block
 ]
 
 
