@@ -204,3 +204,17 @@ def head_softmax_ce(a, wh, bh, labels):
                                 ctypes.byref(loss), logits.ctypes.data_as(_dp), da.ctypes.data_as(_dp),
                                 dW.ctypes.data_as(_dp), db.ctypes.data_as(_dp), _i64(V), _i64(C), _i64(K))
     return {"loss": loss.value, "logits": logits.reshape(a.shape[:-1] + (K,)), "da": da, "dW": dW, "db": db}
+
+
+def sgd_momentum_step(w, v, g, lr, momentum=0.0, weight_decay=0.0):
+    """One step of stochastic gradient descent (the weight-update algorithm of section 1) with
+    the textbook momentum and weight-decay terms, fp64, out of place:
+        v' = momentum * v + (g + weight_decay * w);   w' = w - lr * v'.
+    momentum = weight_decay = 0 is plain SGD, w' = w - lr * g.  Returns (w', v').
+    Pinned in tests/test_oracle_sgd.py by closed forms (geometric momentum sum under a constant
+    gradient, the exact contraction factor on a quadratic) and a two-step hand computation."""
+    w = np.asarray(w, dtype=np.float64)
+    v = np.asarray(v, dtype=np.float64)
+    g = np.asarray(g, dtype=np.float64)
+    v2 = momentum * v + (g + weight_decay * w)
+    return w - lr * v2, v2

@@ -79,3 +79,23 @@ def unet_step(x, labels, params, base, levels=4, store=None):
         d = st(conv3d_bwd_data(g1, P[f"enc{l}.conv1.w"]))
     grads["x"] = d
     return loss, grads, acts
+
+
+def train(x, labels, params, base, levels, steps, lr, momentum=0.0, weight_decay=0.0, store=None, store_w=None):
+    """A short training run on one fixed batch: `steps` times (step gradient, SGD update of every
+    parameter).  Master weights and momentum buffers are fp64; `store_w` (identity, or
+    `oracle.round_bf16`) is applied to the convolution weights each step uses, which models a
+    bf16 working copy of fp32 master weights; biases and the head stay unrounded.  Returns
+    (list of the losses before each update, final master parameters)."""
+    from . import sgd_momentum_step
+    sw = (lambda t: t) if store_w is None else store_w
+    P = {k: np.asarray(v, dtype=np.float64).copy() for k, v in params.items()}
+    V = {k: np.zeros_like(v) for k, v in P.items()}
+    losses = []
+    for _ in range(steps):
+        used = {k: (sw(v) if (k.endswith(".w") and not k.startswith("head")) else v) for k, v in P.items()}
+        loss, grads, _ = unet_step(x, labels, used, base=base, levels=levels, store=store)
+        losses.append(loss)
+        for k in P:
+            P[k], V[k] = sgd_momentum_step(P[k], V[k], grads[k], lr, momentum, weight_decay)
+    return losses, P
