@@ -323,6 +323,14 @@ def bench_unet(args, base, size, n, swap, label, budget_gb=0.0):
            "voxels_per_s_no_swap": round(V / t_noswap, 1), "conv_tflops_no_swap": round(fl / t_noswap / 1e12, 2),
            "pct_mfma_peak_no_swap": round(100 * fl / t_noswap / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2),
            "peak_mem_gb": round(torch.cuda.max_memory_allocated() / 1e9, 2)}
+    # weight update (SGD with momentum over the parameter arena + rebuild of the packed weights)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(5):
+        net.sgd_step(0.0, 0.9, 0.0)   # lr = 0: same work, weights unchanged
+    torch.cuda.synchronize()
+    res["weight_update_ms"] = round((time.perf_counter() - t0) / 5 * 1e3, 3)
+    res["parameters"] = int(net.n_params)
     if swap:
         t_swap, moved = run(True)
         res.update({"ms_per_step_swap": round(t_swap * 1e3, 3), "voxels_per_s_swap": round(V / t_swap, 1),

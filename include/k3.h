@@ -171,6 +171,19 @@ int k3_head_softmax_ce_fwd_bwd(const k3_tensor *ad, const void *a, const float *
                                float *dWh, float *dbh, float *logits, void *ws, size_t ws_bytes,
                                void *stream);
 
+/* ------------------------------------------------------------------ weight update
+ * Stochastic gradient descent, the weight-update algorithm the paper's training runs on
+ * the GPU (section 1), with the usual momentum and weight-decay terms (both may be 0,
+ * which gives plain SGD), on a flat vector of n fp32 parameters:
+ *   v <- momentum * v + (g + weight_decay * w);   w <- w - lr * v.
+ * w (master weights), v (momentum buffer) are updated in place; g is read only.  When
+ * w_bf16 is not NULL it receives the updated weights rounded to bf16 (round to nearest
+ * even), the working copy the bf16 kernels read.  All pointers dev; n = 0 is a no-op.
+ * Any alignment is accepted (16-byte aligned vectors take the wide path).  NaN
+ * hyper-parameters return K3_E_BADARG. */
+int k3_sgd_momentum_step(int64_t n, float *w, float *v, const float *g, float lr, float momentum,
+                         float weight_decay, void *w_bf16, void *stream);
+
 /* ------------------------------------------------------------------ LMS swap engine
  * Tensor swapping between device and host memory so that only the tensors a training
  * step currently needs stay on the GPU (section 2.2): a finished forward activation

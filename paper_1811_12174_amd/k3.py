@@ -200,6 +200,15 @@ def head_softmax_ce_fwd_bwd(a, wh, bh, labels, loss, da, dWh, dbh, logits, ws, r
 
 
 # ------------------------------------------------------------------ LMS swap engine
+def sgd_momentum_step(w, v, g, lr, momentum=0.0, weight_decay=0.0, w_bf16=None):
+    n = w.numel()
+    assert v.numel() == n and g.numel() == n and (w_bf16 is None or w_bf16.numel() == n)
+    _check(lib().k3_sgd_momentum_step(ctypes.c_int64(n), _p(w), _p(v), _p(g), ctypes.c_float(lr),
+                                      ctypes.c_float(momentum), ctypes.c_float(weight_decay),
+                                      _p(w_bf16) if w_bf16 is not None else None, _stream()),
+           "k3_sgd_momentum_step")
+
+
 def lms_create(device_budget_bytes=0):
     ctx = ctypes.c_void_p(0)
     _check(lib().k3_lms_create(ctypes.c_uint64(device_budget_bytes), ctypes.byref(ctx)), "k3_lms_create")

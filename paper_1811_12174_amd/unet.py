@@ -52,17 +52,41 @@ class UNet3D:
         self.code = k3.BF16 if dtype == torch.bfloat16 else k3.F32
         self.w, self.b, self.pk, self.gw, self.gb = {}, {}, {}, {}, {}
         self.kind = {}
-        for name in sorted({k[:-2] for k in params}):
-            wt = torch.from_numpy(params[name + ".w"]).to(device)
-            self.b[name] = torch.from_numpy(params[name + ".b"]).to(device).float().contiguous()
+        # All parameters live in flat arenas so that the weight update is one kernel launch:
+        # fp32 master values, their momentum buffers and their gradients at the same element
+        # offsets; bf16 networks add a bf16 working copy (what the conv kernels read), also at
+        # the same offsets.  Every tensor starts on a 64-element boundary; the gaps stay zero.
+        names = sorted({k[:-2] for k in params})
+        off, self._span = 0, {}
+        for name in names:
+            for suf in (".w", ".b"):
+                n = int(params[name + suf].size)
+                self._span[name + suf] = (off, n)
+                off += (n + 63) // 64 * 64
+        self.n_params = off
+        self.master = torch.zeros(off, device=device, dtype=torch.float32)
+        self.mom = torch.zeros(off, device=device, dtype=torch.float32)
+        self.gflat = torch.zeros(off, device=device, dtype=torch.float32)
+        self.work = torch.zeros(off, device=device, dtype=torch.bfloat16) if dtype == torch.bfloat16 else None
+        for name in names:
+            o, n = self._span[name + ".w"]
+            shape = tuple(params[name + ".w"].shape)
+            self.master[o:o + n].copy_(torch.from_numpy(params[name + ".w"]).reshape(-1).to(device).float())
+            ob, nb = self._span[name + ".b"]
+            self.master[ob:ob + nb].copy_(torch.from_numpy(params[name + ".b"]).reshape(-1).to(device).float())
+            self.b[name] = self.master[ob:ob + nb]
             if name == "head":
                 self.kind[name] = "head"
-                self.w[name] = wt.float().contiguous()
+                self.w[name] = self.master[o:o + n].view(shape)
             else:
                 self.kind[name] = "upconv" if name.endswith(".up") else "conv"
-                self.w[name] = wt.to(dtype).contiguous()
-            self.gw[name] = torch.zeros(self.w[name].shape, device=device, dtype=torch.float32)
-            self.gb[name] = torch.zeros(self.b[name].shape, device=device, dtype=torch.float32)
+                if self.work is not None:
+                    self.work[o:o + n].copy_(self.master[o:o + n])
+                    self.w[name] = self.work[o:o + n].view(shape)
+                else:
+                    self.w[name] = self.master[o:o + n].view(shape)
+            self.gw[name] = self.gflat[o:o + n].view(shape)
+            self.gb[name] = self.gflat[ob:ob + nb]
         self.repack()
         self._ws = None
         self._slots = {}
@@ -92,6 +116,21 @@ class UNet3D:
         for name in self.w:
             out[name + ".w"] = self.gw[name]
             out[name + ".b"] = self.gb[name]
+        return out
+
+    def sgd_step(self, lr, momentum=0.0, weight_decay=0.0):
+        """SGD(-momentum) update of every parameter from the gradients of the last step(): one
+        launch over the parameter arena, then the packed weight forms are rebuilt."""
+        k3.sgd_momentum_step(self.master, self.mom, self.gflat, lr, momentum, weight_decay, w_bf16=self.work)
+        self.repack()
+
+    def parameters(self):
+        """name -> fp32 master tensor (views into the arena)."""
+        out = {}
+        for key, (o, n) in self._span.items():
+            name = key[:-2]
+            shape = self.w[name].shape if key.endswith(".w") else self.b[name].shape
+            out[key] = self.master[o:o + n].view(shape)
         return out
 
     # ------------------------------------------------------------------ helpers
