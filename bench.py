@@ -9,10 +9,12 @@ backward).  A step is one pass of that block; the step is captured in a HIP grap
 exact (in-bounds) convolution FLOPs of the step divided by the step time.
 
 Other workloads: "unet128" (full 4-level U-Net, base 32, 1 x 128^3, no swapping),
-"unet256" (base 64, 2 x 256^3, every encoder activation swapped to pinned host memory and
-prefetched back) and "unet320" (base 64, 4 x 320^3); they report voxels/s and the swap
-traffic in the "unet" object.  With --budget-gb the U-Net step is also run under a
-device-memory limit, without swapping (expected to run out of memory) and with it.
+"unet256" (base 64, 2 x 256^3) and "unet320" (base 64, 4 x 320^3); they report voxels/s
+without swapping and, for the two large ones, under a device-memory budget (--budget-gb,
+default three quarters of what the step holds unswapped): without swapping the step is
+refused, with the swap plan the planner makes for that budget it runs, and the "unet"
+object reports its time, its footprint and the bytes moved each way.  "sweep" plans
+and runs a row of resolutions under one fixed budget and reports the swap overhead of each.
 
 Prints ONE JSON line on stdout.
 """
@@ -293,36 +295,50 @@ def bench_unet(args, base, size, n, swap, label, budget_gb=0.0):
     import numpy as np
     import torch
     import synth
-    from paper_1811_12174_amd import k3
+    from paper_1811_12174_amd import k3, planner
+    from paper_1811_12174_amd.executor import OutOfBudget
     from paper_1811_12174_amd.unet import UNet3D
     params = synth.unet_params(base=base, levels=4, dtype="bf16")
     x = torch.from_numpy(synth.volume_field(7, n, size, dtype="bf16")).cuda().to(torch.bfloat16)
     lab = torch.from_numpy(synth.ellipsoid_labels(8, n, size)).cuda()
     net = UNet3D(params, base=base, levels=4)
     steps, warm = max(1, args.unet_steps), 2
+    prog = net.program(x.shape)
+    fixed = net.fixed_bytes(prog)
 
-    def run(sw):
+    def run(**kw):
         for _ in range(warm):
-            net.step(x, lab, swap=sw)
+            net.step(x, lab, **kw)
         torch.cuda.synchronize()
-        before = dict(net.last_stats) if sw else {}
+        if net.lms is not None:
+            k3.lms_sync(net.lms)
+        torch.cuda.reset_peak_memory_stats()
         t0 = time.perf_counter()
         for _ in range(steps):
-            net.step(x, lab, swap=sw)
+            net.step(x, lab, **kw)
         torch.cuda.synchronize()
-        if sw:
+        if net.lms is not None:
             k3.lms_sync(net.lms)
-        dt = (time.perf_counter() - t0) / steps
-        moved = (net.last_stats["bytes_out"] - before["bytes_out"]) / steps if sw else 0
-        return dt, moved
+        return (time.perf_counter() - t0) / steps
 
-    t_noswap, _ = run(False)
-    fl = unet_flops(base, 4, n, size)
+    def swap_leg(plan, budget):
+        dt = run(swap=plan, budget=budget)
+        r = net.last_run
+        return {"ms_per_step": round(dt * 1e3, 3), "voxels_per_s": round(V / dt, 1),
+                "overhead_pct": round(100 * (dt / t_noswap - 1), 2),
+                "accounted_peak_gb": round(r.peak / 1e9, 3), "allocator_peak_gb": round(torch.cuda.max_memory_allocated() / 1e9, 3),
+                "bytes_out_per_step": int(r.bytes_out), "bytes_in_per_step": int(r.bytes_in),
+                "copy_seconds_at_link_peak": round(max(r.bytes_out, r.bytes_in) / 57e9, 4),
+                "device_copies_dropped": r.releases, "plan": plan.describe()}
+
     V = n * size ** 3
+    t_noswap = run()
+    fl = unet_flops(base, 4, n, size)
     res = {"workload": label, "steps": steps, "ms_per_step_no_swap": round(t_noswap * 1e3, 3),
            "voxels_per_s_no_swap": round(V / t_noswap, 1), "conv_tflops_no_swap": round(fl / t_noswap / 1e12, 2),
            "pct_mfma_peak_no_swap": round(100 * fl / t_noswap / 1e12 / MFMA_BF16_PEAK_TFLOPS, 2),
-           "peak_mem_gb": round(torch.cuda.max_memory_allocated() / 1e9, 2)}
+           "accounted_peak_gb_no_swap": round(net.last_run.peak / 1e9, 3),
+           "allocator_peak_gb_no_swap": round(torch.cuda.max_memory_allocated() / 1e9, 3)}
     # weight update (SGD with momentum over the parameter arena + rebuild of the packed weights)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -331,51 +347,73 @@ def bench_unet(args, base, size, n, swap, label, budget_gb=0.0):
     torch.cuda.synchronize()
     res["weight_update_ms"] = round((time.perf_counter() - t0) / 5 * 1e3, 3)
     res["parameters"] = int(net.n_params)
-    if swap:
-        t_swap, moved = run(True)
-        res.update({"ms_per_step_swap": round(t_swap * 1e3, 3), "voxels_per_s_swap": round(V / t_swap, 1),
-                    "swap_overhead_pct": round(100 * (t_swap / t_noswap - 1), 2),
-                    "swap_bytes_per_direction_per_step": int(moved),
-                    "copy_seconds_at_link_peak": round(moved / 57e9, 4)})
+    # per-call GPU durations of this very workload feed the planner's simulator
+    net.step(x, lab, timing=True)
+    dur = net.call_seconds
+    if swap and not budget_gb:
+        budget_gb = round(0.75 * net.last_run.peak / 1e9, 3)   # default: three quarters of what the step needs unswapped
     if budget_gb:
         # The situation the paper's LMS exists for: a device-memory limit below what the step
-        # needs without swapping.  The limit is enforced by the allocator for every allocation.
-        total = torch.cuda.get_device_properties(0).total_memory
-        res["device_budget_gb"] = budget_gb
-        net.reset()
-        torch.cuda.synchronize()
-        torch.cuda.empty_cache()
-        torch.cuda.set_per_process_memory_fraction(min(1.0, budget_gb * 1e9 / total))
+        # needs without swapping.  The planner picks what leaves the GPU; the limit is enforced
+        # by the step's own accounting and, 20 % above it, by the allocator.
+        budget = int(budget_gb * 1e9)
+        leg = {"device_budget_gb": budget_gb}
         try:
-            try:
-                net.step(x, lab, swap=False)
-                torch.cuda.synchronize()
-                res["no_swap_under_budget"] = "completed"
-            except torch.cuda.OutOfMemoryError:
-                res["no_swap_under_budget"] = "out of memory"
-            net.reset()
+            net.step(x, lab, swap=False, budget=budget)
+            torch.cuda.synchronize()
+            leg["no_swap_under_budget"] = "completed"
+        except OutOfBudget as e:
+            leg["no_swap_under_budget"] = "refused: " + str(e)
+        try:
+            plan = planner.plan_for_budget(prog, budget, fixed_bytes=fixed, durations=dur)
+        except OutOfBudget as e:
+            leg["swap_under_budget"] = "no plan fits: " + str(e)
+            plan = None
+        if plan is not None:
+            leg.update(swap_leg(plan, budget))
+            leg["swap_under_budget"] = "completed"
+            # The timed steps above are bounded by the step's accounting (allocator_peak_gb shows
+            # what the allocator really held).  Two more steps run under a hard limit of the
+            # allocator itself, 20 % above the budget because it splits and rounds blocks; they
+            # are not timed: a fresh limit makes the block cache churn for a few steps.
+            total = torch.cuda.get_device_properties(0).total_memory
             torch.cuda.synchronize()
             torch.cuda.empty_cache()
+            outside = torch.cuda.memory_allocated() - fixed
+            leg["allocator_limit_gb"] = round(1.2 * budget / 1e9, 3)
+            torch.cuda.set_per_process_memory_fraction(min(1.0, (outside + 1.2 * budget) / total))
             try:
-                net.step(x, lab, swap=True)
+                for _ in range(2):
+                    net.step(x, lab, swap=plan, budget=budget)
                 torch.cuda.synchronize()
-                net.stall_count, net.stall_seconds = 0, 0.0
-                t0 = time.perf_counter()
-                for _ in range(steps):
-                    net.step(x, lab, swap=True)
-                torch.cuda.synchronize()
-                k3.lms_sync(net.lms)
-                dt = (time.perf_counter() - t0) / steps
-                res.update({"swap_under_budget": "completed", "ms_per_step_swap_under_budget": round(dt * 1e3, 3),
-                            "voxels_per_s_swap_under_budget": round(V / dt, 1),
-                            "allocations_that_waited_per_step": net.stall_count / steps,
-                            "wait_seconds_per_step": round(net.stall_seconds / steps, 4)})
+                leg["under_allocator_limit"] = "completed"
             except torch.cuda.OutOfMemoryError:
-                res["swap_under_budget"] = "out of memory"
-        finally:
-            torch.cuda.set_per_process_memory_fraction(1.0)
+                leg["under_allocator_limit"] = "allocator out of memory"
+            finally:
+                torch.cuda.set_per_process_memory_fraction(1.0)
+        res["planned_for_budget"] = leg
     net.close()
     return res
+
+
+def bench_sweep(args):
+    """Swap overhead against resolution at a fixed device budget (the paper's section 3 reports
+    the overhead of LMS growing with the image resolution on its 16 GB GPUs): base-64 U-Net, batch
+    2, edge 192 ... 288, every step planned for the same budget."""
+    out = []
+    for size in (192, 208, 224, 240, 256, 272, 288, 304):
+        u = bench_unet(args, 64, size, 2, False, f"U-Net base 64, 2 x {size}^3", budget_gb=args.sweep_budget_gb)
+        leg = u["planned_for_budget"]
+        row = {"edge": size, "no_swap_ms": u["ms_per_step_no_swap"], "no_swap_peak_gb": u["accounted_peak_gb_no_swap"],
+               "no_swap_under_budget": leg["no_swap_under_budget"][:7], "swap_under_budget": leg["swap_under_budget"][:12]}
+        if leg["swap_under_budget"] == "completed":
+            row.update({"planned_ms": leg["ms_per_step"], "overhead_pct": leg["overhead_pct"],
+                        "predicted_ms": leg["plan"]["predicted_ms"], "peak_gb": leg["accounted_peak_gb"],
+                        "gb_out": round(leg["bytes_out_per_step"] / 1e9, 2), "gb_in": round(leg["bytes_in_per_step"] / 1e9, 2),
+                        "tensors_swapped": len(leg["plan"]["swapped_tensors"])})
+        print("sweep", json.dumps(row), file=sys.stderr, flush=True)
+        out.append(row)
+    return {"device_budget_gb": args.sweep_budget_gb, "rows": out}
 
 
 def main():
@@ -383,9 +421,10 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "unet128", "unet256", "unet320"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "unet128", "unet256", "unet320", "sweep"])
     ap.add_argument("--budget-gb", type=float, default=0.0,
                     help="U-Net workloads: also run under this device-memory limit, without and with swapping")
+    ap.add_argument("--sweep-budget-gb", type=float, default=32.0, help="device budget of the sweep workload")
     ap.add_argument("--unet-steps", type=int, default=3)
     ap.add_argument("--with-unet", action="store_true", help="also time the full U-Net steps (cfg3, and cfg4 with swapping)")
     ap.add_argument("--no-graph", action="store_true")
@@ -414,19 +453,30 @@ def main():
         out = bench_cfg2(args)
         if args.with_unet:
             out["unet"] = [bench_unet(args, 32, 128, 1, False, "cfg3: U-Net base 32, 1 x 128^3, no swapping"),
-                           bench_unet(args, 64, 256, 2, True, "cfg4: U-Net base 64, 2 x 256^3, encoder activations swapped")]
+                           bench_unet(args, 64, 256, 2, True, "cfg4: U-Net base 64, 2 x 256^3, swap plan for a device budget")]
+    elif args.workload == "sweep":
+        sw = bench_sweep(args)
+        done = [r for r in sw["rows"] if "planned_ms" in r]
+        last = done[-1]
+        out = {"metric": "U-Net step voxels/s under a device budget", "value": round(2 * last["edge"] ** 3 / (last["planned_ms"] * 1e-3), 1),
+               "unit": "voxels/s", "n_gpus": 1, "steps": max(1, args.unet_steps), "warmup": 2, "ms_per_step": last["planned_ms"],
+               "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+               "config": {"workload": f"swap-overhead sweep, U-Net base 64, batch 2, edge {sw['rows'][0]['edge']}..{sw['rows'][-1]['edge']}, "
+                                      f"budget {sw['device_budget_gb']} GB; value is the largest edge that ran"},
+               "sweep": sw}
     else:
         if args.workload == "unet128":
             u = bench_unet(args, 32, 128, 1, False, "cfg3: U-Net base 32, 1 x 128^3, no swapping")
         elif args.workload == "unet256":
-            u = bench_unet(args, 64, 256, 2, True, "cfg4: U-Net base 64, 2 x 256^3, encoder activations swapped",
+            u = bench_unet(args, 64, 256, 2, True, "cfg4: U-Net base 64, 2 x 256^3, swap plan for a device budget",
                            budget_gb=args.budget_gb)
         else:
-            u = bench_unet(args, 64, 320, 4, True, "cfg5: U-Net base 64, 4 x 320^3, encoder activations swapped",
+            u = bench_unet(args, 64, 320, 4, True, "cfg5: U-Net base 64, 4 x 320^3, swap plan for a device budget",
                            budget_gb=args.budget_gb)
-        key = "voxels_per_s_swap" if "voxels_per_s_swap" in u else "voxels_per_s_no_swap"
-        ms = u.get("ms_per_step_swap", u["ms_per_step_no_swap"])
-        out = {"metric": "U-Net step voxels/s", "value": u[key], "unit": "voxels/s", "n_gpus": 1, "steps": u["steps"],
+        sw = u.get("planned_for_budget", {})
+        value = sw.get("voxels_per_s", u["voxels_per_s_no_swap"])
+        ms = sw.get("ms_per_step", u["ms_per_step_no_swap"])
+        out = {"metric": "U-Net step voxels/s", "value": value, "unit": "voxels/s", "n_gpus": 1, "steps": u["steps"],
                "warmup": 2, "ms_per_step": ms, "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
                "dtype": "bf16", "data": "synthetic", "config": {"workload": u["workload"]}, "unet": u}
     print(json.dumps(out))

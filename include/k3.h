@@ -226,8 +226,19 @@ int k3_lms_release_after(k3_lms *ctx, int handle, void *stream);
  * users of that block), and consumer_stream is made to wait for the copy, so kernels
  * enqueued on it afterwards see the data.  Handle: ON_HOST -> IN_IN_FLIGHT. */
 int k3_lms_prefetch_in(k3_lms *ctx, int handle, void *dev_ptr, void *consumer_stream);
-/* Makes `stream` wait for the prefetch copy of `handle` (for consumers on other streams). */
+/* As k3_lms_prefetch_in, but no stream is made to wait: the copy starts once the work
+ * already enqueued on block_stream (earlier users of the block) has run, and overlaps
+ * whatever is enqueued afterwards.  Every stream that reads the tensor must be given
+ * k3_lms_wait_in before its first reader is enqueued. */
+int k3_lms_prefetch_start(k3_lms *ctx, int handle, void *dev_ptr, void *block_stream);
+/* Makes `stream` wait for the prefetch copy of `handle` (for consumers on other streams,
+ * and after k3_lms_prefetch_start). */
 int k3_lms_wait_in(k3_lms *ctx, int handle, void *stream);
+/* Drops the device copy of a tensor that was brought back and only read since: the host
+ * copy of the earlier swap-out is still its value, so nothing is copied.  `stream` is
+ * made to wait for the copy-in first (a no-op once it finished), so that work enqueued
+ * on it afterwards may reuse the block.  IN_IN_FLIGHT / RESIDENT -> ON_HOST. */
+int k3_lms_evict(k3_lms *ctx, int handle, void *stream);
 /* Drops the handle (any state but a copy still in flight is waited for first). */
 int k3_lms_release(k3_lms *ctx, int handle);
 /* Blocks the host until both copy streams are idle. */

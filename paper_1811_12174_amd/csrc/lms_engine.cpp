@@ -4,7 +4,10 @@
 //             only after that stream waited for ev_out (release_after).
 //  prefetch : ev_ready recorded on the consumer stream (earlier users of the destination
 //             block) -> H2D stream waits for it and for ev_out -> copy -> ev_in recorded on
-//             the H2D stream -> the consumer stream waits for ev_in.
+//             the H2D stream -> the consumer stream waits for ev_in (prefetch_in at once,
+//             prefetch_start leaves that wait to a later wait_in so the copy overlaps the
+//             kernels enqueued in between).
+//  evict    : a tensor that came back and was only read goes ON_HOST again without a copy.
 #include "lms_engine.h"
 
 namespace k3lms {
@@ -132,7 +135,7 @@ int Engine::release_after(int handle, stream_t st)
     return OK;
 }
 
-int Engine::prefetch_in(int handle, void *dev, stream_t consumer)
+int Engine::prefetch_start(int handle, void *dev, stream_t block_stream)
 {
     Slot *s = get(handle);
     if (!s || !dev) return E_BADARG;
@@ -141,16 +144,35 @@ int Engine::prefetch_in(int handle, void *dev, stream_t consumer)
         if (rc) return rc;
     }
     if (s->state != ON_HOST) return E_STATE;
-    BE(be_->event_record(s->ev_ready, consumer));
+    BE(be_->event_record(s->ev_ready, block_stream));
     BE(be_->stream_wait_event(h2d_, s->ev_ready));
     BE(be_->stream_wait_event(h2d_, s->ev_out));  // no-op when the swap-out already finished
     BE(be_->copy_h2d(dev, s->host, s->bytes, h2d_));
     BE(be_->event_record(s->ev_in, h2d_));
-    BE(be_->stream_wait_event(consumer, s->ev_in));
     s->dev = dev;
     s->state = IN_IN_FLIGHT;
     stats_.bytes_in += s->bytes;
     stats_.n_in += 1;
+    return OK;
+}
+
+int Engine::prefetch_in(int handle, void *dev, stream_t consumer)
+{
+    int rc = prefetch_start(handle, dev, consumer);
+    if (rc) return rc;
+    BE(be_->stream_wait_event(consumer, slots_[handle].ev_in));
+    return OK;
+}
+
+int Engine::evict(int handle, stream_t st)
+{
+    Slot *s = get(handle);
+    if (!s) return E_BADARG;
+    if (s->state != IN_IN_FLIGHT && s->state != RESIDENT) return E_STATE;
+    // work enqueued on st from here on (the next user of the block) runs after the copy-in
+    BE(be_->stream_wait_event(st, s->ev_in));
+    s->state = ON_HOST;  // the host copy made by the swap-out is still the tensor's value
+    s->dev = nullptr;
     return OK;
 }
 

@@ -49,6 +49,8 @@ public:
     int swap_out_done(int handle, int *done);
     int release_after(int handle, stream_t s);
     int prefetch_in(int handle, void *dev, stream_t consumer);
+    int prefetch_start(int handle, void *dev, stream_t block_stream);
+    int evict(int handle, stream_t s);
     int wait_in(int handle, stream_t s);
     int release(int handle);
     int sync();

@@ -140,6 +140,11 @@ int k3_lms_prefetch_in(k3_lms *ctx, int handle, void *dev_ptr, void *consumer_st
 {
     return ctx ? map_status(ctx->eng.prefetch_in(handle, dev_ptr, consumer_stream)) : K3_E_BADARG;
 }
+int k3_lms_prefetch_start(k3_lms *ctx, int handle, void *dev_ptr, void *block_stream)
+{
+    return ctx ? map_status(ctx->eng.prefetch_start(handle, dev_ptr, block_stream)) : K3_E_BADARG;
+}
+int k3_lms_evict(k3_lms *ctx, int handle, void *stream) { return ctx ? map_status(ctx->eng.evict(handle, stream)) : K3_E_BADARG; }
 int k3_lms_wait_in(k3_lms *ctx, int handle, void *stream) { return ctx ? map_status(ctx->eng.wait_in(handle, stream)) : K3_E_BADARG; }
 int k3_lms_release(k3_lms *ctx, int handle) { return ctx ? map_status(ctx->eng.release(handle)) : K3_E_BADARG; }
 int k3_lms_sync(k3_lms *ctx) { return ctx ? map_status(ctx->eng.sync()) : K3_E_BADARG; }

@@ -261,6 +261,16 @@ def lms_prefetch_in(ctx, handle, dev_ptr, consumer_stream=None):
     _check(lib().k3_lms_prefetch_in(ctx, ctypes.c_int(handle), ctypes.c_void_p(dev_ptr), s), "k3_lms_prefetch_in")
 
 
+def lms_prefetch_start(ctx, handle, dev_ptr, block_stream=None):
+    st = _stream() if block_stream is None else ctypes.c_void_p(block_stream)
+    _check(lib().k3_lms_prefetch_start(ctx, int(handle), ctypes.c_void_p(dev_ptr), st), "k3_lms_prefetch_start")
+
+
+def lms_evict(ctx, handle, stream=None):
+    st = _stream() if stream is None else ctypes.c_void_p(stream)
+    _check(lib().k3_lms_evict(ctx, int(handle), st), "k3_lms_evict")
+
+
 def lms_wait_in(ctx, handle, stream=None):
     s = _stream() if stream is None else ctypes.c_void_p(stream)
     _check(lib().k3_lms_wait_in(ctx, ctypes.c_int(handle), s), "k3_lms_wait_in")

@@ -8,39 +8,22 @@ a 2x2x2 max-pool; per decoder level a 2x2x2 stride-2 transposed conv, a virtual 
 concatenation [skip, up] (never materialised: the conv kernels take two sources / two
 destinations), two 3x3x3 conv + ReLU layers; a 1x1x1 head with softmax cross-entropy.
 
-With `swap=True` the step follows the paper's LMS scheme (section 2.2): the encoder-side
-tensors of every level but the deepest -- the level input, a1, a2 -- leave the GPU on the
-device-to-host copy stream as soon as their last forward reader is enqueued, and come
-back on the host-to-device stream ahead of their backward (or skip-connection) consumer.
-Device copies of swapped tensors are dropped lazily, when the copy is seen to be complete,
-so the compute stream never waits for an outgoing copy.
-
-Under a device-memory limit (the situation the paper's LMS exists for: the stored
-activations do not fit) an allocation that fails makes the harness wait for the oldest
-outgoing copy, drop that tensor's device copy and try again -- the step then runs at the
-pace of the host link instead of failing.  Without swapping the same limit ends the step
-with an out-of-memory error.
+The step is a static program (program.py) run by an interpreter (executor.py) for which this
+class is the GPU backend.  With swapping on, the step follows the paper's LMS scheme (section
+2.2): chosen tensors are copied to pinned host memory on the device-to-host stream after the
+last reader before an idle gap, their device copies are dropped when an allocation needs the
+room (only then does the compute stream wait for the outgoing copy), and they come back on
+the host-to-device stream a few calls ahead of the next reader, overlapping the kernels in
+between.  Which gaps are used, and the prefetch lead, come from a plan (planner.py): all idle
+gaps of the stored encoder activations, or a selection made for a device-memory budget.
+Without swapping, a step that needs more than the budget fails with OutOfBudget (or the
+allocator's out-of-memory error); with a plan for that budget it runs.
 """
-import time
-
 import torch
 
-from . import k3
-
-
-class _Slot:
-    """A stored activation: on the device, on its way out, or on the host."""
-    __slots__ = ("name", "t", "shape", "nbytes", "host", "host_bytes", "handle", "out_pending")
-
-    def __init__(self, name):
-        self.name = name
-        self.t = None
-        self.shape = None
-        self.nbytes = 0
-        self.host = None
-        self.host_bytes = 0
-        self.handle = None
-        self.out_pending = False
+from . import k3, planner
+from .executor import Executor
+from .program import unet_program
 
 
 class UNet3D:
@@ -89,11 +72,14 @@ class UNet3D:
             self.gb[name] = self.gflat[ob:ob + nb]
         self.repack()
         self._ws = None
-        self._slots = {}
+        self._host = {}        # tensor name -> (pinned host pointer, bytes), kept across steps
+        self._deferred = []    # swap handles whose last copy may still be in flight
+        self._programs = {}
         self.lms = None
         self.loss = torch.zeros(1, device=device, dtype=torch.float32)
         self.last_stats = {}
-        self.stall_count, self.stall_seconds = 0, 0.0   # allocations that had to wait for an outgoing copy
+        self.last_run = None   # the Executor of the last step (peak bytes, bytes moved, drops)
+        self._timing = None
 
     # ------------------------------------------------------------------ parameters
     def repack(self):
@@ -133,268 +119,189 @@ class UNet3D:
             out[key] = self.master[o:o + n].view(shape)
         return out
 
-    # ------------------------------------------------------------------ helpers
-    def _workspace(self, nbytes):
-        if self._ws is None or self._ws.numel() < nbytes:
-            self._ws = None
-            self._ws = torch.empty(max(nbytes, 1 << 20), device=self.dev, dtype=torch.uint8)
-        return self._ws
+    # ------------------------------------------------------------------ program and plans
+    def program(self, x_shape, keep_acts=False):
+        """The static step program for an input of this shape (cached)."""
+        key = (tuple(x_shape), keep_acts)
+        if key not in self._programs:
+            n, d, h, w, c = x_shape
+            if c != self.cin:
+                raise ValueError("input channel count differs from the network's")
+            self._programs[key] = unet_program(self.base, self.cin, self.levels, n, d, h, w,
+                                               ebytes=2 if self.dtype == torch.bfloat16 else 4, keep_acts=keep_acts)
+        return self._programs[key]
 
-    def _empty(self, shape):
-        """Device tensor; when the allocator is out of memory, reclaim swapped-out tensors and retry."""
-        while True:
-            try:
-                return torch.empty(tuple(shape), device=self.dev, dtype=self.dtype)
-            except torch.cuda.OutOfMemoryError:
-                if not self._reclaim():
-                    raise
+    def workspace_bytes(self, prog):
+        """Largest scratch buffer any call of the program needs (shapes only; nothing is launched)."""
+        def meta(name):
+            return None if name is None else torch.empty(prog.tensors[name].shape, device="meta", dtype=self.dtype)
+        need = 1 << 20
+        for c in prog.calls:
+            if c.fn == "conv_wgrad":
+                need = max(need, k3.conv3d_bwd_weight_workspace_bytes(meta(c.args["x"]), meta(c.args["g"]), x2=meta(c.args["x2"])))
+            elif c.fn == "up_wgrad":
+                need = max(need, k3.upconv3d_bwd_weight_workspace_bytes(meta(c.args["x"]), meta(c.args["dy"])))
+            elif c.fn == "head":
+                need = max(need, k3.head_workspace_bytes(meta(c.args["a"])))
+        return need
 
-    def _new(self, like_shape, c):
-        n, d, h, w, _ = like_shape
-        return self._empty((n, d, h, w, c))
+    def fixed_bytes(self, prog):
+        """Device bytes a step holds besides its activations: the parameter arenas (master, momentum,
+        gradient, working copy), the packed weights, the scratch buffer and the caller's batch."""
+        n = sum(t.numel() * t.element_size() for t in (self.master, self.mom, self.gflat) if t is not None)
+        if self.work is not None:
+            n += self.work.numel() * 2
+        n += sum(t.numel() for t in self.pk.values() if t is not None)
+        n += self.workspace_bytes(prog)
+        n += sum(i.nbytes for i in prog.tensors.values() if i.external)
+        return n
 
-    def _conv(self, name, x, x2=None, relu=True):
-        y = self._new(x.shape, self.w[name].shape[4])
-        k3.conv3d_fwd(x, self.w[name], self.pk[name], self.b[name], relu, y, x2=x2)
-        return y
+    # ------------------------------------------------------------------ backend of the interpreter
+    def alloc(self, info):
+        return torch.empty(info.shape, device=self.dev, dtype=self.dtype)
 
-    def _conv_bwd(self, name, x, x2, g, need_dx=True, dx_mask=None):
-        """Weight / bias gradients of layer `name`, and dx (split like the inputs).
+    def free(self, block):
+        pass    # the last reference goes with the interpreter's table entry
 
-        g is the gradient of the layer's pre-activation: every producer of an activation
-        gradient (head, pool backward, transposed-conv backward, conv backward-data) applies
-        the ReLU mask of the tensor it differentiates, so no mask is read here.  dx_mask is
-        the stored ReLU output that the first input x is (None when x is not a ReLU output)."""
-        ws = self._workspace(k3.conv3d_bwd_weight_workspace_bytes(x, g, x2=x2))
-        k3.conv3d_bwd_weight(x, g, None, self.gw[name], self.gb[name], ws, x2=x2)
-        if not need_dx:
-            return None, None
-        dx = self._empty(x.shape)
-        dx2 = self._empty(x2.shape) if x2 is not None else None
-        k3.conv3d_bwd_data(g, None, self.w[name], self.pk[name], dx, dx2=dx2, dx_mask=dx_mask)
-        return dx, dx2
+    def swap_out(self, info, block):
+        host = self._host.get(info.name)
+        if host is None or host[1] < info.nbytes:
+            if host is not None:
+                k3.lms_host_free(host[0])
+            host = self._host[info.name] = (k3.lms_host_alloc(info.nbytes), info.nbytes)
+        return k3.lms_swap_out(self.lms, block.data_ptr(), info.nbytes, host[0])
 
-    # ------------------------------------------------------------------ swapping
-    def _slot(self, name):
-        s = self._slots.get(name)
-        if s is None:
-            s = self._slots[name] = _Slot(name)
-        return s
+    def release_after(self, h):
+        k3.lms_release_after(self.lms, h)
 
-    def _swap_out(self, name, t):
-        s = self._slot(name)
-        s.t, s.shape, s.nbytes = t, tuple(t.shape), t.numel() * t.element_size()
-        if self.lms is None:
-            return
-        if s.host is None or s.host_bytes < s.nbytes:
-            if s.host is not None:
-                k3.lms_host_free(s.host)
-            s.host, s.host_bytes = k3.lms_host_alloc(s.nbytes), s.nbytes
-        s.handle = k3.lms_swap_out(self.lms, t.data_ptr(), s.nbytes, s.host)
-        s.out_pending = True
+    def prefetch_start(self, h, block):
+        k3.lms_prefetch_start(self.lms, h, block.data_ptr())
 
-    def _poll(self):
-        """Drop device copies whose outgoing copy has completed (never blocks)."""
-        if self.lms is None:
-            return
-        for s in self._slots.values():
-            if s.out_pending and k3.lms_swap_out_done(self.lms, s.handle):
-                s.out_pending = False
-                s.t = None
+    def wait_in(self, h):
+        k3.lms_wait_in(self.lms, h)
 
-    def _reclaim(self):
-        """Free device memory held by tensors that are on their way to the host: drop every copy
-        that has completed, else block on the oldest outgoing copy.  False when nothing can be freed."""
-        if self.lms is None:
-            return False
-        pending = [s for s in self._slots.values() if s.out_pending]
-        if not pending:
-            return False
-        self.stall_count += 1
-        t0 = time.perf_counter()
-        while True:
-            done = [s for s in pending if k3.lms_swap_out_done(self.lms, s.handle)]
-            if done:
-                break
-            time.sleep(0.0002)
-        for s in done:
-            s.out_pending = False
-            s.t = None
-        self.stall_seconds += time.perf_counter() - t0
-        return True
+    def evict(self, h):
+        k3.lms_evict(self.lms, h)
 
-    def _prefetch(self, name):
-        """Start bringing a swapped tensor back (no-op while it is still on the device)."""
-        s = self._slots[name]
-        if s.t is not None or self.lms is None:
-            s.out_pending = False
-            return
-        s.t = self._empty(s.shape)
-        k3.lms_prefetch_in(self.lms, s.handle, s.t.data_ptr())
+    def release(self, h):
+        """Handles are returned to the engine once their last copy has finished; asking earlier
+        would block the host behind the GPU."""
+        self._deferred.append(h)
+        self._drain(False)
 
-    def _get(self, name):
-        s = self._slots[name]
-        if s.t is None:
-            self._prefetch(name)
-        return s.t
+    def _drain(self, block):
+        keep = []
+        for h in self._deferred:
+            if not block and k3.lms_handle_state(self.lms, h) in (k3.LMS_OUT_IN_FLIGHT, k3.LMS_IN_IN_FLIGHT):
+                keep.append(h)
+            else:
+                k3.lms_release(self.lms, h)
+        self._deferred = keep
 
-    def _drop(self, name):
-        s = self._slots[name]
-        if s.handle is not None and self.lms is not None:
-            k3.lms_release(self.lms, s.handle)
-        s.handle, s.t, s.out_pending = None, None, False
-
-    def reset(self):
-        """Drop every stored activation and swap handle (after a step that ended in an error)."""
-        if self.lms is not None:
-            k3.lms_sync(self.lms)
-        for s in self._slots.values():
-            if s.handle is not None and self.lms is not None:
-                k3.lms_release(self.lms, s.handle)
-            s.handle, s.t, s.out_pending = None, None, False
-        self._ws = None
-
-    def close(self):
-        for s in self._slots.values():
-            if s.handle is not None and self.lms is not None:
-                k3.lms_release(self.lms, s.handle)
-                s.handle = None
-            if s.host is not None:
-                k3.lms_host_free(s.host)
-                s.host = None
-        if self.lms is not None:
-            k3.lms_destroy(self.lms)
-            self.lms = None
+    def call(self, c, t):
+        a = c.args
+        if c.fn == "conv_fwd":
+            k3.conv3d_fwd(t[a["x"]], self.w[c.layer], self.pk[c.layer], self.b[c.layer], a["relu"], t[a["y"]],
+                          x2=t.get(a["x2"]))
+        elif c.fn == "conv_wgrad":
+            # g is the gradient of the layer's pre-activation: every producer of an activation
+            # gradient applies the ReLU mask of the tensor it differentiates
+            k3.conv3d_bwd_weight(t[a["x"]], t[a["g"]], None, self.gw[c.layer], self.gb[c.layer], self._ws, x2=t.get(a["x2"]))
+        elif c.fn == "conv_dgrad":
+            k3.conv3d_bwd_data(t[a["g"]], None, self.w[c.layer], self.pk[c.layer], t[a["dx"]], dx2=t.get(a["dx2"]),
+                               dx_mask=t.get(a["mask"]))
+        elif c.fn == "pool_fwd":
+            k3.pool3d_fwd(t[a["x"]], t[a["y"]])
+        elif c.fn == "pool_bwd":
+            k3.pool3d_bwd(t[a["x"]], t[a["dy"]], t.get(a["add"]), t[a["dx"]], relu_mask=a["relu_mask"])
+        elif c.fn == "up_fwd":
+            k3.upconv3d_fwd(t[a["x"]], self.w[c.layer], self.pk[c.layer], self.b[c.layer], t[a["y"]])
+        elif c.fn == "up_wgrad":
+            k3.upconv3d_bwd_weight(t[a["x"]], t[a["dy"]], self.gw[c.layer], self.gb[c.layer], self._ws)
+        elif c.fn == "up_dgrad":
+            k3.upconv3d_bwd_data(t[a["dy"]], self.w[c.layer], self.pk[c.layer], t[a["dx"]], dx_mask=t.get(a["mask"]))
+        elif c.fn == "head":
+            k3.head_softmax_ce_fwd_bwd(t[a["a"]], self.w["head"], self.b["head"], t["labels"], self.loss, t[a["da"]],
+                                       self.gw["head"], self.gb["head"], None, self._ws, relu_mask=True)
+        else:
+            raise ValueError(c.fn)
+        if self._timing is not None:
+            ev = torch.cuda.Event(enable_timing=True)
+            ev.record()
+            self._timing.append(ev)
 
     # ------------------------------------------------------------------ the step
-    def step(self, x, labels, swap=False, prefetch_distance=2, keep_acts=False):
+    def step(self, x, labels, swap=False, budget=None, keep_acts=False, timing=False):
         """Forward + backward on x (N,D,H,W,cin) and uint8 labels (N,D,H,W).
 
         Fills the gradient buffers and self.loss (device scalar); returns self.loss.
-        With keep_acts=True (swap must be off) the forward activations are returned too."""
-        L = self.levels
-        if swap and self.lms is None:
+          swap=False        nothing leaves the GPU.
+          swap=True         the stored encoder activations spend their idle gaps in host memory, under
+                            the smallest budget that selection can run in.
+          swap=<Plan>       a plan from planner.plan_for_budget / planner.swap_all.
+        budget (bytes, with a plan; default: the plan's own peak) bounds the accounted device memory
+        of the step: device copies of swapped tensors are dropped only when an allocation needs the
+        room, oldest first.
+        With keep_acts=True (swap must be off) the forward activations are returned too.
+        With timing=True the per-call GPU durations (seconds) are left in self.call_seconds."""
+        prog = self.program(x.shape, keep_acts)
+        if swap is True:
+            swap = self._default_plan(prog)
+        plan = swap if swap else None
+        if plan is not None and budget is None:
+            budget = plan.peak_bytes
+        if keep_acts and plan is not None:
+            raise ValueError("keep_acts needs swap off")
+        if plan is not None and self.lms is None:
             self.lms = k3.lms_create(0)
-        if not swap and self.lms is not None:
-            k3.lms_sync(self.lms)
-        lms_saved = self.lms
-        if not swap:
-            self.lms = None
-        acts = {}
-        try:
-            # ---------------- forward, encoder
-            cur = x
-            for l in range(L):
-                a1 = self._conv(f"enc{l}.conv1", cur)
-                a2 = self._conv(f"enc{l}.conv2", a1)
-                swap_level = l < L - 1
-                self._slot(f"in{l}").t = cur
-                if swap_level:
-                    self._swap_out(f"in{l}", cur)
-                    self._swap_out(f"a1_{l}", a1)
-                else:
-                    self._slot(f"a1_{l}").t = a1
-                if l < L - 1:
-                    pooled = self._empty((a2.shape[0], a2.shape[1] // 2, a2.shape[2] // 2, a2.shape[3] // 2, a2.shape[4]))
-                    k3.pool3d_fwd(a2, pooled)
-                    self._swap_out(f"a2_{l}", a2)
-                    nxt = pooled
-                else:
-                    self._slot(f"a2_{l}").t = a2
-                    nxt = a2
-                if keep_acts:
-                    acts[f"enc{l}.a1"], acts[f"enc{l}.a2"] = a1, a2
-                    if l < L - 1:
-                        acts[f"enc{l}.pool"] = nxt
-                del a1, a2, cur
-                cur = nxt
-                self._poll()
-            del nxt
-            # ---------------- forward, decoder
-            if L >= 2:
-                self._prefetch(f"a2_{L - 2}")
-            for l in range(L - 2, -1, -1):
-                if l >= 1:
-                    self._prefetch(f"a2_{l - 1}")   # one level ahead of its skip-connection reader
-                name = f"dec{l}.up"
-                up = self._empty((cur.shape[0], cur.shape[1] * 2, cur.shape[2] * 2, cur.shape[3] * 2, self.w[name].shape[4]))
-                k3.upconv3d_fwd(cur, self.w[name], self.pk[name], self.b[name], up)
-                skip = self._get(f"a2_{l}")
-                a1 = self._conv(f"dec{l}.conv1", skip, x2=up)
-                a2 = self._conv(f"dec{l}.conv2", a1)
-                self._slot(f"dbelow{l}").t = cur
-                self._slot(f"dup{l}").t = up
-                self._slot(f"da1_{l}").t = a1
-                # a2 is kept only as the input of the next transposed conv (slot dbelow) or of the
-                # head: its own backward needs the gradient mask only, which the producer of that
-                # gradient applies
-                if keep_acts:
-                    acts[f"dec{l}.up"], acts[f"dec{l}.a1"], acts[f"dec{l}.a2"] = up, a1, a2
-                del up, a1, skip, cur
-                cur = a2
-                del a2
-                self._poll()
-            # ---------------- head: loss and the gradient of the last activation
-            d = self._empty(cur.shape)
-            ws = self._workspace(k3.head_workspace_bytes(cur))
-            k3.head_softmax_ce_fwd_bwd(cur, self.w["head"], self.b["head"], labels, self.loss, d,
-                                       self.gw["head"], self.gb["head"], None, ws, relu_mask=True)
-            del cur
-            # ---------------- backward: stage list, with prefetches issued `prefetch_distance` stages ahead
-            stages = [("dec", l) for l in range(0, L - 1)] + [("enc", l) for l in range(L - 1, -1, -1)]
+        need = self.workspace_bytes(prog)
+        if self._ws is None or self._ws.numel() < need:
+            self._ws = None
+            self._ws = torch.empty(need, device=self.dev, dtype=torch.uint8)
+        if self.lms is not None:
+            self._drain(False)
+        ins = prog.instructions(plan.gaps, plan.lead, plan.at) if plan is not None else prog.instructions()
+        ex = Executor(self, prog, budget=budget, eager=bool(plan is not None and plan.eager), fixed_bytes=self.fixed_bytes(prog))
+        self._timing = [] if timing else None
+        if timing:
+            start = torch.cuda.Event(enable_timing=True)
+            start.record()
+        ex.run(ins, {"x": x, "labels": labels})
+        self.last_run = ex
+        if timing:
+            torch.cuda.synchronize()
+            evs = [start] + self._timing
+            self.call_seconds = [evs[i].elapsed_time(evs[i + 1]) * 1e-3 for i in range(len(evs) - 1)]
+            self._timing = None
+        if self.lms is not None:
+            self.last_stats = k3.lms_get_stats(self.lms)
+        if keep_acts:
+            names = {}
+            for l in range(self.levels):
+                names[f"a1_{l}"], names[f"a2_{l}"], names[f"p_{l}"] = f"enc{l}.a1", f"enc{l}.a2", f"enc{l}.pool"
+                names[f"up_{l}"], names[f"da1_{l}"], names[f"da2_{l}"] = f"dec{l}.up", f"dec{l}.a1", f"dec{l}.a2"
+            return self.loss, {names[k]: v for k, v in ex.kept.items() if k in names}
+        return self.loss
 
-            def needs(stage):
-                kind, l = stage
-                if kind == "enc" and l < L - 1:
-                    return [f"a1_{l}", f"in{l}"]
-                return []
-            issued = set()
-            skip_grad = {}
-            for si, stage in enumerate(stages):
-                for sj in range(si, min(si + prefetch_distance + 1, len(stages))):
-                    for nm in needs(stages[sj]):
-                        if nm not in issued:
-                            self._prefetch(nm)
-                            issued.add(nm)
-                kind, l = stage
-                if kind == "dec":
-                    a1 = self._slots[f"da1_{l}"].t
-                    up, below = self._slots[f"dup{l}"].t, self._slots[f"dbelow{l}"].t
-                    skip = self._get(f"a2_{l}")
-                    # d already carries the ReLU mask of a2 (applied by its producer)
-                    d1, _ = self._conv_bwd(f"dec{l}.conv2", a1, None, d, dx_mask=a1)
-                    del d, a1
-                    self._slots[f"da1_{l}"].t = None   # not read again: free it before the next allocations
-                    dskip, dup = self._conv_bwd(f"dec{l}.conv1", skip, up, d1)
-                    del d1
-                    skip_grad[l] = dskip
-                    name = f"dec{l}.up"
-                    ws = self._workspace(k3.upconv3d_bwd_weight_workspace_bytes(below, dup))
-                    k3.upconv3d_bwd_weight(below, dup, self.gw[name], self.gb[name], ws)
-                    d = self._empty(below.shape)
-                    k3.upconv3d_bwd_data(dup, self.w[name], self.pk[name], d, dx_mask=below)
-                    del dup, dskip, up, below, skip
-                    for nm in (f"da1_{l}", f"dup{l}", f"dbelow{l}"):
-                        self._slots[nm].t = None
-                else:
-                    a2 = self._get(f"a2_{l}")
-                    if l < L - 1:
-                        dd = self._empty(a2.shape)
-                        k3.pool3d_bwd(a2, d, skip_grad.pop(l), dd, relu_mask=True)
-                        d = dd
-                        del dd
-                    a1 = self._get(f"a1_{l}")
-                    d1, _ = self._conv_bwd(f"enc{l}.conv2", a1, None, d, dx_mask=a1)
-                    del d
-                    inp = self._get(f"in{l}")
-                    d, _ = self._conv_bwd(f"enc{l}.conv1", inp, None, d1, need_dx=(l > 0))
-                    del d1, a1, a2, inp
-                    for nm in (f"a2_{l}", f"a1_{l}", f"in{l}"):
-                        self._drop(nm)
-                self._poll()
-            if self.lms is not None:
-                st = k3.lms_get_stats(self.lms)
-                self.last_stats = st
-        finally:
-            self.lms = lms_saved
-        return (self.loss, acts) if keep_acts else self.loss
+    def _default_plan(self, prog):
+        if getattr(prog, "_encoder_plan", None) is None:
+            prog._encoder_plan = planner.swap_all(prog, only=planner.is_encoder_activation, fixed_bytes=self.fixed_bytes(prog))
+        return prog._encoder_plan
+
+    def reset(self):
+        """Wait for the copy streams and return every swap handle (after a step that ended in an error)."""
+        if self.lms is not None:
+            k3.lms_sync(self.lms)
+            self._drain(True)
+
+    def close(self):
+        if self.lms is not None:
+            torch.cuda.synchronize()
+            k3.lms_sync(self.lms)
+            self._drain(True)
+        for ptr, _ in self._host.values():
+            k3.lms_host_free(ptr)
+        self._host = {}
+        if self.lms is not None:
+            k3.lms_destroy(self.lms)
+            self.lms = None

@@ -177,6 +177,8 @@ int mock_swap_out(void *c, const void *dev, size_t n, void *host, void *stream, 
 int mock_swap_out_done(void *c, int h, int *done) { return ((Ctx *)c)->eng.swap_out_done(h, done); }
 int mock_release_after(void *c, int h, void *stream) { return ((Ctx *)c)->eng.release_after(h, stream); }
 int mock_prefetch_in(void *c, int h, void *dev, void *stream) { return ((Ctx *)c)->eng.prefetch_in(h, dev, stream); }
+int mock_prefetch_start(void *c, int h, void *dev, void *stream) { return ((Ctx *)c)->eng.prefetch_start(h, dev, stream); }
+int mock_evict(void *c, int h, void *stream) { return ((Ctx *)c)->eng.evict(h, stream); }
 int mock_wait_in(void *c, int h, void *stream) { return ((Ctx *)c)->eng.wait_in(h, stream); }
 int mock_release(void *c, int h) { return ((Ctx *)c)->eng.release(h); }
 int mock_sync(void *c) { return ((Ctx *)c)->eng.sync(); }

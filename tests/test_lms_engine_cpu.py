@@ -40,6 +40,8 @@ def mock(tmp_path_factory):
     L.mock_release_after.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
     L.mock_prefetch_in.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
     L.mock_wait_in.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
+    L.mock_prefetch_start.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p, ctypes.c_void_p]
+    L.mock_evict.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.c_void_p]
     L.mock_release.argtypes = [ctypes.c_void_p, ctypes.c_int]
     L.mock_sync.argtypes = [ctypes.c_void_p]
     L.mock_state.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
@@ -217,4 +219,55 @@ def test_many_handles_recycle(mock):
     h = ctypes.c_int(-1)
     assert mock.mock_swap_out(e.c, e.dev.ctypes.data, 64, e.host.ctypes.data, e.compute, ctypes.byref(h)) == OK
     assert h.value in hs
+    e.close()
+
+
+def test_prefetch_start_overlaps_until_wait_in(mock):
+    """prefetch_start does not fence the compute stream: a kernel enqueued after it but before
+    wait_in may run before the copy lands, one enqueued after wait_in may not."""
+    e = Env(mock)
+    h = ctypes.c_int(-1)
+    assert mock.mock_swap_out(e.c, e.dev.ctypes.data, e.n, e.host.ctypes.data, e.compute, ctypes.byref(h)) == OK
+    mock.mock_pump(e.c)
+    assert mock.mock_release_after(e.c, h.value, e.compute) == OK
+    dst = np.zeros(e.n, dtype=np.uint8)
+    mock.mock_enqueue_fill(e.c, e.compute, dst.ctypes.data, 0x44, e.n)        # earlier user of the block
+    assert mock.mock_prefetch_start(e.c, h.value, dst.ctypes.data, e.compute) == OK
+    assert e.state(h.value) == IN_IN_FLIGHT
+    assert mock.mock_wait_in(e.c, h.value, e.compute) == OK
+    probe = np.zeros(1, dtype=np.uint8)
+    mock.mock_enqueue_fill(e.c, e.compute, probe.ctypes.data, 1, 1)           # "consumer"
+    mock.mock_pump(e.c)
+    assert np.array_equal(dst, e.orig)      # the copy landed after the 0x44 fill, not before
+    assert probe[0] == 1 and e.state(h.value) == RESIDENT
+    assert mock.mock_release(e.c, h.value) == OK
+    e.close()
+
+
+def test_evict_keeps_the_host_copy_and_allows_a_second_prefetch(mock):
+    e = Env(mock)
+    h = ctypes.c_int(-1)
+    assert mock.mock_swap_out(e.c, e.dev.ctypes.data, e.n, e.host.ctypes.data, e.compute, ctypes.byref(h)) == OK
+    assert mock.mock_evict(e.c, h.value, e.compute) == E_STATE                # still going out
+    mock.mock_pump(e.c)
+    assert mock.mock_evict(e.c, h.value, e.compute) == E_STATE                # ON_HOST: nothing to drop
+    assert mock.mock_release_after(e.c, h.value, e.compute) == OK
+    first = np.zeros(e.n, dtype=np.uint8)
+    assert mock.mock_prefetch_start(e.c, h.value, first.ctypes.data, e.compute) == OK
+    # evicted while the copy-in is still in flight: the stream is fenced behind the copy, so a
+    # later overwrite of the block cannot be overtaken by it
+    assert mock.mock_evict(e.c, h.value, e.compute) == OK
+    assert e.state(h.value) == ON_HOST
+    mock.mock_enqueue_fill(e.c, e.compute, first.ctypes.data, 0x55, e.n)      # block reused
+    mock.mock_pump(e.c)
+    assert np.all(first == 0x55)
+    second = np.zeros(e.n, dtype=np.uint8)
+    assert mock.mock_prefetch_in(e.c, h.value, second.ctypes.data, e.compute) == OK
+    mock.mock_pump(e.c)
+    assert np.array_equal(second, e.orig)
+    st = e.stats()
+    assert st[0] == e.n and st[1] == 2 * e.n and st[2] == 1 and st[3] == 2   # one copy out, two in
+    assert mock.mock_evict(e.c, h.value, e.compute) == OK                     # RESIDENT -> ON_HOST
+    assert mock.mock_evict(e.c, 999, e.compute) == E_BADARG
+    assert mock.mock_release(e.c, h.value) == OK
     e.close()

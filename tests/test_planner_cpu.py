@@ -1,0 +1,151 @@
+"""Host-only tests of the step program, the interpreter's memory accounting and the swap planner."""
+import pytest
+
+from paper_1811_12174_amd import planner
+from paper_1811_12174_amd.executor import Executor, OutOfBudget
+from paper_1811_12174_amd.program import unet_program
+
+
+def _prog(levels=3, base=8, n=1, s=16):
+    return unet_program(base, 1, levels, n, s, s, s)
+
+
+@pytest.mark.parametrize("levels", [1, 2, 3, 4])
+def test_program_is_well_formed(levels):
+    """Every call finds its tensors on the device (the simulator asserts it), every step-owned
+    tensor is allocated once and freed once after its last use, nothing is left at the end."""
+    p = _prog(levels)
+    # per level: 2 conv + (pool) forward, 2 x (wgrad + dgrad) (+ pool) backward, minus the input's dgrad;
+    # per decoder level: up + 2 conv forward, 3 x (wgrad + dgrad) backward; the head
+    assert len(p.calls) == 6 * levels - 1 + 2 * (levels - 1) + 9 * (levels - 1) + 1
+    ins = p.instructions()
+    allocs = [a for op, a in ins if op == "alloc"]
+    frees = [a for op, a in ins if op == "free"]
+    owned = [t for t, i in p.tensors.items() if not i.external]
+    assert sorted(allocs) == sorted(owned) == sorted(frees)
+    pos = {(op, a if op != "call" else id(a)): k for k, (op, a) in enumerate(ins)}
+    for k, (op, a) in enumerate(ins):
+        if op == "call":
+            for t in a.touches():
+                if not p.tensors[t].external:
+                    assert pos[("alloc", t)] < k < pos[("free", t)]
+    ex, be = planner.simulate(p, fixed_bytes=123)
+    assert ex.used == 123 and ex.peak > 123
+
+
+def test_single_level_peak_by_hand():
+    # x -> a1 -> a2 -> head(g:a2) -> [a2 freed] wgrad2, dgrad2 (g:a1) -> [g:a2, a1... freed] wgrad1
+    # live sets: {a1}, {a1,a2}, {a1,a2,g:a2} = 3 tensors, then {a1,g:a2,g:a1} = 3: peak is 3 tensors
+    p = unet_program(8, 1, 1, 2, 8, 8, 8)
+    one = 2 * 8 * 8 * 8 * 8 * 2
+    assert planner.simulate(p)[0].peak == 3 * one
+
+
+def test_gaps_of_the_stored_activations():
+    p = _prog(3)
+    gaps = {(g.tensor, g.index): g for g in p.gaps()}
+    uses = p.uses()
+    # a1_0: written by conv1, read by conv2, then idle until its weight-gradient / mask use in the last stage
+    assert uses["a1_0"][:2] == [0, 1] and ("a1_0", 1) in gaps and gaps[("a1_0", 1)].last > len(p.calls) - 6
+    # a2_0 (skip connection): idle encoder -> decoder forward, and again decoder backward -> pool backward
+    a2 = [(g.first, g.last) for k, g in sorted(gaps.items()) if k[0] == "a2_0"]
+    names = [[(p.calls[a].fn, p.calls[a].layer), (p.calls[b].fn, p.calls[b].layer)] for a, b in a2]
+    assert names == [[("pool_fwd", None), ("conv_fwd", "dec0.conv1")],
+                     [("conv_fwd", "dec0.conv1"), ("conv_wgrad", "dec0.conv1")],
+                     [("conv_wgrad", "dec0.conv1"), ("pool_bwd", None)]]
+    assert all(not p.tensors[g.tensor].external for g in gaps.values())
+
+
+def test_rewrite_places_swap_instructions():
+    p = _prog(3)
+    gs = [g for g in p.gaps() if g.tensor in ("a1_0", "a2_0")]
+    ins = p.instructions(gs, lead=2)
+    ops = [(op, a) for op, a in ins if op != "call" and a in ("a1_0", "a2_0")]
+    assert sum(1 for op, a in ops if op == "swap_out") == 2            # once per tensor, however many gaps
+    assert sum(1 for op, a in ops if op == "evict") == len(gs) == sum(1 for op, a in ops if op == "prefetch")
+    # per tensor the order is alloc, swap_out, (evict, prefetch, wait)*, free
+    for t in ("a1_0", "a2_0"):
+        seq = [op for op, a in ops if a == t]
+        assert seq[0] == "alloc" and seq[1] == "swap_out" and seq[-1] == "free"
+        body = seq[2:-1]
+        assert body == ["evict", "prefetch", "wait"] * (len(body) // 3)
+    # a wait sits directly in front of (the allocations of) the call that reads the tensor
+    for k, (op, a) in enumerate(ins):
+        if op == "wait":
+            nxt = next(x for x in ins[k:] if x[0] == "call")[1]
+            assert a in nxt.touches()
+
+
+def test_budget_is_respected_and_loose_budgets_swap_nothing():
+    p = unet_program(32, 1, 4, 1, 64, 64, 64)
+    need = planner.simulate(p)[0].peak
+    plan = planner.plan_for_budget(p, need)
+    assert plan.gaps == [] and plan.bytes_out == 0 and plan.seconds == plan.no_swap_seconds
+    last_time = plan.seconds
+    for frac in (0.95, 0.85, 0.75):
+        plan = planner.plan_for_budget(p, int(frac * need))
+        assert plan.peak_bytes <= int(frac * need) and plan.gaps
+        assert plan.seconds >= plan.no_swap_seconds
+        # the executor under that budget, on a fresh simulator, reproduces the plan's figures
+        ex, be = planner.simulate(p, plan.gaps, plan.lead, int(frac * need), at=plan.at)
+        assert (ex.peak, ex.bytes_out, ex.bytes_in) == (plan.peak_bytes, plan.bytes_out, plan.bytes_in)
+        assert abs(be.seconds - plan.seconds) < 1e-12
+        last_time = plan.seconds
+    with pytest.raises(OutOfBudget):
+        planner.plan_for_budget(p, int(0.3 * need))
+    with pytest.raises(OutOfBudget):
+        planner.simulate(p, budget=need - 1)
+
+
+def test_fixed_bytes_count_against_the_budget():
+    p = _prog(3)
+    need = planner.simulate(p)[0].peak
+    assert planner.simulate(p, fixed_bytes=1000)[0].peak == need + 1000
+    with pytest.raises(OutOfBudget):
+        planner.simulate(p, budget=need + 999, fixed_bytes=1000)
+    planner.simulate(p, budget=need + 1000, fixed_bytes=1000)
+
+
+def test_lazy_and_eager_drops():
+    p = unet_program(32, 1, 4, 1, 64, 64, 64)
+    gaps = [g for g in p.gaps() if planner.is_encoder_activation(g.tensor)]
+    lazy, _ = planner.simulate(p, gaps, 2)                       # no budget: nothing is ever dropped
+    eager, be_e = planner.simulate(p, gaps, 2, eager=True)
+    none, be_n = planner.simulate(p)
+    assert lazy.peak == none.peak and lazy.releases == 0 and lazy.bytes_in == 0 and lazy.bytes_out > 0
+    assert eager.peak < none.peak and eager.releases > 0 and eager.bytes_in > 0
+    tight, be_t = planner.simulate(p, gaps, 2, budget=eager.peak)  # lazy drops reach the eager footprint
+    assert tight.peak <= eager.peak
+    assert be_t.seconds <= be_e.seconds + 1e-12                    # ... and never wait more than eager drops
+    plan = planner.swap_all(p, only=planner.is_encoder_activation)   # same footprint, prefetch points advanced
+    floor = planner.simulate(p, gaps, 1, eager=True)[0].peak
+    assert plan.peak_bytes <= floor and plan.seconds <= planner.simulate(p, gaps, 1, budget=floor)[1].seconds
+    ex, be = planner.simulate(p, plan.gaps, plan.lead, floor, at=plan.at)
+    assert ex.peak == plan.peak_bytes and abs(be.seconds - plan.seconds) < 1e-12
+
+
+def test_simulated_stream_ordering():
+    """A device copy is dropped only after its copy-out (the compute clock waits), a copy-in
+    starts after the copy-out and after the compute point it was issued at, and a reader waits
+    for the copy-in: forced with a slow link."""
+    from paper_1811_12174_amd.program import TensorInfo
+    be = planner.SimBackend(link=1e6)
+    info = TensorInfo("t", (1, 1, 1, 1, 500000), 2)               # 1 MB: one second on this link
+    be.tc = 0.25
+    h = be.swap_out(info, None)
+    assert h["out"] == pytest.approx(1.25)
+    be.release_after(h)
+    assert be.tc == pytest.approx(1.25) and be.stall == pytest.approx(1.0)
+    be.tc = 1.5
+    be.prefetch_start(h, None)
+    assert h["in"] == pytest.approx(2.5)
+    be.tc = 2.0                                                    # kernels overlapped the copy-in
+    be.wait_in(h)
+    assert be.tc == pytest.approx(2.5) and be.stall == pytest.approx(1.5)
+    assert be.seconds == pytest.approx(2.5)
+
+
+def test_cost_model_orders_of_magnitude():
+    p = unet_program(64, 1, 4, 2, 256, 256, 256)
+    t = planner.simulate(p)[1].seconds
+    assert 0.1 < t < 0.25      # measured on the GPU: 0.145 s
