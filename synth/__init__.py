@@ -14,11 +14,12 @@ patterns.
 from .rng import (SEED, uniform, normal, f32_to_bf16_bits, bf16_bits_to_f32,
                   round_to_bf16)
 from .tensors import (conv_weights, upconv_weights, head_weights, activations,
-                      volume_field, ellipsoid_labels, unet_plan, unet_params)
+                      volume_field, ellipsoid_labels, unet_plan, unet_params, bp_plan, bp_params,
+                      inverse_frequency_class_weights)
 
 __all__ = [
     "SEED", "uniform", "normal", "f32_to_bf16_bits", "bf16_bits_to_f32",
     "round_to_bf16", "conv_weights", "upconv_weights", "head_weights",
     "activations", "volume_field", "ellipsoid_labels", "unet_plan",
-    "unet_params",
+    "unet_params", "bp_plan", "bp_params", "inverse_frequency_class_weights",
 ]
