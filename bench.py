@@ -355,7 +355,7 @@ def bench_unet(args, base, size, n, swap, label, budget_gb=0.0):
     if budget_gb:
         # The situation the paper's LMS exists for: a device-memory limit below what the step
         # needs without swapping.  The planner picks what leaves the GPU; the limit is enforced
-        # by the step's own accounting and, 20 % above it, by the allocator.
+        # by the step's own slab allocator; allocator_peak_gb is what torch's allocator really handed out.
         budget = int(budget_gb * 1e9)
         leg = {"device_budget_gb": budget_gb}
         try:
@@ -372,25 +372,6 @@ def bench_unet(args, base, size, n, swap, label, budget_gb=0.0):
         if plan is not None:
             leg.update(swap_leg(plan, budget))
             leg["swap_under_budget"] = "completed"
-            # The timed steps above are bounded by the step's accounting (allocator_peak_gb shows
-            # what the allocator really held).  Two more steps run under a hard limit of the
-            # allocator itself, 20 % above the budget because it splits and rounds blocks; they
-            # are not timed: a fresh limit makes the block cache churn for a few steps.
-            total = torch.cuda.get_device_properties(0).total_memory
-            torch.cuda.synchronize()
-            torch.cuda.empty_cache()
-            outside = torch.cuda.memory_allocated() - fixed
-            leg["allocator_limit_gb"] = round(1.2 * budget / 1e9, 3)
-            torch.cuda.set_per_process_memory_fraction(min(1.0, (outside + 1.2 * budget) / total))
-            try:
-                for _ in range(2):
-                    net.step(x, lab, swap=plan, budget=budget)
-                torch.cuda.synchronize()
-                leg["under_allocator_limit"] = "completed"
-            except torch.cuda.OutOfMemoryError:
-                leg["under_allocator_limit"] = "allocator out of memory"
-            finally:
-                torch.cuda.set_per_process_memory_fraction(1.0)
         res["planned_for_budget"] = leg
     net.close()
     return res

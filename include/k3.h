@@ -170,6 +170,34 @@ int k3_head_softmax_ce_fwd_bwd(const k3_tensor *ad, const void *a, const float *
                                const uint8_t *labels, float *loss, void *da, int relu_mask,
                                float *dWh, float *dbh, float *logits, void *ws, size_t ws_bytes,
                                void *stream);
+/* The same with class-weighted voxels (section 4.1: the weight of voxels is adjusted for the
+ * class imbalance of the training set): voxel v counts w_v = class_w[label_v],
+ *   loss = -(1/V) sum_v w_v log p[v, label_v];   dz = w_v (p - onehot(label)) / V.
+ * The normalisation by the voxel count V (not by the sum of the weights) is a reading: the
+ * paper does not give it.  class_w: three fp32 values, dev. */
+int k3_head_softmax_wce_fwd_bwd(const k3_tensor *ad, const void *a, const float *wh, const float *bh,
+                                const uint8_t *labels, const float *class_w, float *loss, void *da,
+                                int relu_mask, float *dWh, float *dbh, float *logits, void *ws,
+                                size_t ws_bytes, void *stream);
+/* Inference read-out (section 4.1: the classification emitted is the class with the
+ * maximum likelihood): classes[v] = argmax_k z[v,k] of the head's logits, lowest k on ties,
+ * decided on the fp32 logits the kernel computes; logits: optional fp32 [V][3] (NULL to
+ * skip).  a: dev, ad->dtype; wh [C][3], bh [3] (may be NULL): fp32 dev; classes: uint8 dev. */
+int k3_head_classify(const k3_tensor *ad, const void *a, const float *wh, const float *bh, uint8_t *classes,
+                     float *logits, void *stream);
+
+/* ------------------------------------------------------------------ up-sampling layer
+ * The up-sampling layer that follows each decoder convolution of the section-4.1 model,
+ * read as nearest-neighbour up-sampling by 2 per axis (the paper does not name the
+ * interpolation):  y[n, 2d+i, 2h+j, 2w+k, c] = x[n, d, h, w, c] for i, j, k in {0, 1}.
+ * Backward (the adjoint): dx[n,d,h,w,c] = sum_{i,j,k} dy[n, 2d+i, 2h+j, 2w+k, c], summed in
+ * fp32 in a fixed order; when x_mask is not NULL it is the stored ReLU output x and dx is
+ * zeroed where x <= 0 (see k3_conv3d_bwd_data, dx_mask).  Descriptors: x / dx are
+ * (n, d, h, w, c), y / dy are (n, 2d, 2h, 2w, c), same dtype (K3_E_SHAPE otherwise).
+ * All pointers dev; x_mask has the shape of dx. */
+int k3_upsample3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *yd, void *y, void *stream);
+int k3_upsample3d_bwd(const k3_tensor *dyd, const void *dy, const void *x_mask, const k3_tensor *dxd, void *dx,
+                      void *stream);
 
 /* ------------------------------------------------------------------ weight update
  * Stochastic gradient descent, the weight-update algorithm the paper's training runs on

@@ -19,8 +19,10 @@ template <typename T>
 __global__ __launch_bounds__(256) void head_kernel(const T *__restrict__ a, const float *__restrict__ wh,
                                                   const float *__restrict__ bh, const uint8_t *__restrict__ labels,
                                                   T *__restrict__ da, float *__restrict__ logits,
-                                                  float *__restrict__ partial, int64_t V, int C, float invV, int relu_mask)
+                                                  float *__restrict__ partial, int64_t V, int C, float invV, int relu_mask,
+                                                  const float *__restrict__ cw)
 {
+    const float cw0 = cw ? cw[0] : 1.f, cw1 = cw ? cw[1] : 1.f, cw2 = cw ? cw[2] : 1.f;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
     const int rowb = C * (int)sizeof(T) + 4;  // padded row: consecutive voxels start in consecutive banks
     unsigned char *as = smem;
@@ -67,10 +69,12 @@ __global__ __launch_bounds__(256) void head_kernel(const T *__restrict__ a, cons
             float inv = 1.f / den;
             int lab = labels[v0 + tid];
             float zl = lab == 0 ? z0 : (lab == 1 ? z1 : z2);
-            lossacc += (m - zl) + logf(den);
-            float d0 = (e0 * inv - (lab == 0 ? 1.f : 0.f)) * invV;
-            float d1 = (e1 * inv - (lab == 1 ? 1.f : 0.f)) * invV;
-            float d2 = (e2 * inv - (lab == 2 ? 1.f : 0.f)) * invV;
+            const float wl = lab == 0 ? cw0 : (lab == 1 ? cw1 : cw2);   // class weight of this voxel
+            const float sc = invV * wl;
+            lossacc += wl * ((m - zl) + logf(den));
+            float d0 = (e0 * inv - (lab == 0 ? 1.f : 0.f)) * sc;
+            float d1 = (e1 * inv - (lab == 1 ? 1.f : 0.f)) * sc;
+            float d2 = (e2 * inv - (lab == 2 ? 1.f : 0.f)) * sc;
             db0 += d0; db1 += d1; db2 += d2;
             dzs[tid * 4 + 0] = d0; dzs[tid * 4 + 1] = d1; dzs[tid * 4 + 2] = d2;
             T *drow = reinterpret_cast<T *>(ds + tid * rowb);
@@ -134,9 +138,10 @@ __global__ __launch_bounds__(256) void head_stream_kernel(const bf16_t *__restri
                                                          const float *__restrict__ bh,
                                                          const uint8_t *__restrict__ labels, bf16_t *__restrict__ da,
                                                          float *__restrict__ logits, float *__restrict__ partial,
-                                                         int64_t V, float invV, int relu_mask)
+                                                         int64_t V, float invV, int relu_mask, const float *__restrict__ cw)
 {
     constexpr int C = 16 * LPV;
+    const float cw0 = cw ? cw[0] : 1.f, cw1 = cw ? cw[1] : 1.f, cw2 = cw ? cw[2] : 1.f;
     constexpr int VPB = 256 / LPV;   // voxels per workgroup and step
     __shared__ float red[256 * 49];
     const int tid = threadIdx.x, sub = tid % LPV;
@@ -183,12 +188,14 @@ __global__ __launch_bounds__(256) void head_stream_kernel(const bf16_t *__restri
         const float e0 = expf(z0 - mx), e1 = expf(z1 - mx), e2 = expf(z2 - mx);
         const float den = e0 + e1 + e2, inv = 1.f / den;
         const float zl = lab == 0 ? z0 : (lab == 1 ? z1 : z2);
-        float d0 = (e0 * inv - (lab == 0 ? 1.f : 0.f)) * invV;
-        float d1 = (e1 * inv - (lab == 1 ? 1.f : 0.f)) * invV;
-        float d2 = (e2 * inv - (lab == 2 ? 1.f : 0.f)) * invV;
+        const float wl = lab == 0 ? cw0 : (lab == 1 ? cw1 : cw2);   // class weight of this voxel
+        const float sc = invV * wl;
+        float d0 = (e0 * inv - (lab == 0 ? 1.f : 0.f)) * sc;
+        float d1 = (e1 * inv - (lab == 1 ? 1.f : 0.f)) * sc;
+        float d2 = (e2 * inv - (lab == 2 ? 1.f : 0.f)) * sc;
         if (!on) d0 = d1 = d2 = 0.f;
         if (on && sub == 0) {
-            lossacc += (mx - zl) + logf(den);
+            lossacc += wl * ((mx - zl) + logf(den));
             db0 += d0; db1 += d1; db2 += d2;
             if (logits) {
                 float *lp = logits + v * 3;
@@ -286,9 +293,9 @@ extern "C" int k3_head_workspace_bytes(const k3_tensor *ad, size_t *bytes)
     return K3_OK;
 }
 
-extern "C" int k3_head_softmax_ce_fwd_bwd(const k3_tensor *ad, const void *a, const float *wh, const float *bh,
-                                          const uint8_t *labels, float *loss, void *da, int relu_mask, float *dWh,
-                                          float *dbh, float *logits, void *ws, size_t ws_bytes, void *stream)
+static int head_run(const k3_tensor *ad, const void *a, const float *wh, const float *bh, const uint8_t *labels,
+                    const float *cw, float *loss, void *da, int relu_mask, float *dWh, float *dbh, float *logits, void *ws,
+                    size_t ws_bytes, void *stream)
 {
     size_t need = 0;
     int rc = k3_head_workspace_bytes(ad, &need);
@@ -310,23 +317,150 @@ extern "C" int k3_head_softmax_ce_fwd_bwd(const k3_tensor *ad, const void *a, co
         float *pw = (float *)ws;
         const int rm = relu_mask ? 1 : 0;
         switch (C / 16) {
-        case 1: head_stream_kernel<1><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm); break;
-        case 2: head_stream_kernel<2><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm); break;
-        case 4: head_stream_kernel<4><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm); break;
-        case 8: head_stream_kernel<8><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm); break;
-        default: head_stream_kernel<16><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm); break;
+        case 1: head_stream_kernel<1><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm, cw); break;
+        case 2: head_stream_kernel<2><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm, cw); break;
+        case 4: head_stream_kernel<4><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm, cw); break;
+        case 8: head_stream_kernel<8><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm, cw); break;
+        default: head_stream_kernel<16><<<nb, 256, 0, st>>>(ap, wh, bh, labels, dp, logits, pw, V, invV, rm, cw); break;
         }
     } else if (ad->dtype == K3_BF16) {
         K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&head_kernel<bf16_t>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        head_kernel<bf16_t><<<nb, 256, lds, st>>>((const bf16_t *)a, wh, bh, labels, (bf16_t *)da, logits, (float *)ws, V, C, invV, relu_mask ? 1 : 0);
+        head_kernel<bf16_t><<<nb, 256, lds, st>>>((const bf16_t *)a, wh, bh, labels, (bf16_t *)da, logits, (float *)ws, V, C, invV, relu_mask ? 1 : 0, cw);
     } else {
         K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&head_kernel<float>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds));
-        head_kernel<float><<<nb, 256, lds, st>>>((const float *)a, wh, bh, labels, (float *)da, logits, (float *)ws, V, C, invV, relu_mask ? 1 : 0);
+        head_kernel<float><<<nb, 256, lds, st>>>((const float *)a, wh, bh, labels, (float *)da, logits, (float *)ws, V, C, invV, relu_mask ? 1 : 0, cw);
     }
     K3_LAUNCH_CHECK();
     head_reduce_kernel<<<C * 3 + 4, 256, 0, st>>>((const float *)ws, nb, C, invV, dWh, dbh, loss);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
+extern "C" int k3_head_softmax_ce_fwd_bwd(const k3_tensor *ad, const void *a, const float *wh, const float *bh,
+                                          const uint8_t *labels, float *loss, void *da, int relu_mask, float *dWh,
+                                          float *dbh, float *logits, void *ws, size_t ws_bytes, void *stream)
+{
+    return head_run(ad, a, wh, bh, labels, nullptr, loss, da, relu_mask, dWh, dbh, logits, ws, ws_bytes, stream);
+}
+
+extern "C" int k3_head_softmax_wce_fwd_bwd(const k3_tensor *ad, const void *a, const float *wh, const float *bh,
+                                           const uint8_t *labels, const float *class_w, float *loss, void *da,
+                                           int relu_mask, float *dWh, float *dbh, float *logits, void *ws,
+                                           size_t ws_bytes, void *stream)
+{
+    if (!class_w) return K3_E_BADARG;
+    return head_run(ad, a, wh, bh, labels, class_w, loss, da, relu_mask, dWh, dbh, logits, ws, ws_bytes, stream);
+}
+
+namespace k3 {
+
+// Inference read-out: logits of the 1x1x1 head and the most likely class (lowest index on ties).
+// LPV lanes share a voxel (16 channels each, 32-byte loads), as in head_stream_kernel.
+template <int LPV>
+__global__ __launch_bounds__(256) void head_classify_stream_kernel(const bf16_t *__restrict__ a, const float *__restrict__ wh,
+                                                                  const float *__restrict__ bh, uint8_t *__restrict__ cls,
+                                                                  float *__restrict__ logits, int64_t V)
+{
+    constexpr int C = 16 * LPV;
+    constexpr int VPB = 256 / LPV;
+    const int tid = threadIdx.x, sub = tid % LPV;
+    float w0[16], w1[16], w2[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        w0[i] = wh[(sub * 16 + i) * 3 + 0];
+        w1[i] = wh[(sub * 16 + i) * 3 + 1];
+        w2[i] = wh[(sub * 16 + i) * 3 + 2];
+    }
+    const float b0 = bh ? bh[0] : 0.f, b1 = bh ? bh[1] : 0.f, b2 = bh ? bh[2] : 0.f;
+    const int64_t nstep = (V + VPB - 1) / VPB;
+    for (int64_t st = blockIdx.x; st < nstep; st += gridDim.x) {
+        const int64_t v = st * VPB + tid / LPV;
+        const bool on = v < V;
+        const int64_t vv = on ? v : V - 1;
+        const uint4 *src = reinterpret_cast<const uint4 *>(a + vv * C + sub * 16);
+        const uint4 r0 = src[0], r1 = src[1];
+        const uint32_t raw[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
+        float z0 = 0.f, z1 = 0.f, z2 = 0.f;
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+            const float lo = __uint_as_float(raw[i] << 16), hi = __uint_as_float(raw[i] & 0xffff0000u);
+            z0 += lo * w0[2 * i]; z1 += lo * w1[2 * i]; z2 += lo * w2[2 * i];
+            z0 += hi * w0[2 * i + 1]; z1 += hi * w1[2 * i + 1]; z2 += hi * w2[2 * i + 1];
+        }
+#pragma unroll
+        for (int m = 1; m < LPV; m <<= 1) {
+            z0 += __shfl_xor(z0, m);
+            z1 += __shfl_xor(z1, m);
+            z2 += __shfl_xor(z2, m);
+        }
+        z0 += b0; z1 += b1; z2 += b2;
+        if (on && sub == 0) {
+            cls[v] = (uint8_t)(z1 > z0 ? (z2 > z1 ? 2 : 1) : (z2 > z0 ? 2 : 0));
+            if (logits) {
+                float *lp = logits + v * 3;
+                lp[0] = z0; lp[1] = z1; lp[2] = z2;
+            }
+        }
+    }
+}
+
+// Any dtype / channel count: one thread per voxel.
+template <typename T>
+__global__ __launch_bounds__(256) void head_classify_kernel(const T *__restrict__ a, const float *__restrict__ wh,
+                                                           const float *__restrict__ bh, uint8_t *__restrict__ cls,
+                                                           float *__restrict__ logits, int64_t V, int C)
+{
+    const int64_t stride = (int64_t)gridDim.x * blockDim.x;
+    for (int64_t v = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; v < V; v += stride) {
+        const T *row = a + v * C;
+        float z0 = bh ? bh[0] : 0.f, z1 = bh ? bh[1] : 0.f, z2 = bh ? bh[2] : 0.f;
+        for (int c = 0; c < C; ++c) {
+            const float av = elem<T>::ld(row + c);
+            z0 += av * wh[c * 3 + 0];
+            z1 += av * wh[c * 3 + 1];
+            z2 += av * wh[c * 3 + 2];
+        }
+        cls[v] = (uint8_t)(z1 > z0 ? (z2 > z1 ? 2 : 1) : (z2 > z0 ? 2 : 0));
+        if (logits) {
+            float *lp = logits + v * 3;
+            lp[0] = z0; lp[1] = z1; lp[2] = z2;
+        }
+    }
+}
+
+}  // namespace k3
+
+extern "C" int k3_head_classify(const k3_tensor *ad, const void *a, const float *wh, const float *bh, uint8_t *classes,
+                                float *logits, void *stream)
+{
+    if (!desc_ok(ad)) return K3_E_BADARG;
+    if (!a || !wh || !classes) return K3_E_BADARG;
+    const int C = (int)ad->c;
+    if (ad->c > 4096) return K3_E_UNSUPPORTED;
+    const int64_t V = voxels(ad);
+    hipStream_t st = (hipStream_t)stream;
+    if (ad->dtype == K3_BF16 && (C == 16 || C == 32 || C == 64 || C == 128 || C == 256)) {
+        const int lpv = C / 16;
+        const int64_t want = (V + 256 / lpv - 1) / (256 / lpv);
+        const int nb = (int)(want < 4096 ? want : 4096);
+        const bf16_t *ap = (const bf16_t *)a;
+        switch (lpv) {
+        case 1: head_classify_stream_kernel<1><<<nb, 256, 0, st>>>(ap, wh, bh, classes, logits, V); break;
+        case 2: head_classify_stream_kernel<2><<<nb, 256, 0, st>>>(ap, wh, bh, classes, logits, V); break;
+        case 4: head_classify_stream_kernel<4><<<nb, 256, 0, st>>>(ap, wh, bh, classes, logits, V); break;
+        case 8: head_classify_stream_kernel<8><<<nb, 256, 0, st>>>(ap, wh, bh, classes, logits, V); break;
+        default: head_classify_stream_kernel<16><<<nb, 256, 0, st>>>(ap, wh, bh, classes, logits, V); break;
+        }
+    } else {
+        const int64_t want = (V + 255) / 256;
+        const int nb = (int)(want < 4096 ? want : 4096);
+        if (ad->dtype == K3_BF16)
+            head_classify_kernel<bf16_t><<<nb, 256, 0, st>>>((const bf16_t *)a, wh, bh, classes, logits, V, C);
+        else
+            head_classify_kernel<float><<<nb, 256, 0, st>>>((const float *)a, wh, bh, classes, logits, V, C);
+    }
     K3_LAUNCH_CHECK();
     return K3_OK;
 }

@@ -130,6 +130,91 @@ static int pool_launch(bool bwd, const void *x, const void *dy, const void *add,
     return K3_OK;
 }
 
+// Nearest-neighbour up-sampling by 2 per axis.  D, H, W are the INPUT sizes; the output is
+// (2D, 2H, 2W).  Forward: one thread per VEC channels of one OUTPUT voxel (each input vector is
+// read by the eight threads of its block, served by the cache; every store is coalesced).
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void upsample_fwd_kernel(const T *__restrict__ x, T *__restrict__ y, int64_t total,
+                                                          int D, int H, int W, int C)
+{
+    int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= total) return;
+    int cv = C / VEC;
+    int c = (int)(gid % cv) * VEC;
+    int64_t o = gid / cv;
+    int w = (int)(o % (2 * W));
+    int h = (int)((o / (2 * W)) % (2 * H));
+    int d = (int)((o / ((int64_t)4 * W * H)) % (2 * D));
+    int64_t n = o / ((int64_t)8 * W * H * D);
+    int64_t u = ((n * D + (d >> 1)) * H + (h >> 1)) * (int64_t)W + (w >> 1);
+    float v[VEC];
+    vec_io<T, VEC>::ld(x + u * C + c, v);
+    vec_io<T, VEC>::st(y + o * C + c, v);
+}
+
+// Backward: the adjoint, dx = sum of dy over the 2x2x2 block in a fixed order (fp32), then the
+// ReLU mask of the stored forward input when one is given.  One thread per VEC channels of one
+// INPUT voxel.
+template <typename T, int VEC>
+__global__ __launch_bounds__(256) void upsample_bwd_kernel(const T *__restrict__ dy, const T *__restrict__ xmask,
+                                                          T *__restrict__ dx, int64_t total, int D, int H, int W, int C)
+{
+    int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= total) return;
+    int cv = C / VEC;
+    int c = (int)(gid % cv) * VEC;
+    int64_t o = gid / cv;
+    int w = (int)(o % W);
+    int h = (int)((o / W) % H);
+    int d = (int)((o / ((int64_t)W * H)) % D);
+    int64_t n = o / ((int64_t)W * H * D);
+    float acc[VEC], v[VEC];
+#pragma unroll
+    for (int e = 0; e < VEC; ++e) acc[e] = 0.f;
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        int64_t u = ((n * 2 * D + 2 * d + (p >> 2)) * 2 * H + 2 * h + ((p >> 1) & 1)) * (2 * (int64_t)W) + 2 * w + (p & 1);
+        vec_io<T, VEC>::ld(dy + u * C + c, v);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e) acc[e] += v[e];
+    }
+    if (xmask) {
+        vec_io<T, VEC>::ld(xmask + o * C + c, v);
+#pragma unroll
+        for (int e = 0; e < VEC; ++e)
+            if (!(v[e] > 0.f)) acc[e] = 0.f;
+    }
+    vec_io<T, VEC>::st(dx + o * C + c, acc);
+}
+
+template <typename T, int VEC>
+static int upsample_launch(bool bwd, const void *in, const void *xmask, void *out, int64_t N, int64_t D, int64_t H, int64_t W,
+                           int64_t C, hipStream_t st)
+{
+    int64_t total = N * D * H * W * (C / VEC) * (bwd ? 1 : 8);
+    int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+    if (!bwd)
+        upsample_fwd_kernel<T, VEC><<<dim3((unsigned)blocks), 256, 0, st>>>((const T *)in, (T *)out, total, (int)D, (int)H,
+                                                                            (int)W, (int)C);
+    else
+        upsample_bwd_kernel<T, VEC><<<dim3((unsigned)blocks), 256, 0, st>>>((const T *)in, (const T *)xmask, (T *)out, total,
+                                                                            (int)D, (int)H, (int)W, (int)C);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
+static int upsample_dispatch(bool bwd, int dtype, const void *in, const void *xmask, void *out, int64_t N, int64_t D, int64_t H,
+                             int64_t W, int64_t C, hipStream_t st)
+{
+    if (dtype == K3_BF16) {
+        if (C % 8 == 0) return upsample_launch<bf16_t, 8>(bwd, in, xmask, out, N, D, H, W, C, st);
+        return upsample_launch<bf16_t, 1>(bwd, in, xmask, out, N, D, H, W, C, st);
+    }
+    if (C % 4 == 0) return upsample_launch<float, 4>(bwd, in, xmask, out, N, D, H, W, C, st);
+    return upsample_launch<float, 1>(bwd, in, xmask, out, N, D, H, W, C, st);
+}
+
 static int pool_dispatch(bool bwd, int dtype, const void *x, const void *dy, const void *add, int relu_mask, void *out, int64_t N,
                          int64_t D, int64_t H, int64_t W, int64_t C, hipStream_t st)
 {
@@ -171,4 +256,23 @@ extern "C" int k3_pool3d_bwd(const k3_tensor *xd, const void *x, const k3_tensor
     if (rc != K3_OK) return rc;
     if (!x || !dy || !dx) return K3_E_BADARG;
     return pool_dispatch(true, xd->dtype, x, dy, add, relu_mask ? 1 : 0, dx, dyd->n, dyd->d, dyd->h, dyd->w, dyd->c, (hipStream_t)stream);
+}
+
+// xd: the small tensor (D, H, W); yd: the large one (2D, 2H, 2W): the same relation pool_check tests,
+// with the roles of input and output exchanged.
+extern "C" int k3_upsample3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *yd, void *y, void *stream)
+{
+    int rc = pool_check(yd, xd);
+    if (rc != K3_OK) return rc;
+    if (!x || !y) return K3_E_BADARG;
+    return upsample_dispatch(false, xd->dtype, x, nullptr, y, xd->n, xd->d, xd->h, xd->w, xd->c, (hipStream_t)stream);
+}
+
+extern "C" int k3_upsample3d_bwd(const k3_tensor *dyd, const void *dy, const void *x_mask, const k3_tensor *dxd, void *dx,
+                                 void *stream)
+{
+    int rc = pool_check(dyd, dxd);
+    if (rc != K3_OK) return rc;
+    if (!dy || !dx) return K3_E_BADARG;
+    return upsample_dispatch(true, dxd->dtype, dy, x_mask, dx, dxd->n, dxd->d, dxd->h, dxd->w, dxd->c, (hipStream_t)stream);
 }

@@ -200,6 +200,25 @@ def head_softmax_ce_fwd_bwd(a, wh, bh, labels, loss, da, dWh, dbh, logits, ws, r
 
 
 # ------------------------------------------------------------------ LMS swap engine
+def head_softmax_wce_fwd_bwd(a, wh, bh, labels, class_w, loss, da, dWh, dbh, logits, ws, relu_mask=False):
+    _check(lib().k3_head_softmax_wce_fwd_bwd(_d(a), _p(a), _p(wh), _p(bh), _p(labels), _p(class_w), _p(loss), _p(da),
+                                             ctypes.c_int(int(relu_mask)), _p(dWh), _p(dbh), _p(logits), _p(ws),
+                                             ctypes.c_size_t(ws.numel() * ws.element_size()), _stream()),
+           "k3_head_softmax_wce_fwd_bwd")
+
+
+def head_classify(a, wh, bh, classes, logits=None):
+    _check(lib().k3_head_classify(_d(a), _p(a), _p(wh), _p(bh), _p(classes), _p(logits), _stream()), "k3_head_classify")
+
+
+def upsample3d_fwd(x, y):
+    _check(lib().k3_upsample3d_fwd(_d(x), _p(x), _d(y), _p(y), _stream()), "k3_upsample3d_fwd")
+
+
+def upsample3d_bwd(dy, dx, x_mask=None):
+    _check(lib().k3_upsample3d_bwd(_d(dy), _p(dy), _p(x_mask), _d(dx), _p(dx), _stream()), "k3_upsample3d_bwd")
+
+
 def sgd_momentum_step(w, v, g, lr, momentum=0.0, weight_decay=0.0, w_bf16=None):
     n = w.numel()
     assert v.numel() == n and g.numel() == n and (w_bf16 is None or w_bf16.numel() == n)

@@ -25,7 +25,7 @@ from .executor import Executor, OutOfBudget
 CONV_RATE = {"conv_fwd": (0.62e15, 1.10e15, 1.27e15), "conv_dgrad": (0.55e15, 1.05e15, 1.25e15),
              "conv_wgrad": (0.50e15, 1.20e15, 1.27e15)}
 STREAM_RATE = {"pool_fwd": 5.4e12, "pool_bwd": 5.4e12, "up_fwd": 4.0e12, "up_wgrad": 5.1e12, "up_dgrad": 2.8e12,
-               "head": 3.5e12, "first_fwd": 3.1e12, "first_wgrad": 3.3e12}
+               "head": 3.5e12, "first_fwd": 3.1e12, "first_wgrad": 3.3e12, "upsample_fwd": 5.0e12, "upsample_bwd": 5.0e12}
 LAUNCH_SECONDS = 12e-6
 LINK_BYTES_PER_S = 50e9
 
@@ -52,7 +52,10 @@ class SimBackend:
         self._n = 0
         self.timeline = []     # compute clock after each call
 
-    def alloc(self, info):
+    def slab(self, nbytes):
+        pass
+
+    def alloc(self, info, offset):
         return info.name
 
     def free(self, block):
@@ -105,6 +108,7 @@ class Plan:
         self.gaps, self.lead, self.eager, self.at = list(gaps), lead, eager, dict(at or {})
         self.peak_bytes = self.seconds = self.stall_seconds = self.bytes_out = self.bytes_in = None
         self.no_swap_seconds = None
+        self.budget = None      # the device budget the plan was made for
 
     def describe(self):
         names = sorted({g.tensor for g in self.gaps})
@@ -146,10 +150,12 @@ def swap_all(program, fixed_bytes=0, min_gap_calls=3, durations=None, only=None)
         except OutOfBudget as e:
             return None, e
     ok, err = attempt(gaps)
-    if ok is None:
-        raise err
+    while ok is None:      # the byte floor may not be reachable in address space: holes do not always line up
+        floor = int(floor * 1.02)
+        ok, err = attempt(gaps)
     at, ok = _advance_prefetches(program, gaps, attempt, ok)
     plan = _fill(Plan(gaps, 1, at=at), ok[0], ok[1])
+    plan.budget = floor
     plan.no_swap_seconds = simulate(program, fixed_bytes=fixed_bytes, durations=durations)[1].seconds
     return plan
 
@@ -226,5 +232,6 @@ def plan_for_budget(program, budget, fixed_bytes=0, min_gap_calls=3, durations=N
             chosen, ok = rest, r
     at, ok = _advance_prefetches(program, chosen, attempt, ok)
     plan = _fill(Plan(chosen, 1, at=at), ok[0], ok[1])
+    plan.budget = budget
     plan.no_swap_seconds = base
     return plan

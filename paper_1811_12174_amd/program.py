@@ -114,10 +114,17 @@ class Program:
         self._add(Call("up_dgrad", layer, dict(dy=dy, dx=dx, mask=mask), [dy, mask], [dx],
                        2 * 8 * v * ci * co, self._nb(dy, dx, mask), v, ci, co))
 
-    def head(self, a, da, c):
+    def head(self, a, da, c, relu_mask=True):
         v = self._vox(a)
-        self._add(Call("head", "head", dict(a=a, da=da), [a, "labels"], [da], 2 * 2 * 3 * v * c,
+        self._add(Call("head", "head", dict(a=a, da=da, relu_mask=relu_mask), [a, "labels"], [da], 2 * 2 * 3 * v * c,
                        self._nb(a, da) + v, v, c, 3))
+
+    def upsample_fwd(self, x, y):
+        self._add(Call("upsample_fwd", None, dict(x=x, y=y), [x], [y], 0, self._nb(x, y), self._vox(y), 0, 0))
+
+    def upsample_bwd(self, dy, dx, mask):
+        self._add(Call("upsample_bwd", None, dict(dy=dy, dx=dx, mask=mask), [dy, mask], [dx], 0, self._nb(dy, dx, mask),
+                       self._vox(dy), 0, 0))
 
     # ---- analysis
     def finish(self, keep=()):
@@ -253,5 +260,44 @@ def unet_program(base, cin, levels, n, d, h, w, ebytes=2, keep_acts=False):
         if l > 0:
             p.conv_dgrad(f"enc{l}.conv1", f"g:a1_{l}", p.new(f"g:p_{l - 1}", sh(l, F[l - 1])), None, None, ci, Fl)
             g = f"g:p_{l - 1}"
+    keep = [t for t, i in p.tensors.items() if not i.external and not t.startswith("g")] if keep_acts else []
+    return p.finish(keep)
+
+
+def bp_program(cin, channels, n, d, h, w, ebytes=2, keep_acts=False):
+    """The section-4.1 encoder / decoder step: two encoder layers (3x3x3 conv + ReLU, 2x2x2
+    max-pool), two decoder layers (3x3x3 conv + ReLU, up-sampling by 2), the per-voxel class
+    likelihoods with the class-weighted loss; then the backward pass.  The up-sampling backward
+    applies the ReLU mask of the convolution output it differentiates; the head does not (its
+    input is an up-sampled tensor, whose gradient goes through that adjoint first)."""
+    if (d | h | w) % 4:
+        raise ValueError("volume edges must be divisible by 4")
+    p = Program(ebytes)
+    C = channels
+
+    def sh(l, c):
+        return (n, d >> l, h >> l, w >> l, c)
+    p.external("x", sh(0, cin))
+    p.external("labels", (n, d, h, w), 1)
+    p.conv_fwd("enc0.conv", "x", None, p.new("a1", sh(0, C)), cin, C)
+    p.pool_fwd("a1", p.new("p1", sh(1, C)))
+    p.conv_fwd("enc1.conv", "p1", None, p.new("a2", sh(1, C)), C, C)
+    p.pool_fwd("a2", p.new("p2", sh(2, C)))
+    p.conv_fwd("dec1.conv", "p2", None, p.new("a3", sh(2, C)), C, C)
+    p.upsample_fwd("a3", p.new("u1", sh(1, C)))
+    p.conv_fwd("dec0.conv", "u1", None, p.new("a4", sh(1, C)), C, C)
+    p.upsample_fwd("a4", p.new("u2", sh(0, C)))
+    p.head("u2", p.new("g:u2", sh(0, C)), C, relu_mask=False)
+    p.upsample_bwd("g:u2", p.new("g:a4", sh(1, C)), "a4")
+    p.conv_wgrad("dec0.conv", "u1", None, "g:a4", C, C)
+    p.conv_dgrad("dec0.conv", "g:a4", p.new("g:u1", sh(1, C)), None, None, C, C)
+    p.upsample_bwd("g:u1", p.new("g:a3", sh(2, C)), "a3")
+    p.conv_wgrad("dec1.conv", "p2", None, "g:a3", C, C)
+    p.conv_dgrad("dec1.conv", "g:a3", p.new("g:p2", sh(2, C)), None, None, C, C)
+    p.pool_bwd("a2", "g:p2", None, p.new("g:a2", sh(1, C)), True)
+    p.conv_wgrad("enc1.conv", "p1", None, "g:a2", C, C)
+    p.conv_dgrad("enc1.conv", "g:a2", p.new("g:p1", sh(1, C)), None, None, C, C)
+    p.pool_bwd("a1", "g:p1", None, p.new("g:a1", sh(0, C)), True)
+    p.conv_wgrad("enc0.conv", "x", None, "g:a1", cin, C)
     keep = [t for t, i in p.tensors.items() if not i.external and not t.startswith("g")] if keep_acts else []
     return p.finish(keep)

@@ -23,15 +23,23 @@ import torch
 
 from . import k3, planner
 from .executor import Executor
-from .program import unet_program
+from .program import bp_program, unet_program
 
 
-class UNet3D:
-    def __init__(self, params, base=32, cin=1, levels=4, classes=3, dtype=torch.bfloat16, device="cuda"):
-        """params: dict name -> float32 numpy array (see synth.unet_params)."""
-        if classes != 3:
+class StepNet:
+    """Parameters, GPU backend of the interpreter and the training step of a network whose step
+    program a subclass supplies (`_build_program`)."""
+
+    def __init__(self, params, dtype=torch.bfloat16, device="cuda", class_weights=None):
+        """params: dict name -> float32 numpy array, name + '.w' / '.b' per layer; a layer named
+        'head' is the 1x1x1 classifier, names ending in '.up' are transposed convolutions, all
+        others 3x3x3 convolutions.  class_weights: three per-class voxel weights for the loss
+        (None: unweighted)."""
+        self.dtype, self.dev = dtype, device
+        self.class_w = None if class_weights is None else torch.tensor([float(v) for v in class_weights], device=device,
+                                                                       dtype=torch.float32)
+        if self.class_w is not None and self.class_w.numel() != 3:
             raise ValueError("the head kernel is written for the paper's three classes")
-        self.base, self.cin, self.levels, self.dtype, self.dev = base, cin, levels, dtype, device
         self.code = k3.BF16 if dtype == torch.bfloat16 else k3.F32
         self.w, self.b, self.pk, self.gw, self.gb = {}, {}, {}, {}, {}
         self.kind = {}
@@ -80,6 +88,7 @@ class UNet3D:
         self.last_stats = {}
         self.last_run = None   # the Executor of the last step (peak bytes, bytes moved, drops)
         self._timing = None
+        self._slab = None
 
     # ------------------------------------------------------------------ parameters
     def repack(self):
@@ -124,11 +133,7 @@ class UNet3D:
         """The static step program for an input of this shape (cached)."""
         key = (tuple(x_shape), keep_acts)
         if key not in self._programs:
-            n, d, h, w, c = x_shape
-            if c != self.cin:
-                raise ValueError("input channel count differs from the network's")
-            self._programs[key] = unet_program(self.base, self.cin, self.levels, n, d, h, w,
-                                               ebytes=2 if self.dtype == torch.bfloat16 else 4, keep_acts=keep_acts)
+            self._programs[key] = self._build_program(tuple(x_shape), 2 if self.dtype == torch.bfloat16 else 4, keep_acts)
         return self._programs[key]
 
     def workspace_bytes(self, prog):
@@ -157,8 +162,16 @@ class UNet3D:
         return n
 
     # ------------------------------------------------------------------ backend of the interpreter
-    def alloc(self, info):
-        return torch.empty(info.shape, device=self.dev, dtype=self.dtype)
+    def slab(self, nbytes):
+        """One device buffer for every tensor of a budgeted step (kept across steps)."""
+        if self._slab is None or self._slab.numel() != nbytes:
+            self._slab = None
+            self._slab = torch.empty(nbytes, device=self.dev, dtype=torch.uint8)
+
+    def alloc(self, info, offset):
+        if offset is None:
+            return torch.empty(info.shape, device=self.dev, dtype=self.dtype)
+        return self._slab[offset:offset + info.nbytes].view(self.dtype).view(info.shape)
 
     def free(self, block):
         pass    # the last reference goes with the interpreter's table entry
@@ -221,8 +234,17 @@ class UNet3D:
         elif c.fn == "up_dgrad":
             k3.upconv3d_bwd_data(t[a["dy"]], self.w[c.layer], self.pk[c.layer], t[a["dx"]], dx_mask=t.get(a["mask"]))
         elif c.fn == "head":
-            k3.head_softmax_ce_fwd_bwd(t[a["a"]], self.w["head"], self.b["head"], t["labels"], self.loss, t[a["da"]],
-                                       self.gw["head"], self.gb["head"], None, self._ws, relu_mask=True)
+            if self.class_w is None:
+                k3.head_softmax_ce_fwd_bwd(t[a["a"]], self.w["head"], self.b["head"], t["labels"], self.loss, t[a["da"]],
+                                           self.gw["head"], self.gb["head"], None, self._ws, relu_mask=a["relu_mask"])
+            else:
+                k3.head_softmax_wce_fwd_bwd(t[a["a"]], self.w["head"], self.b["head"], t["labels"], self.class_w, self.loss,
+                                            t[a["da"]], self.gw["head"], self.gb["head"], None, self._ws,
+                                            relu_mask=a["relu_mask"])
+        elif c.fn == "upsample_fwd":
+            k3.upsample3d_fwd(t[a["x"]], t[a["y"]])
+        elif c.fn == "upsample_bwd":
+            k3.upsample3d_bwd(t[a["dy"]], t[a["dx"]], x_mask=t.get(a["mask"]))
         else:
             raise ValueError(c.fn)
         if self._timing is not None:
@@ -239,9 +261,10 @@ class UNet3D:
           swap=True         the stored encoder activations spend their idle gaps in host memory, under
                             the smallest budget that selection can run in.
           swap=<Plan>       a plan from planner.plan_for_budget / planner.swap_all.
-        budget (bytes, with a plan; default: the plan's own peak) bounds the accounted device memory
-        of the step: device copies of swapped tensors are dropped only when an allocation needs the
-        room, oldest first.
+        budget (bytes; with a plan the default is the budget the plan was made for) bounds the device
+        memory of the step: its tensors then live in one slab of budget minus the fixed part (see
+        fixed_bytes), and device copies of swapped tensors are dropped only when an allocation finds
+        no room, oldest first.
         With keep_acts=True (swap must be off) the forward activations are returned too.
         With timing=True the per-call GPU durations (seconds) are left in self.call_seconds."""
         prog = self.program(x.shape, keep_acts)
@@ -249,7 +272,7 @@ class UNet3D:
             swap = self._default_plan(prog)
         plan = swap if swap else None
         if plan is not None and budget is None:
-            budget = plan.peak_bytes
+            budget = plan.budget
         if keep_acts and plan is not None:
             raise ValueError("keep_acts needs swap off")
         if plan is not None and self.lms is None:
@@ -276,16 +299,15 @@ class UNet3D:
         if self.lms is not None:
             self.last_stats = k3.lms_get_stats(self.lms)
         if keep_acts:
-            names = {}
-            for l in range(self.levels):
-                names[f"a1_{l}"], names[f"a2_{l}"], names[f"p_{l}"] = f"enc{l}.a1", f"enc{l}.a2", f"enc{l}.pool"
-                names[f"up_{l}"], names[f"da1_{l}"], names[f"da2_{l}"] = f"dec{l}.up", f"dec{l}.a1", f"dec{l}.a2"
-            return self.loss, {names[k]: v for k, v in ex.kept.items() if k in names}
+            return self.loss, self._name_acts(ex.kept)
         return self.loss
+
+    def _name_acts(self, kept):
+        return dict(kept)
 
     def _default_plan(self, prog):
         if getattr(prog, "_encoder_plan", None) is None:
-            prog._encoder_plan = planner.swap_all(prog, only=planner.is_encoder_activation, fixed_bytes=self.fixed_bytes(prog))
+            prog._encoder_plan = planner.swap_all(prog, only=self._swap_by_default, fixed_bytes=self.fixed_bytes(prog))
         return prog._encoder_plan
 
     def reset(self):
@@ -305,3 +327,69 @@ class UNet3D:
         if self.lms is not None:
             k3.lms_destroy(self.lms)
             self.lms = None
+
+
+class UNet3D(StepNet):
+    def __init__(self, params, base=32, cin=1, levels=4, classes=3, dtype=torch.bfloat16, device="cuda", class_weights=None):
+        """params: dict name -> float32 numpy array (see synth.unet_params)."""
+        if classes != 3:
+            raise ValueError("the head kernel is written for the paper's three classes")
+        self.base, self.cin, self.levels = base, cin, levels
+        super().__init__(params, dtype=dtype, device=device, class_weights=class_weights)
+
+    _swap_by_default = staticmethod(planner.is_encoder_activation)
+
+    def _build_program(self, x_shape, ebytes, keep_acts):
+        n, d, h, w, c = x_shape
+        if c != self.cin:
+            raise ValueError("input channel count differs from the network's")
+        return unet_program(self.base, self.cin, self.levels, n, d, h, w, ebytes=ebytes, keep_acts=keep_acts)
+
+    def _name_acts(self, kept):
+        names = {}
+        for l in range(self.levels):
+            names[f"a1_{l}"], names[f"a2_{l}"], names[f"p_{l}"] = f"enc{l}.a1", f"enc{l}.a2", f"enc{l}.pool"
+            names[f"up_{l}"], names[f"da1_{l}"], names[f"da2_{l}"] = f"dec{l}.up", f"dec{l}.a1", f"dec{l}.a2"
+        return {names[k]: v for k, v in kept.items() if k in names}
+
+
+class EncoderDecoder3D(StepNet):
+    """The section-4.1 model: two (conv, max-pool) encoder layers, two (conv, up-sampling) decoder
+    layers, `channels` channels per voxel, three-class likelihoods, class-weighted loss."""
+
+    def __init__(self, params, cin=1, channels=128, dtype=torch.bfloat16, device="cuda", class_weights=None):
+        self.cin, self.channels = cin, channels
+        super().__init__(params, dtype=dtype, device=device, class_weights=class_weights)
+
+    @staticmethod
+    def _swap_by_default(name):
+        return name in ("a1", "p1", "a2", "p2", "a3", "u1", "a4")
+
+    def _build_program(self, x_shape, ebytes, keep_acts):
+        n, d, h, w, c = x_shape
+        if c != self.cin:
+            raise ValueError("input channel count differs from the network's")
+        return bp_program(self.cin, self.channels, n, d, h, w, ebytes=ebytes, keep_acts=keep_acts)
+
+    def classify(self, x):
+        """Inference: forward pass and the most likely class per voxel (uint8), through the same kernels."""
+        n, d, h, w, _ = x.shape
+        C = self.channels
+
+        def new(l):
+            return torch.empty((n, d >> l, h >> l, w >> l, C), device=self.dev, dtype=self.dtype)
+
+        def conv(name, src, dst):
+            k3.conv3d_fwd(src, self.w[name], self.pk[name], self.b[name], True, dst)
+            return dst
+        a1 = conv("enc0.conv", x, new(0))
+        p1 = new(1); k3.pool3d_fwd(a1, p1); del a1
+        a2 = conv("enc1.conv", p1, new(1)); del p1
+        p2 = new(2); k3.pool3d_fwd(a2, p2); del a2
+        a3 = conv("dec1.conv", p2, new(2)); del p2
+        u1 = new(1); k3.upsample3d_fwd(a3, u1); del a3
+        a4 = conv("dec0.conv", u1, new(1)); del u1
+        u2 = new(0); k3.upsample3d_fwd(a4, u2); del a4
+        cls = torch.empty((n, d, h, w), device=self.dev, dtype=torch.uint8)
+        k3.head_classify(u2, self.w["head"], self.b["head"], cls)
+        return cls

@@ -1,0 +1,169 @@
+"""GPU parity of the section-4.1 encoder / decoder workload: up-sampling layer, class-weighted
+loss, arg-max read-out and the composed training step, against the oracle."""
+import numpy as np
+import pytest
+
+import synth
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("sp,C,dt", [((1, 4, 4, 4), 16, "bf16"), ((2, 3, 5, 7), 32, "bf16"), ((1, 2, 3, 4), 6, "bf16"),
+                                     ((1, 3, 2, 5), 8, "f32"), ((1, 2, 2, 3), 5, "f32"), ((2, 16, 16, 16), 128, "bf16"),
+                                     ((1, 1, 1, 1), 16, "bf16")])
+def test_upsample(orc, sp, C, dt):
+    import torch
+    from oracle import bp
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, to_f64, empty, rel_l2
+    N, D, H, W = sp
+    x = synth.activations(80, (N, D, H, W, C), dt)
+    x = np.maximum(x, 0)                       # a stored ReLU output: about half the entries are zero
+    dy = synth.activations(81, (N, 2 * D, 2 * H, 2 * W, C), dt)
+    xd, dyd = to_dev(x, dt), to_dev(dy, dt)
+    y = empty(dy.shape, dt)
+    k3.upsample3d_fwd(xd, y)
+    dx, dxm = empty(x.shape, dt), empty(x.shape, dt)
+    k3.upsample3d_bwd(dyd, dx)
+    k3.upsample3d_bwd(dyd, dxm, x_mask=xd)
+    torch.cuda.synchronize()
+    assert np.array_equal(to_f64(y), bp.upsample3d_fwd(x.astype(np.float64)))        # a copy: exact
+    ref = bp.upsample3d_bwd(dy.astype(np.float64))
+    tol = 4e-3 if dt == "bf16" else 1e-6      # one bf16 rounding of an fp32 sum of eight terms
+    assert rel_l2(to_f64(dx), ref) < tol
+    refm = orc.relu_bwd(ref, x.astype(np.float64))
+    assert rel_l2(to_f64(dxm), refm) < tol
+    assert np.array_equal(to_f64(dxm) == 0, (refm == 0) | (to_f64(dxm) == 0)) and np.all(to_f64(dxm)[x <= 0] == 0)
+
+
+def test_upsample_rejects_mismatched_shapes():
+    import torch
+    from paper_1811_12174_amd import k3
+    x = torch.zeros((1, 2, 2, 2, 8), device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(k3.K3Error):
+        k3.upsample3d_fwd(x, torch.zeros((1, 4, 4, 5, 8), device="cuda", dtype=torch.bfloat16))
+    with pytest.raises(k3.K3Error):
+        k3.upsample3d_fwd(x, torch.zeros((1, 4, 4, 4, 8), device="cuda", dtype=torch.float32))
+    with pytest.raises(k3.K3Error):
+        k3.upsample3d_bwd(torch.zeros((1, 4, 4, 4, 16), device="cuda", dtype=torch.bfloat16), x)
+
+
+@pytest.mark.parametrize("sp,C,dt", [((1, 8, 8, 8), 32, "bf16"), ((2, 5, 7, 9), 128, "bf16"), ((1, 4, 4, 4), 8, "f32"),
+                                     ((1, 3, 5, 3), 20, "bf16"), ((1, 7, 9, 11), 16, "bf16")])
+def test_weighted_head_and_classification(orc, sp, C, dt):
+    import torch
+    from oracle import bp
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, to_f64, empty, rel_l2, TOL
+    N, D, H, W = sp
+    V = N * D * H * W
+    a = synth.activations(82, (N, D, H, W, C), dt)
+    wh = synth.head_weights(83, C)
+    bh = (synth.normal(synth.SEED, 84, (3,), np.float64) * 0.3).astype(np.float32)
+    lab = (synth.uniform(synth.SEED, 85, V) * 3).astype(np.uint8).reshape(N, D, H, W)
+    cw = np.array([1.34, 4.63, 0.49], dtype=np.float32)       # the paper's class split, inverted
+    ad = to_dev(a, dt)
+    whd, bhd, cwd = torch.from_numpy(wh).cuda(), torch.from_numpy(bh).cuda(), torch.from_numpy(cw).cuda()
+    labd = torch.from_numpy(lab).cuda()
+    loss = torch.full((1,), float("nan"), device="cuda")
+    da = empty(a.shape, dt)
+    dW = torch.full((C, 3), float("nan"), device="cuda")
+    db = torch.full((3,), float("nan"), device="cuda")
+    logits = torch.full((V, 3), float("nan"), device="cuda")
+    ws = torch.empty(k3.head_workspace_bytes(ad), device="cuda", dtype=torch.uint8)
+    k3.head_softmax_wce_fwd_bwd(ad, whd, bhd, labd, cwd, loss, da, dW, db, logits, ws)
+    cls = torch.full((N, D, H, W), 9, device="cuda", dtype=torch.uint8)
+    logits2 = torch.full((V, 3), float("nan"), device="cuda")
+    k3.head_classify(ad, whd, bhd, cls, logits2)
+    torch.cuda.synchronize()
+    ref = bp.head_softmax_wce(a.astype(np.float64), wh.astype(np.float64), bh.astype(np.float64), lab, cw.astype(np.float64))
+    assert abs(loss.item() - ref["loss"]) < 1e-5 * abs(ref["loss"])
+    assert rel_l2(to_f64(da), ref["da"]) < TOL[dt]
+    assert rel_l2(to_f64(dW), ref["dW"]) < 1e-4
+    assert np.abs(to_f64(db) - ref["db"]).max() < 1e-5 * max(1e-3, np.abs(ref["db"]).max()) + 1e-7
+    # read-out: logits against the oracle; the class is decided on the kernel's own fp32 logits
+    # (exactly), and agrees with the oracle's wherever the oracle's top two are clearly apart
+    z = to_f64(logits2)
+    rz = ref["logits"].reshape(-1, 3)
+    assert rel_l2(z, rz) < 1e-5
+    got = cls.cpu().numpy().reshape(-1)
+    assert np.array_equal(got, np.argmax(logits2.cpu().numpy(), axis=1).astype(np.uint8))
+    top = np.sort(rz, axis=1)
+    clear = (top[:, 2] - top[:, 1]) > 1e-4 * (1 + np.abs(top[:, 2]))
+    assert clear.mean() > 0.95 and np.array_equal(got[clear], bp.classify(rz)[clear])
+
+
+def test_classify_ties_take_the_lowest_class():
+    import torch
+    from paper_1811_12174_amd import k3
+    a = torch.zeros((1, 1, 1, 4, 16), device="cuda", dtype=torch.bfloat16)
+    wh = torch.zeros((16, 3), device="cuda")
+    cls = torch.full((1, 1, 1, 4), 9, device="cuda", dtype=torch.uint8)
+    for bias, want in (([0.0, 0.0, 0.0], 0), ([-1.0, 2.0, 2.0], 1), ([1.0, 0.0, 1.0], 0), ([0.0, 0.0, 0.5], 2)):
+        k3.head_classify(a, wh, torch.tensor(bias, device="cuda"), cls)
+        torch.cuda.synchronize()
+        assert cls.cpu().numpy().reshape(-1).tolist() == [want] * 4
+
+
+def _bp_run(channels, size, n, dt, swap=False, keep=False):
+    import torch
+    from paper_1811_12174_amd.unet import EncoderDecoder3D
+    from gpu_util import to_dev
+    params = synth.bp_params(cin=1, channels=channels, dtype=dt, bias_scale=0.05)
+    x = synth.volume_field(7, n, size, sigma=2.0, dtype=dt)
+    lab = synth.ellipsoid_labels(8, n, size)
+    cw = synth.inverse_frequency_class_weights(lab)
+    net = EncoderDecoder3D(params, cin=1, channels=channels, dtype=torch.bfloat16 if dt == "bf16" else torch.float32,
+                           class_weights=cw)
+    out = net.step(to_dev(x, dt), torch.from_numpy(lab).cuda(), swap=swap, keep_acts=keep)
+    torch.cuda.synchronize()
+    return net, out, params, x, lab, cw
+
+
+@pytest.mark.parametrize("channels,size,n,dt", [(8, 16, 2, "f32"), (16, 16, 1, "bf16"), (32, 16, 2, "bf16"), (128, 16, 1, "bf16")])
+def test_encoder_decoder_step_matches_oracle(orc, channels, size, n, dt):
+    from oracle import bp
+    from gpu_util import to_f64, rel_l2
+    net, (loss, acts), params, x, lab, cw = _bp_run(channels, size, n, dt, keep=True)
+    store = orc.round_bf16 if dt == "bf16" else None
+    p64 = {k: v.astype(np.float64) for k, v in params.items()}
+    rl, rg, ra = bp.bp_step(x.astype(np.float64), lab, p64, cw.astype(np.float64), store=store)
+    tol_l, tol_g = (2e-2, 2e-2) if dt == "bf16" else (1e-5, 1e-4)
+    assert abs(loss.item() - rl) < tol_l * abs(rl), (loss.item(), rl)
+    for k, t in acts.items():
+        assert rel_l2(to_f64(t), ra[k]) < tol_g, k
+    if dt == "bf16":
+        _, rg_exact, _ = bp.bp_step(x.astype(np.float64), lab, p64, cw.astype(np.float64))
+    for k, g in net.grads().items():
+        e = rel_l2(to_f64(g), rg[k])
+        bound = 1e-4 if dt != "bf16" else max(2e-2, 3.0 * rel_l2(rg[k], rg_exact[k]))
+        assert e < bound, (k, e, bound)
+    net.close()
+
+
+def test_encoder_decoder_at_the_paper_shape():
+    """Batch of 8 blocks of 64^3 voxels, 128 channels: swapping is bit-identical, a few SGD steps
+    lower the loss, and the arg-max read-out agrees with the logits of the training pass."""
+    import torch
+    from gpu_util import to_dev
+    net, loss, params, x, lab, cw = _bp_run(128, 64, 8, "bf16")
+    l0 = net.loss.clone()
+    g0 = {k: v.clone() for k, v in net.grads().items()}
+    xd, labd = to_dev(x, "bf16"), torch.from_numpy(lab).cuda()
+    net.step(xd, labd, swap=True)
+    torch.cuda.synchronize()
+    assert torch.equal(net.loss, l0) and net.last_run.bytes_out > 0
+    for k, v in net.grads().items():
+        assert torch.equal(v, g0[k]), k
+    losses = []
+    for _ in range(6):
+        net.step(xd, labd)
+        losses.append(net.loss.item())
+        net.sgd_step(0.01, 0.9)
+    torch.cuda.synchronize()
+    assert np.isfinite(losses).all() and losses[-1] < 0.95 * losses[0], losses
+    cls = net.classify(xd)
+    torch.cuda.synchronize()
+    counts = torch.bincount(cls.reshape(-1).long(), minlength=3)
+    assert int(counts.sum()) == cls.numel() and int(cls.max()) <= 2
+    net.close()
