@@ -13,7 +13,9 @@ Other workloads: "unet128" (full 4-level U-Net, base 32, 1 x 128^3, no swapping)
 without swapping and, for the two large ones, under a device-memory budget (--budget-gb,
 default three quarters of what the step holds unswapped): without swapping the step is
 refused, with the swap plan the planner makes for that budget it runs, and the "unet"
-object reports its time, its footprint and the bytes moved each way.  "sweep" plans
+object reports its time, its footprint and the bytes moved each way.  "bp64" / "bp96" time
+the paper's second model (section 4.1: two conv+pool encoder layers, two conv+up-sampling
+decoder layers, 128 channels, batch of 8 blocks, class-weighted loss) in training and inference.  "sweep" plans
 and runs a row of resolutions under one fixed budget and reports the swap overhead of each.
 
 Prints ONE JSON line on stdout.
@@ -377,6 +379,50 @@ def bench_unet(args, base, size, n, swap, label, budget_gb=0.0):
     return res
 
 
+def bench_bp(args, size):
+    """The section-4.1 encoder / decoder: batch of 8 blocks of size^3 voxels, 128 channels,
+    class-weighted loss; one step = forward + backward + SGD update.  Also the inference pass
+    (forward + arg-max read-out)."""
+    import torch
+    import synth
+    from paper_1811_12174_amd.unet import EncoderDecoder3D
+    n, ch = 8, 128
+    params = synth.bp_params(cin=1, channels=ch, dtype="bf16")
+    x = torch.from_numpy(synth.volume_field(7, n, size, dtype="bf16")).cuda().to(torch.bfloat16)
+    labh = synth.ellipsoid_labels(8, n, size)
+    lab = torch.from_numpy(labh).cuda()
+    net = EncoderDecoder3D(params, cin=1, channels=ch, class_weights=synth.inverse_frequency_class_weights(labh))
+    steps, warm = max(1, args.unet_steps) * 5, 3
+
+    def timed(fn):
+        for _ in range(warm):
+            fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(steps):
+            fn()
+        torch.cuda.synchronize()
+        return (time.perf_counter() - t0) / steps
+
+    def train():
+        net.step(x, lab)
+        net.sgd_step(0.0, 0.9, 0.0)   # lr = 0: the full update work, weights unchanged
+    t_train = timed(train)
+    t_infer = timed(lambda: net.classify(x))
+    net.step(x, lab, timing=True)
+    prog = net.program(x.shape)
+    per_call = sorted(((d, f"{c.fn} {c.layer or ''}".strip()) for c, d in zip(prog.calls, net.call_seconds)), reverse=True)[:6]
+    fl = sum(c.flops for c in prog.calls if c.fn.startswith("conv_"))
+    V = n * size ** 3
+    res = {"workload": f"section-4.1 encoder/decoder, 8 x {size}^3, 128 channels, class-weighted loss", "steps": steps,
+           "ms_per_training_step": round(t_train * 1e3, 3), "training_voxels_per_s": round(V / t_train, 1),
+           "conv_tflops": round(fl / t_train / 1e12, 2), "ms_per_inference_pass": round(t_infer * 1e3, 3),
+           "inference_voxels_per_s": round(V / t_infer, 1), "accounted_peak_gb": round(net.last_run.peak / 1e9, 3),
+           "slowest_calls_ms": [[name, round(d * 1e3, 3)] for d, name in per_call]}
+    net.close()
+    return res
+
+
 def bench_sweep(args):
     """Swap overhead against resolution at a fixed device budget (the paper's section 3 reports
     the overhead of LMS growing with the image resolution on its 16 GB GPUs): base-64 U-Net, batch
@@ -402,7 +448,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=300)
     ap.add_argument("--warmup", type=int, default=30)
-    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "unet128", "unet256", "unet320", "sweep"])
+    ap.add_argument("--workload", default="cfg2", choices=["cfg2", "unet128", "unet256", "unet320", "sweep", "bp64", "bp96"])
     ap.add_argument("--budget-gb", type=float, default=0.0,
                     help="U-Net workloads: also run under this device-memory limit, without and with swapping")
     ap.add_argument("--sweep-budget-gb", type=float, default=32.0, help="device budget of the sweep workload")
@@ -435,6 +481,12 @@ def main():
         if args.with_unet:
             out["unet"] = [bench_unet(args, 32, 128, 1, False, "cfg3: U-Net base 32, 1 x 128^3, no swapping"),
                            bench_unet(args, 64, 256, 2, True, "cfg4: U-Net base 64, 2 x 256^3, swap plan for a device budget")]
+    elif args.workload in ("bp64", "bp96"):
+        u = bench_bp(args, 64 if args.workload == "bp64" else 96)
+        out = {"metric": "encoder/decoder training step voxels/s", "value": u["training_voxels_per_s"], "unit": "voxels/s",
+               "n_gpus": 1, "steps": u["steps"], "warmup": 3, "ms_per_step": u["ms_per_training_step"], "higher_is_better": True,
+               "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
+               "config": {"workload": u["workload"]}, "encoder_decoder": u}
     elif args.workload == "sweep":
         sw = bench_sweep(args)
         done = [r for r in sw["rows"] if "planned_ms" in r]

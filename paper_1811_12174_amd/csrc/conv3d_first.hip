@@ -294,10 +294,11 @@ __global__ __launch_bounds__(256) void conv_first_fwd_mfma_kernel(const bf16_t *
 template <int MB>
 __global__ __launch_bounds__(256) void conv_first_wgrad_mfma_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ dy,
                                                                    float *__restrict__ ws, int64_t per_split, int D, int H,
-                                                                   int W, int ntd, int nth, int ntw, int64_t ntiles)
+                                                                   int W, int ntd, int nth, int ntw, int64_t ntiles,
+                                                                   int ctot, int coff)
 {
+    // This launch handles the 32 * MB channels [coff, coff + 32 * MB) of a layer with ctot channels.
     using namespace firstm;
-    constexpr int cout = 32 * MB;
     constexpr int GB = NVOX * 64;          // one 32-channel block of the dy tile
     constexpr int GSTAGE = MB * GB;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2][GSTAGE] dy, then 2 x halo tiles, then 4 KB
@@ -316,12 +317,12 @@ __global__ __launch_bounds__(256) void conv_first_wgrad_mfma_kernel(const bf16_t
         const int slot = (wv + 4 * k) * 64 + lane;
         const int cb = slot >> 11, vox = (slot >> 2) & 511, part = slot & 3;
         const int ld = vox >> 7, lh = (vox >> 4) & 7, lw = vox & 15;
-        goff[k] = ((ld * H + lh) * W + lw) * cout * 2 + cb * 64 + part * 16;
+        goff[k] = ((ld * H + lh) * W + lw) * ctot * 2 + (coff + cb * 32) * 2 + part * 16;
         gco[k] = ld | (lh << 8) | (lw << 16);
     }
     auto issue_g = [&](int64_t tile, int buf) __attribute__((always_inline)) {
         const FirstTile t = first_tile(tile, ntd, nth, ntw);
-        const unsigned char *gb = reinterpret_cast<const unsigned char *>(dy + ((((int64_t)t.n * D + t.d0) * H + t.h0) * W + t.w0) * cout);
+        const unsigned char *gb = reinterpret_cast<const unsigned char *>(dy + ((((int64_t)t.n * D + t.d0) * H + t.h0) * W + t.w0) * ctot);
 #pragma unroll
         for (int k = 0; k < GK; ++k) {
             const int ld = gco[k] & 255, lh = (gco[k] >> 8) & 255, lw = gco[k] >> 16;
@@ -388,7 +389,7 @@ __global__ __launch_bounds__(256) void conv_first_wgrad_mfma_kernel(const bf16_t
             if (row < 28) red[wv * 64 + lane] = acc[mb][i];
             __syncthreads();
             if (wv == 0 && row < 28)
-                out[(int64_t)row * cout + mb * 32 + (lane & 31)] = ((red[lane] + red[64 + lane]) + red[128 + lane]) + red[192 + lane];
+                out[(int64_t)row * ctot + coff + mb * 32 + (lane & 31)] = ((red[lane] + red[64 + lane]) + red[128 + lane]) + red[192 + lane];
         }
 }
 
@@ -409,7 +410,7 @@ static int64_t first_tiles(const ConvArgs &a, int *ntd, int *nth, int *ntw)
 static bool first_mfma_ok(const ConvArgs &a)
 {
     // 32-bit byte offsets inside a tile
-    return (a.cout == 32 || a.cout == 64) && (int64_t)(first::TD + 1) * a.H * a.W * a.cout * 2 < 0x7fffffffLL;
+    return (a.cout == 32 || a.cout == 64 || a.cout == 128) && (int64_t)(first::TD + 1) * a.H * a.W * a.cout * 2 < 0x7fffffffLL;
 }
 
 int conv_first_fwd(const ConvArgs &a, hipStream_t st)
@@ -419,7 +420,10 @@ int conv_first_fwd(const ConvArgs &a, hipStream_t st)
     if (ntiles > 0x7fffffffLL) return K3_E_UNSUPPORTED;
     if (first_mfma_ok(a)) {
         const unsigned grid = (unsigned)(ntiles < 2048 ? ntiles : 2048);
-        if (a.cout == 64)
+        if (a.cout == 128)
+            conv_first_fwd_mfma_kernel<4><<<dim3(grid), 256, 0, st>>>((const bf16_t *)a.x, (const bf16_t *)a.w, a.bias, a.relu,
+                                                                     (bf16_t *)a.y, (int)a.D, (int)a.H, (int)a.W, ntd, nth, ntw, ntiles);
+        else if (a.cout == 64)
             conv_first_fwd_mfma_kernel<2><<<dim3(grid), 256, 0, st>>>((const bf16_t *)a.x, (const bf16_t *)a.w, a.bias, a.relu,
                                                                      (bf16_t *)a.y, (int)a.D, (int)a.H, (int)a.W, ntd, nth, ntw, ntiles);
         else
@@ -440,7 +444,7 @@ static int64_t first_nsplit_mfma(int64_t ntiles) { return ntiles < 256 ? ntiles 
 
 template <int MB>
 static int launch_first_wgrad_mfma(const ConvArgs &a, float *ws, int64_t per, int ntd, int nth, int ntw, int64_t ntiles,
-                                   hipStream_t st)
+                                   hipStream_t st, int coff = 0)
 {
     constexpr int lds = 2 * MB * firstm::NVOX * 64 + 2 * (firstm::NHALO + 8) * 2 + 256 * 4;
     static_assert(lds <= 160 * 1024, "LDS budget");
@@ -451,7 +455,7 @@ static int launch_first_wgrad_mfma(const ConvArgs &a, float *ws, int64_t per, in
         attr_done = true;
     }
     conv_first_wgrad_mfma_kernel<MB><<<dim3((unsigned)first_nsplit_mfma(ntiles)), 256, lds, st>>>(
-        (const bf16_t *)a.x, (const bf16_t *)a.dy, ws, per, (int)a.D, (int)a.H, (int)a.W, ntd, nth, ntw, ntiles);
+        (const bf16_t *)a.x, (const bf16_t *)a.dy, ws, per, (int)a.D, (int)a.H, (int)a.W, ntd, nth, ntw, ntiles, (int)a.cout, coff);
     K3_LAUNCH_CHECK();
     return K3_OK;
 }
@@ -470,8 +474,11 @@ int conv_first_wgrad(const ConvArgs &a, float *dW, float *db, float *ws, hipStre
     int64_t nsplit = first_nsplit(ntiles);
     int64_t per = 28 * a.cout;   // 27 tap rows + the bias row: canonical [27][1][cout] followed by db
     if (first_mfma_ok(a) && !a.ymask) {
-        int rc = a.cout == 64 ? launch_first_wgrad_mfma<2>(a, ws, per, ntd, nth, ntw, ntiles, st)
-                              : launch_first_wgrad_mfma<1>(a, ws, per, ntd, nth, ntw, ntiles, st);
+        // 128 channels: two passes of 64 (the double-buffered dy tile of 128 channels exceeds LDS);
+        // they write disjoint columns of the same partial sums
+        int rc = a.cout == 32 ? launch_first_wgrad_mfma<1>(a, ws, per, ntd, nth, ntw, ntiles, st)
+                              : launch_first_wgrad_mfma<2>(a, ws, per, ntd, nth, ntw, ntiles, st);
+        if (rc == K3_OK && a.cout == 128) rc = launch_first_wgrad_mfma<2>(a, ws, per, ntd, nth, ntw, ntiles, st, 64);
         if (rc != K3_OK) return rc;
         return launch_reduce_partials(ws, dW, db, 27 * a.cout, per, (int)first_nsplit_mfma(ntiles), st);
     }

@@ -12,6 +12,7 @@ FWD_CASES = [
     (2, 5, 6, 7, 3, 2, 5, "f32"),          # odd sizes, two sources, direct
     (1, 9, 10, 11, 1, 0, 32, "bf16"),      # single-channel first layer kernels
     (2, 6, 5, 7, 1, 0, 64, "bf16"),        # first layer, two samples (borders between samples)
+    (2, 9, 11, 19, 1, 0, 128, "bf16"),     # first layer of the encoder/decoder model: 128 channels (two 64-channel wgrad passes)
     (1, 5, 6, 7, 3, 2, 5, "bf16"),         # direct kernels in bf16
     (1, 16, 16, 16, 32, 0, 32, "bf16"),    # MFMA, MB=1, 8 tiles
     (1, 12, 20, 9, 32, 0, 64, "bf16"),     # MFMA, MB=2, ragged tiles

@@ -142,6 +142,7 @@ BIG_CASES = [
     (1, 14, 20, 28, 64, 64, 128),    # 4x8x8 tiles, two sources / destinations, ragged
     (1, 40, 36, 50, 1, 0, 64),       # single-channel first layer (MFMA im2col kernels), ragged tiles
     (2, 20, 24, 48, 1, 0, 32),       # first layer, two samples, one output block
+    (2, 36, 40, 44, 1, 0, 128),      # first layer with 128 channels, ragged tiles
 ]
 
 
