@@ -98,3 +98,25 @@ def bp_step(x, labels, params, class_w, store=None):
     ga1 = st(relu_bwd(pool3d_bwd(a1, gp1), a1))
     g["enc0.conv.w"], g["enc0.conv.b"] = conv3d_bwd_weight(x, ga1)
     return hd["loss"], g, acts
+
+
+def confusion_counts(classes, labels, k=3):
+    """counts[t, p] = number of voxels with label t that were classified p (plain loop over voxels)."""
+    c = np.zeros((k, k), dtype=np.int64)
+    for p, t in zip(np.asarray(classes).reshape(-1).tolist(), np.asarray(labels).reshape(-1).tolist()):
+        c[min(t, k - 1), min(p, k - 1)] += 1
+    return c
+
+
+def dice_coefficients(classes, labels, k=3):
+    """Dice coefficient per class between the predicted and the labelled voxel sets (section 3.1
+    lists it among the figures compared between runs):  D_c = 2 |P_c and T_c| / (|P_c| + |T_c|),
+    taken as 1 for a class that neither set contains."""
+    classes = np.asarray(classes).reshape(-1)
+    labels = np.asarray(labels).reshape(-1)
+    out = np.empty(k, dtype=np.float64)
+    for c in range(k):
+        P, T = classes == c, labels == c
+        den = int(P.sum()) + int(T.sum())
+        out[c] = 1.0 if den == 0 else 2.0 * int((P & T).sum()) / den
+    return out

@@ -122,3 +122,23 @@ def test_step_gradients_by_finite_differences(orc):
     lp = bp.bp_step(x, lab, {k: params[k] + eps * direction[k] for k in params}, cw)[0]
     lm = bp.bp_step(x, lab, {k: params[k] - eps * direction[k] for k in params}, cw)[0]
     assert abs((lp - lm) / (2 * eps) - analytic) < 1e-6 * max(1.0, abs(analytic)), ((lp - lm) / (2 * eps), analytic)
+
+
+def test_dice_by_hand_and_special_cases(orc):
+    bp = _bp()
+    pred = np.array([0, 0, 1, 2, 2, 2, 1, 0], dtype=np.uint8)
+    true = np.array([0, 1, 1, 2, 2, 0, 1, 0], dtype=np.uint8)
+    # class 0: P = {0,1,7}, T = {0,5,7}, both = {0,7}: 2*2/6.  class 1: P = {2,6}, T = {1,2,6}: 2*2/5.
+    # class 2: P = {3,4,5}, T = {3,4}: 2*2/5
+    assert np.allclose(bp.dice_coefficients(pred, true), [4 / 6, 4 / 5, 4 / 5])
+    c = bp.confusion_counts(pred, true)
+    assert c.tolist() == [[2, 0, 1], [1, 2, 0], [0, 0, 2]] and c.sum() == 8
+    # the coefficients follow from the confusion matrix: 2 c_kk / (row_k + column_k)
+    assert np.allclose(bp.dice_coefficients(pred, true), 2 * np.diag(c) / (c.sum(0) + c.sum(1)))
+    assert bp.dice_coefficients(true, true).tolist() == [1.0, 1.0, 1.0]
+    assert bp.dice_coefficients(np.zeros(4, np.uint8), np.full(4, 2, np.uint8)).tolist() == [0.0, 1.0, 0.0]
+    # symmetric in its arguments
+    rng = np.random.default_rng(11)
+    a, b = rng.integers(0, 3, 200), rng.integers(0, 3, 200)
+    assert np.array_equal(bp.dice_coefficients(a, b), bp.dice_coefficients(b, a))
+    assert np.array_equal(bp.confusion_counts(a, b), bp.confusion_counts(b, a).T)
