@@ -186,6 +186,18 @@ int k3_head_softmax_wce_fwd_bwd(const k3_tensor *ad, const void *a, const float 
 int k3_head_classify(const k3_tensor *ad, const void *a, const float *wh, const float *bh, uint8_t *classes,
                      float *logits, void *stream);
 
+/* ------------------------------------------------------------------ Dice coefficient
+ * The Dice coefficient the paper lists among the figures compared between training runs
+ * (section 3.1), per class, between the classified and the labelled voxel sets:
+ *   counts[t][p] = number of voxels with label t classified as p  (3 x 3, uint64, row-major);
+ *   dice[k] = 2 counts[k][k] / (sum_p counts[k][p] + sum_t counts[t][k]), 1 when that
+ *   denominator is 0 (a class neither set contains).
+ * classes, labels: uint8 dev, one per voxel, values above 2 count as class 2; counts: dev,
+ * 9 uint64, overwritten; dice: dev, 3 fp32, or NULL to get the counts only.  voxels = 0 gives
+ * zero counts and dice = 1.  Exact integer counting: the result does not depend on order. */
+int k3_dice_coefficients(const uint8_t *classes, const uint8_t *labels, int64_t voxels, uint64_t *counts,
+                         float *dice, void *stream);
+
 /* ------------------------------------------------------------------ up-sampling layer
  * The up-sampling layer that follows each decoder convolution of the section-4.1 model,
  * read as nearest-neighbour up-sampling by 2 per axis (the paper does not name the

@@ -219,6 +219,14 @@ def upsample3d_bwd(dy, dx, x_mask=None):
     _check(lib().k3_upsample3d_bwd(_d(dy), _p(dy), _p(x_mask), _d(dx), _p(dx), _stream()), "k3_upsample3d_bwd")
 
 
+def dice_coefficients(classes, labels, counts, dice=None):
+    """classes, labels: uint8 tensors of equal size; counts: int64[9] device tensor; dice: float32[3] or None."""
+    n = classes.numel()
+    assert labels.numel() == n and counts.numel() == 9 and counts.element_size() == 8
+    _check(lib().k3_dice_coefficients(_p(classes), _p(labels), ctypes.c_int64(n), _p(counts), _p(dice), _stream()),
+           "k3_dice_coefficients")
+
+
 def sgd_momentum_step(w, v, g, lr, momentum=0.0, weight_decay=0.0, w_bf16=None):
     n = w.numel()
     assert v.numel() == n and g.numel() == n and (w_bf16 is None or w_bf16.numel() == n)

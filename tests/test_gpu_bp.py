@@ -167,3 +167,53 @@ def test_encoder_decoder_at_the_paper_shape():
     counts = torch.bincount(cls.reshape(-1).long(), minlength=3)
     assert int(counts.sum()) == cls.numel() and int(cls.max()) <= 2
     net.close()
+
+
+@pytest.mark.parametrize("n,shift", [(0, 0), (1, 0), (15, 0), (16, 0), (17, 3), (4097, 0), ((1 << 20) + 5, 1), (3 * 64 ** 3, 0)])
+def test_dice_counts_are_exact(orc, n, shift):
+    import torch
+    from oracle import bp
+    from paper_1811_12174_amd import k3
+    pred = (synth.uniform(synth.SEED, 90, n) * 3.2).astype(np.uint8)     # a few values of 3: counted as class 2
+    true = (synth.uniform(synth.SEED, 91, n) * 3).astype(np.uint8)
+    if n > 10:
+        pred[: n // 3] = true[: n // 3]                                   # make the diagonal heavy, like a trained model
+    pd = torch.zeros(n + shift, device="cuda", dtype=torch.uint8)[shift:]
+    td = torch.zeros(n + shift, device="cuda", dtype=torch.uint8)[shift:]
+    pd.copy_(torch.from_numpy(pred)); td.copy_(torch.from_numpy(true))
+    counts = torch.full((9,), -1, device="cuda", dtype=torch.int64)
+    dice = torch.full((3,), float("nan"), device="cuda")
+    k3.dice_coefficients(pd, td, counts, dice)
+    torch.cuda.synchronize()
+    ref = np.zeros((3, 3), dtype=np.int64)
+    np.add.at(ref, (np.minimum(true, 2), np.minimum(pred, 2)), 1)
+    if n <= 5000:
+        assert np.array_equal(ref, bp.confusion_counts(pred, true))      # the oracle's voxel loop, where it is quick
+    assert np.array_equal(counts.cpu().numpy().reshape(3, 3), ref)
+    want = bp.dice_coefficients(np.minimum(pred, 2), np.minimum(true, 2))
+    assert np.allclose(dice.cpu().numpy(), want, rtol=0, atol=1e-7)
+    only = torch.full((9,), -1, device="cuda", dtype=torch.int64)
+    k3.dice_coefficients(pd, td, only)                                    # counts only
+    torch.cuda.synchronize()
+    assert torch.equal(only, counts)
+
+
+def test_dice_of_the_trained_read_out(orc):
+    """End to end: train the encoder/decoder for a few steps, classify, and score with the Dice kernel."""
+    import torch
+    from oracle import bp
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev
+    net, loss, params, x, lab, cw = _bp_run(16, 32, 2, "bf16")
+    xd, labd = to_dev(x, "bf16"), torch.from_numpy(lab).cuda()
+    for _ in range(5):
+        net.step(xd, labd)
+        net.sgd_step(0.02, 0.9)
+    cls = net.classify(xd)
+    counts = torch.zeros(9, device="cuda", dtype=torch.int64)
+    dice = torch.zeros(3, device="cuda")
+    k3.dice_coefficients(cls, labd, counts, dice)
+    torch.cuda.synchronize()
+    assert np.allclose(dice.cpu().numpy(), bp.dice_coefficients(cls.cpu().numpy(), lab), atol=1e-7)
+    assert int(counts.sum()) == lab.size
+    net.close()
