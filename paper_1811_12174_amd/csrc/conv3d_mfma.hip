@@ -291,6 +291,71 @@ struct PipeTile {
     bool valid;
 };
 
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+
+// 16-byte global load whose completion the caller tracks itself (wait_vm below): the compiler
+// inserts no wait for it, so a value may only be used after a wait that covers it.  Used where a
+// compiler-generated wait would also wait for the asynchronous copies issued in between.
+__device__ __forceinline__ u32x4 gload16_nowait(const void *ptr)
+{
+    u32x4 v;
+    asm volatile("global_load_dwordx4 %0, %1, off" : "=v"(v) : "v"(ptr) : "memory");
+    return v;
+}
+
+// s_waitcnt vmcnt(n) for a count that is a compile-time constant after unrolling (the instruction
+// takes an immediate; every case folds away but one)
+#define K3_WVM(n) case n: asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory"); break;
+__device__ __forceinline__ void wait_vm(int n)
+{
+    switch (n) {
+        K3_WVM(0) K3_WVM(1) K3_WVM(2) K3_WVM(3) K3_WVM(4) K3_WVM(5) K3_WVM(6) K3_WVM(7) K3_WVM(8) K3_WVM(9) K3_WVM(10)
+        K3_WVM(11) K3_WVM(12) K3_WVM(13) K3_WVM(14) K3_WVM(15) K3_WVM(16) K3_WVM(17) K3_WVM(18) K3_WVM(19) K3_WVM(20)
+        K3_WVM(21) K3_WVM(22) K3_WVM(23) K3_WVM(24) K3_WVM(25) K3_WVM(26) K3_WVM(27) K3_WVM(28) K3_WVM(29) K3_WVM(30)
+        K3_WVM(31) K3_WVM(32) K3_WVM(33) K3_WVM(34) K3_WVM(35) K3_WVM(36) K3_WVM(37) K3_WVM(38) K3_WVM(39) K3_WVM(40)
+    default: asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); break;   // never less safe: waits for everything
+    }
+}
+#undef K3_WVM
+
+// Masked output (the backward-data pass that applies the ReLU mask of its result): the 32 mask
+// bytes of every accumulator block are requested into registers long before the block is
+// finished.  The first R patches are requested one stage before the last stage of the tile; that
+// stage ends with a wait that leaves fewer operations outstanding than it issued itself, so
+// those requests have completed when the last stage starts.  With more than R patches per wave
+// (R is what the register file allows) patch q >= R is requested into the slot of patch q - R
+// right after that patch's last block was stored, and waited for by count:
+// loads, asynchronous copies and stores of a wave complete in the order they were issued and
+// share one counter, so "at most n operations outstanding" covers exactly the operations issued
+// before the last n.  Inside item i of the last stage the order is: matrix instructions; the
+// item's copy (items j * SP, j < NOPS); the two stores of a finished block (block (e, 0) in item
+// (e + 1) * 9 + 2, block (e, MB - 1) in item (e + 1) * 9 + 5 when MB > 1; the last patch after
+// the loop); mask requests (2 * MB per patch).  after(q) = operations issued behind the requests
+// of patch q and before the stores of its first block.
+template <int NBW, int MB, int NOPS, int SP>
+struct MaskOrder {
+    static constexpr int R = MB == 1 ? NBW : (NBW < 4 ? NBW : 4);
+    static constexpr int NI = 9 * NBW;
+    static constexpr int last_store_item(int e) { return (e + 1) * 9 + (MB > 1 ? 5 : 2); }
+    static constexpr int issue_item(int q) { return last_store_item(q - R); }                // q >= R
+    static constexpr int use_item(int q) { return q + 1 < NBW ? (q + 1) * 9 + 2 : NI; }      // NI: after the loop
+    static constexpr int after(int q)
+    {
+        const int I = issue_item(q), U = use_item(q);
+        int n = 0;
+        for (int j = 0; j < NOPS; ++j)          // copies behind the requests (same item: before them), up to item U
+            if (j * SP > I && j * SP <= U) ++n;
+        for (int r = q + 1; r < NBW; ++r)       // mask requests of later patches
+            if (issue_item(r) < U) n += 2 * MB;
+        for (int e = 0; e + 1 < NBW; ++e) {     // stores of blocks finished in between
+            const int i0 = (e + 1) * 9 + 2, i1 = (e + 1) * 9 + 5;
+            if (i0 > I && i0 < U) n += 2;
+            if (MB > 1 && i1 > I && i1 < U) n += 2;
+        }
+        return n;
+    }
+};
+
 template <class C, bool OMASK>
 __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
 {
@@ -444,6 +509,40 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             }
         }
     }
+    // Requests the 32 mask bytes of every block of patch nb of tile t (the stored ReLU output at
+    // the block's own output position); lanes outside the volume and blocks of the unmasked second
+    // destination read the zero block, so that every wave issues the same number of requests.
+    typedef MaskOrder<C::NBW, C::MB, NOPS, (C::MB == 1 ? 3 : 2)> MO;
+    u32x4 mk[MO::R][C::MB][2];
+    auto mask_request = [&](const PipeTile &t, int nb, u32x4 (&dst)[C::MB][2]) __attribute__((always_inline)) {
+        const int bw = (nb % PPL) % C::PW, bh = (nb % PPL) / C::PW, bd = wv * WPL + nb / PPL;
+        const bool inb = bd < p.D - t.d0 && bh * 4 + lrow < p.H - t.h0 && bw * 8 + lcol < p.W - t.w0;
+        const int pvox = (bd * p.H + bh * 4) * p.W + bw * 8 + lvox;
+#pragma unroll
+        for (int mb = 0; mb < C::MB; ++mb) {
+            const int co0 = (t.mb0 + mb) * 32;
+            const bool d1 = co0 < p.cd1;
+            const bf16_t *mp = p.omask + t.origin * p.cd1 + co0 + (pvox * p.cd1 + hb * 16);
+            const unsigned char *ptr = (d1 && inb) ? reinterpret_cast<const unsigned char *>(mp) : zero;
+            dst[mb][0] = gload16_nowait(ptr);
+            dst[mb][1] = gload16_nowait(ptr + 16);
+        }
+    };
+    auto mask_pin = [&](u32x4 (&dst)[C::MB][2]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int mb = 0; mb < C::MB; ++mb) asm volatile("" : "+v"(dst[mb][0]), "+v"(dst[mb][1]));
+    };
+    if constexpr (OMASK) {
+        // first tile: requested with the prologue's copies and complete after the wait below
+#pragma unroll
+        for (int nb = 0; nb < MO::R; ++nb) mask_request(cur, nb, mk[nb]);
+    } else {
+#pragma unroll
+        for (int r = 0; r < MO::R; ++r)
+#pragma unroll
+            for (int mb = 0; mb < C::MB; ++mb) mk[r][mb][0] = mk[r][mb][1] = u32x4{0u, 0u, 0u, 0u};
+    }
+    bool first_tile = true;
     // while the first copies are in flight: the bias vector goes to LDS for the whole kernel
     // (zeros when there is none), and the next tile is decoded
     {
@@ -479,7 +578,7 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
 
         // Finishes one accumulator block: bias, ReLU, optional output mask, round to bf16, store
         // 32 contiguous bytes per lane.
-        auto emit = [&](int nb, int mb) __attribute__((always_inline)) {
+        auto emit = [&](int nb, int mb, u32x4 m0, u32x4 m1) __attribute__((always_inline)) {
             const int bw = (nb % PPL) % C::PW, bh = (nb % PPL) / C::PW, bd = wv * WPL + nb / PPL;
             const bool inb = bd < dlim && bh * 4 + lrow < hlim && bw * 8 + lcol < wlim;
             const int pvox = (bd * p.H + bh * 4) * p.W + bw * 8 + lvox;
@@ -499,10 +598,8 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             const int loff = pvox * cd + hb * 16;
             if constexpr (OMASK) {
                 if (d1) {
-                    const uint4 *mp = reinterpret_cast<const uint4 *>(p.omask + ubase + (inb ? loff : hb * 16));
-                    uint4 m0 = mp[0], m1 = mp[1];
-                    o0.x = mask_pair(o0.x, m0.x); o0.y = mask_pair(o0.y, m0.y); o0.z = mask_pair(o0.z, m0.z); o0.w = mask_pair(o0.w, m0.w);
-                    o1.x = mask_pair(o1.x, m1.x); o1.y = mask_pair(o1.y, m1.y); o1.z = mask_pair(o1.z, m1.z); o1.w = mask_pair(o1.w, m1.w);
+                    o0.x = mask_pair(o0.x, m0[0]); o0.y = mask_pair(o0.y, m0[1]); o0.z = mask_pair(o0.z, m0[2]); o0.w = mask_pair(o0.w, m0[3]);
+                    o1.x = mask_pair(o1.x, m1[0]); o1.y = mask_pair(o1.y, m1[1]); o1.z = mask_pair(o1.z, m1[2]); o1.w = mask_pair(o1.w, m1[3]);
                 }
             }
             // buffer stores relative to the tile's first voxel: lanes outside the volume get an
@@ -510,7 +607,6 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             bf16_t *dbase = (d1 ? p.dst1 : p.dst2) + ubase;
             __amdgpu_buffer_rsrc_t rsrc = __builtin_amdgcn_make_buffer_rsrc(dbase, 0, 0x7ffffff0, 0x00020000);
             const int boff = inb ? loff * 2 : -1;
-            typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
             __builtin_amdgcn_raw_buffer_store_b128(u32x4{o0.x, o0.y, o0.z, o0.w}, rsrc, boff, 0, 0);
             __builtin_amdgcn_raw_buffer_store_b128(u32x4{o1.x, o1.y, o1.z, o1.w}, rsrc, boff, 16, 0);
         };
@@ -589,13 +685,33 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
                         acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[i % RF][mb], bq[i % RF], acc[nb][mb], 0, 0, 0);
                     if (i % SP == 0 && i / SP < NOPS) issue_op(ss, i / SP, gtag);
                     // blocks of the previous patch: one after taps 2 and 5 of this patch
-                    if (nb > 0 && tl == 2) emit(nb - 1, 0);
-                    if (nb > 0 && tl == 5 && C::MB > 1) emit(nb - 1, C::MB - 1);
+                    if (nb > 0 && tl == 2) {
+                        if constexpr (OMASK) {
+                            if (nb - 1 >= MO::R) {
+                                wait_vm(MO::after(nb - 1));
+                                mask_pin(mk[(nb - 1) % MO::R]);   // the values are defined from here on
+                            }
+                        }
+                        emit(nb - 1, 0, mk[(nb - 1) % MO::R][0][0], mk[(nb - 1) % MO::R][0][1]);
+                    }
+                    if (nb > 0 && tl == 5 && C::MB > 1)
+                        emit(nb - 1, C::MB - 1, mk[(nb - 1) % MO::R][C::MB - 1][0], mk[(nb - 1) % MO::R][C::MB - 1][1]);
+                    if constexpr (OMASK) {
+                        // the slot of patch nb - 1 is free once its last block is stored
+                        if (nb > 0 && tl == (C::MB > 1 ? 5 : 2) && nb - 1 + MO::R < C::NBW)
+                            mask_request(cur, nb - 1 + MO::R, mk[(nb - 1) % MO::R]);
+                    }
                     __builtin_amdgcn_sched_barrier(0);
+                }
+                if constexpr (OMASK) {
+                    if (C::NBW - 1 >= MO::R) {
+                        wait_vm(MO::after(C::NBW - 1));
+                        mask_pin(mk[(C::NBW - 1) % MO::R]);
+                    }
                 }
 #pragma unroll
                 for (int mb = 0; mb < C::MB; ++mb) {
-                    emit(C::NBW - 1, mb);
+                    emit(C::NBW - 1, mb, mk[(C::NBW - 1) % MO::R][mb][0], mk[(C::NBW - 1) % MO::R][mb][1]);
                     __builtin_amdgcn_sched_barrier(0);
                 }
             }
@@ -615,20 +731,25 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             xpar ^= 1;
         }
         stage(nkc - 1, std::integral_constant<int, 0>(), std::false_type());
-        stage(nkc - 1, std::integral_constant<int, 1>(), std::false_type());
-        if constexpr (!OMASK) {
-            stage(nkc - 1, std::integral_constant<int, 2>(), std::true_type());
-        } else {
-            // With an output mask the blocks are finished after the stage instead: their mask
-            // loads then wait for nothing but themselves (inside the stage every wait on a load
-            // would also wait for the copies in flight) and are all issued together.
-            stage(nkc - 1, std::integral_constant<int, 2>(), std::false_type());
+        if constexpr (OMASK) {
+            // Tiles after the first: one stage ahead of their use.  The wait that ends the next
+            // stage leaves fewer operations outstanding than that stage issues, so these requests
+            // are complete after it.  (Requested at the start of every tile instead they compete
+            // with the first stage's copies and measured slower.)
+            static_assert(C::XG_WAVE < NOPS, "a stage-end wait must cover operations issued before the stage");
+            if (!first_tile) {
 #pragma unroll
-            for (int nb = 0; nb < C::NBW; ++nb)
-#pragma unroll
-                for (int mb = 0; mb < C::MB; ++mb) emit(nb, mb);
+                for (int nb = 0; nb < MO::R; ++nb) mask_request(cur, nb, mk[nb]);
+            }
         }
+        stage(nkc - 1, std::integral_constant<int, 1>(), std::false_type());
+        if constexpr (OMASK) {
+#pragma unroll
+            for (int nb = 0; nb < MO::R; ++nb) mask_pin(mk[nb]);
+        }
+        stage(nkc - 1, std::integral_constant<int, 2>(), std::true_type());
         xpar ^= 1;
+        first_tile = false;
         if (!nxt.valid) break;
         cur = nxt;
         vb_next += gridDim.x;
