@@ -223,7 +223,9 @@ __device__ __forceinline__ uint32_t up_mask_pair(uint32_t v, uint32_t m)
 }
 
 // ------------------------------------------------------------------ MFMA backward-data
-// wave = 32 consecutive input voxels x MB 32-channel blocks of dx; contraction over (tap, C_out)
+// wave = 32 consecutive input voxels x MB 32-channel blocks of dx; contraction over (tap, C_out).
+// This first form requests one fragment pair per 16-channel step and serves the channel counts
+// the tap-preload form below has no instantiation for.
 template <int MB>
 __global__ __launch_bounds__(256) void up_dgrad_mfma_kernel(const bf16_t *__restrict__ dy,
                                                            const bf16_t *__restrict__ packed, bf16_t *__restrict__ dx,
@@ -278,6 +280,108 @@ __global__ __launch_bounds__(256) void up_dgrad_mfma_kernel(const bf16_t *__rest
         dst[0] = o0;
         dst[1] = o1;
     }
+}
+
+// Variant with the loads of a whole tap in flight at once: the NKC dy fragments and the MB * NKC
+// weight fragments of tap t are requested before the tap's matrix instructions, so a wave pays
+// one memory round trip per tap instead of one per 16-channel step.  NKC = C_out / 16 is a
+// template parameter so that the fragments live in registers.
+template <int MB, int NKC, int KCH>
+__global__ __launch_bounds__(256) void up_dgrad_tap_kernel(const bf16_t *__restrict__ dy, const bf16_t *__restrict__ packed,
+                                                          bf16_t *__restrict__ dx, const bf16_t *__restrict__ omask,
+                                                          int64_t V, int D, int H, int W, int cin)
+{
+    constexpr int cout = NKC * 16;
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
+    const int hb = lane >> 5, vl = lane & 31;
+    const int64_t nb = (int64_t)blockIdx.x * 4 + wv;
+    const int cib0 = blockIdx.y * MB;
+    const int64_t v = nb * 32 + vl;
+    const bool live = v < V;
+    const int64_t vv = live ? v : V - 1;   // dead lanes read a valid voxel and store nothing
+    const int w = (int)(vv % W);
+    const int h = (int)((vv / W) % H);
+    const int d = (int)((vv / ((int64_t)W * H)) % D);
+    const int64_t n = vv / ((int64_t)W * H * D);
+    f32x16 acc[MB];
+#pragma unroll
+    for (int m = 0; m < MB; ++m)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) acc[m][i] = 0.f;
+    const uint4 *ap = reinterpret_cast<const uint4 *>(packed) + lane;
+#pragma unroll 1
+    for (int t = 0; t < 8; ++t) {
+        const int64_t o = ((n * 2 * D + 2 * d + (t >> 2)) * 2 * H + 2 * h + ((t >> 1) & 1)) * (2 * (int64_t)W) + 2 * w + (t & 1);
+        const uint4 *gp = reinterpret_cast<const uint4 *>(dy + o * cout + hb * 8);
+#pragma unroll
+        for (int k0 = 0; k0 < NKC; k0 += KCH) {
+            uint4 braw[KCH], araw[MB][KCH];
+#pragma unroll
+            for (int kc = 0; kc < KCH; ++kc) braw[kc] = gp[(k0 + kc) * 2];
+#pragma unroll
+            for (int m = 0; m < MB; ++m)
+#pragma unroll
+                for (int kc = 0; kc < KCH; ++kc) araw[m][kc] = ap[(((int64_t)(cib0 + m) * 8 + t) * NKC + k0 + kc) * 64];
+#pragma unroll
+            for (int kc = 0; kc < KCH; ++kc)
+#pragma unroll
+                for (int m = 0; m < MB; ++m)
+                    acc[m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, araw[m][kc]),
+                                                                     __builtin_bit_cast(bf16x8, braw[kc]), acc[m], 0, 0, 0);
+        }
+    }
+    if (!live) return;
+#pragma unroll
+    for (int m = 0; m < MB; ++m) {
+        const int64_t eo = v * cin + (cib0 + m) * 32 + hb * 16;
+        uint4 o0 = make_uint4(pack2bf(acc[m][0], acc[m][1]), pack2bf(acc[m][2], acc[m][3]), pack2bf(acc[m][4], acc[m][5]),
+                              pack2bf(acc[m][6], acc[m][7]));
+        uint4 o1 = make_uint4(pack2bf(acc[m][8], acc[m][9]), pack2bf(acc[m][10], acc[m][11]),
+                              pack2bf(acc[m][12], acc[m][13]), pack2bf(acc[m][14], acc[m][15]));
+        if (omask) {
+            const uint4 *mp = reinterpret_cast<const uint4 *>(omask + eo);
+            uint4 m0 = mp[0], m1 = mp[1];
+            o0.x = up_mask_pair(o0.x, m0.x); o0.y = up_mask_pair(o0.y, m0.y); o0.z = up_mask_pair(o0.z, m0.z); o0.w = up_mask_pair(o0.w, m0.w);
+            o1.x = up_mask_pair(o1.x, m1.x); o1.y = up_mask_pair(o1.y, m1.y); o1.z = up_mask_pair(o1.z, m1.z); o1.w = up_mask_pair(o1.w, m1.w);
+        }
+        uint4 *dst = reinterpret_cast<uint4 *>(dx + eo);
+        dst[0] = o0;
+        dst[1] = o1;
+    }
+}
+
+template <int MB, int NKC, int KCH>
+static void launch_up_dgrad_tap(const bf16_t *dy, const bf16_t *pb, bf16_t *dx, const bf16_t *mask, int64_t V, int D, int H,
+                                int W, int cin, hipStream_t st)
+{
+    const int64_t blocks = (V + 127) / 128;
+    up_dgrad_tap_kernel<MB, NKC, KCH><<<dim3((unsigned)blocks, (unsigned)(cin / 32 / MB)), 256, 0, st>>>(dy, pb, dx, mask, V, D, H, W, cin);
+}
+
+// Picks the tap-preload instantiation for the shape; false when there is none (C_out not 32, 64,
+// 128 or 256).  MB (32-channel blocks of dx per wave) is the largest of 4, 2, 1 that divides the
+// block count and still gives the chip at least one workgroup per compute unit: small volumes
+// want many short waves, large ones want dy fetched by as few channel groups as possible.  The
+// fragments of KCH 16-channel steps are in registers at once: (MB + 1) * KCH vectors of four.
+static bool up_dgrad_tap_dispatch(const bf16_t *dy, const bf16_t *pb, bf16_t *dx, const bf16_t *mask, int64_t V, int D, int H,
+                                  int W, int cin, int cout, hipStream_t st)
+{
+    const int nb = cin / 32;
+    const int64_t blocks = (V + 127) / 128;
+    int mb = 1;
+    if (nb % 4 == 0 && blocks * (nb / 4) >= 256) mb = 4;
+    else if (nb % 2 == 0 && blocks * (nb / 2) >= 256) mb = 2;
+#define K3_UPT(MBV, NKCV, KCHV)                                                         \
+    if (mb == MBV && cout == NKCV * 16) {                                               \
+        launch_up_dgrad_tap<MBV, NKCV, KCHV>(dy, pb, dx, mask, V, D, H, W, cin, st);    \
+        return true;                                                                    \
+    }
+    K3_UPT(1, 2, 2) K3_UPT(2, 2, 2) K3_UPT(4, 2, 2)
+    K3_UPT(1, 4, 4) K3_UPT(2, 4, 4) K3_UPT(4, 4, 4)
+    K3_UPT(1, 8, 8) K3_UPT(2, 8, 8) K3_UPT(4, 8, 4)
+    K3_UPT(1, 16, 8) K3_UPT(2, 16, 8) K3_UPT(4, 16, 4)
+#undef K3_UPT
+    return false;
 }
 
 // ------------------------------------------------------------------ MFMA backward-weight
@@ -726,6 +830,10 @@ int k3_upconv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *w, co
         int64_t blocks = (V + 127) / 128;
         if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
         int nb = cin / 32;
+        if (up_dgrad_tap_dispatch((const bf16_t *)dy, pb, (bf16_t *)dx, (const bf16_t *)dx_mask, V, D, H, W, cin, cout, st)) {
+            K3_LAUNCH_CHECK();
+            return K3_OK;
+        }
         if (nb % 4 == 0)
             up_dgrad_mfma_kernel<4><<<dim3((unsigned)blocks, (unsigned)(nb / 4)), 256, 0, st>>>((const bf16_t *)dy, pb, (bf16_t *)dx, (const bf16_t *)dx_mask, V, D, H, W, cin, cout);
         else if (nb % 2 == 0)

@@ -270,3 +270,37 @@ def test_tensor_with_more_than_4gi_elements(orc):
     torch.cuda.synchronize()
     assert rel(host64(dW4), 4.0 * host64(dW1)) < 1e-5
     assert rel(host64(db4), 4.0 * host64(db1)) < 1e-5
+
+
+@pytest.mark.parametrize("sp,ci,co", [((1, 32, 32, 32), 128, 64),     # four channel blocks per wave, 4 steps per tap
+                                      ((1, 32, 32, 32), 64, 32),      # two blocks per wave
+                                      ((1, 32, 32, 32), 128, 128),    # four blocks, 8 steps in two halves
+                                      ((1, 16, 32, 32), 256, 256),    # 16 steps in chunks of 4
+                                      ((1, 20, 24, 44), 128, 64),     # ragged last voxel block
+                                      ((1, 8, 8, 16), 256, 128)])     # small volume: one block per wave
+def test_upconv_bwd_data_at_unet_sizes(orc, sp, ci, co):
+    """The transposed-conv backward-data instantiations that only large volumes select.  The pass is
+    local (dx at an input voxel reads the 2x2x2 output voxels it covers), so the oracle runs on
+    crops of whole blocks, cut at the corners and inside."""
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, to_f64, empty
+    N, D, H, W = sp
+    x = np.maximum(synth.activations(64, (N, D, H, W, ci), "bf16"), 0)       # the stored ReLU output used as mask
+    w = synth.upconv_weights(65, ci, co, "bf16")
+    dy = synth.activations(66, (N, 2 * D, 2 * H, 2 * W, co), "bf16")
+    xd, wd, dyd = to_dev(x, "bf16"), to_dev(w, "bf16"), to_dev(dy, "bf16")
+    pk = torch.empty(k3.upconv3d_packed_bytes(ci, co, k3.BF16), device="cuda", dtype=torch.uint8)
+    k3.upconv3d_pack_weights(wd, pk)
+    dx, dxm = empty(x.shape, "bf16"), empty(x.shape, "bf16")
+    k3.upconv3d_bwd_data(dyd, wd, pk, dx)
+    k3.upconv3d_bwd_data(dyd, wd, pk, dxm, dx_mask=xd)
+    torch.cuda.synchronize()
+    got, gotm = to_f64(dx), to_f64(dxm)
+    cd, ch, cw = min(4, D), min(4, H), min(8, W)
+    for (d0, h0, w0) in [(0, 0, 0), (D - cd, H - ch, W - cw), (D // 2 - 1, H // 3, W // 2 - 3), (0, H - ch, W // 2)]:
+        crop = dy[:, 2 * d0:2 * (d0 + cd), 2 * h0:2 * (h0 + ch), 2 * w0:2 * (w0 + cw), :].astype(np.float64)
+        ref = orc.upconv3d_bwd_data(crop, w.astype(np.float64))
+        sl = (slice(None), slice(d0, d0 + cd), slice(h0, h0 + ch), slice(w0, w0 + cw))
+        assert rel(got[sl], ref) < 4e-3, (d0, h0, w0)
+        assert rel(gotm[sl], orc.relu_bwd(ref, x[sl].astype(np.float64))) < 4e-3, (d0, h0, w0)
