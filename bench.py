@@ -428,7 +428,7 @@ def bench_sweep(args):
     the overhead of LMS growing with the image resolution on its 16 GB GPUs): base-64 U-Net, batch
     2, edge 192 ... 288, every step planned for the same budget."""
     out = []
-    for size in (192, 208, 224, 240, 256, 272, 288, 304):
+    for size in args.sweep_edges:
         u = bench_unet(args, 64, size, 2, False, f"U-Net base 64, 2 x {size}^3", budget_gb=args.sweep_budget_gb)
         leg = u["planned_for_budget"]
         row = {"edge": size, "no_swap_ms": u["ms_per_step_no_swap"], "no_swap_peak_gb": u["accounted_peak_gb_no_swap"],
@@ -440,6 +440,11 @@ def bench_sweep(args):
                         "tensors_swapped": len(leg["plan"]["swapped_tensors"])})
         print("sweep", json.dumps(row), file=sys.stderr, flush=True)
         out.append(row)
+        import gc
+        import torch
+        gc.collect()
+        torch.cuda.synchronize()
+        torch.cuda.empty_cache()   # every size starts from an empty block cache
     return {"device_budget_gb": args.sweep_budget_gb, "rows": out}
 
 
@@ -452,6 +457,8 @@ def main():
     ap.add_argument("--budget-gb", type=float, default=0.0,
                     help="U-Net workloads: also run under this device-memory limit, without and with swapping")
     ap.add_argument("--sweep-budget-gb", type=float, default=32.0, help="device budget of the sweep workload")
+    ap.add_argument("--sweep-edges", type=int, nargs="+", default=[192, 208, 224, 240, 256, 272, 288, 304],
+                    help="volume edges of the sweep workload (multiples of 8)")
     ap.add_argument("--unet-steps", type=int, default=3)
     ap.add_argument("--with-unet", action="store_true", help="also time the full U-Net steps (cfg3, and cfg4 with swapping)")
     ap.add_argument("--no-graph", action="store_true")

@@ -27,7 +27,8 @@ CONV_RATE = {"conv_fwd": (0.62e15, 1.10e15, 1.27e15), "conv_dgrad": (0.55e15, 1.
 STREAM_RATE = {"pool_fwd": 5.4e12, "pool_bwd": 5.4e12, "up_fwd": 4.0e12, "up_wgrad": 5.1e12, "up_dgrad": 2.8e12,
                "head": 3.5e12, "first_fwd": 3.1e12, "first_wgrad": 3.3e12, "upsample_fwd": 5.0e12, "upsample_bwd": 5.0e12}
 LAUNCH_SECONDS = 12e-6
-LINK_BYTES_PER_S = 50e9
+LINK_ONE_BYTES_PER_S = 55e9     # one copy direction busy
+LINK_BOTH_BYTES_PER_S = 48.7e9  # each direction, both busy
 
 
 def kernel_seconds(call):
@@ -42,15 +43,32 @@ def kernel_seconds(call):
     return LAUNCH_SECONDS + call.nbytes / STREAM_RATE[call.fn]
 
 
-class SimBackend:
-    """Virtual-time backend: three clocks and the swap engine's ordering rules."""
+class _Copy:
+    __slots__ = ("ready", "dep", "left", "end")
 
-    def __init__(self, seconds_of=kernel_seconds, link=LINK_BYTES_PER_S, durations=None):
-        self.tc = self.d2h = self.h2d = 0.0
+    def __init__(self, ready, nbytes, dep=None):
+        self.ready, self.dep, self.left, self.end = ready, dep, float(nbytes), None
+
+
+class SimBackend:
+    """Virtual-time backend: a compute clock and the two copy streams with the swap engine's
+    ordering rules.  Each copy stream is a FIFO; a copy starts when its predecessor is done, the
+    compute stream has reached the point it was issued at and (copy-in) the copy-out of the same
+    tensor has finished.  The link is shared: a direction moves link_one bytes/s while the other
+    is idle and link_both while both are busy (measured: 55 and 48.7 GB/s), so copy end times
+    are resolved lazily, when the compute stream asks for them (a wait, or the end of the step)."""
+
+    def __init__(self, seconds_of=kernel_seconds, link=None, durations=None, link_one=LINK_ONE_BYTES_PER_S,
+                 link_both=LINK_BOTH_BYTES_PER_S):
+        self.tc = 0.0
         self.stall = 0.0
-        self.seconds_of, self.link, self.durations = seconds_of, link, durations
+        self.seconds_of, self.durations = seconds_of, durations
+        self.r1, self.r2 = (link, link) if link is not None else (link_one, link_both)
         self._n = 0
         self.timeline = []     # compute clock after each call
+        self._q = ([], [])     # pending copies: device-to-host, host-to-device (FIFO each)
+        self._t = 0.0          # both streams are simulated up to here
+        self.copy_end = 0.0    # end of the last finished copy
 
     def slab(self, nbytes):
         pass
@@ -69,35 +87,89 @@ class SimBackend:
         self.tc += d
         self.timeline.append(self.tc)
 
+    # ---- the two copy streams
+    def _advance(self, until, target=None):
+        """Simulate both streams up to time `until` (no copy is issued meanwhile), or, with a
+        target, until that copy has finished."""
+        inf = float("inf")
+        while True:
+            heads = [q[0] if q else None for q in self._q]
+            if heads[0] is None and heads[1] is None:
+                break
+            starts = []
+            for h in heads:
+                if h is None:
+                    starts.append(inf)
+                elif h.dep is not None and h.dep.end is None:
+                    starts.append(inf)          # its copy-out is still queued on the other stream
+                else:
+                    starts.append(max(h.ready, h.dep.end if h.dep is not None else 0.0))
+            active = [st <= self._t for st in starts]
+            rate = self.r2 if (active[0] and active[1]) else self.r1
+            nxt = until
+            for h, st, a in zip(heads, starts, active):
+                if a:
+                    nxt = min(nxt, self._t + h.left / rate)
+                elif st < inf:
+                    nxt = min(nxt, st)
+            if nxt == inf or nxt < self._t:
+                break
+            dt = nxt - self._t
+            self._t = nxt
+            for q, h, a in zip(self._q, heads, active):
+                if a:
+                    h.left -= dt * rate
+                    if h.left <= 1e-3:
+                        h.end = nxt
+                        self.copy_end = max(self.copy_end, nxt)
+                        q.pop(0)
+            if target is not None and target.end is not None:
+                return
+            if self._t >= until:
+                return
+        if until < inf:
+            self._t = max(self._t, until)
+
+    def _end_of(self, c):
+        self._advance(self.tc)
+        if c.end is None:
+            self._advance(float("inf"), target=c)
+        return c.end
+
     def _wait(self, until):
         if until > self.tc:
             self.stall += until - self.tc
             self.tc = until
 
     def swap_out(self, info, block):
-        start = max(self.d2h, self.tc)
-        self.d2h = start + info.nbytes / self.link
-        return {"out": self.d2h, "in": 0.0, "bytes": info.nbytes}
+        c = _Copy(self.tc, info.nbytes)
+        self._advance(self.tc)
+        self._q[0].append(c)
+        return {"out": c, "in": None, "bytes": info.nbytes}
 
     def release_after(self, h):
-        self._wait(h["out"])
+        self._wait(self._end_of(h["out"]))
 
     def prefetch_start(self, h, block):
-        start = max(self.h2d, self.tc, h["out"])
-        self.h2d = h["in"] = start + h["bytes"] / self.link
+        c = _Copy(self.tc, h["bytes"], dep=h["out"])
+        self._advance(self.tc)
+        self._q[1].append(c)
+        h["in"] = c
 
     def wait_in(self, h):
-        self._wait(h["in"])
+        self._wait(self._end_of(h["in"]))
 
     def evict(self, h):
-        self._wait(h["in"])
+        self._wait(self._end_of(h["in"]))
 
     def release(self, h):
         pass
 
     @property
     def seconds(self):
-        return max(self.tc, self.d2h, self.h2d)
+        self._advance(self.tc)
+        self._advance(float("inf"))
+        return max(self.tc, self.copy_end)
 
 
 class Plan:

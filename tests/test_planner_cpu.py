@@ -160,16 +160,50 @@ def test_simulated_stream_ordering():
     info = TensorInfo("t", (1, 1, 1, 1, 500000), 2)               # 1 MB: one second on this link
     be.tc = 0.25
     h = be.swap_out(info, None)
-    assert h["out"] == pytest.approx(1.25)
     be.release_after(h)
+    assert h["out"].end == pytest.approx(1.25)
     assert be.tc == pytest.approx(1.25) and be.stall == pytest.approx(1.0)
     be.tc = 1.5
     be.prefetch_start(h, None)
-    assert h["in"] == pytest.approx(2.5)
     be.tc = 2.0                                                    # kernels overlapped the copy-in
     be.wait_in(h)
+    assert h["in"].end == pytest.approx(2.5)
     assert be.tc == pytest.approx(2.5) and be.stall == pytest.approx(1.5)
     assert be.seconds == pytest.approx(2.5)
+    # a copy-in issued while the copy-out of the same tensor is still running starts when that ends
+    be = planner.SimBackend(link=1e6)
+    h = be.swap_out(info, None)                                    # runs 0 .. 1
+    be.tc = 0.5
+    be.prefetch_start(h, None)                                     # may start at 1.0, ends 2.0
+    be.wait_in(h)
+    assert be.tc == pytest.approx(2.0)
+
+
+def test_the_two_directions_share_the_link():
+    """One direction alone moves link_one bytes/s, both together link_both each; a copy that
+    overlaps the other direction for part of its life is priced piecewise."""
+    from paper_1811_12174_amd.program import TensorInfo
+    a = TensorInfo("a", (1, 1, 1, 1, 500000), 2)                   # 1 MB
+    b = TensorInfo("b", (1, 1, 1, 1, 500000), 2)
+    be = planner.SimBackend(link_one=1e6, link_both=0.5e6)
+    ha = be.swap_out(a, None); be.release_after(ha)                # a goes out alone: 0 .. 1
+    assert be.tc == pytest.approx(1.0)
+    be.prefetch_start(ha, None)                                    # a comes back from t = 1 ...
+    hb = be.swap_out(b, None)                                      # ... while b goes out: both at half rate
+    be.wait_in(ha)
+    assert be.tc == pytest.approx(3.0)                             # 1 MB at 0.5 MB/s
+    be.release_after(hb)
+    assert be.tc == pytest.approx(3.0)                             # b finished at the same moment
+    # unequal overlap: c alone for 0.5 s (0.5 MB), then shares with d
+    be = planner.SimBackend(link_one=1e6, link_both=0.5e6)
+    hc = be.swap_out(a, None); be.release_after(hc)                # out: 0 .. 1
+    be.prefetch_start(hc, None)                                    # in from 1.0
+    be.tc = 1.5
+    hd = be.swap_out(b, None)                                      # out from 1.5: both busy
+    be.wait_in(hc)                                                 # 0.5 MB alone + 0.5 MB at half rate = 1.0 .. 2.5
+    assert be.tc == pytest.approx(2.5)
+    be.release_after(hd)                                           # d: 0.5 MB shared until 2.5, then 0.5 MB alone
+    assert be.tc == pytest.approx(3.0)
 
 
 def test_cost_model_orders_of_magnitude():
