@@ -218,3 +218,29 @@ def sgd_momentum_step(w, v, g, lr, momentum=0.0, weight_decay=0.0):
     g = np.asarray(g, dtype=np.float64)
     v2 = momentum * v + (g + weight_decay * w)
     return w - lr * v2, v2
+
+
+def relu_bits(y):
+    """Bit mask of a stored ReLU output: one uint16 word per 16 consecutive channels of a voxel,
+    bit i of word j set iff y[..., 16 j + i] > 0 (the derivative of ReLU as section 4.1's layers
+    use it in the backward pass, one bit per element).  y: [..., C] with C a multiple of 16;
+    returns [..., C // 16] uint16.  Pinned in tests/test_oracle_conv.py against relu_bwd."""
+    y = np.asarray(y, dtype=np.float64)
+    C = y.shape[-1]
+    assert C % 16 == 0
+    pos = (y > 0).reshape(y.shape[:-1] + (C // 16, 16))
+    out = np.zeros(pos.shape[:-1], dtype=np.uint32)
+    for i in range(16):
+        out |= pos[..., i].astype(np.uint32) << i
+    return out.astype(np.uint16)
+
+
+def apply_relu_bits(dy, bits):
+    """dy with every element zeroed whose bit is clear (the inverse reading of relu_bits)."""
+    dy = np.asarray(dy, dtype=np.float64)
+    C = dy.shape[-1]
+    keep = np.zeros(dy.shape, dtype=bool).reshape(dy.shape[:-1] + (C // 16, 16))
+    b = np.asarray(bits).astype(np.uint32)
+    for i in range(16):
+        keep[..., i] = ((b >> i) & 1).astype(bool)
+    return dy * keep.reshape(dy.shape)

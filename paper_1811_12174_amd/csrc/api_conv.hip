@@ -12,7 +12,7 @@ using namespace k3;
 
 extern "C" {
 
-int k3_version(void) { return 100; }
+int k3_version(void) { return 101; }
 int k3_last_hip_error(void) { return g_last_hip_error; }
 
 const char *k3_status_string(int s)

@@ -199,3 +199,18 @@ def test_against_torch_cpu_fp64(orc):
     dW, db = orc.conv3d_bwd_weight(x, g)
     np.testing.assert_allclose(dW, wt.grad.permute(2, 3, 4, 1, 0).numpy(), atol=1e-10)
     np.testing.assert_allclose(db, bt.grad.numpy(), atol=1e-10)
+
+
+def test_relu_bits_by_hand_and_against_relu_bwd(orc):
+    y = np.zeros((1, 1, 1, 2, 32))
+    y[0, 0, 0, 0, [0, 3, 15, 16, 31]] = [1.0, 0.5, 2.0, 1e-30, 7.0]
+    y[0, 0, 0, 1, [1, 17]] = [-1.0, 3.0]                       # a negative value sets no bit
+    b = orc.relu_bits(y)
+    assert b.shape == (1, 1, 1, 2, 2) and b.dtype == np.uint16
+    assert b[0, 0, 0, 0].tolist() == [(1 << 0) | (1 << 3) | (1 << 15), (1 << 0) | (1 << 15)]
+    assert b[0, 0, 0, 1].tolist() == [0, 1 << 1]
+    rng = np.random.default_rng(12)
+    y = np.maximum(rng.normal(size=(2, 3, 2, 5, 48)), 0)
+    dy = rng.normal(size=y.shape)
+    assert np.array_equal(orc.apply_relu_bits(dy, orc.relu_bits(y)), orc.relu_bwd(dy, y))
+    assert orc.relu_bits(np.ones((1, 1, 1, 1, 16)))[0, 0, 0, 0, 0] == 0xFFFF
