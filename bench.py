@@ -83,8 +83,12 @@ def bench_cfg2(args):
     db1, db2 = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
     ws = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(x, a1), device="cuda", dtype=torch.uint8)
 
+    a1bits = torch.empty(k3.relu_bits_bytes(a1) // 2, device="cuda", dtype=torch.int16)
+
     def step():
-        k3.conv3d_fwd(x, w1, pk1, b1, 1, a1)
+        # conv1 also writes the one-bit-per-element ReLU mask of its output, which conv2's
+        # backward-data pass applies to the gradient it produces
+        k3.conv3d_fwd_bits(x, w1, pk1, b1, 1, a1, a1bits)
         k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2)
         k3.pool3d_fwd(a2, p)
         # each producer of an activation gradient applies the ReLU mask of the tensor it
@@ -92,7 +96,7 @@ def bench_cfg2(args):
         # passes read no mask
         k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True)
         k3.conv3d_bwd_weight(a1, da2, None, dW2, db2, ws)
-        k3.conv3d_bwd_data(da2, None, w2, pk2, da1, dx_mask=a1)
+        k3.conv3d_bwd_data_bits(da2, None, w2, pk2, da1, a1bits)
         k3.conv3d_bwd_weight(x, da1, None, dW1, db1, ws)
         k3.conv3d_bwd_data(da1, None, w1, pk1, dx)
 
@@ -123,16 +127,16 @@ def bench_cfg2(args):
     it = max(20, args.steps // 4)
     kern = {
         "conv3d_fwd": time_calls(lambda: k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2), it),
-        "conv3d_bwd_data": time_calls(lambda: k3.conv3d_bwd_data(da2, None, w2, pk2, da1, dx_mask=a1), it),
+        "conv3d_bwd_data": time_calls(lambda: k3.conv3d_bwd_data_bits(da2, None, w2, pk2, da1, a1bits), it),
         "conv3d_bwd_weight": time_calls(lambda: k3.conv3d_bwd_weight(a1, da2, None, dW2, db2, ws), it),
         "pool3d_fwd": time_calls(lambda: k3.pool3d_fwd(a2, p), it),
         "pool3d_bwd": time_calls(lambda: k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True), it),
     }
 
     def mix():   # the implicit-GEMM kernel as the step launches it: 2 forward + 2 backward-data passes
-        k3.conv3d_fwd(x, w1, pk1, b1, 1, a1)
+        k3.conv3d_fwd_bits(x, w1, pk1, b1, 1, a1, a1bits)
         k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2)
-        k3.conv3d_bwd_data(da2, None, w2, pk2, da1, dx_mask=a1)
+        k3.conv3d_bwd_data_bits(da2, None, w2, pk2, da1, a1bits)
         k3.conv3d_bwd_data(da1, None, w1, pk1, dx)
     mfma_ms = time_calls(mix, it) / 4.0
     # (the weight-gradient call is two launches: the MFMA kernel and the small split-K reduction)
@@ -223,13 +227,15 @@ def pmc_pass(args):
     p = torch.empty_like(dyp)
     dW, db = torch.empty((3, 3, 3, C, C), device="cuda"), torch.empty(C, device="cuda")
     ws = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(x, a1), device="cuda", dtype=torch.uint8)
+    a1bits = torch.empty(k3.relu_bits_bytes(a1) // 2, device="cuda", dtype=torch.int16)
     for _ in range(3):
-        k3.conv3d_fwd(x, w, pk, b, 1, a1)
+        k3.conv3d_fwd_bits(x, w, pk, b, 1, a1, a1bits)
         k3.conv3d_fwd(a1, w, pk, b, 1, a2)
         k3.pool3d_fwd(a2, p)
         k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True)
         k3.conv3d_bwd_weight(a1, da2, None, dW, db, ws)
-        k3.conv3d_bwd_data(da2, None, w, pk, da1, dx_mask=a1)
+        k3.conv3d_bwd_data_bits(da2, None, w, pk, da1, a1bits)
+        k3.conv3d_bwd_data(da1, None, w, pk, a2)
     torch.cuda.synchronize()
     print(json.dumps({"pmc_pass": "done", "copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4}))
 

@@ -103,6 +103,22 @@ int k3_conv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *y_mask,
                        const k3_tensor *dxd, void *dx, const k3_tensor *dx2d, void *dx2,
                        const void *dx_mask, void *stream);
 
+/* One-bit-per-element form of the ReLU mask.  A stored ReLU output y with C channels
+ * (C a multiple of 16, K3_E_UNSUPPORTED otherwise) has the bit tensor
+ *   bits[v][j] (uint16, j < C / 16), bit i of word j set iff y[v][16 j + i] > 0,
+ * k3_relu_bits_bytes reports its size.  k3_conv3d_fwd_bits is k3_conv3d_fwd that also writes
+ * relu_bits (dev) for its output; k3_conv3d_bwd_data_bits is k3_conv3d_bwd_data whose mask for
+ * the first destination (see dx_mask there) is given as such bits instead of as the bf16 /
+ * fp32 tensor: the backward pass then reads 1/16 of the bytes.  Results are identical to the
+ * tensor-mask forms. */
+int k3_relu_bits_bytes(const k3_tensor *yd, size_t *bytes);
+int k3_conv3d_fwd_bits(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2, const void *w,
+                       const void *packed, const float *bias, int relu, const k3_tensor *yd, void *y,
+                       void *relu_bits, void *stream);
+int k3_conv3d_bwd_data_bits(const k3_tensor *dyd, const void *dy, const void *y_mask, const void *w,
+                            const void *packed, const k3_tensor *dxd, void *dx, const k3_tensor *dx2d, void *dx2,
+                            const void *dx_mask_bits, void *stream);
+
 /* Workspace bytes k3_conv3d_bwd_weight needs for these shapes (split-K partial sums). */
 int k3_conv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor *x2d,
                                          const k3_tensor *dyd, size_t *bytes);

@@ -68,36 +68,84 @@ static int fill_args(ConvArgs &a, const k3_tensor *xd, const k3_tensor *x2d, con
     return K3_OK;
 }
 
-int k3_conv3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2, const void *w,
-                  const void *packed, const float *bias, int relu, const k3_tensor *yd, void *y, void *stream)
+static int conv_fwd_any(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2, const void *w,
+                        const void *packed, const float *bias, int relu, const k3_tensor *yd, void *y, void *relu_bits,
+                        void *stream)
 {
     ConvArgs a;
     int rc = fill_args(a, xd, x2d, x2, yd);
     if (rc != K3_OK) return rc;
     if (!x || !w || !y) return K3_E_BADARG;
-    a.x = x; a.x2 = x2; a.w = w; a.packed = packed; a.bias = bias; a.relu = relu ? 1 : 0; a.y = y;
+    if (relu_bits && a.cout % 16 != 0) return K3_E_UNSUPPORTED;
+    a.x = x; a.x2 = x2; a.w = w; a.packed = packed; a.bias = bias; a.relu = relu ? 1 : 0; a.y = y; a.ybits = relu_bits;
+    hipStream_t st = (hipStream_t)stream;
     if (mfma_ok(a.dtype, a.c1, a.c2, a.cout)) {
         if (!packed) return K3_E_BADARG;
-        return conv_fwd_mfma(a, (hipStream_t)stream);
+        return conv_fwd_mfma(a, st);   // writes the bits itself (or runs the generic pass)
     }
-    if (conv_first_ok(a.dtype, a.c1, a.c2, a.cout)) return conv_first_fwd(a, (hipStream_t)stream);
-    return conv_fwd_direct(a, (hipStream_t)stream);
+    if (conv_first_ok(a.dtype, a.c1, a.c2, a.cout)) return conv_first_fwd(a, st);   // likewise
+    rc = conv_fwd_direct(a, st);
+    if (rc == K3_OK && relu_bits) rc = launch_relu_bits(a.dtype, y, relu_bits, a.V() * a.cout / 16, st);
+    return rc;
+}
+
+int k3_conv3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2, const void *w,
+                  const void *packed, const float *bias, int relu, const k3_tensor *yd, void *y, void *stream)
+{
+    return conv_fwd_any(xd, x, x2d, x2, w, packed, bias, relu, yd, y, nullptr, stream);
+}
+
+int k3_relu_bits_bytes(const k3_tensor *yd, size_t *bytes)
+{
+    if (!desc_ok(yd) || !bytes) return K3_E_BADARG;
+    if (yd->c % 16 != 0) return K3_E_UNSUPPORTED;
+    *bytes = (size_t)voxels(yd) * (size_t)(yd->c / 16) * sizeof(uint16_t);
+    return K3_OK;
+}
+
+int k3_conv3d_fwd_bits(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2, const void *w,
+                       const void *packed, const float *bias, int relu, const k3_tensor *yd, void *y, void *relu_bits,
+                       void *stream)
+{
+    if (!relu_bits) return K3_E_BADARG;
+    return conv_fwd_any(xd, x, x2d, x2, w, packed, bias, relu, yd, y, relu_bits, stream);
+}
+
+static int conv_dgrad_any(const k3_tensor *dyd, const void *dy, const void *y_mask, const void *w, const void *packed,
+                          const k3_tensor *dxd, void *dx, const k3_tensor *dx2d, void *dx2, const void *dx_mask,
+                          const void *dx_mask_bits, void *stream)
+{
+    ConvArgs a;
+    int rc = fill_args(a, dxd, dx2d, dx2, dyd);
+    if (rc != K3_OK) return rc;
+    if (!dy || !w || !dx) return K3_E_BADARG;
+    if (dx_mask && dx_mask_bits) return K3_E_BADARG;
+    if (dx_mask_bits && a.c1 % 16 != 0) return K3_E_UNSUPPORTED;
+    a.dy = dy; a.ymask = y_mask; a.w = w; a.packed = packed; a.dx = dx; a.dx2 = dx2; a.omask = dx_mask;
+    a.omask_bits = dx_mask_bits;
+    hipStream_t st = (hipStream_t)stream;
+    if (mfma_ok(a.dtype, a.c1, a.c2, a.cout)) {
+        if (!packed) return K3_E_BADARG;
+        return conv_dgrad_mfma(a, st);   // reads the bits itself (or runs the generic pass)
+    }
+    rc = conv_dgrad_direct(a, st);
+    if (rc == K3_OK && dx_mask_bits) rc = launch_apply_relu_bits(a.dtype, dx, dx_mask_bits, a.V() * a.c1 / 16, st);
+    return rc;
 }
 
 int k3_conv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *y_mask, const void *w, const void *packed,
                        const k3_tensor *dxd, void *dx, const k3_tensor *dx2d, void *dx2, const void *dx_mask,
                        void *stream)
 {
-    ConvArgs a;
-    int rc = fill_args(a, dxd, dx2d, dx2, dyd);
-    if (rc != K3_OK) return rc;
-    if (!dy || !w || !dx) return K3_E_BADARG;
-    a.dy = dy; a.ymask = y_mask; a.w = w; a.packed = packed; a.dx = dx; a.dx2 = dx2; a.omask = dx_mask;
-    if (mfma_ok(a.dtype, a.c1, a.c2, a.cout)) {
-        if (!packed) return K3_E_BADARG;
-        return conv_dgrad_mfma(a, (hipStream_t)stream);
-    }
-    return conv_dgrad_direct(a, (hipStream_t)stream);
+    return conv_dgrad_any(dyd, dy, y_mask, w, packed, dxd, dx, dx2d, dx2, dx_mask, nullptr, stream);
+}
+
+int k3_conv3d_bwd_data_bits(const k3_tensor *dyd, const void *dy, const void *y_mask, const void *w, const void *packed,
+                            const k3_tensor *dxd, void *dx, const k3_tensor *dx2d, void *dx2, const void *dx_mask_bits,
+                            void *stream)
+{
+    if (!dx_mask_bits) return K3_E_BADARG;
+    return conv_dgrad_any(dyd, dy, y_mask, w, packed, dxd, dx, dx2d, dx2, nullptr, dx_mask_bits, stream);
 }
 
 int k3_conv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor *x2d, const k3_tensor *dyd, size_t *bytes)

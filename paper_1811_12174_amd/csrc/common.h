@@ -50,6 +50,46 @@ __device__ __forceinline__ uint32_t pack2bf(float lo, float hi)
 }
 __device__ __forceinline__ bf16_t f2bf(float f) { return (bf16_t)(pack2bf(f, 0.f) & 0xffffu); }
 
+// One-bit-per-element ReLU masks: word layout is bit i <-> element i of 16 consecutive channels.
+// The 16 stored bf16 values arrive as 8 packed pairs d[0..7] (element 2k in the low half of d[k]).
+typedef __attribute__((ext_vector_type(2))) short s16x2_t;
+typedef __attribute__((ext_vector_type(2))) unsigned short u16x2_t;
+// bit 0: the low bf16 half is > 0, bit 16: the high half is (as signed 16-bit integers the positive
+// bf16 values are exactly the positive integers; -0.0 and negative values are not)
+__device__ __forceinline__ uint32_t bf16_pair_positive(uint32_t d)
+{
+    s16x2_t h = __builtin_bit_cast(s16x2_t, d);
+    const s16x2_t one = {1, 1}, zero = {0, 0};
+    h = __builtin_elementwise_max(__builtin_elementwise_min(h, one), zero);
+    return __builtin_bit_cast(uint32_t, h);
+}
+__device__ __forceinline__ unsigned relu_bits16(const uint32_t (&d)[8])
+{
+    // even elements gather in bits 0..7, odd ones in bits 16..23, then both bytes are spread to
+    // every other bit at once and interleaved
+    unsigned z = bf16_pair_positive(d[0]);
+#pragma unroll
+    for (int k = 1; k < 8; ++k) z |= bf16_pair_positive(d[k]) << k;
+    z = (z | (z << 4)) & 0x0F0F0F0Fu;
+    z = (z | (z << 2)) & 0x33333333u;
+    z = (z | (z << 1)) & 0x55555555u;
+    return (z | (z >> 15)) & 0xffffu;
+}
+// zeroes the bf16 halves of d[0..7] whose bit in m is clear
+__device__ __forceinline__ void apply_bits16(uint32_t (&d)[8], unsigned m)
+{
+    // inverse of the interleave: even bits to 0..7, odd bits to 16..23
+    unsigned z = (m | (m << 15)) & 0x55555555u;
+    z = (z | (z >> 1)) & 0x33333333u;
+    z = (z | (z >> 2)) & 0x0F0F0F0Fu;
+    z = (z | (z >> 4)) & 0x00FF00FFu;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const u16x2_t keep = __builtin_bit_cast(u16x2_t, (z >> k) & 0x00010001u);   // 0 or 1 per half
+        d[k] = __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2_t, d[k]) * keep);
+    }
+}
+
 // Asynchronous copy global -> LDS, 16 bytes per lane (global_load_lds_dwordx4): lane l of the
 // wave writes the 16 bytes at its own global address gptr to LDS byte address lds_base + 16*l
 // (lds_base is wave-uniform).  Completion is tracked by vmcnt; the compiler does not see the

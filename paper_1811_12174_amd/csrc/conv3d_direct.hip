@@ -280,6 +280,53 @@ static int fwd_direct_t(const ConvArgs &a, hipStream_t st)
     K3_LAUNCH_CHECK();
     return K3_OK;
 }
+// ---- one-bit-per-element ReLU masks, generic passes (the MFMA kernels produce / consume the
+// bits themselves; these serve the kernels that do not)
+template <typename T>
+__global__ __launch_bounds__(256) void relu_bits_kernel(const T *__restrict__ y, unsigned short *__restrict__ bits, int64_t nwords)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nwords; i += stride) {
+        unsigned m = 0u;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) m |= (elem<T>::ld(y + i * 16 + e) > 0.f ? 1u : 0u) << e;
+        bits[i] = (unsigned short)m;
+    }
+}
+
+template <typename T>
+__global__ __launch_bounds__(256) void apply_relu_bits_kernel(T *__restrict__ t, const unsigned short *__restrict__ bits,
+                                                             int64_t nwords)
+{
+    const int64_t stride = (int64_t)gridDim.x * 256;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < nwords; i += stride) {
+        const unsigned m = bits[i];
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            if (!((m >> e) & 1u)) elem<T>::st(t + i * 16 + e, 0.f);
+    }
+}
+
+int launch_relu_bits(int dtype, const void *y, void *bits, int64_t nwords, hipStream_t st)
+{
+    const int64_t want = (nwords + 255) / 256;
+    const unsigned grid = (unsigned)(want < 8192 ? (want > 0 ? want : 1) : 8192);
+    if (dtype == K3_F32) relu_bits_kernel<float><<<dim3(grid), 256, 0, st>>>((const float *)y, (unsigned short *)bits, nwords);
+    else relu_bits_kernel<bf16_t><<<dim3(grid), 256, 0, st>>>((const bf16_t *)y, (unsigned short *)bits, nwords);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
+int launch_apply_relu_bits(int dtype, void *t, const void *bits, int64_t nwords, hipStream_t st)
+{
+    const int64_t want = (nwords + 255) / 256;
+    const unsigned grid = (unsigned)(want < 8192 ? (want > 0 ? want : 1) : 8192);
+    if (dtype == K3_F32) apply_relu_bits_kernel<float><<<dim3(grid), 256, 0, st>>>((float *)t, (const unsigned short *)bits, nwords);
+    else apply_relu_bits_kernel<bf16_t><<<dim3(grid), 256, 0, st>>>((bf16_t *)t, (const unsigned short *)bits, nwords);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
 int conv_fwd_direct(const ConvArgs &a, hipStream_t st)
 {
     return a.dtype == K3_F32 ? fwd_direct_t<float>(a, st) : fwd_direct_t<bf16_t>(a, st);

@@ -215,8 +215,9 @@ __device__ __forceinline__ bf16x8 gather8(const unsigned char *p)
 template <int MB>
 __global__ __launch_bounds__(256) void conv_first_fwd_mfma_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
                                                                  const float *__restrict__ bias, int relu,
-                                                                 bf16_t *__restrict__ y, int D, int H, int W, int ntd,
-                                                                 int nth, int ntw, int64_t ntiles)
+                                                                 bf16_t *__restrict__ y, unsigned short *__restrict__ ybits,
+                                                                 int D, int H, int W, int ntd, int nth, int ntw,
+                                                                 int64_t ntiles)
 {
     using namespace firstm;
     constexpr int cout = 32 * MB;
@@ -277,8 +278,12 @@ __global__ __launch_bounds__(256) void conv_first_fwd_mfma_kernel(const bf16_t *
 #pragma unroll
                     for (int i = 0; i < 16; ++i) v[i] = fmaxf(acc[i], floor_);
                     uint4 *dst = reinterpret_cast<uint4 *>(y + vox * cout + mb * 32 + hb * 16);
-                    dst[0] = make_uint4(pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]));
-                    dst[1] = make_uint4(pack2bf(v[8], v[9]), pack2bf(v[10], v[11]), pack2bf(v[12], v[13]), pack2bf(v[14], v[15]));
+                    const uint32_t dd[8] = {pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]),
+                                            pack2bf(v[8], v[9]), pack2bf(v[10], v[11]), pack2bf(v[12], v[13]), pack2bf(v[14], v[15])};
+                    dst[0] = make_uint4(dd[0], dd[1], dd[2], dd[3]);
+                    dst[1] = make_uint4(dd[4], dd[5], dd[6], dd[7]);
+                    if (ybits)   // one bit per stored element: set where it is > 0
+                        ybits[vox * (cout / 16) + mb * 2 + hb] = (unsigned short)relu_bits16(dd);
                 }
             }
         }
@@ -422,13 +427,16 @@ int conv_first_fwd(const ConvArgs &a, hipStream_t st)
         const unsigned grid = (unsigned)(ntiles < 2048 ? ntiles : 2048);
         if (a.cout == 128)
             conv_first_fwd_mfma_kernel<4><<<dim3(grid), 256, 0, st>>>((const bf16_t *)a.x, (const bf16_t *)a.w, a.bias, a.relu,
-                                                                     (bf16_t *)a.y, (int)a.D, (int)a.H, (int)a.W, ntd, nth, ntw, ntiles);
+                                                                     (bf16_t *)a.y, (unsigned short *)a.ybits, (int)a.D, (int)a.H,
+                                                                     (int)a.W, ntd, nth, ntw, ntiles);
         else if (a.cout == 64)
             conv_first_fwd_mfma_kernel<2><<<dim3(grid), 256, 0, st>>>((const bf16_t *)a.x, (const bf16_t *)a.w, a.bias, a.relu,
-                                                                     (bf16_t *)a.y, (int)a.D, (int)a.H, (int)a.W, ntd, nth, ntw, ntiles);
+                                                                     (bf16_t *)a.y, (unsigned short *)a.ybits, (int)a.D, (int)a.H,
+                                                                     (int)a.W, ntd, nth, ntw, ntiles);
         else
             conv_first_fwd_mfma_kernel<1><<<dim3(grid), 256, 0, st>>>((const bf16_t *)a.x, (const bf16_t *)a.w, a.bias, a.relu,
-                                                                     (bf16_t *)a.y, (int)a.D, (int)a.H, (int)a.W, ntd, nth, ntw, ntiles);
+                                                                     (bf16_t *)a.y, (unsigned short *)a.ybits, (int)a.D, (int)a.H,
+                                                                     (int)a.W, ntd, nth, ntw, ntiles);
         K3_LAUNCH_CHECK();
         return K3_OK;
     }
@@ -436,6 +444,7 @@ int conv_first_fwd(const ConvArgs &a, hipStream_t st)
                                                                   (bf16_t *)a.y, (int)a.D, (int)a.H, (int)a.W, (int)a.cout,
                                                                   ntd, nth, ntw);
     K3_LAUNCH_CHECK();
+    if (a.ybits) return launch_relu_bits(a.dtype, a.y, a.ybits, a.V() * a.cout / 16, st);
     return K3_OK;
 }
 

@@ -73,6 +73,8 @@ struct MfmaParams {
     int relu;
     bf16_t *dst1, *dst2;
     const bf16_t *omask;               // optional: dst1 is zeroed where omask (same shape) is <= 0
+    const unsigned short *omask_bits;  // the same mask as one bit per element (word j of a voxel: channels 16j..16j+15)
+    unsigned short *bits_out;          // optional: receives that bit mask of dst1 (set where the stored value is > 0)
     int cd1, cd2;                      // output channels per destination
     int N, D, H, W;
     int ntd, nth, ntw;                 // tiles per axis
@@ -303,6 +305,13 @@ __device__ __forceinline__ u32x4 gload16_nowait(const void *ptr)
     return v;
 }
 
+__device__ __forceinline__ unsigned gload_u16_nowait(const void *ptr)
+{
+    unsigned v;
+    asm volatile("global_load_ushort %0, %1, off" : "=v"(v) : "v"(ptr) : "memory");
+    return v;
+}
+
 // s_waitcnt vmcnt(n) for a count that is a compile-time constant after unrolling (the instruction
 // takes an immediate; every case folds away but one)
 #define K3_WVM(n) case n: asm volatile("s_waitcnt vmcnt(" #n ")" ::: "memory"); break;
@@ -356,7 +365,7 @@ struct MaskOrder {
     }
 };
 
-template <class C, bool OMASK>
+template <class C, int OMASK>   // 0: no output mask, 1: mask given as the bf16 tensor, 2: as one bit per element
 __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -532,7 +541,31 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
 #pragma unroll
         for (int mb = 0; mb < C::MB; ++mb) asm volatile("" : "+v"(dst[mb][0]), "+v"(dst[mb][1]));
     };
-    if constexpr (!OMASK) {
+    // one-bit-per-element form: 2 bytes per block and lane, so all blocks of the wave are
+    // requested at once (one register each)
+    unsigned mkb[C::NBW][C::MB];
+    auto maskbits_request = [&](const PipeTile &t) __attribute__((always_inline)) {
+#pragma unroll
+        for (int nb = 0; nb < C::NBW; ++nb) {
+            const int bw = (nb % PPL) % C::PW, bh = (nb % PPL) / C::PW, bd = wv * WPL + nb / PPL;
+            const bool inb = bd < p.D - t.d0 && bh * 4 + lrow < p.H - t.h0 && bw * 8 + lcol < p.W - t.w0;
+            const int pvox = (bd * p.H + bh * 4) * p.W + bw * 8 + lvox;
+#pragma unroll
+            for (int mb = 0; mb < C::MB; ++mb) {
+                const int co0 = (t.mb0 + mb) * 32;
+                const bool d1 = co0 < p.cd1;
+                const unsigned short *mp = p.omask_bits + (t.origin * p.cd1 + co0) / 16 + (pvox * (p.cd1 / 16) + hb);
+                mkb[nb][mb] = gload_u16_nowait((d1 && inb) ? reinterpret_cast<const unsigned char *>(mp) : zero);
+            }
+        }
+    };
+    if constexpr (OMASK != 2) {
+#pragma unroll
+        for (int nb = 0; nb < C::NBW; ++nb)
+#pragma unroll
+            for (int mb = 0; mb < C::MB; ++mb) mkb[nb][mb] = 0u;
+    }
+    if constexpr (OMASK != 1) {
 #pragma unroll
         for (int r = 0; r < MO::R; ++r)
 #pragma unroll
@@ -574,6 +607,7 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
         // Finishes one accumulator block: bias, ReLU, optional output mask, round to bf16, store
         // 32 contiguous bytes per lane.
         auto emit = [&](int nb, int mb, u32x4 m0, u32x4 m1) __attribute__((always_inline)) {
+            const unsigned mbits = mkb[nb][mb];
             const int bw = (nb % PPL) % C::PW, bh = (nb % PPL) / C::PW, bd = wv * WPL + nb / PPL;
             const bool inb = bd < dlim && bh * 4 + lrow < hlim && bw * 8 + lcol < wlim;
             const int pvox = (bd * p.H + bh * 4) * p.W + bw * 8 + lvox;
@@ -591,10 +625,27 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             // wave-uniform 64-bit part + per-lane 32-bit element offset (fits: checked at launch)
             const int64_t ubase = cur.origin * cd + (d1 ? co0 : co0 - p.cd1);
             const int loff = pvox * cd + hb * 16;
-            if constexpr (OMASK) {
+            if constexpr (OMASK == 1) {
                 if (d1) {
                     o0.x = mask_pair(o0.x, m0[0]); o0.y = mask_pair(o0.y, m0[1]); o0.z = mask_pair(o0.z, m0[2]); o0.w = mask_pair(o0.w, m0[3]);
                     o1.x = mask_pair(o1.x, m1[0]); o1.y = mask_pair(o1.y, m1[1]); o1.z = mask_pair(o1.z, m1[2]); o1.w = mask_pair(o1.w, m1[3]);
+                }
+            }
+            if constexpr (OMASK == 2) {
+                if (d1) {
+                    uint32_t dd[8] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y, o1.z, o1.w};
+                    apply_bits16(dd, mbits);
+                    o0 = make_uint4(dd[0], dd[1], dd[2], dd[3]);
+                    o1 = make_uint4(dd[4], dd[5], dd[6], dd[7]);
+                }
+            }
+            if constexpr (OMASK == 0) {
+                if (p.bits_out && d1) {   // wave-uniform: the bit mask of what is stored below
+                    const uint32_t dd[8] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y, o1.z, o1.w};
+                    const unsigned m = relu_bits16(dd);
+                    unsigned short *bbase = p.bits_out + ubase / 16;
+                    __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(bbase, 0, 0x7ffffff0, 0x00020000);
+                    __builtin_amdgcn_raw_buffer_store_b16((short)m, brsrc, inb ? (loff / 16) * 2 : -1, 0, 0);
                 }
             }
             // buffer stores relative to the tile's first voxel: lanes outside the volume get an
@@ -681,7 +732,7 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
                     if (i % SP == 0 && i / SP < NOPS) issue_op(ss, i / SP, gtag);
                     // blocks of the previous patch: one after taps 2 and 5 of this patch
                     if (nb > 0 && tl == 2) {
-                        if constexpr (OMASK) {
+                        if constexpr (OMASK == 1) {
                             if (nb - 1 >= MO::R) {
                                 wait_vm(MO::after(nb - 1));
                                 mask_pin(mk[(nb - 1) % MO::R]);   // the values are defined from here on
@@ -691,14 +742,14 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
                     }
                     if (nb > 0 && tl == 5 && C::MB > 1)
                         emit(nb - 1, C::MB - 1, mk[(nb - 1) % MO::R][C::MB - 1][0], mk[(nb - 1) % MO::R][C::MB - 1][1]);
-                    if constexpr (OMASK) {
+                    if constexpr (OMASK == 1) {
                         // the slot of patch nb - 1 is free once its last block is stored
                         if (nb > 0 && tl == (C::MB > 1 ? 5 : 2) && nb - 1 + MO::R < C::NBW)
                             mask_request(cur, nb - 1 + MO::R, mk[(nb - 1) % MO::R]);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                if constexpr (OMASK) {
+                if constexpr (OMASK == 1) {
                     if (C::NBW - 1 >= MO::R) {
                         wait_vm(MO::after(C::NBW - 1));
                         mask_pin(mk[(C::NBW - 1) % MO::R]);
@@ -726,7 +777,11 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             xpar ^= 1;
         }
         stage(nkc - 1, std::integral_constant<int, 0>(), std::false_type());
-        if constexpr (OMASK) {
+        if constexpr (OMASK == 2) {
+            static_assert(C::XG_WAVE < NOPS, "a stage-end wait must cover operations issued before the stage");
+            maskbits_request(cur);   // one stage ahead, complete after the next stage's closing wait
+        }
+        if constexpr (OMASK == 1) {
             // One stage ahead of their use: the wait that ends the next stage leaves fewer
             // operations outstanding than that stage issues, so these requests are complete after
             // it.  (Requested at the start of the tile, or with the prologue's copies, they compete
@@ -736,9 +791,15 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             for (int nb = 0; nb < MO::R; ++nb) mask_request(cur, nb, mk[nb]);
         }
         stage(nkc - 1, std::integral_constant<int, 1>(), std::false_type());
-        if constexpr (OMASK) {
+        if constexpr (OMASK == 1) {
 #pragma unroll
             for (int nb = 0; nb < MO::R; ++nb) mask_pin(mk[nb]);
+        }
+        if constexpr (OMASK == 2) {
+#pragma unroll
+            for (int nb = 0; nb < C::NBW; ++nb)
+#pragma unroll
+                for (int mb = 0; mb < C::MB; ++mb) asm volatile("" : "+v"(mkb[nb][mb]));
         }
         stage(nkc - 1, std::integral_constant<int, 2>(), std::true_type());
         xpar ^= 1;
@@ -761,16 +822,19 @@ static int launch_pipe(MfmaParams p, int64_t mblocks, hipStream_t st)
     if (p.per_xcd * 8 > 0x7fffffffLL) return K3_E_UNSUPPORTED;
     static bool attr_done = false;
     if (!attr_done) {
-        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, false>),
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, 0>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
-        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, true>),
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, 1>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, 2>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
         attr_done = true;
     }
     // persistent workgroups, one per CU (fewer when there is less work); a multiple of 8
     int64_t grid = p.per_xcd * 8 < 256 ? p.per_xcd * 8 : 256;
-    if (p.omask) conv_mfma_pipe_kernel<C, true><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
-    else conv_mfma_pipe_kernel<C, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    if (p.omask_bits) conv_mfma_pipe_kernel<C, 2><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    else if (p.omask) conv_mfma_pipe_kernel<C, 1><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    else conv_mfma_pipe_kernel<C, 0><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
     K3_LAUNCH_CHECK();
     return K3_OK;
 }
@@ -796,25 +860,35 @@ static int launch_cfg(MfmaParams p, int64_t mblocks, hipStream_t st)
     return K3_OK;
 }
 
+// Which kernel serves the launch: 1-4 the pipelined one-workgroup-per-CU kernel (8x8x16 tiles when
+// they give every CU a tile, else 4x8x8 tiles -- the deep, small-volume levels of the network --
+// taking one output block per workgroup where two would leave CUs without work), 0 the first kernel.
+static int mfma_variant(const MfmaParams &p, int64_t mblocks)
+{
+    const int cmax = p.cd1 > p.cd2 ? p.cd1 : p.cd2;
+    // the halo tile's voxel offsets and the per-lane output offsets are kept in 32 bits
+    const bool fits = (int64_t)10 * p.H * p.W * (cmax > 1 ? cmax : 1) < 0x7fffffffLL && p.cd1 + p.cd2 <= 1024;
+    if (!p.mask && fits) {
+        const int64_t big = (int64_t)p.N * ((p.D + 7) / 8) * ((p.H + 7) / 8) * ((p.W + 15) / 16);
+        const int64_t small = (int64_t)p.N * ((p.D + 3) / 4) * ((p.H + 7) / 8) * ((p.W + 7) / 8);
+        const bool even = mblocks % 2 == 0;
+        if (even && big * (mblocks / 2) >= 256) return 1;
+        if (!even && big * mblocks >= 256) return 2;
+        if (even && small * (mblocks / 2) >= 192) return 3;
+        if (small * mblocks >= 48) return 4;
+    }
+    return 0;
+}
+
 static int launch_mfma(MfmaParams p, int64_t mchannels, hipStream_t st)
 {
     int64_t mblocks = mchannels / 32;
-    // The pipelined one-workgroup-per-CU kernel: 8x8x16 tiles when they give every CU a tile,
-    // else 4x8x8 tiles (the deep, small-volume levels of the network), taking one output block
-    // per workgroup where two would leave CUs without work.
-    {
-        const int cmax = p.cd1 > p.cd2 ? p.cd1 : p.cd2;
-        // the halo tile's voxel offsets and the per-lane output offsets are kept in 32 bits
-        const bool fits = (int64_t)10 * p.H * p.W * (cmax > 1 ? cmax : 1) < 0x7fffffffLL && p.cd1 + p.cd2 <= 1024;
-        if (!p.mask && fits) {
-            const int64_t big = (int64_t)p.N * ((p.D + 7) / 8) * ((p.H + 7) / 8) * ((p.W + 15) / 16);
-            const int64_t small = (int64_t)p.N * ((p.D + 3) / 4) * ((p.H + 7) / 8) * ((p.W + 7) / 8);
-            const bool even = mblocks % 2 == 0;
-            if (even && big * (mblocks / 2) >= 256) return launch_pipe<PipeCfg<8, 8, 16, 2>>(p, mblocks, st);
-            if (!even && big * mblocks >= 256) return launch_pipe<PipeCfg<8, 8, 16, 1>>(p, mblocks, st);
-            if (even && small * (mblocks / 2) >= 192) return launch_pipe<PipeCfg<4, 8, 8, 2>>(p, mblocks, st);
-            if (small * mblocks >= 48) return launch_pipe<PipeCfg<4, 8, 8, 1>>(p, mblocks, st);
-        }
+    switch (mfma_variant(p, mblocks)) {
+    case 1: return launch_pipe<PipeCfg<8, 8, 16, 2>>(p, mblocks, st);
+    case 2: return launch_pipe<PipeCfg<8, 8, 16, 1>>(p, mblocks, st);
+    case 3: return launch_pipe<PipeCfg<4, 8, 8, 2>>(p, mblocks, st);
+    case 4: return launch_pipe<PipeCfg<4, 8, 8, 1>>(p, mblocks, st);
+    default: break;
     }
     if (mblocks % 2 == 0) return launch_cfg<TileCfg<8, 8, 8, 2, 9>>(p, mblocks, st);
     return launch_cfg<TileCfg<8, 8, 8, 1, 27>>(p, mblocks, st);
@@ -836,7 +910,13 @@ int conv_fwd_mfma(const ConvArgs &a, hipStream_t st)
     p.cd1 = (int)a.cout;
     p.cd2 = 0;
     p.N = (int)a.N; p.D = (int)a.D; p.H = (int)a.H; p.W = (int)a.W;
-    return launch_mfma(p, a.cout, st);
+    // the pipelined kernel writes the bit mask of its output itself; behind the first kernel a
+    // small pass derives it from the stored tensor
+    const bool native = mfma_variant(p, a.cout / 32) != 0;
+    p.bits_out = native ? (unsigned short *)a.ybits : nullptr;
+    int rc = launch_mfma(p, a.cout, st);
+    if (rc == K3_OK && a.ybits && !native) rc = launch_relu_bits(a.dtype, a.y, a.ybits, a.V() * a.cout / 16, st);
+    return rc;
 }
 
 int conv_dgrad_mfma(const ConvArgs &a, hipStream_t st)
@@ -857,7 +937,12 @@ int conv_dgrad_mfma(const ConvArgs &a, hipStream_t st)
     p.cd1 = (int)a.c1;
     p.cd2 = (int)a.c2;
     p.N = (int)a.N; p.D = (int)a.D; p.H = (int)a.H; p.W = (int)a.W;
-    return launch_mfma(p, cin, st);
+    // mask given as bits: read by the pipelined kernel; behind the first kernel a small pass applies it
+    const bool native = mfma_variant(p, cin / 32) != 0;
+    p.omask_bits = native ? (const unsigned short *)a.omask_bits : nullptr;
+    int rc = launch_mfma(p, cin, st);
+    if (rc == K3_OK && a.omask_bits && !native) rc = launch_apply_relu_bits(a.dtype, a.dx, a.omask_bits, a.V() * a.c1 / 16, st);
+    return rc;
 }
 
 }  // namespace k3

@@ -20,6 +20,8 @@ struct ConvArgs {
     const void *dy = nullptr, *ymask = nullptr;
     void *dx = nullptr, *dx2 = nullptr;
     const void *omask = nullptr;   // optional mask applied to dx (first destination) by the producer
+    const void *omask_bits = nullptr;   // the same mask as one bit per element (alternative to omask)
+    void *ybits = nullptr;              // optional: bit mask of the forward output (set where y > 0)
     int64_t V() const { return N * D * H * W; }
 };
 
@@ -49,6 +51,11 @@ bool conv_first_ok(int dtype, int64_t c1, int64_t c2, int64_t cout);
 int conv_first_fwd(const ConvArgs &a, hipStream_t st);
 int conv_first_wgrad(const ConvArgs &a, float *dW, float *db, float *ws, hipStream_t st);
 size_t conv_first_wgrad_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cout);
+
+// one uint16 word per 16 consecutive channels: bit i set iff element 16 * word + i is > 0
+int launch_relu_bits(int dtype, const void *y, void *bits, int64_t nwords, hipStream_t st);
+// zeroes the elements of t whose bit is clear
+int launch_apply_relu_bits(int dtype, void *t, const void *bits, int64_t nwords, hipStream_t st);
 
 int launch_reduce_partials(const float *ws, float *dW, float *db, int64_t countW, int64_t count, int nsplit,
                            hipStream_t st);

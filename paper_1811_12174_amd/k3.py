@@ -118,9 +118,27 @@ def conv3d_fwd(x, w, packed, bias, relu, y, x2=None):
                                _d(y), _p(y), _stream()), "k3_conv3d_fwd")
 
 
+def relu_bits_bytes(y):
+    out = ctypes.c_size_t(0)
+    _check(lib().k3_relu_bits_bytes(_d(y), ctypes.byref(out)), "k3_relu_bits_bytes")
+    return out.value
+
+
+def conv3d_fwd_bits(x, w, packed, bias, relu, y, relu_bits, x2=None):
+    """conv3d_fwd that also writes the one-bit-per-element mask of y into relu_bits (see relu_bits_bytes)."""
+    _check(lib().k3_conv3d_fwd_bits(_d(x), _p(x), _d(x2), _p(x2), _p(w), _p(packed), _p(bias), ctypes.c_int(int(relu)),
+                                    _d(y), _p(y), _p(relu_bits), _stream()), "k3_conv3d_fwd_bits")
+
+
 def conv3d_bwd_data(dy, y_mask, w, packed, dx, dx2=None, dx_mask=None):
     _check(lib().k3_conv3d_bwd_data(_d(dy), _p(dy), _p(y_mask), _p(w), _p(packed), _d(dx), _p(dx), _d(dx2), _p(dx2),
                                     _p(dx_mask), _stream()), "k3_conv3d_bwd_data")
+
+
+def conv3d_bwd_data_bits(dy, y_mask, w, packed, dx, dx_mask_bits, dx2=None):
+    """conv3d_bwd_data with the mask of dx given as bits."""
+    _check(lib().k3_conv3d_bwd_data_bits(_d(dy), _p(dy), _p(y_mask), _p(w), _p(packed), _d(dx), _p(dx), _d(dx2), _p(dx2),
+                                         _p(dx_mask_bits), _stream()), "k3_conv3d_bwd_data_bits")
 
 
 def conv3d_bwd_weight_workspace_bytes(x, dy, x2=None):

@@ -16,10 +16,13 @@ from collections import namedtuple
 
 
 class TensorInfo:
-    __slots__ = ("name", "shape", "ebytes", "external")
+    """kind: "act" (an activation or gradient in the network's dtype), "bits" (a one-bit-per-element
+    ReLU mask: uint16 words, one per 16 channels) or "labels"."""
+    __slots__ = ("name", "shape", "ebytes", "external", "kind")
 
-    def __init__(self, name, shape, ebytes, external=False):
+    def __init__(self, name, shape, ebytes, external=False, kind="act"):
         self.name, self.shape, self.ebytes, self.external = name, tuple(int(s) for s in shape), ebytes, external
+        self.kind = kind
 
     @property
     def nbytes(self):
@@ -68,6 +71,14 @@ class Program:
         self._pending_allocs.append(name)
         return name
 
+    def new_bits(self, name, like):
+        """The bit mask of the ReLU output `like` (allocated with the same call)."""
+        n, d, h, w, c = self.tensors[like].shape
+        assert c % 16 == 0 and name not in self.tensors
+        self.tensors[name] = TensorInfo(name, (n, d, h, w, c // 16), 2, kind="bits")
+        self._pending_allocs.append(name)
+        return name
+
     def _vox(self, name):
         n, d, h, w, _ = self.tensors[name].shape
         return n * d * h * w
@@ -79,20 +90,22 @@ class Program:
         call.allocs, self._pending_allocs = self._pending_allocs, []
         self.calls.append(call)
 
-    def conv_fwd(self, layer, x, x2, y, ci, co, relu=True):
+    def conv_fwd(self, layer, x, x2, y, ci, co, relu=True, bits=None):
         v = self._vox(y)
-        self._add(Call("conv_fwd", layer, dict(x=x, x2=x2, y=y, relu=relu), [x, x2], [y],
-                       2 * 27 * v * ci * co, self._nb(x, x2, y), v, ci, co))
+        self._add(Call("conv_fwd", layer, dict(x=x, x2=x2, y=y, relu=relu, bits=bits), [x, x2], [y, bits],
+                       2 * 27 * v * ci * co, self._nb(x, x2, y, bits), v, ci, co))
 
     def conv_wgrad(self, layer, x, x2, g, ci, co):
         v = self._vox(g)
         self._add(Call("conv_wgrad", layer, dict(x=x, x2=x2, g=g), [x, x2, g], [],
                        2 * 27 * v * ci * co, self._nb(x, x2, g), v, ci, co))
 
-    def conv_dgrad(self, layer, g, dx, dx2, mask, ci, co):
+    def conv_dgrad(self, layer, g, dx, dx2, mask, ci, co, mask_bits=None):
+        """mask: the stored ReLU output dx is masked with; mask_bits: the same as a bit tensor."""
+        assert mask is None or mask_bits is None
         v = self._vox(g)
-        self._add(Call("conv_dgrad", layer, dict(g=g, dx=dx, dx2=dx2, mask=mask), [g, mask], [dx, dx2],
-                       2 * 27 * v * ci * co, self._nb(g, mask, dx, dx2), v, ci, co))
+        self._add(Call("conv_dgrad", layer, dict(g=g, dx=dx, dx2=dx2, mask=mask, mask_bits=mask_bits), [g, mask, mask_bits],
+                       [dx, dx2], 2 * 27 * v * ci * co, self._nb(g, mask, mask_bits, dx, dx2), v, ci, co))
 
     def pool_fwd(self, x, y):
         self._add(Call("pool_fwd", None, dict(x=x, y=y), [x], [y], 0, self._nb(x, y), self._vox(x), 0, 0))
@@ -219,10 +232,17 @@ def unet_program(base, cin, levels, n, d, h, w, ebytes=2, keep_acts=False):
         return (n, d >> l, h >> l, w >> l, c)
     p.external("x", sh(0, cin))
     p.external("labels", (n, d, h, w), 1)
+    # The first convolution of every level is differentiated through its ReLU by the second one's
+    # backward-data pass; with bf16 tensors and channel counts in whole 16s that mask travels as
+    # one bit per element, written by the forward pass (1/16 of the bytes in the backward pass).
+    use_bits = ebytes == 2 and base % 16 == 0
+
+    def bits_of(t):
+        return p.new_bits("b:" + t, t) if use_bits else None
     cur = "x"
     for l in range(L):
         ci = cin if l == 0 else F[l - 1]
-        p.conv_fwd(f"enc{l}.conv1", cur, None, p.new(f"a1_{l}", sh(l, F[l])), ci, F[l])
+        p.conv_fwd(f"enc{l}.conv1", cur, None, p.new(f"a1_{l}", sh(l, F[l])), ci, F[l], bits=bits_of(f"a1_{l}"))
         p.conv_fwd(f"enc{l}.conv2", f"a1_{l}", None, p.new(f"a2_{l}", sh(l, F[l])), F[l], F[l])
         if l < L - 1:
             p.pool_fwd(f"a2_{l}", p.new(f"p_{l}", sh(l + 1, F[l])))
@@ -233,7 +253,8 @@ def unet_program(base, cin, levels, n, d, h, w, ebytes=2, keep_acts=False):
     for l in range(L - 2, -1, -1):
         below[l] = cur
         p.up_fwd(f"dec{l}.up", cur, p.new(f"up_{l}", sh(l, F[l])), F[l + 1], F[l])
-        p.conv_fwd(f"dec{l}.conv1", f"a2_{l}", f"up_{l}", p.new(f"da1_{l}", sh(l, F[l])), 2 * F[l], F[l])
+        p.conv_fwd(f"dec{l}.conv1", f"a2_{l}", f"up_{l}", p.new(f"da1_{l}", sh(l, F[l])), 2 * F[l], F[l],
+                   bits=bits_of(f"da1_{l}"))
         p.conv_fwd(f"dec{l}.conv2", f"da1_{l}", None, p.new(f"da2_{l}", sh(l, F[l])), F[l], F[l])
         cur = f"da2_{l}"
     p.head(cur, p.new("g:" + cur, p.tensors[cur].shape), F[0])
@@ -241,7 +262,8 @@ def unet_program(base, cin, levels, n, d, h, w, ebytes=2, keep_acts=False):
     for l in range(0, L - 1):
         Fl = F[l]
         p.conv_wgrad(f"dec{l}.conv2", f"da1_{l}", None, g, Fl, Fl)
-        p.conv_dgrad(f"dec{l}.conv2", g, p.new(f"g:da1_{l}", sh(l, Fl)), None, f"da1_{l}", Fl, Fl)
+        p.conv_dgrad(f"dec{l}.conv2", g, p.new(f"g:da1_{l}", sh(l, Fl)), None, None if use_bits else f"da1_{l}", Fl, Fl,
+                     mask_bits=f"b:da1_{l}" if use_bits else None)
         p.conv_wgrad(f"dec{l}.conv1", f"a2_{l}", f"up_{l}", f"g:da1_{l}", 2 * Fl, Fl)
         p.conv_dgrad(f"dec{l}.conv1", f"g:da1_{l}", p.new(f"gs_{l}", sh(l, Fl)), p.new(f"g:up_{l}", sh(l, Fl)), None, 2 * Fl, Fl)
         p.up_wgrad(f"dec{l}.up", below[l], f"g:up_{l}", F[l + 1], Fl)
@@ -253,14 +275,15 @@ def unet_program(base, cin, levels, n, d, h, w, ebytes=2, keep_acts=False):
             p.pool_bwd(f"a2_{l}", g, f"gs_{l}", p.new(f"g:a2_{l}", sh(l, Fl)), True)
             g = f"g:a2_{l}"
         p.conv_wgrad(f"enc{l}.conv2", f"a1_{l}", None, g, Fl, Fl)
-        p.conv_dgrad(f"enc{l}.conv2", g, p.new(f"g:a1_{l}", sh(l, Fl)), None, f"a1_{l}", Fl, Fl)
+        p.conv_dgrad(f"enc{l}.conv2", g, p.new(f"g:a1_{l}", sh(l, Fl)), None, None if use_bits else f"a1_{l}", Fl, Fl,
+                     mask_bits=f"b:a1_{l}" if use_bits else None)
         inp = "x" if l == 0 else f"p_{l - 1}"
         ci = cin if l == 0 else F[l - 1]
         p.conv_wgrad(f"enc{l}.conv1", inp, None, f"g:a1_{l}", ci, Fl)
         if l > 0:
             p.conv_dgrad(f"enc{l}.conv1", f"g:a1_{l}", p.new(f"g:p_{l - 1}", sh(l, F[l - 1])), None, None, ci, Fl)
             g = f"g:p_{l - 1}"
-    keep = [t for t, i in p.tensors.items() if not i.external and not t.startswith("g")] if keep_acts else []
+    keep = [t for t, i in p.tensors.items() if not i.external and i.kind == "act" and not t.startswith("g")] if keep_acts else []
     return p.finish(keep)
 
 

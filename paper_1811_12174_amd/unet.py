@@ -169,9 +169,10 @@ class StepNet:
             self._slab = torch.empty(nbytes, device=self.dev, dtype=torch.uint8)
 
     def alloc(self, info, offset):
+        dt = torch.int16 if info.kind == "bits" else self.dtype
         if offset is None:
-            return torch.empty(info.shape, device=self.dev, dtype=self.dtype)
-        return self._slab[offset:offset + info.nbytes].view(self.dtype).view(info.shape)
+            return torch.empty(info.shape, device=self.dev, dtype=dt)
+        return self._slab[offset:offset + info.nbytes].view(dt).view(info.shape)
 
     def free(self, block):
         pass    # the last reference goes with the interpreter's table entry
@@ -214,15 +215,23 @@ class StepNet:
     def call(self, c, t):
         a = c.args
         if c.fn == "conv_fwd":
-            k3.conv3d_fwd(t[a["x"]], self.w[c.layer], self.pk[c.layer], self.b[c.layer], a["relu"], t[a["y"]],
-                          x2=t.get(a["x2"]))
+            if a.get("bits") is None:
+                k3.conv3d_fwd(t[a["x"]], self.w[c.layer], self.pk[c.layer], self.b[c.layer], a["relu"], t[a["y"]],
+                              x2=t.get(a["x2"]))
+            else:
+                k3.conv3d_fwd_bits(t[a["x"]], self.w[c.layer], self.pk[c.layer], self.b[c.layer], a["relu"], t[a["y"]],
+                                   t[a["bits"]], x2=t.get(a["x2"]))
         elif c.fn == "conv_wgrad":
             # g is the gradient of the layer's pre-activation: every producer of an activation
             # gradient applies the ReLU mask of the tensor it differentiates
             k3.conv3d_bwd_weight(t[a["x"]], t[a["g"]], None, self.gw[c.layer], self.gb[c.layer], self._ws, x2=t.get(a["x2"]))
         elif c.fn == "conv_dgrad":
-            k3.conv3d_bwd_data(t[a["g"]], None, self.w[c.layer], self.pk[c.layer], t[a["dx"]], dx2=t.get(a["dx2"]),
-                               dx_mask=t.get(a["mask"]))
+            if a.get("mask_bits") is None:
+                k3.conv3d_bwd_data(t[a["g"]], None, self.w[c.layer], self.pk[c.layer], t[a["dx"]], dx2=t.get(a["dx2"]),
+                                   dx_mask=t.get(a["mask"]))
+            else:
+                k3.conv3d_bwd_data_bits(t[a["g"]], None, self.w[c.layer], self.pk[c.layer], t[a["dx"]], t[a["mask_bits"]],
+                                        dx2=t.get(a["dx2"]))
         elif c.fn == "pool_fwd":
             k3.pool3d_fwd(t[a["x"]], t[a["y"]])
         elif c.fn == "pool_bwd":

@@ -189,3 +189,54 @@ def test_error_codes():
     with pytest.raises(k3.K3Error) as e:
         k3.conv3d_bwd_weight(x, y, None, dW, None, ws)
     assert e.value.status == k3.E_WORKSPACE
+
+
+BITS_CASES = [
+    (1, 16, 16, 16, 32, 0, 32),      # pipelined kernel, one output block per workgroup, 4x8x8 tiles
+    (1, 12, 20, 35, 32, 0, 64),      # ragged tiles, two blocks per workgroup
+    (2, 9, 10, 11, 1, 0, 64),        # first layer (im2col kernel writes the bits)
+    (1, 6, 7, 9, 1, 0, 48),          # first layer, thread-per-channel kernel + generic bits pass
+    (1, 10, 8, 8, 32, 32, 32),       # two sources forward / two destinations backward (mask on the first)
+    (1, 4, 4, 4, 128, 0, 128),       # small volume: first MFMA kernel + generic passes
+    (1, 5, 6, 7, 3, 2, 16),          # direct kernels
+]
+
+
+@pytest.mark.parametrize("N,D,H,W,c1,c2,co", BITS_CASES)
+def test_relu_bit_masks(orc, N, D, H, W, c1, c2, co):
+    """The forward pass's bit mask is exactly the oracle's mask of the stored output, and
+    backward-data with the mask given as bits is bit-identical to backward-data with the mask
+    given as the tensor (and so inherits its parity with the oracle)."""
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, to_f64, empty, packed_for
+    cin = c1 + c2
+    x = synth.activations(20, (N, D, H, W, cin), "bf16")
+    w = synth.conv_weights(21, cin, co, "bf16")
+    b = (synth.normal(synth.SEED, 22, (co,), np.float64) * 0.3).astype(np.float32)
+    xd, wd, bd = to_dev(x, "bf16"), to_dev(w, "bf16"), torch.from_numpy(b).cuda()
+    x1 = xd[..., :c1].contiguous()
+    x2 = xd[..., c1:].contiguous() if c2 else None
+    pk = packed_for(wd)
+    y0, y1 = empty((N, D, H, W, co), "bf16"), empty((N, D, H, W, co), "bf16")
+    k3.conv3d_fwd(x1, wd, pk, bd, 1, y0, x2=x2)
+    bits = torch.full((N, D, H, W, co // 16), -1, device="cuda", dtype=torch.int16)
+    assert k3.relu_bits_bytes(y1) == bits.numel() * 2
+    k3.conv3d_fwd_bits(x1, wd, pk, bd, 1, y1, bits, x2=x2)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    assert np.array_equal(bits.cpu().numpy().view(np.uint16), orc.relu_bits(to_f64(y1)))
+    # backward through a layer whose first input is a stored ReLU output with the shape of x1
+    if c1 % 16 == 0:
+        m = torch.relu(x1)
+        mbits = torch.from_numpy(orc.relu_bits(to_f64(m)).view(np.int16)).cuda()
+        g = to_dev(synth.activations(23, (N, D, H, W, co), "bf16"), "bf16")
+        dxa, dxb = empty(x1.shape, "bf16"), empty(x1.shape, "bf16")
+        dx2a = empty(x2.shape, "bf16") if c2 else None
+        dx2b = empty(x2.shape, "bf16") if c2 else None
+        k3.conv3d_bwd_data(g, None, wd, pk, dxa, dx2=dx2a, dx_mask=m)
+        k3.conv3d_bwd_data_bits(g, None, wd, pk, dxb, mbits, dx2=dx2b)
+        torch.cuda.synchronize()
+        assert torch.equal(dxa, dxb)
+        assert c2 == 0 or torch.equal(dx2a, dx2b)
+        assert np.array_equal(to_f64(dxb), orc.apply_relu_bits(to_f64(dxb), mbits.cpu().numpy().view(np.uint16)))

@@ -91,12 +91,13 @@ def test_cfg2_block_as_benchmarked(orc):
     dW1, dW2 = torch.empty((3, 3, 3, C, C), device="cuda"), torch.empty((3, 3, 3, C, C), device="cuda")
     db1, db2 = torch.empty(C, device="cuda"), torch.empty(C, device="cuda")
     ws = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(x, a1), device="cuda", dtype=torch.uint8)
-    k3.conv3d_fwd(x, w1, pk1, b1, 1, a1)
+    a1bits = torch.empty(k3.relu_bits_bytes(a1) // 2, device="cuda", dtype=torch.int16)
+    k3.conv3d_fwd_bits(x, w1, pk1, b1, 1, a1, a1bits)
     k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2)
     k3.pool3d_fwd(a2, p)
     k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True)
     k3.conv3d_bwd_weight(a1, da2, None, dW2, db2, ws)
-    k3.conv3d_bwd_data(da2, None, w2, pk2, da1, dx_mask=a1)
+    k3.conv3d_bwd_data_bits(da2, None, w2, pk2, da1, a1bits)
     k3.conv3d_bwd_weight(x, da1, None, dW1, db1, ws)
     k3.conv3d_bwd_data(da1, None, w1, pk1, dx)
     torch.cuda.synchronize()
@@ -304,3 +305,46 @@ def test_upconv_bwd_data_at_unet_sizes(orc, sp, ci, co):
         sl = (slice(None), slice(d0, d0 + cd), slice(h0, h0 + ch), slice(w0, w0 + cw))
         assert rel(got[sl], ref) < 4e-3, (d0, h0, w0)
         assert rel(gotm[sl], orc.relu_bwd(ref, x[sl].astype(np.float64))) < 4e-3, (d0, h0, w0)
+
+
+@pytest.mark.parametrize("N,S,c1,c2,co", [(1, 64, 32, 0, 32),      # 8x8x16 tiles, one output block per workgroup (the benchmark's layer)
+                                           (1, 64, 64, 0, 64),      # two blocks per workgroup: ring of mask words vs bits
+                                           (1, 32, 128, 0, 128),    # 4x8x8 tiles, two blocks
+                                           (1, 48, 64, 64, 64),     # two sources / two destinations, mask on the first
+                                           (1, 40, 32, 0, 64)])     # ragged 8x8x16 tiles
+def test_relu_bit_masks_in_the_pipelined_kernels(orc, N, S, c1, c2, co):
+    """Bit masks written by the pipelined forward kernel against the oracle's mask of the stored
+    output, and backward-data with the mask as bits against backward-data with the mask as tensor
+    (bit-identical), at sizes that select every tile variant."""
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, packed_for
+    cin = c1 + c2
+    D = H = S
+    W = S + (4 if S == 40 else 0)
+    x = synth.activations(24, (N, D, H, W, cin), "bf16")
+    wd = to_dev(synth.conv_weights(25, cin, co, "bf16"), "bf16")
+    bd = torch.from_numpy((synth.normal(synth.SEED, 26, (co,), np.float64) * 0.3).astype(np.float32)).cuda()
+    xd = to_dev(x, "bf16")
+    x1 = xd[..., :c1].contiguous()
+    x2 = xd[..., c1:].contiguous() if c2 else None
+    pk = packed_for(wd)
+    y0 = torch.empty((N, D, H, W, co), device="cuda", dtype=torch.bfloat16)
+    y1 = torch.empty_like(y0)
+    bits = torch.full((N, D, H, W, co // 16), -1, device="cuda", dtype=torch.int16)
+    k3.conv3d_fwd(x1, wd, pk, bd, 1, y0, x2=x2)
+    k3.conv3d_fwd_bits(x1, wd, pk, bd, 1, y1, bits, x2=x2)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    assert np.array_equal(bits.cpu().numpy().view(np.uint16), orc.relu_bits(host64(y1)))
+    m = torch.relu(x1)
+    mbits = torch.from_numpy(orc.relu_bits(host64(m)).view(np.int16)).cuda()
+    g = to_dev(synth.activations(27, (N, D, H, W, co), "bf16"), "bf16")
+    dxa, dxb = torch.empty_like(x1), torch.empty_like(x1)
+    dx2a = torch.empty_like(x2) if c2 else None
+    dx2b = torch.empty_like(x2) if c2 else None
+    k3.conv3d_bwd_data(g, None, wd, pk, dxa, dx2=dx2a, dx_mask=m)
+    k3.conv3d_bwd_data_bits(g, None, wd, pk, dxb, mbits, dx2=dx2b)
+    torch.cuda.synchronize()
+    assert torch.equal(dxa, dxb)
+    assert c2 == 0 or torch.equal(dx2a, dx2b)
