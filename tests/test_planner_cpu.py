@@ -210,3 +210,71 @@ def test_cost_model_orders_of_magnitude():
     p = unet_program(64, 1, 4, 2, 256, 256, 256)
     t = planner.simulate(p)[1].seconds
     assert 0.1 < t < 0.25      # measured on the GPU: 0.145 s
+
+
+def test_arena_random_sequences_never_overlap_and_coalesce_fully():
+    """Random allocation / free traffic: live ranges never overlap, stay inside the slab, a request
+    fails only when no hole can take it, and freeing everything leaves one hole."""
+    import random
+    from paper_1811_12174_amd.executor import Arena
+    rng = random.Random(1811)
+    for trial in range(30):
+        size = rng.randrange(20, 200) * 512
+        a = Arena(size)
+        live = {}
+        for step in range(300):
+            if live and (rng.random() < 0.45 or len(live) > 40):
+                key = rng.choice(list(live))
+                off, n = live.pop(key)
+                a.free(off, n)
+            else:
+                n = rng.randrange(1, size // 3)
+                top = rng.random() < 0.5
+                biggest = max((ln for _, ln in a.holes), default=0)
+                off = a.alloc(n, top=top)
+                if off is None:
+                    assert biggest < Arena.rounded(n)
+                    continue
+                assert biggest >= Arena.rounded(n)
+                assert 0 <= off and off + Arena.rounded(n) <= a.size and off % 512 == 0
+                for o2, n2 in live.values():
+                    assert off + Arena.rounded(n) <= o2 or o2 + Arena.rounded(n2) <= off
+                live[step] = (off, n)
+            # holes are sorted, disjoint, not adjacent (fully coalesced), and complement the live ranges
+            for (o1, l1), (o2, l2) in zip(a.holes, a.holes[1:]):
+                assert o1 + l1 < o2
+            assert sum(ln for _, ln in a.holes) + sum(Arena.rounded(n) for _, n in live.values()) == a.size
+        for off, n in live.values():
+            a.free(off, n)
+        assert a.holes == [(0, a.size)]
+
+
+def test_random_plans_keep_the_interpreter_consistent():
+    """Random gap selections and prefetch points on a small program, with and without a budget: every
+    call finds its tensors on the device (the simulator asserts it), the accounting returns to the
+    fixed part, the peak respects the budget, and bytes in never exceed what the gaps allow."""
+    import random
+    rng = random.Random(12174)
+    p = unet_program(16, 1, 3, 1, 32, 32, 32)
+    gaps = p.gaps()
+    need = planner.simulate(p)[0].peak
+    ran = refused = 0
+    for trial in range(60):
+        chosen = [g for g in gaps if rng.random() < 0.4]
+        at = {(g.tensor, g.index): rng.randrange(g.first + 1, g.last + 1) for g in chosen if rng.random() < 0.7}
+        budget = None if trial % 3 == 0 else int(need * rng.uniform(0.6, 1.1))
+        eager = trial % 5 == 0
+        try:
+            ex, be = planner.simulate(p, chosen, rng.randrange(1, 6), budget, eager, fixed_bytes=1000, at=at)
+        except OutOfBudget:
+            refused += 1
+            assert budget is not None
+            continue
+        ran += 1
+        assert ex.used == 1000 and ex.peak >= 1000
+        if budget is not None:
+            assert ex.peak <= budget and ex.arena.high_water <= budget - 1000
+        assert ex.bytes_out == sum(p.tensors[t].nbytes for t in {g.tensor for g in chosen})
+        assert ex.bytes_in <= sum(p.tensors[g.tensor].nbytes for g in chosen)
+        assert be.seconds >= planner.simulate(p, fixed_bytes=1000)[1].seconds - 1e-12
+    assert ran > 20 and refused > 0
