@@ -10,10 +10,12 @@ exact (in-bounds) convolution FLOPs of the step divided by the step time.
 
 Other workloads: "unet128" (full 4-level U-Net, base 32, 1 x 128^3, no swapping),
 "unet256" (base 64, 2 x 256^3) and "unet320" (base 64, 4 x 320^3); they report voxels/s
-without swapping and, for the two large ones, under a device-memory budget (--budget-gb,
-default three quarters of what the step holds unswapped): without swapping the step is
-refused, with the swap plan the planner makes for that budget it runs, and the "unet"
-object reports its time, its footprint and the bytes moved each way.  "bp64" / "bp96" time
+without swapping and, for the two large ones, (1) with every stored encoder activation swapped
+and (2) under a device-memory budget (--budget-gb, default three quarters of what the step
+holds unswapped): without swapping the step is refused, with the swap plan the planner makes
+for that budget it runs.  The "unet" object reports for each its time, its footprint, the
+bytes moved each way, the time of the same copies without the kernels, the overlap fraction
+and the link rates (with the box's pinned-memory copy rates beside them).  "bp64" / "bp96" time
 the paper's second model (section 4.1: two conv+pool encoder layers, two conv+up-sampling
 decoder layers, 128 channels, batch of 8 blocks, class-weighted loss) in training and inference.  "sweep" plans
 and runs a row of resolutions under one fixed budget and reports the swap overhead of each.
@@ -306,6 +308,56 @@ def unet_flops(base, levels, n, size):
     return total
 
 
+def measure_link(nbytes=1 << 30, reps=4):
+    """Rates (GB/s) of the swap engine's own copies (hipMemcpyAsync between device and page-locked
+    host memory on its two copy streams) on this machine: each direction alone, and each direction
+    with both busy."""
+    import torch
+    from paper_1811_12174_amd import k3
+    dev_a = torch.empty(nbytes, device="cuda", dtype=torch.uint8)
+    dev_b = torch.empty(nbytes, device="cuda", dtype=torch.uint8)
+    ctx = k3.lms_create(0)
+    h1, h2 = k3.lms_host_alloc(nbytes), k3.lms_host_alloc(nbytes)
+
+    def timed(fn):
+        fn()
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(reps):
+            fn()
+        torch.cuda.synchronize()
+        return round(nbytes * reps / (time.perf_counter() - t0) / 1e9, 1)
+    try:
+        def out():
+            h = k3.lms_swap_out(ctx, dev_a.data_ptr(), nbytes, h1)
+            k3.lms_sync(ctx)
+            k3.lms_release(ctx, h)
+        d2h = timed(out)
+        hb = k3.lms_swap_out(ctx, dev_b.data_ptr(), nbytes, h2)
+        k3.lms_sync(ctx)
+        k3.lms_release_after(ctx, hb)
+
+        def back():
+            k3.lms_prefetch_start(ctx, hb, dev_b.data_ptr())
+            k3.lms_sync(ctx)
+            k3.lms_evict(ctx, hb)
+        h2d = timed(back)
+
+        def both():
+            ha = k3.lms_swap_out(ctx, dev_a.data_ptr(), nbytes, h1)
+            k3.lms_prefetch_start(ctx, hb, dev_b.data_ptr())
+            k3.lms_sync(ctx)
+            k3.lms_evict(ctx, hb)
+            k3.lms_release(ctx, ha)
+        each = timed(both)
+        k3.lms_release(ctx, hb)
+    finally:
+        k3.lms_host_free(h1)
+        k3.lms_host_free(h2)
+        k3.lms_destroy(ctx)
+    return {"d2h_alone": d2h, "h2d_alone": h2d, "each_direction_both_busy": each}
+
+
 def bench_unet(args, base, size, n, swap, label, budget_gb=0.0):
     import numpy as np
     import torch
@@ -337,17 +389,56 @@ def bench_unet(args, base, size, n, swap, label, budget_gb=0.0):
         return (time.perf_counter() - t0) / steps
 
     def swap_leg(plan, budget):
+        net.step(x, lab, swap=plan, budget=budget)       # creates the swap context on first use
+        torch.cuda.synchronize()
+        k3.lms_sync(net.lms)
+        k3.lms_set_copy_timing(net.lms, True)
+        busy0 = k3.lms_copy_busy_ms(net.lms)
         dt = run(swap=plan, budget=budget)
+        busy1 = k3.lms_copy_busy_ms(net.lms)
+        k3.lms_set_copy_timing(net.lms, False)
         r = net.last_run
+        n_steps = warm + steps
+        busy_out, busy_in = (busy1[0] - busy0[0]) / n_steps * 1e-3, (busy1[1] - busy0[1]) / n_steps * 1e-3
+        # the same instruction stream with its copies but without its kernels: what the link alone needs
+        net.copies_only = True
+        try:
+            t_copy = run(swap=plan, budget=budget)
+        finally:
+            net.copies_only = False
+        shorter = min(t_noswap, t_copy)
         return {"ms_per_step": round(dt * 1e3, 3), "voxels_per_s": round(V / dt, 1),
                 "overhead_pct": round(100 * (dt / t_noswap - 1), 2),
+                "ms_compute_only": round(t_noswap * 1e3, 3), "ms_copies_only": round(t_copy * 1e3, 3),
+                "overlap_fraction": round((t_noswap + t_copy - dt) / shorter, 3) if shorter > 0 else None,
+                # achieved rate of the engine's copies inside the real step: bytes over the time the
+                # copy stream of that direction was busy (timed event pairs around every copy)
+                "copy_busy_ms_out": round(busy_out * 1e3, 2), "copy_busy_ms_in": round(busy_in * 1e3, 2),
+                "achieved_gbs_out": round(r.bytes_out / busy_out / 1e9, 1) if busy_out > 0 else None,
+                "achieved_gbs_in": round(r.bytes_in / busy_in / 1e9, 1) if busy_in > 0 else None,
+                "achieved_pct_of_one_direction_peak": (round(100 * min(r.bytes_out / busy_out / 1e9 / link["d2h_alone"],
+                                                                       r.bytes_in / busy_in / 1e9 / link["h2d_alone"]), 1)
+                                                       if link and busy_out > 0 and busy_in > 0 else None),
+                "link_gbs_out_copies_only": round(r.bytes_out / t_copy / 1e9, 1) if t_copy > 0 else None,
+                "link_gbs_in_copies_only": round(r.bytes_in / t_copy / 1e9, 1) if t_copy > 0 else None,
+                # the copies alone against the best the link could do with these byte counts: both
+                # directions busy for the smaller count, one direction for the rest
+                "copies_only_pct_of_link": (round(100 * link_seconds(r.bytes_out, r.bytes_in, link) / t_copy, 1)
+                                            if link and t_copy > 0 else None),
                 "accounted_peak_gb": round(r.peak / 1e9, 3), "allocator_peak_gb": round(torch.cuda.max_memory_allocated() / 1e9, 3),
                 "bytes_out_per_step": int(r.bytes_out), "bytes_in_per_step": int(r.bytes_in),
                 "copy_seconds_at_link_peak": round(max(r.bytes_out, r.bytes_in) / 57e9, 4),
                 "device_copies_dropped": r.releases, "plan": plan.describe()}
 
+    link = measure_link() if (swap or budget_gb) else None
+
+    def link_seconds(b_out, b_in, rates):
+        lo, hi = min(b_out, b_in), max(b_out, b_in)
+        return lo / (rates["each_direction_both_busy"] * 1e9) + (hi - lo) / (min(rates["d2h_alone"], rates["h2d_alone"]) * 1e9)
+
     V = n * size ** 3
     t_noswap = run()
+    need = net.last_run.peak      # accounted bytes the unswapped step holds
     fl = unet_flops(base, 4, n, size)
     res = {"workload": label, "steps": steps, "ms_per_step_no_swap": round(t_noswap * 1e3, 3),
            "voxels_per_s_no_swap": round(V / t_noswap, 1), "conv_tflops_no_swap": round(fl / t_noswap / 1e12, 2),
@@ -365,8 +456,16 @@ def bench_unet(args, base, size, n, swap, label, budget_gb=0.0):
     # per-call GPU durations of this very workload feed the planner's simulator
     net.step(x, lab, timing=True)
     dur = net.call_seconds
+    if link:
+        res["link_gbs"] = link
+    if swap:
+        # every stored encoder activation spends its idle gaps in host memory (the paper's default:
+        # swap the feature maps), in the smallest budget that selection can run in
+        plan = planner.swap_all(prog, only=planner.is_encoder_activation, fixed_bytes=fixed, durations=dur)
+        res["encoder_activations_swapped"] = swap_leg(plan, plan.budget)
+        res["encoder_activations_swapped"]["device_budget_gb"] = round(plan.budget / 1e9, 3)
     if swap and not budget_gb:
-        budget_gb = round(0.75 * net.last_run.peak / 1e9, 3)   # default: three quarters of what the step needs unswapped
+        budget_gb = round(0.75 * need / 1e9, 3)   # default: three quarters of what the step needs unswapped
     if budget_gb:
         # The situation the paper's LMS exists for: a device-memory limit below what the step
         # needs without swapping.  The planner picks what leaves the GPU; the limit is enforced

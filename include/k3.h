@@ -307,6 +307,13 @@ typedef struct k3_lms_stats {
     uint64_t live_handles;
 } k3_lms_stats;
 int k3_lms_get_stats(k3_lms *ctx, k3_lms_stats *out);
+/* Measurement aid: with timing on (off by default) every copy is bracketed by a pair of timed
+ * events on its copy stream.  k3_lms_copy_busy_ms returns the accumulated time, in
+ * milliseconds since the context was created, that the device-to-host and the host-to-device
+ * copy stream spent copying (copies of one direction run one after the other, so the sum of
+ * their durations is that stream's busy time); copies still in flight are not counted yet. */
+int k3_lms_set_copy_timing(k3_lms *ctx, int on);
+int k3_lms_copy_busy_ms(k3_lms *ctx, double *out_ms, double *in_ms);
 int k3_lms_handle_state(k3_lms *ctx, int handle, int *state);
 
 enum { K3_LMS_RESIDENT = 0, K3_LMS_OUT_IN_FLIGHT = 1, K3_LMS_ON_HOST = 2, K3_LMS_IN_IN_FLIGHT = 3 };

@@ -2,6 +2,7 @@
 // dedicated non-blocking streams at the default priority (one per direction, so both DMA
 // directions can be busy at once) and are fenced with timing-disabled events.
 #include <new>
+#include <vector>
 
 #include "common.h"
 #include "lms_engine.h"
@@ -10,6 +11,56 @@ namespace {
 
 struct HipBackend : k3lms::Backend {
     int last = 0;
+    // optional timing of the copies (off by default): a timed event pair around every copy; the
+    // copies of a direction run one after the other on one stream, so the sum of the pairs is the
+    // time that direction's copy engine was busy
+    struct Timed { hipEvent_t t0, t1; int dir; };
+    bool timing = false;
+    std::vector<Timed> pending;
+    std::vector<hipEvent_t> spare;
+    double busy_ms[2] = {0.0, 0.0};
+    hipEvent_t timed_event()
+    {
+        if (!spare.empty()) { hipEvent_t e = spare.back(); spare.pop_back(); return e; }
+        hipEvent_t e = nullptr;
+        if (hipEventCreate(&e) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+        return e;
+    }
+    void collect()   // adds the pairs whose copy has finished
+    {
+        size_t keep = 0;
+        for (size_t i = 0; i < pending.size(); ++i) {
+            Timed &t = pending[i];
+            float ms = 0.f;
+            hipError_t r = hipEventElapsedTime(&ms, t.t0, t.t1);
+            if (r == hipSuccess) {
+                busy_ms[t.dir] += ms;
+                spare.push_back(t.t0);
+                spare.push_back(t.t1);
+            } else {
+                (void)hipGetLastError();   // not ready yet
+                pending[keep++] = t;
+            }
+        }
+        pending.resize(keep);
+    }
+    int timed_copy(void *dst, const void *src, size_t bytes, hipMemcpyKind kind, hipStream_t st, int dir)
+    {
+        if (!timing) return chk(hipMemcpyAsync(dst, src, bytes, kind, st));
+        hipEvent_t t0 = timed_event(), t1 = timed_event();
+        if (!t0 || !t1) return chk(hipMemcpyAsync(dst, src, bytes, kind, st));
+        if (chk(hipEventRecord(t0, st))) return 1;
+        if (chk(hipMemcpyAsync(dst, src, bytes, kind, st))) return 1;
+        if (chk(hipEventRecord(t1, st))) return 1;
+        pending.push_back(Timed{t0, t1, dir});
+        if (pending.size() > 256) collect();
+        return 0;
+    }
+    ~HipBackend()
+    {
+        for (Timed &t : pending) { (void)hipEventDestroy(t.t0); (void)hipEventDestroy(t.t1); }
+        for (hipEvent_t e : spare) (void)hipEventDestroy(e);
+    }
     int chk(hipError_t e)
     {
         if (e != hipSuccess) {
@@ -51,11 +102,11 @@ struct HipBackend : k3lms::Backend {
     int event_sync(k3lms::event_t e) override { return chk(hipEventSynchronize((hipEvent_t)e)); }
     int copy_d2h(void *host, const void *dev, size_t bytes, k3lms::stream_t s) override
     {
-        return chk(hipMemcpyAsync(host, dev, bytes, hipMemcpyDeviceToHost, (hipStream_t)s));
+        return timed_copy(host, dev, bytes, hipMemcpyDeviceToHost, (hipStream_t)s, 0);
     }
     int copy_h2d(void *dev, const void *host, size_t bytes, k3lms::stream_t s) override
     {
-        return chk(hipMemcpyAsync(dev, host, bytes, hipMemcpyHostToDevice, (hipStream_t)s));
+        return timed_copy(dev, const_cast<void *>(host), bytes, hipMemcpyHostToDevice, (hipStream_t)s, 1);
     }
     bool is_pinned(const void *host, size_t bytes) override
     {
@@ -149,6 +200,22 @@ int k3_lms_wait_in(k3_lms *ctx, int handle, void *stream) { return ctx ? map_sta
 int k3_lms_release(k3_lms *ctx, int handle) { return ctx ? map_status(ctx->eng.release(handle)) : K3_E_BADARG; }
 int k3_lms_sync(k3_lms *ctx) { return ctx ? map_status(ctx->eng.sync()) : K3_E_BADARG; }
 int k3_lms_handle_state(k3_lms *ctx, int handle, int *state) { return ctx ? map_status(ctx->eng.handle_state(handle, state)) : K3_E_BADARG; }
+
+int k3_lms_set_copy_timing(k3_lms *ctx, int on)
+{
+    if (!ctx) return K3_E_BADARG;
+    ctx->be.timing = on != 0;
+    return K3_OK;
+}
+
+int k3_lms_copy_busy_ms(k3_lms *ctx, double *out_ms, double *in_ms)
+{
+    if (!ctx || !out_ms || !in_ms) return K3_E_BADARG;
+    ctx->be.collect();
+    *out_ms = ctx->be.busy_ms[0];
+    *in_ms = ctx->be.busy_ms[1];
+    return K3_OK;
+}
 
 int k3_lms_get_stats(k3_lms *ctx, k3_lms_stats *out)
 {

@@ -335,6 +335,17 @@ def lms_get_stats(ctx):
     return {k: getattr(st, k) for k, _ in LmsStats._fields_}
 
 
+def lms_set_copy_timing(ctx, on):
+    _check(lib().k3_lms_set_copy_timing(ctx, ctypes.c_int(1 if on else 0)), "k3_lms_set_copy_timing")
+
+
+def lms_copy_busy_ms(ctx):
+    """(device-to-host, host-to-device) busy milliseconds of the copy streams since the context was created."""
+    a, b = ctypes.c_double(0.0), ctypes.c_double(0.0)
+    _check(lib().k3_lms_copy_busy_ms(ctx, ctypes.byref(a), ctypes.byref(b)), "k3_lms_copy_busy_ms")
+    return a.value, b.value
+
+
 def lms_handle_state(ctx, handle):
     s = ctypes.c_int(-1)
     _check(lib().k3_lms_handle_state(ctx, ctypes.c_int(handle), ctypes.byref(s)), "k3_lms_handle_state")

@@ -89,6 +89,7 @@ class StepNet:
         self.last_run = None   # the Executor of the last step (peak bytes, bytes moved, drops)
         self._timing = None
         self._slab = None
+        self.copies_only = False   # when set, step() issues the plan's copies but launches no kernel
 
     # ------------------------------------------------------------------ parameters
     def repack(self):
@@ -213,6 +214,8 @@ class StepNet:
         self._deferred = keep
 
     def call(self, c, t):
+        if self.copies_only:   # measurement aid: the step's copy traffic without its kernels
+            return
         a = c.args
         if c.fn == "conv_fwd":
             if a.get("bits") is None:

@@ -195,3 +195,38 @@ def test_swap_errors_on_gpu():
         assert e.value.status == k3.E_BADARG
     finally:
         k3.lms_destroy(ctx)
+
+
+def test_copy_busy_time_measurement():
+    """With timing on, the engine reports how long each copy stream was busy; off, nothing is counted."""
+    import torch
+    from paper_1811_12174_amd import k3
+    ctx = k3.lms_create(0)
+    n = 64 << 20
+    t = torch.zeros(n, device="cuda", dtype=torch.uint8)
+    host = k3.lms_host_alloc(n)
+    try:
+        h = k3.lms_swap_out(ctx, t.data_ptr(), n, host)
+        k3.lms_sync(ctx)
+        assert k3.lms_copy_busy_ms(ctx) == (0.0, 0.0)
+        k3.lms_release(ctx, h)
+        k3.lms_set_copy_timing(ctx, True)
+        for _ in range(3):
+            h = k3.lms_swap_out(ctx, t.data_ptr(), n, host)
+            k3.lms_release_after(ctx, h)
+            k3.lms_prefetch_in(ctx, h, t.data_ptr())
+            k3.lms_sync(ctx)
+            torch.cuda.synchronize()
+            k3.lms_release(ctx, h)
+        out_ms, in_ms = k3.lms_copy_busy_ms(ctx)
+        # 3 x 64 MiB each way: between 5 and 200 GB/s is a sane link
+        for ms in (out_ms, in_ms):
+            assert 3 * n / 200e9 * 1e3 < ms < 3 * n / 5e9 * 1e3, (out_ms, in_ms)
+        k3.lms_set_copy_timing(ctx, False)
+        h = k3.lms_swap_out(ctx, t.data_ptr(), n, host)
+        k3.lms_sync(ctx)
+        k3.lms_release(ctx, h)
+        assert k3.lms_copy_busy_ms(ctx) == (out_ms, in_ms)
+    finally:
+        k3.lms_host_free(host)
+        k3.lms_destroy(ctx)
