@@ -810,6 +810,470 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
     }
 }
 
+// ---------------------------------------------------------------------------- plane-streaming kernel
+// The 32-output-channel case (one MFMA row block per workgroup).  In the pipelined kernel above
+// every activation fragment read from LDS feeds a single matrix instruction there, and the LDS
+// read rate, not the matrix cores, sets the pace.  Here a wave owns one 4x8 patch position in all
+// 8 depth planes of an 8x8x16 tile and walks the 10 halo planes of a 16-channel chunk in depth
+// order: the fragment of halo plane z, tap (kh, kw) is read once and multiplied into the
+// accumulators of output planes z, z-1, z-2 with the weights of taps kd = 0, 1, 2, which stay in
+// registers for the whole chunk (27 fragments = 108 registers).  LDS traffic per matrix
+// instruction drops 2.7x.  Walking the planes in order has two more effects:
+//   * the first chunk of a workgroup is consumed while it arrives: plane z is waited for by
+//     count (copies complete in issue order), so the matrix cores start after two copy
+//     operations per wave instead of after the whole halo tile;
+//   * an output plane is complete after halo plane d + 2 of the last chunk, and is converted and
+//     stored, one register pair per step, between the matrix instructions of the next plane.
+// Weight registers are recycled plane by plane: taps kd = 0 are last used in plane 7, so the next
+// chunk's kd = 0 fragments are read from LDS during plane 8, kd = 1 during plane 9 and kd = 2
+// during the next chunk's plane 0.  Two barriers per chunk: after plane 0 (every wave has taken
+// its weights: the next chunk's weights may be copied into the one weight buffer, and the halo
+// buffer of the chunk before is free) and before plane 8 (the next chunk's weights and halo tile
+// have landed).
+struct ZsCfg {
+    static constexpr int TD = 8, TH = 8, TW = 16;
+    static constexpr int HD = 10, HH = 10, HW = 18;
+    static constexpr int ROWSLOTS = HW * 2 + 1;               // 16-byte slots per halo row (as PipeCfg)
+    static constexpr int XS_ROW = ROWSLOTS * 16;
+    static constexpr int XS_PLANE = HH * XS_ROW;
+    static constexpr int PLANE_SLOTS = HH * ROWSLOTS;
+    static constexpr int NSLOT = HD * PLANE_SLOTS;
+    static constexpr int XGROUPS = (NSLOT + 63) / 64;         // 1 KB copy groups per chunk, in plane order
+    static constexpr int XS_BYTES = XGROUPS * 1024;
+    static constexpr int XOPS = (XGROUPS + 3) / 4;            // halo copies per wave and chunk
+    static constexpr int WOPS = 7;                            // weight copies per wave and chunk (27 fragments)
+    static constexpr int W_OFF = 2 * XS_BYTES;
+    static constexpr int BIAS_OFF = W_OFF + 27 * 1024;
+    static constexpr int BIAS_MAX = 1024;
+    static constexpr int DUMP_OFF = BIAS_OFF + BIAS_MAX * 4;
+    static constexpr int LDS_BYTES = DUMP_OFF + 1024;
+    // halo copies of a wave (in issue order) that must be complete before plane z is read
+    static constexpr int need(int z) { return (((z + 1) * PLANE_SLOTS - 1) / 64) / 4 + 1; }
+    // copies a wave issues inside a chunk before plane z: the 7 weight copies in plane 1, three
+    // halo copies in each of planes 2..6
+    static constexpr int issued_before(int z) { return (z >= 2 ? WOPS : 0) + 3 * (z < 2 ? 0 : (z > 7 ? 5 : z - 2)); }
+    static_assert(LDS_BYTES <= 160 * 1024, "LDS budget");
+};
+static_assert(ZsCfg::XOPS == 15 && ZsCfg::need(9) == ZsCfg::XOPS, "the copy schedule assumes 15 halo copies per wave");
+
+// Halo slot of (copy k, thread): halo coordinates ld | lh << 8 | lw << 16, bit 24 = the slot
+// holds the upper 8 channels of its voxel, bit 25 = the slot is a real (voxel, half) item (not
+// row padding, not beyond the tile).  Shape-independent, so it is a table and not arithmetic.
+struct ZsSlotTable {
+    int v[ZsCfg::XOPS * 256];
+    constexpr ZsSlotTable() : v()
+    {
+        for (int k = 0; k < ZsCfg::XOPS; ++k)
+            for (int t = 0; t < 256; ++t) {
+                const int G = k * 4 + t / 64, slot = G * 64 + t % 64;
+                const int r = slot / ZsCfg::ROWSLOTS, pos = slot - r * ZsCfg::ROWSLOTS;
+                const int ld = r / ZsCfg::HH, lh = r - ld * ZsCfg::HH, lw = pos >> 1;
+                const bool ok = G < ZsCfg::XGROUPS && slot < ZsCfg::NSLOT && pos < ZsCfg::ROWSLOTS - 1;
+                v[k * 256 + t] = ok ? (ld | (lh << 8) | (lw << 16) | ((pos & 1) << 24) | (1 << 25)) : 0;
+            }
+    }
+};
+static __device__ const ZsSlotTable g_zs_slots = ZsSlotTable();
+
+// Asynchronous copy through a buffer descriptor: lane l writes 16 bytes to LDS byte address
+// lds_base + 16 * l from descriptor base + soff + voff.  A lane whose voff lies beyond the
+// descriptor's range (0xffffffff is used for "nothing to copy") writes zeros: out-of-volume halo
+// items and padding need neither a branch nor a zero block.  Tracked by vmcnt like dma16.
+__device__ __forceinline__ void dma16_buf(unsigned lds_base, __amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+
+template <int OMASK>   // 0: no output mask, 2: one bit per element
+__global__ __launch_bounds__(256, 1) void conv_mfma_zs_kernel(MfmaParams p)
+{
+    typedef ZsCfg C;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int hb = lane >> 5, vl = lane & 31;
+    const int nkc = (p.c1 + p.c2) / 16;
+    const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
+
+    // ---- loads the compiler waits for (everything issued before them completes with them), so
+    // they come before the first copy: the slot table and the bias vector
+    int coords[C::XOPS];
+#pragma unroll
+    for (int k = 0; k < C::XOPS; ++k) coords[k] = g_zs_slots.v[k * 256 + tid];
+    {
+        float *bl = reinterpret_cast<float *>(smem + C::BIAS_OFF);
+        const int nco = p.cd1 + p.cd2;
+        for (int i = tid; i < nco; i += 256) bl[i] = p.bias ? p.bias[i] : 0.f;
+    }
+    // byte offset of each slot from the halo tile's first voxel (the sources have equal strides;
+    // every factor is below 2^24 and the product below 2^31: checked at launch)
+    const unsigned strideB = p.c1 * 2;
+    unsigned xb[C::XOPS];
+    auto slot_offset = [&](int cw) __attribute__((always_inline)) {
+        const unsigned ld = cw & 255, lh = (cw >> 8) & 255, lw = (cw >> 16) & 255;
+        const unsigned vox = __umul24(__umul24(ld, p.H) + lh, p.W) + lw;
+        return __umul24(vox, strideB) + ((cw >> 24) & 1) * 16;
+    };
+    // the slot lies inside the volume for a tile whose halo starts at voxel (dlo, hlo, wlo) - 1 ...
+    auto slot_inside = [&](int cw, unsigned dlo, unsigned hlo, unsigned wlo) __attribute__((always_inline)) {
+        const unsigned ld = cw & 255, lh = (cw >> 8) & 255, lw = (cw >> 16) & 255;
+        return ((cw >> 25) & 1) && ld - dlo < (unsigned)p.D && lh - hlo < (unsigned)p.H && lw - wlo < (unsigned)p.W;
+    };
+
+    // persistent workgroups and XCD-aware tile order as in conv_mfma_pipe_kernel
+    auto decode = [&](int64_t vb, bool with_mask) {
+        PipeTile t;
+        const int64_t logical = (vb & 7) * p.per_xcd + (vb >> 3);
+        t.valid = (vb >> 3) < p.per_xcd && logical < p.total;
+        t.n = t.d0 = t.h0 = t.w0 = t.mb0 = 0;
+        t.origin = 0;
+        t.vmask = 0;
+        if (t.valid) {
+            unsigned tile = (unsigned)logical;
+            const int cg = (int)(tile % (unsigned)p.ncg);
+            tile /= (unsigned)p.ncg;
+            const int twi = (int)(tile % (unsigned)p.ntw);
+            tile /= (unsigned)p.ntw;
+            const int thi = (int)(tile % (unsigned)p.nth);
+            tile /= (unsigned)p.nth;
+            const int tdi = (int)(tile % (unsigned)p.ntd);
+            t.n = (int)(tile / (unsigned)p.ntd);
+            t.d0 = tdi * C::TD; t.h0 = thi * C::TH; t.w0 = twi * C::TW;
+            t.mb0 = cg;
+            t.origin = (((int64_t)t.n * p.D + t.d0) * p.H + t.h0) * p.W + t.w0;
+            if (with_mask) {
+                // halo coordinate l is inside the volume iff 0 <= t0 + l - 1 < size
+                unsigned vm = 0;
+#pragma unroll
+                for (int k = 0; k < C::XOPS; ++k)
+                    vm |= (slot_inside(coords[k], 1 - t.d0, 1 - t.h0, 1 - t.w0) ? 1u : 0u) << k;
+                t.vmask = vm;
+            }
+        }
+        return t;
+    };
+
+    // Source of the copies of one chunk (all wave-uniform but ninv).  Every wave issues exactly
+    // WOPS + XOPS copies per chunk so that the waits below can count them; a copy with nothing
+    // to move writes zeros to a dump area of LDS.
+    struct Src {
+        __amdgpu_buffer_rsrc_t wrs, xrs;   // packed weights of (output block, tap 0, chunk) / the halo tile's first voxel, first channel of the chunk
+        unsigned ninv;                     // bit k clear: halo slot k of this lane is inside the volume
+        unsigned wvoff;                    // lane offset inside a weight fragment, or "nothing"
+        unsigned xl, xl_last, wl, wl_last; // LDS destinations of this wave's copies 0 / of its last copy
+    };
+    const unsigned dump = lds0 + C::DUMP_OFF;
+    const unsigned wso0 = (unsigned)(wv * nkc) * 1024u, wstep = (unsigned)(4 * nkc) * 1024u;
+    auto set_src = [&](Src &s, const PipeTile &t, int c, int buf, bool ok) {
+        const int ch0 = c * 16;
+        const bool first = ch0 < p.c1;
+        const bf16_t *src = first ? p.src1 : p.src2;
+        const int chs = first ? ch0 : ch0 - p.c1;
+        const int64_t halo0 = t.origin - ((int64_t)p.H * p.W + p.W + 1);
+        const unsigned char *wp = reinterpret_cast<const unsigned char *>(p.packed) + (((int64_t)t.mb0 * 27) * nkc + c) * 1024;
+        const unsigned char *xp = reinterpret_cast<const unsigned char *>(src) + (halo0 * p.c1 + chs) * 2;
+        s.wrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(wp), 0, 0x7ffffff0, 0x00020000);
+        s.xrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(xp), 0, 0x7ffffff0, 0x00020000);
+        s.ninv = ok ? ~t.vmask : 0xffffffffu;
+        s.wvoff = ok ? (unsigned)lane * 16u : 0xffffffffu;
+        s.xl = lds0 + buf * C::XS_BYTES + wv * 1024;
+        s.xl_last = (C::XOPS - 1) * 4 + wv < C::XGROUPS ? s.xl + (C::XOPS - 1) * 4096 : dump;
+        s.wl = lds0 + C::W_OFF + wv * 1024;
+        s.wl_last = (C::WOPS - 1) * 4 + wv < 27 ? s.wl + (C::WOPS - 1) * 4096 : dump;
+    };
+    auto issue_w = [&](const Src &s, int j) __attribute__((always_inline)) {
+        // fragment (tap) f = 4 j + wv; the one beyond the 27 taps reads nothing into the dump area
+        const bool lastj = j == C::WOPS - 1;
+        const unsigned voff = (lastj && wv == 3) ? 0xffffffffu : s.wvoff;
+        dma16_buf(lastj ? s.wl_last : s.wl + j * 4096, s.wrs, voff, wso0 + j * wstep);
+    };
+    auto issue_x = [&](const Src &s, int k) __attribute__((always_inline)) {
+        // all ones where the slot is outside the volume (sign-extended bit k)
+        const unsigned inv = (unsigned)__builtin_amdgcn_sbfe(s.ninv, k, 1);
+        dma16_buf(k == C::XOPS - 1 ? s.xl_last : s.xl + k * 4096, s.xrs, xb[k] | inv, 0u);
+    };
+
+    // the wave's patch position inside a plane, and the lane's voxel inside the patch
+    const int bh = wv >> 1, bw = wv & 1;
+    const int lrow = vl >> 3, lcol = vl & 7;
+    const int vbase = (bh * 4 + lrow) * C::XS_ROW + (bw * 8 + lcol) * 32 + hb * 16;   // LDS offset, tap (0,0,0), plane 0
+    const int lvox = (bh * 4 + lrow) * p.W + bw * 8 + lcol;                          // voxel offset inside an output plane
+
+    PipeTile cur = decode(blockIdx.x, false);
+    if (!cur.valid) return;
+    int64_t vb_next = (int64_t)blockIdx.x + gridDim.x;
+
+    // ---- prologue: weights and halo tile of chunk 0 of the first tile, halo in plane order; each
+    // slot's copy leaves as soon as its offset and validity are known
+    {
+        Src s0;
+        set_src(s0, cur, 0, 0, true);
+#pragma unroll
+        for (int j = 0; j < C::WOPS; ++j) issue_w(s0, j);
+        unsigned vm = 0;
+#pragma unroll
+        for (int k = 0; k < C::XOPS; ++k) {
+            xb[k] = slot_offset(coords[k]);
+            const bool in = slot_inside(coords[k], 1 - cur.d0, 1 - cur.h0, 1 - cur.w0);
+            vm |= (in ? 1u : 0u) << k;
+            dma16_buf(k == C::XOPS - 1 ? s0.xl_last : s0.xl + k * 4096, s0.xrs, in ? xb[k] : 0xffffffffu, 0u);
+        }
+        cur.vmask = vm;
+    }
+    PipeTile nxt = decode(vb_next, true);
+    // With more than one chunk the first chunk is consumed while its planes arrive (it is not
+    // the one that stores, which keeps the counted waits free of conditional stores).
+    const bool stream0 = nkc > 1;
+    if (stream0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::XOPS) : "memory");   // the weights: issued first
+    else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    __syncthreads();
+    bf16x8 A[27];
+    auto lda = [&](int tap) __attribute__((always_inline)) {
+        return *reinterpret_cast<const bf16x8 *>(smem + C::W_OFF + tap * 1024 + lane * 16);
+    };
+#pragma unroll
+    for (int t = 0; t < 27; ++t) A[t] = lda(t);
+
+    unsigned mkb[8];   // OMASK == 2: the mask word of the lane's block in each output plane
+#pragma unroll
+    for (int d = 0; d < 8; ++d) mkb[d] = 0u;
+
+    int xpar = 0;
+    const float relu_floor = p.relu ? 0.f : -__builtin_inff();
+    bool first = stream0;
+    while (true) {
+        f32x16 acc[8];
+        {
+            const f32x4 *bl = reinterpret_cast<const f32x4 *>(smem + C::BIAS_OFF) + (cur.mb0 * 32 + hb * 16) / 4;
+            f32x4 q[4];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) q[i] = bl[i];
+#pragma unroll
+            for (int d = 0; d < 8; ++d) {
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[d][i] = q[i >> 2][i & 3];
+                asm volatile("" : "+a"(acc[d]));
+            }
+        }
+        // where the tile's results go: descriptor at the tile's first voxel and output channel,
+        // the lane's byte offset inside an output plane (beyond the range where the lane's voxel
+        // is outside the volume: such stores are dropped), the byte pitch of a plane
+        const int dlim = p.D - cur.d0;
+        const bool inhw = bh * 4 + lrow < p.H - cur.h0 && bw * 8 + lcol < p.W - cur.w0;
+        const int co0 = cur.mb0 * 32;   // the lane's 16 channels start at co0 + hb * 16
+        const bool d1 = co0 < p.cd1;
+        const int cd = d1 ? p.cd1 : p.cd2;
+        const int64_t ubase = cur.origin * cd + (d1 ? co0 : co0 - p.cd1);
+        __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc((d1 ? p.dst1 : p.dst2) + ubase, 0, 0x7ffffff0, 0x00020000);
+        const int obase = inhw ? (lvox * cd + hb * 16) * 2 : -1;
+        const int oplane = p.H * p.W * cd * 2;
+        // bit words (16 channels each): written (forward) or read (masked backward-data)
+        const bool wbits = OMASK == 0 && p.bits_out != nullptr && d1;
+        __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
+            (OMASK == 0 ? (p.bits_out ? p.bits_out : (unsigned short *)p.dst1) : (unsigned short *)p.omask_bits) + (d1 ? ubase / 16 : 0),
+            0, 0x7ffffff0, 0x00020000);
+        const int bbase = inhw ? (lvox * (cd / 16) + hb) * 2 : -1;
+        const int bplane = p.H * p.W * (cd / 16) * 2;
+
+        // Output plane d leaves in 8 steps: step i converts values 2i, 2i+1 (ReLU, round to bf16),
+        // step 3 stores the lower 16 bytes of the lane's 32, step 7 the upper 16 and the mask word.
+        uint32_t ob[8];
+        unsigned zb = 0;
+        auto emit_cvt = [&](int d, int i) __attribute__((always_inline)) {
+            if (i == 0) asm volatile("" : "+a"(acc[d]));   // the block stays in accumulator registers until here
+            const float v0 = fmaxf(acc[d][2 * i], relu_floor), v1 = fmaxf(acc[d][2 * i + 1], relu_floor);
+            uint32_t o = pack2bf(v0, v1);
+            if constexpr (OMASK == 2) {
+                if (d1) {
+                    const unsigned kk = (mkb[d] >> (2 * i)) & 3u;
+                    const u16x2_t keep = __builtin_bit_cast(u16x2_t, (kk | (kk << 15)) & 0x00010001u);
+                    o = __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2_t, o) * keep);
+                }
+            }
+            ob[i] = o;
+        };
+        auto emit_aux = [&](int d, int i) __attribute__((always_inline)) {
+            if constexpr (OMASK == 0) {
+                if (wbits) zb = i == 0 ? bf16_pair_positive(ob[i]) : (zb | (bf16_pair_positive(ob[i]) << i));
+            }
+            if (i == 3 || i == 7) {
+                const int voff = d < dlim ? obase : -1;
+                if (i == 3) __builtin_amdgcn_raw_buffer_store_b128(u32x4{ob[0], ob[1], ob[2], ob[3]}, orsrc, voff, d * oplane, 0);
+                else __builtin_amdgcn_raw_buffer_store_b128(u32x4{ob[4], ob[5], ob[6], ob[7]}, orsrc, voff, d * oplane + 16, 0);
+                if constexpr (OMASK == 0) {
+                    if (i == 7 && wbits) {
+                        unsigned z = zb;   // even elements in bits 0..7, odd ones in bits 16..23 (see relu_bits16)
+                        z = (z | (z << 4)) & 0x0F0F0F0Fu;
+                        z = (z | (z << 2)) & 0x33333333u;
+                        z = (z | (z << 1)) & 0x55555555u;
+                        z = (z | (z >> 15)) & 0xffffu;
+                        __builtin_amdgcn_raw_buffer_store_b16((short)z, brsrc, d < dlim ? bbase : -1, d * bplane, 0);
+                    }
+                }
+            }
+        };
+
+        // One 16-channel chunk: 10 halo planes x 9 taps (kh, kw) x up to 3 output planes.  A wave
+        // issues in order and alone on its SIMD, so whatever is not a matrix instruction is spread
+        // thinly between the matrix instructions (one short group behind each).
+        auto chunk = [&](int c, auto streamtag, auto lasttag) __attribute__((always_inline)) {
+            constexpr bool STREAM = decltype(streamtag)::value;   // the chunk whose copies the prologue issued
+            constexpr bool LAST = decltype(lasttag)::value;       // the chunk that completes the tile
+            static_assert(!(STREAM && LAST), "the streamed chunk does not store");
+            Src ns;
+            if (c + 1 < nkc) set_src(ns, cur, c + 1, xpar ^ 1, true);
+            else set_src(ns, nxt, 0, xpar ^ 1, nxt.valid);
+            const unsigned char *xs = smem + xpar * C::XS_BYTES + vbase;
+            auto ldb = [&](int q) __attribute__((always_inline)) {   // q = plane * 9 + tap
+                return *reinterpret_cast<const bf16x8 *>(xs + (q / 9) * C::XS_PLANE + ((q % 9) / 3) * C::XS_ROW + (q % 3) * 32);
+            };
+            if constexpr (LAST && OMASK == 2) {
+                // requested now, used from plane 3 on (the wait there counts the copies in between)
+                if (d1) {
+#pragma unroll
+                    for (int d = 0; d < 8; ++d) {
+                        unsigned v;
+                        asm volatile("buffer_load_ushort %0, %1, %2, %3 offen" : "=v"(v) : "v"(d < dlim ? bbase : -1), "s"(brsrc), "s"(d * bplane) : "memory");
+                        mkb[d] = v;
+                    }
+                } else {
+#pragma unroll
+                    for (int d = 0; d < 8; ++d) {
+                        unsigned v;
+                        asm volatile("buffer_load_ushort %0, %1, %2, %3 offen" : "=v"(v) : "v"(-1), "s"(brsrc), "s"(0) : "memory");
+                        mkb[d] = v;
+                    }
+                }
+            }
+            constexpr int PD = 3;
+            bf16x8 bq[4];
+            if constexpr (!STREAM) {
+#pragma unroll
+                for (int q = 0; q < PD; ++q) bq[q] = ldb(q);
+            }
+#pragma unroll
+            for (int z = 0; z < 10; ++z) {
+                if constexpr (STREAM) {
+                    if (z < 8) {
+                        // plane z of the prologue's copies has landed once at most this many later
+                        // operations of the wave are outstanding
+                        wait_vm(C::XOPS - C::need(z) + C::issued_before(z));
+                        __syncthreads();
+                    }
+                }
+                if (z == 8) {
+                    // the next chunk's weights and halo tile; behind the last copy (plane 6, tap 7) the
+                    // wave issued the store of that step and the two of plane 7
+                    wait_vm(LAST ? 3 : 0);
+                    __syncthreads();
+                }
+                if constexpr (STREAM) {
+#pragma unroll
+                    for (int t = 0; t < PD; ++t) bq[(z * 9 + t) & 3] = ldb(z * 9 + t);
+                }
+#pragma unroll
+                for (int t = 0; t < 9; ++t) {
+                    const int q = z * 9 + t;
+                    const int dA = z < 8 ? z : z - 1 < 8 ? z - 1 : z - 2;   // output planes of this step, oldest last
+                    int nm = 0;
+#pragma unroll
+                    for (int kd = 0; kd < 3; ++kd) {
+                        const int d = z - kd;
+                        if (d < 0 || d >= 8) continue;
+                        acc[d] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(A[kd * 9 + t], bq[q & 3], acc[d], 0, 0, 0);
+                        // behind the first matrix instruction of the step: the fragment three steps ahead
+                        // and the step's copy; behind the second: conversion; behind the third: the rest
+                        if (nm == 0) {
+                            if constexpr (STREAM) {
+                                if (t + PD < 9) bq[(q + PD) & 3] = ldb(q + PD);
+                            } else {
+                                if (q + PD < 90) bq[(q + PD) & 3] = ldb(q + PD);
+                            }
+                            if (z == 1 && t < C::WOPS) issue_w(ns, t);
+                            if (z >= 2 && z <= 6 && t % 3 == 1) issue_x(ns, (z - 2) * 3 + t / 3);
+                        }
+                        if (nm == 1 || (z == 9 && nm == 0)) {
+                            if constexpr (LAST) {
+                                if (z >= 3 && t < 8) {
+                                    if constexpr (OMASK == 2) {
+                                        if (z == 3 && t == 0) {
+                                            // behind the mask requests: 7 weight copies, 3 halo copies of plane 2
+                                            wait_vm(C::WOPS + 3);
+#pragma unroll
+                                            for (int dd = 0; dd < 8; ++dd) asm volatile("" : "+v"(mkb[dd]));
+                                        }
+                                    }
+                                    emit_cvt(z - 3, t);
+                                }
+                            }
+                        }
+                        ++nm;
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                    (void)dA;
+                    // weight registers whose taps are done for this chunk take the next chunk's
+                    if (z == 8) A[t] = lda(t);
+                    if (z == 9) A[9 + t] = lda(9 + t);
+                    if (z == 0 && !STREAM) A[18 + t] = lda(18 + t);
+                    if constexpr (LAST) {
+                        if (z >= 3 && t < 8) emit_aux(z - 3, t);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
+                if (z == 0 && !STREAM) __syncthreads();   // every wave holds this chunk's weights and is done with the chunk before
+            }
+            if constexpr (LAST) {
+#pragma unroll
+                for (int i = 0; i < 8; ++i) {
+                    emit_cvt(7, i);
+                    emit_aux(7, i);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            xpar ^= 1;
+        };
+
+        int c = 0;
+        if (first) {
+            chunk(0, std::true_type(), std::false_type());
+            c = 1;
+            first = false;
+        }
+        for (; c + 1 < nkc; ++c) chunk(c, std::false_type(), std::false_type());
+        chunk(nkc - 1, std::false_type(), std::true_type());
+        if (!nxt.valid) break;
+        cur = nxt;
+        vb_next += gridDim.x;
+        nxt = decode(vb_next, true);
+    }
+}
+
+static int launch_zs(MfmaParams p, int64_t mblocks, hipStream_t st)
+{
+    typedef ZsCfg C;
+    p.ntd = (p.D + C::TD - 1) / C::TD;
+    p.nth = (p.H + C::TH - 1) / C::TH;
+    p.ntw = (p.W + C::TW - 1) / C::TW;
+    p.ncg = (int)mblocks;
+    p.total = (int64_t)p.N * p.ntd * p.nth * p.ntw * p.ncg;
+    p.per_xcd = (p.total + 7) / 8;
+    if (p.per_xcd * 8 > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+    static bool attr_done = false;
+    if (!attr_done) {
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<0>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<2>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+        attr_done = true;
+    }
+    int64_t grid = p.per_xcd * 8 < 256 ? p.per_xcd * 8 : 256;
+    if (p.omask_bits) conv_mfma_zs_kernel<2><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    else conv_mfma_zs_kernel<0><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
 template <class C>
 static int launch_pipe(MfmaParams p, int64_t mblocks, hipStream_t st)
 {
@@ -885,7 +1349,14 @@ static int launch_mfma(MfmaParams p, int64_t mchannels, hipStream_t st)
     int64_t mblocks = mchannels / 32;
     switch (mfma_variant(p, mblocks)) {
     case 1: return launch_pipe<PipeCfg<8, 8, 16, 2>>(p, mblocks, st);
-    case 2: return launch_pipe<PipeCfg<8, 8, 16, 1>>(p, mblocks, st);
+    case 2: {
+        // the plane-streaming kernel: mask as bits or none, sources of equal channel counts, halo
+        // tile offsets that fit its 24-bit multiplies and 31-bit byte offsets
+        const bool zs = !p.omask && (p.c2 == 0 || p.c2 == p.c1) && (int64_t)11 * p.H * p.W < (1 << 24) &&
+                        (int64_t)11 * p.H * p.W * p.c1 * 2 < 0x7fffffffLL;
+        if (zs) return launch_zs(p, mblocks, st);
+        return launch_pipe<PipeCfg<8, 8, 16, 1>>(p, mblocks, st);
+    }
     case 3: return launch_pipe<PipeCfg<4, 8, 8, 2>>(p, mblocks, st);
     case 4: return launch_pipe<PipeCfg<4, 8, 8, 1>>(p, mblocks, st);
     default: break;

@@ -23,6 +23,9 @@ FWD_CASES = [
     (1, 7, 20, 35, 32, 0, 64, "bf16"),     # several 16x16 columns with ragged edges, odd depth
     (2, 3, 17, 16, 64, 32, 32, "bf16"),    # two sources, one row past a column, two samples
     (1, 40, 16, 18, 32, 0, 32, "bf16"),    # long depth run
+    (3, 36, 44, 50, 32, 0, 32, "bf16"),    # plane-streaming kernel (32 output channels, a tile per CU and more): ragged on every axis
+    (2, 32, 40, 48, 32, 32, 96, "bf16"),   # plane-streaming forward: two sources, four chunks, three output blocks
+    (2, 32, 40, 48, 32, 64, 32, "bf16"),   # plane-streaming backward-data into two destinations (three blocks)
 ]
 
 
@@ -199,6 +202,8 @@ BITS_CASES = [
     (1, 10, 8, 8, 32, 32, 32),       # two sources forward / two destinations backward (mask on the first)
     (1, 4, 4, 4, 128, 0, 128),       # small volume: first MFMA kernel + generic passes
     (1, 5, 6, 7, 3, 2, 16),          # direct kernels
+    (3, 36, 44, 50, 32, 0, 32),      # plane-streaming kernel writes / reads the bits, ragged tiles, two tiles per workgroup
+    (2, 32, 40, 48, 32, 64, 32),     # plane-streaming backward-data: mask on the first of two destinations
 ]
 
 
