@@ -99,6 +99,16 @@ __device__ __forceinline__ void dma16(unsigned lds_base, const void *gptr)
     asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_base), "v"(gptr) : "memory");
 }
 
+// Asynchronous copy through a buffer descriptor: lane l writes 16 bytes to LDS byte address
+// lds_base + 16 * l from descriptor base + soff + voff.  A lane whose voff lies beyond the
+// descriptor's range (0xffffffff is used for "nothing to copy") writes zeros: out-of-volume halo
+// items and padding need neither a branch nor a zero block.  Tracked by vmcnt like dma16.
+__device__ __forceinline__ void dma16_buf(unsigned lds_base, __amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
+                 ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
+}
+
 template <typename T> struct elem;
 template <> struct elem<float> {
     static __device__ __forceinline__ float ld(const float *p) { return *p; }

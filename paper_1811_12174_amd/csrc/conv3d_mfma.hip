@@ -875,16 +875,6 @@ struct ZsSlotTable {
 };
 static __device__ const ZsSlotTable g_zs_slots = ZsSlotTable();
 
-// Asynchronous copy through a buffer descriptor: lane l writes 16 bytes to LDS byte address
-// lds_base + 16 * l from descriptor base + soff + voff.  A lane whose voff lies beyond the
-// descriptor's range (0xffffffff is used for "nothing to copy") writes zeros: out-of-volume halo
-// items and padding need neither a branch nor a zero block.  Tracked by vmcnt like dma16.
-__device__ __forceinline__ void dma16_buf(unsigned lds_base, __amdgpu_buffer_rsrc_t rsrc, unsigned voff, unsigned soff)
-{
-    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tbuffer_load_dwordx4 %1, %2, %3 offen lds"
-                 ::"s"(__builtin_amdgcn_readfirstlane(lds_base)), "v"(voff), "s"(rsrc), "s"(soff) : "memory");
-}
-
 template <int OMASK>   // 0: no output mask, 2: one bit per element
 __global__ __launch_bounds__(256, 1) void conv_mfma_zs_kernel(MfmaParams p)
 {

@@ -11,7 +11,11 @@
 //    once per column and serves the three depth taps; g planes alternate between two buffers.
 //  * While a stage is multiplied, x and g planes one or two stages ahead move from global
 //    memory straight into the free LDS buffers (asynchronous 16-byte-per-lane copies); one
-//    vmcnt wait and one barrier per stage.  Voxels outside the volume read a block of zeros.
+//    vmcnt wait and one barrier per stage.  The copies go through buffer descriptors: an item
+//    outside the volume carries an offset beyond the descriptor's range and arrives as zeros,
+//    a plane outside the volume (or beyond the run) gets a descriptor of size zero.  They are
+//    issued one at a time between the MFMAs of the stage (a wave issues in order and is alone
+//    on its SIMD: a burst of copy instructions would idle the matrix core).
 //  * The four waves split the 27 taps (7, 7, 7, 6); the spare slot of the last wave
 //    multiplies g by ones, which yields the bias gradient.  Inside a stage the operand
 //    fragments of K-step s+1 are requested from LDS between the MFMAs of K-step s.
@@ -56,8 +60,6 @@ struct WgradPipeParams {
     int total, per_xcd;
 };
 
-static __device__ uint4 g_wzero[4];   // zero-initialised: source of every out-of-volume item
-
 __device__ __forceinline__ bf16x8 wp_tr_pair(const unsigned char *base, int off)
 {
     typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
@@ -72,9 +74,10 @@ __device__ __forceinline__ bf16x8 wp_tr_pair(const unsigned char *base, int off)
 // 8*(s%2) .. +7 of the 16x16 patch; xa[t] / ga are the lane's LDS byte offsets of the tap-t x
 // fragment and of the g fragment for K-step 0.  last (wave-uniform): the seventh slot is the
 // ones product (its x fragment is still read, from a valid address, and dropped).
-template <int COBN>
+// extra(s) is called once per K-step, behind its first MFMA (the stage's copies).
+template <int COBN, class Extra>
 __device__ __forceinline__ void wp_stage(f32x16 (&acc)[7][COBN], const unsigned char *smem, const int (&xa)[7], int ga,
-                                         bf16x8 ones, bool last)
+                                         bf16x8 ones, bool last, Extra extra)
 {
     using namespace wp;
     constexpr int NF = COBN + 7;        // fragments per K-step
@@ -98,6 +101,7 @@ __device__ __forceinline__ void wp_stage(f32x16 (&acc)[7][COBN], const unsigned 
             const int t = m / COBN, c = m % COBN;
             const bf16x8 a = (t == 6 && last) ? ones : fr[s & 1][COBN + t];
             acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, fr[s & 1][c], acc[t][c], 0, 0, 0);
+            if (m == 0) extra(s);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
@@ -112,7 +116,6 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hb = lane >> 5, g16 = (lane >> 4) & 1, j = lane & 15;
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
-    const unsigned char *zero = reinterpret_cast<const unsigned char *>(g_wzero);
     constexpr int NXB = nxb(PF), NGB = ngb(PF);
     // LDS map: the g ring first, then the ring of x planes, then the dump area of the padding
     // copies.  (Measured: with the x ring first and the g buffers behind it the same kernel ran
@@ -122,6 +125,7 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
     constexpr int XOFF = NGB * GBUF;
     constexpr int GK = COBN * 4;              // g copies per wave and plane
     constexpr int OPS = XK + GK;              // copies per wave and stage (always exactly this many)
+    static_assert(OPS <= 16, "one copy per K-step");
     const unsigned dump = lds0 + dump_off(COBN, PF);
 
     // XCD-aware order: consecutive block ids go round-robin to the 8 XCDs, so the logical order
@@ -140,14 +144,14 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
     const int chx = first ? cib * 32 : cib * 32 - p.c1;
 
     // ---- per-lane description of the copy items (tile independent)
-    int xoff[XK], xco[XK];     // byte offset from the column origin / halo coords lh | lw << 8
+    int xoff[XK], xco[XK];     // byte offset from the halo plane's first voxel / halo coords lh | lw << 8
     unsigned xsl = 0;          // slot holds a voxel of the 18x18 plane
 #pragma unroll
     for (int k = 0; k < XK; ++k) {
         const int slot = (wv + 4 * k) * 64 + lane;
         const int vox = slot >> 2, part = slot & 3;
         const int lh = vox / HW, lw = vox - lh * HW;
-        xoff[k] = ((lh - 1) * p.W + (lw - 1)) * Cx * 2 + part * 16;
+        xoff[k] = (lh * p.W + lw) * Cx * 2 + part * 16;
         xco[k] = lh | (lw << 8);
         xsl |= ((wv + 4 * k < XP_GROUPS && vox < HH * HW) ? 1u : 0u) << k;
     }
@@ -201,42 +205,65 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
         const int n = (int)((unsigned)q1 / (unsigned)p.nth);
         const int h0 = thi * TH, w0 = twi * TW;
 
-        unsigned xvm = 0, gvm = 0;   // item lies inside the volume (in-plane test)
+        // per-lane offsets of this column's items; beyond every descriptor's range where the item
+        // lies outside the volume (in-plane test) or is padding
+        unsigned xo[XK], go[GK];
 #pragma unroll
         for (int k = 0; k < XK; ++k) {
-            const int gh = h0 + (xco[k] & 255) - 1, gw = w0 + (xco[k] >> 8) - 1;
-            xvm |= ((gh >= 0 && gh < p.H && gw >= 0 && gw < p.W) ? 1u : 0u) << k;
+            const unsigned gh = h0 + (xco[k] & 255) - 1, gw = w0 + (xco[k] >> 8) - 1;
+            xo[k] = (((xsl >> k) & 1) && gh < (unsigned)p.H && gw < (unsigned)p.W) ? (unsigned)xoff[k] : 0xffffffffu;
         }
-        xvm &= xsl;
 #pragma unroll
         for (int k = 0; k < GK; ++k) {
             const int gh = h0 + (gco[k] & 255), gw = w0 + (gco[k] >> 8);
-            gvm |= ((gh < p.H && gw < p.W) ? 1u : 0u) << k;
+            go[k] = (gh < p.H && gw < p.W) ? (unsigned)goff[k] : 0xffffffffu;
         }
         // element index of voxel (n, 0, h0, w0); planes are p.H * p.W voxels apart
         const int64_t vox0 = (((int64_t)n * p.D) * p.H + h0) * p.W + w0;
         const int64_t plane = (int64_t)p.H * p.W;
 
         // x plane with run index q (plane dlo - 1 + q) -> ring buffer buf; `on` false: padding copies
-        auto issue_x = [&](int q, int buf, bool on) __attribute__((always_inline)) {
+        struct PlaneSrc {
+            __amdgpu_buffer_rsrc_t rs;
+            unsigned lds;     // LDS address of this wave's first copy group in the destination buffer
+            bool on;
+        };
+        auto x_plane = [&](int q, int buf, bool on) __attribute__((always_inline)) {
             const int d = dlo - 1 + q;
             const bool din = on && d >= 0 && d < p.D;
-            const unsigned char *base = reinterpret_cast<const unsigned char *>(xsrc + (vox0 + d * plane) * Cx + chx);
-#pragma unroll
-            for (int k = 0; k < XK; ++k) {
-                const bool grp = on && wv + 4 * k < XP_GROUPS;
-                const unsigned char *ptr = (din && ((xvm >> k) & 1)) ? base + xoff[k] : zero;
-                dma16(grp ? lds0 + XOFF + buf * XP_BYTES + (wv + 4 * k) * 1024 : dump, ptr);
-            }
+            // the halo plane's first voxel: one row and one column before the column's origin
+            const bf16_t *base = xsrc + (vox0 + d * plane - (p.W + 1)) * Cx + chx;
+            PlaneSrc s;
+            s.rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(base), 0, din ? 0x7ffffff0 : 0, 0x00020000);
+            s.lds = lds0 + XOFF + buf * XP_BYTES + wv * 1024;
+            s.on = on;
+            return s;
+        };
+        auto x_copy = [&](const PlaneSrc &s, int k) __attribute__((always_inline)) {
+            const bool grp = s.on && wv + 4 * k < XP_GROUPS;
+            dma16_buf(grp ? s.lds + k * 4096 : dump, s.rs, xo[k], 0u);
         };
         // g plane with run index i (plane dlo + i)
-        auto issue_g = [&](int i, int buf, bool on) __attribute__((always_inline)) {
-            const unsigned char *base = reinterpret_cast<const unsigned char *>(p.dy + (vox0 + (dlo + i) * plane) * p.cout);
+        auto g_plane = [&](int i, int buf, bool on) __attribute__((always_inline)) {
+            const bf16_t *base = p.dy + (vox0 + (dlo + i) * plane) * p.cout;
+            PlaneSrc s;
+            s.rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(base), 0, on ? 0x7ffffff0 : 0, 0x00020000);
+            s.lds = lds0 + GOFF + buf * GBUF + wv * 1024;
+            s.on = on;
+            return s;
+        };
+        auto g_copy = [&](const PlaneSrc &s, int k) __attribute__((always_inline)) {
+            dma16_buf(s.on ? s.lds + k * 4096 : dump, s.rs, go[k], 0u);
+        };
+        auto issue_x = [&](int q, int buf, bool on) __attribute__((always_inline)) {
+            const PlaneSrc s = x_plane(q, buf, on);
 #pragma unroll
-            for (int k = 0; k < GK; ++k) {
-                const unsigned char *ptr = (on && ((gvm >> k) & 1)) ? base + goff[k] : zero;
-                dma16(on ? lds0 + GOFF + buf * GBUF + (wv + 4 * k) * 1024 : dump, ptr);
-            }
+            for (int k = 0; k < XK; ++k) x_copy(s, k);
+        };
+        auto issue_g = [&](int i, int buf, bool on) __attribute__((always_inline)) {
+            const PlaneSrc s = g_plane(i, buf, on);
+#pragma unroll
+            for (int k = 0; k < GK; ++k) g_copy(s, k);
         };
 
         // Prologue of the run: what stage 0 reads (x planes 0..2, g plane 0), then the planes the
@@ -259,13 +286,10 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
 
         int xb = 0, gb = 0;   // ring buffers of x plane i and g plane i
         for (int i = 0; i < n_run; ++i) {
-            {
-                int xn = xb + 2 + PF; if (xn >= NXB) xn -= NXB; if (xn >= NXB) xn -= NXB;
-                int gn = gb + PF; if (gn >= NGB) gn -= NGB;
-                const bool on = i + PF < n_run;
-                issue_x(i + 2 + PF, xn, on);
-                issue_g(i + PF, gn, on);
-            }
+            int xn = xb + 2 + PF; if (xn >= NXB) xn -= NXB; if (xn >= NXB) xn -= NXB;
+            int gn = gb + PF; if (gn >= NGB) gn -= NGB;
+            const bool on = i + PF < n_run;
+            const PlaneSrc sx = x_plane(i + 2 + PF, xn, on), sg = g_plane(i + PF, gn, on);
             int xa[7];
 #pragma unroll
             for (int t = 0; t < 7; ++t) {
@@ -273,7 +297,10 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
                 xa[t] = bsel * XP_BYTES + tapoff[t];
             }
             const int ga = lane_g + gb * GBUF;
-            wp_stage<COBN>(acc, smem, xa, ga, ones, wv == 3);
+            wp_stage<COBN>(acc, smem, xa, ga, ones, wv == 3, [&](int s) __attribute__((always_inline)) {
+                if (s < XK) x_copy(sx, s);
+                else if (s < OPS) g_copy(sg, s - XK);
+            });
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PF - 1) * OPS) : "memory");
             __syncthreads();
             if (++xb == NXB) xb = 0;
