@@ -143,9 +143,9 @@ def bench_cfg2(args):
     mfma_ms = time_calls(mix, it) / 4.0
     # (the weight-gradient call is two launches: the MFMA kernel and the small split-K reduction)
     wgrad_ms = kern["conv3d_bwd_weight"]
-    share = {"conv_mfma_pipe_kernel": 4 * mfma_ms, "conv_wgrad_pipe_kernel": 2 * wgrad_ms}
+    share = {"conv_mfma_zs_kernel": 4 * mfma_ms, "conv_wgrad_pipe_kernel": 2 * wgrad_ms}
     dominant = max(share, key=share.get)
-    dom_ms = mfma_ms if dominant == "conv_mfma_pipe_kernel" else wgrad_ms
+    dom_ms = mfma_ms if dominant == "conv_mfma_zs_kernel" else wgrad_ms
     achieved = f1 / (dom_ms * 1e-3) / 1e12
     roofline = {"bound": "mfma", "kernel": dominant, "achieved": round(achieved, 2), "peak": MFMA_BF16_PEAK_TFLOPS,
                 "unit": "TFLOP/s", "frac": round(achieved / MFMA_BF16_PEAK_TFLOPS, 4),

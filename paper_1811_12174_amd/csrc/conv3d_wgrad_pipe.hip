@@ -22,6 +22,12 @@
 //  * Each workgroup writes one partial sum per (split, tap, ci, co); the partials are added
 //    in a fixed order by reduce_partials_kernel (no atomics: run-to-run identical).
 //
+//  * Short problems (a handful of planes per workgroup) pay mostly for the partial sums: every
+//    workgroup writes 27 x 32 x 32 floats whatever its share of the voxels.  The KS variant
+//    therefore gives a workgroup one of the four tap groups and four times the planes: its
+//    four waves split the K-steps of a plane (4 each) instead of the taps, add their
+//    accumulators through LDS at the end (fixed order), and the partial sums shrink 4x.
+//
 // The kernel takes no ReLU mask: backward passes that need one hand over a gradient already
 // masked by its producer, or use the kernel in conv3d_wgrad.hip.
 #include "common.h"
@@ -74,14 +80,17 @@ __device__ __forceinline__ bf16x8 wp_tr_pair(const unsigned char *base, int off)
 // 8*(s%2) .. +7 of the 16x16 patch; xa[t] / ga are the lane's LDS byte offsets of the tap-t x
 // fragment and of the g fragment for K-step 0.  last (wave-uniform): the seventh slot is the
 // ones product (its x fragment is still read, from a valid address, and dropped).
-// extra(s) is called once per K-step, behind its first MFMA (the stage's copies).
-template <int COBN, class Extra>
+// The stage runs NK K-steps starting at the K-step the offsets xa / ga point to.  extra(e),
+// e = 0 .. NE-1, is called behind evenly spaced MFMAs (the stage's copies).
+template <int COBN, int NK, int NE, class Extra>
 __device__ __forceinline__ void wp_stage(f32x16 (&acc)[7][COBN], const unsigned char *smem, const int (&xa)[7], int ga,
                                          bf16x8 ones, bool last, Extra extra)
 {
     using namespace wp;
     constexpr int NF = COBN + 7;        // fragments per K-step
     constexpr int NM = 7 * COBN;        // MFMAs per K-step
+    constexpr int STEP = NK * NM / NE;  // MFMAs between two calls of extra
+    static_assert(STEP >= 1, "more copies than MFMAs");
     bf16x8 fr[2][COBN + 7];
     auto load = [&](int s, int f) __attribute__((always_inline)) -> bf16x8 {
         const int r2 = 2 * (s >> 1), q = 8 * (s & 1);
@@ -91,23 +100,23 @@ __device__ __forceinline__ void wp_stage(f32x16 (&acc)[7][COBN], const unsigned 
 #pragma unroll
     for (int f = 0; f < NF; ++f) fr[0][f] = load(0, f);
 #pragma unroll
-    for (int s = 0; s < 16; ++s) {
+    for (int s = 0; s < NK; ++s) {
 #pragma unroll
         for (int m = 0; m < NM; ++m) {
-            if (s + 1 < 16) {
+            if (s + 1 < NK) {
 #pragma unroll
                 for (int f = m * NF / NM; f < (m + 1) * NF / NM; ++f) fr[(s + 1) & 1][f] = load(s + 1, f);
             }
             const int t = m / COBN, c = m % COBN;
             const bf16x8 a = (t == 6 && last) ? ones : fr[s & 1][COBN + t];
             acc[t][c] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, fr[s & 1][c], acc[t][c], 0, 0, 0);
-            if (m == 0) extra(s);
+            if ((s * NM + m) % STEP == 0 && (s * NM + m) / STEP < NE) extra((s * NM + m) / STEP);
             __builtin_amdgcn_sched_barrier(0);
         }
     }
 }
 
-template <int COBN, int PF>
+template <int COBN, int PF, bool KS>
 __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams p)
 {
     using namespace wp;
@@ -125,7 +134,7 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
     constexpr int XOFF = NGB * GBUF;
     constexpr int GK = COBN * 4;              // g copies per wave and plane
     constexpr int OPS = XK + GK;              // copies per wave and stage (always exactly this many)
-    static_assert(OPS <= 16, "one copy per K-step");
+    constexpr int NK = KS ? 4 : 16;           // K-steps of a plane a wave multiplies
     const unsigned dump = lds0 + dump_off(COBN, PF);
 
     // XCD-aware order: consecutive block ids go round-robin to the 8 XCDs, so the logical order
@@ -133,9 +142,12 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
     // blocks) are neighbours in the logical order and share an L2.
     const unsigned logical = (blockIdx.x & 7u) * (unsigned)p.per_xcd + (blockIdx.x >> 3);
     if ((blockIdx.x >> 3) >= (unsigned)p.per_xcd || logical >= (unsigned)p.total) return;
+    // KS: the tap group varies fastest, so the four workgroups that read the same planes are neighbours
+    const int tg = KS ? (int)(logical & 3u) : wv;        // tap group of this wave: taps 7 tg .. 7 tg + 6
+    const unsigned lg = KS ? logical >> 2 : logical;
     const unsigned yz = (unsigned)(p.ncib * p.ncog);
-    const int split = (int)(logical / yz);
-    const int r = (int)(logical - (unsigned)split * yz);
+    const int split = (int)(lg / yz);
+    const int r = (int)(lg - (unsigned)split * yz);
     const int cib = r % p.ncib, cob0 = (r / p.ncib) * COBN;
     const int cin = p.c1 + p.c2;
     const bool first = cib * 32 < p.c1;
@@ -167,12 +179,14 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
     }
 
     // ---- lane-constant parts of the transposing-read addresses and the wave's taps
-    const int lane_x = XOFF + (hb * HW + (j >> 2)) * 64 + g16 * 32 + (j & 3) * 8;
-    const int lane_g = GOFF + (hb * TW + (j >> 2)) * 64 + g16 * 32 + (j & 3) * 8;
+    // (KS: the wave's K-steps 4 wv .. 4 wv + 3 are rows 4 wv .. 4 wv + 3 of the patch)
+    const int krow = KS ? 4 * wv : 0;
+    const int lane_x = XOFF + ((krow + hb) * HW + (j >> 2)) * 64 + g16 * 32 + (j & 3) * 8;
+    const int lane_g = GOFF + ((krow + hb) * TW + (j >> 2)) * 64 + g16 * 32 + (j & 3) * 8;
     int tapoff[7], tapkd[7];
 #pragma unroll
     for (int t = 0; t < 7; ++t) {
-        int tap = wv * 7 + t;
+        int tap = tg * 7 + t;
         if (tap > 26) tap = 26;   // slot of the ones product: address unused
         tapkd[t] = tap / 9;
         tapoff[t] = lane_x + (((tap / 3) % 3) * HW + tap % 3) * 64;
@@ -297,9 +311,9 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
                 xa[t] = bsel * XP_BYTES + tapoff[t];
             }
             const int ga = lane_g + gb * GBUF;
-            wp_stage<COBN>(acc, smem, xa, ga, ones, wv == 3, [&](int s) __attribute__((always_inline)) {
-                if (s < XK) x_copy(sx, s);
-                else if (s < OPS) g_copy(sg, s - XK);
+            wp_stage<COBN, NK, OPS>(acc, smem, xa, ga, ones, tg == 3, [&](int e) __attribute__((always_inline)) {
+                if (e < XK) x_copy(sx, e);
+                else g_copy(sg, e - XK);
             });
             asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PF - 1) * OPS) : "memory");
             __syncthreads();
@@ -308,10 +322,39 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
         }
     }
 
+    if constexpr (KS) {
+        // the four waves hold sums over different voxels of the same taps: through LDS (the rings
+        // are no longer read after the barrier that ended the last stage), wave w adds up taps w
+        // and w + 4 of the group in the fixed order wave 0, 1, 2, 3
+        static_assert(COBN == 1, "K split is built for one output block");
+        static_assert(4 * 7 * 16 * 256 <= lds_bytes(COBN, PF), "reduction buffer fits the rings");
+        f32x4 *red = reinterpret_cast<f32x4 *>(smem);
+#pragma unroll
+        for (int t = 0; t < 7; ++t)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                red[((wv * 7 + t) * 4 + q) * 64 + lane] = f32x4{acc[t][0][4 * q], acc[t][0][4 * q + 1], acc[t][0][4 * q + 2], acc[t][0][4 * q + 3]};
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < 7; ++t) {
+            if (t != wv && t != wv + 4) continue;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                f32x4 s = red[((0 * 7 + t) * 4 + q) * 64 + lane];
+#pragma unroll
+                for (int u = 1; u < 4; ++u) {
+                    const f32x4 v = red[((u * 7 + t) * 4 + q) * 64 + lane];
+                    s[0] += v[0]; s[1] += v[1]; s[2] += v[2]; s[3] += v[3];
+                }
+                acc[t][0][4 * q] = s[0]; acc[t][0][4 * q + 1] = s[1]; acc[t][0][4 * q + 2] = s[2]; acc[t][0][4 * q + 3] = s[3];
+            }
+        }
+    }
     float *out = p.ws + (int64_t)split * p.per_split;
 #pragma unroll
     for (int t = 0; t < 7; ++t) {
-        const int tap = wv * 7 + t;
+        if (KS && t != wv && t != wv + 4) continue;
+        const int tap = tg * 7 + t;
 #pragma unroll
         for (int c = 0; c < COBN; ++c) {
             const int co = (cob0 + c) * 32 + (lane & 31);
@@ -343,13 +386,17 @@ static int wp_num_cus()
 
 static constexpr int wp_pf(int cobn) { return cobn == 1 ? 2 : 1; }   // deeper read-ahead where a stage is short
 
+// ks: with fewer than 12 planes per workgroup the workgroups take one tap group each and four
+// times the planes (see the KS variant of the kernel)
 static void wp_plan(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout, int *cobn, int64_t *P,
-                    int *S)
+                    int *S, bool *ks)
 {
     *cobn = (cout % 64 == 0) ? 2 : 1;
     *P = N * ((H + wp::TH - 1) / wp::TH) * ((W + wp::TW - 1) / wp::TW) * D;
     const int64_t yz = (cin / 32) * (cout / (32 * *cobn));
     int64_t s = wp_num_cus() / yz;   // one workgroup per CU in total
+    *ks = *cobn == 1 && s >= 4 && *P < 12 * s && *P >= s / 4;
+    if (*ks) s /= 4;
     if (s > *P) s = *P;
     if (s < 1) s = 1;
     *S = (int)s;
@@ -368,11 +415,12 @@ size_t conv_wgrad_pipe_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int6
 {
     int cobn, S;
     int64_t P;
-    wp_plan(N, D, H, W, cin, cout, &cobn, &P, &S);
+    bool ks;
+    wp_plan(N, D, H, W, cin, cout, &cobn, &P, &S, &ks);
     return (size_t)S * (size_t)(27 * cin * cout + cout) * sizeof(float);
 }
 
-template <int COBN>
+template <int COBN, bool KS>
 static int launch_wgrad_pipe(const WgradPipeParams &p, hipStream_t st)
 {
     constexpr int PF = wp_pf(COBN);
@@ -380,11 +428,11 @@ static int launch_wgrad_pipe(const WgradPipeParams &p, hipStream_t st)
     static_assert(lds <= 160 * 1024, "LDS budget");
     static bool attr_done = false;
     if (!attr_done) {
-        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_wgrad_pipe_kernel<COBN, PF>),
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_wgrad_pipe_kernel<COBN, PF, KS>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, lds));
         attr_done = true;
     }
-    conv_wgrad_pipe_kernel<COBN, PF><<<dim3((unsigned)(p.per_xcd * 8)), 256, lds, st>>>(p);
+    conv_wgrad_pipe_kernel<COBN, PF, KS><<<dim3((unsigned)(p.per_xcd * 8)), 256, lds, st>>>(p);
     K3_LAUNCH_CHECK();
     return K3_OK;
 }
@@ -395,7 +443,8 @@ int conv_wgrad_pipe(const ConvArgs &a, float *dW, float *db, float *ws, hipStrea
     const int64_t cin = a.c1 + a.c2;
     int cobn;
     int64_t P;
-    wp_plan(a.N, a.D, a.H, a.W, cin, a.cout, &cobn, &P, &p.S);
+    bool ks;
+    wp_plan(a.N, a.D, a.H, a.W, cin, a.cout, &cobn, &P, &p.S, &ks);
     p.P = (int)P;
     p.pbase = p.P / p.S;
     p.prem = p.P % p.S;
@@ -412,11 +461,12 @@ int conv_wgrad_pipe(const ConvArgs &a, float *dW, float *db, float *ws, hipStrea
     p.ntw = (int)((a.W + wp::TW - 1) / wp::TW);
     p.ncib = (int)(cin / 32);
     p.ncog = (int)(a.cout / (32 * cobn));
-    const int64_t total = (int64_t)p.S * p.ncib * p.ncog;
+    const int64_t total = (int64_t)p.S * p.ncib * p.ncog * (ks ? 4 : 1);
     if (total > 0x3fffffffLL) return K3_E_UNSUPPORTED;
     p.total = (int)total;
     p.per_xcd = (p.total + 7) / 8;
-    int rc = cobn == 2 ? launch_wgrad_pipe<2>(p, st) : launch_wgrad_pipe<1>(p, st);
+    int rc = cobn == 2 ? launch_wgrad_pipe<2, false>(p, st)
+                       : (ks ? launch_wgrad_pipe<1, true>(p, st) : launch_wgrad_pipe<1, false>(p, st));
     if (rc != K3_OK) return rc;
     return launch_reduce_partials(ws, dW, db, 27 * cin * a.cout, p.per_split, p.S, st);
 }
