@@ -378,6 +378,7 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
 
     // ---- tile-independent description of the halo slots this lane copies in each stage part
     int coords[3 * C::XG_WAVE];        // halo coordinates of the slot, packed ld | lh << 8 | lw << 16
+    unsigned hvox[3 * C::XG_WAVE];     // voxel offset of the slot from the halo tile's first voxel
     unsigned smask = 0, hmask = 0;     // slot is a real (voxel, half) item / holds the upper 8 channels
 #pragma unroll
     for (int g = 0; g < 3; ++g)
@@ -390,6 +391,7 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             const int ld = r / C::HH, lh = r - ld * C::HH, lw = pos >> 1;
             const bool ok = G < C::XGROUPS && slot < C::NSLOT && pos < C::ROWSLOTS - 1;
             coords[idx] = ld | (lh << 8) | (lw << 16);
+            hvox[idx] = (unsigned)((ld * p.H + lh) * p.W + lw);
             smask |= (ok ? 1u : 0u) << idx;
             hmask |= (unsigned)(pos & 1) << idx;
         }
@@ -430,19 +432,29 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
     };
 
     // Source of one stage's asynchronous copies (all wave-uniform): the weight fragments of the
-    // next stage and one third of the next chunk's halo tile.
+    // next stage and one third of the next chunk's halo tile.  The copies go through buffer
+    // descriptors: a lane with nothing to copy (halo item outside the volume, row padding, no next
+    // stage) carries an offset beyond the descriptor's range and writes zeros.
     struct StageSrc {
-        const unsigned char *wbase;   // packed weights of (first output block, first tap, chunk) of the stage
-        const unsigned char *xbase;   // channel chs of the tile's origin voxel
-        int strideB;                  // bytes per voxel of the x source
-        unsigned vmask;               // halo validity bits of the tile
+        __amdgpu_buffer_rsrc_t wrs;   // packed weights of (first output block, first tap, chunk) of the stage
+        __amdgpu_buffer_rsrc_t xrs;   // first channel of the chunk at the halo tile's first voxel
+        unsigned strideB;             // bytes per voxel of the x source
+        unsigned ninv;                // bit idx clear: the lane's halo slot idx lies inside the volume
+        unsigned wvoff;               // lane offset inside a weight fragment, or "nothing"
         unsigned wlds, xlds;          // LDS byte addresses of the destination buffers
-        bool wok, xok;
+    };
+    auto no_src = [&](StageSrc &s) {
+        s.wrs = s.xrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(p.packed), 0, 0, 0x00020000);
+        s.strideB = 0;
+        s.ninv = 0xffffffffu;
+        s.wvoff = 0xffffffffu;
+        s.wlds = s.xlds = lds0 + C::DUMP_OFF;
     };
     auto w_src = [&](StageSrc &s, const PipeTile &t, int c, int g, int buf) {
-        s.wbase = reinterpret_cast<const unsigned char *>(p.packed) + ((((int64_t)t.mb0 * 27 + g * 9) * nkc + c) * 1024);
+        const unsigned char *wp = reinterpret_cast<const unsigned char *>(p.packed) + ((((int64_t)t.mb0 * 27 + g * 9) * nkc + c) * 1024);
+        s.wrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(wp), 0, 0x7ffffff0, 0x00020000);
+        s.wvoff = (unsigned)lane * 16u;
         s.wlds = lds0 + 2 * C::XS_BYTES + buf * C::WS_BYTES;
-        s.wok = true;
     };
     auto x_src = [&](StageSrc &s, const PipeTile &t, int c, int buf) {
         const int ch0 = c * 16;
@@ -450,40 +462,42 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
         const bf16_t *src = first ? p.src1 : p.src2;
         const int Csrc = first ? p.c1 : p.c2;
         const int chs = first ? ch0 : ch0 - p.c1;
-        s.xbase = reinterpret_cast<const unsigned char *>(src + t.origin * Csrc + chs);
+        const int64_t halo0 = t.origin - ((int64_t)p.H * p.W + p.W + 1);
+        const unsigned char *xp = reinterpret_cast<const unsigned char *>(src) + (halo0 * Csrc + chs) * 2;
+        s.xrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<unsigned char *>(xp), 0, 0x7ffffff0, 0x00020000);
         s.strideB = Csrc * 2;
-        s.vmask = t.vmask;
+        s.ninv = ~t.vmask;
         s.xlds = lds0 + buf * C::XS_BYTES;
-        s.xok = true;
     };
     // copy operation j of a stage: first the weight fragments, then the halo groups of part g
     constexpr int NOPS = C::WF_WAVE + C::XG_WAVE;
     // Every wave issues exactly NOPS copies per stage, so that the number of copies still in
     // flight at a stage end is known at compile time (s_waitcnt takes an immediate): a slot that
     // has nothing to copy moves the zero block into a dump area of LDS.
+    // packed-weight offset of this wave's weight copy j: fragment f = 4 j + wv is (tap f / MB, block f % MB)
+    unsigned wso[C::WF_WAVE];
+#pragma unroll
+    for (int j = 0; j < C::WF_WAVE; ++j) {
+        const int f = j * 4 + wv, tl = f / C::MB, mb = f - tl * C::MB;
+        wso[j] = (unsigned)((mb * 27 + tl) * nkc) * 1024u;
+    }
     auto issue_op = [&](const StageSrc &s, int j, auto gtag) __attribute__((always_inline)) {
         constexpr int g = decltype(gtag)::value;
         const unsigned dump = lds0 + C::DUMP_OFF;
         if (j < C::WF_WAVE) {
             const int f = j * 4 + wv;   // fragment (tap tl, block mb) of the stage
-            const bool ok = s.wok && f < C::WFRAGS;
-            const int tl = f / C::MB, mb = f - tl * C::MB;
-            const unsigned char *ptr = ok ? s.wbase + ((int64_t)(mb * 27 + tl) * nkc) * 1024 + lane * 16 : zero;
-            dma16(ok ? s.wlds + f * 1024 : dump, ptr);
+            const bool ok = f < C::WFRAGS;
+            dma16_buf(ok ? s.wlds + f * 1024 : dump, s.wrs, ok ? s.wvoff : 0xffffffffu, ok ? wso[j] : 0u);
         } else {
             const int k = j - C::WF_WAVE;
             const int idx = g * C::XG_WAVE + k;
             const int G = g * C::XG_STAGE + k * 4 + wv;
-            const bool ok = s.xok && k * 4 + wv < C::XG_STAGE && G < C::XGROUPS;
-            // unpacked here, per copy: the opaque move keeps the compiler from hoisting the
-            // unpacked values of all slots out of the loops (they would occupy ~60 registers)
-            int cw = coords[idx];
-            asm volatile("" : "+v"(cw));
-            const int ld = cw & 255, lh = (cw >> 8) & 255, lw = cw >> 16;
-            const int voxoff = ((ld - 1) * p.H + (lh - 1)) * p.W + (lw - 1);   // from the tile origin
-            const unsigned char *ptr = s.xbase + (int64_t)voxoff * s.strideB + ((hmask >> idx) & 1) * 16;
-            if (!ok || !((s.vmask >> idx) & 1)) ptr = zero;
-            dma16(ok ? s.xlds + G * 1024 : dump, ptr);
+            const bool ok = k * 4 + wv < C::XG_STAGE && G < C::XGROUPS;
+            // every factor is below 2^24 and the byte offset below 2^31 (checked at launch); all
+            // ones where the slot is outside the volume (sign-extended bit idx)
+            const unsigned off = __umul24(hvox[idx], s.strideB) + ((hmask >> idx) & 1) * 16;
+            const unsigned inv = (unsigned)__builtin_amdgcn_sbfe(s.ninv, idx, 1);
+            dma16_buf(ok ? s.xlds + G * 1024 : dump, s.xrs, ok ? (off | inv) : 0xffffffffu, 0u);
         }
     };
 
@@ -505,8 +519,8 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
 
     // ---- prologue: chunk 0 of the first tile and the weights of its stage (0, 0)
     {
-        StageSrc s0{};
-        s0.wbase = s0.xbase = zero;
+        StageSrc s0;
+        no_src(s0);
         w_src(s0, cur, 0, 0, 0);
         x_src(s0, cur, 0, 0);
 #pragma unroll
@@ -665,8 +679,8 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             // the data of the next stage (possibly the first stage of the next tile) starts moving
             // now; its copies are issued one at a time between the matrix instructions below
             const bool more = c + 1 < nkc;
-            StageSrc ss{};
-            ss.wbase = ss.xbase = zero;
+            StageSrc ss;
+            no_src(ss);
             if (g < 2) w_src(ss, cur, c, g + 1, wpar ^ 1);
             else if (more) w_src(ss, cur, c + 1, 0, wpar ^ 1);
             else if (nxt.valid) w_src(ss, nxt, 0, 0, wpar ^ 1);
@@ -1321,7 +1335,10 @@ static int mfma_variant(const MfmaParams &p, int64_t mblocks)
 {
     const int cmax = p.cd1 > p.cd2 ? p.cd1 : p.cd2;
     // the halo tile's voxel offsets and the per-lane output offsets are kept in 32 bits
-    const bool fits = (int64_t)10 * p.H * p.W * (cmax > 1 ? cmax : 1) < 0x7fffffffLL && p.cd1 + p.cd2 <= 1024;
+    const int smax = p.c1 > p.c2 ? p.c1 : p.c2;
+    // ... and the halo tile's voxel offsets in 24 bits, its byte offsets in 31 (the copies' offset arithmetic)
+    const bool fits = (int64_t)10 * p.H * p.W * (cmax > 1 ? cmax : 1) < 0x7fffffffLL && p.cd1 + p.cd2 <= 1024 &&
+                      (int64_t)11 * p.H * p.W < (1 << 24) && (int64_t)11 * p.H * p.W * smax * 2 < 0x7fffffffLL;
     if (!p.mask && fits) {
         const int64_t big = (int64_t)p.N * ((p.D + 7) / 8) * ((p.H + 7) / 8) * ((p.W + 15) / 16);
         const int64_t small = (int64_t)p.N * ((p.D + 3) / 4) * ((p.H + 7) / 8) * ((p.W + 7) / 8);
@@ -1340,10 +1357,8 @@ static int launch_mfma(MfmaParams p, int64_t mchannels, hipStream_t st)
     switch (mfma_variant(p, mblocks)) {
     case 1: return launch_pipe<PipeCfg<8, 8, 16, 2>>(p, mblocks, st);
     case 2: {
-        // the plane-streaming kernel: mask as bits or none, sources of equal channel counts, halo
-        // tile offsets that fit its 24-bit multiplies and 31-bit byte offsets
-        const bool zs = !p.omask && (p.c2 == 0 || p.c2 == p.c1) && (int64_t)11 * p.H * p.W < (1 << 24) &&
-                        (int64_t)11 * p.H * p.W * p.c1 * 2 < 0x7fffffffLL;
+        // the plane-streaming kernel: mask as bits or none, sources of equal channel counts
+        const bool zs = !p.omask && (p.c2 == 0 || p.c2 == p.c1);
         if (zs) return launch_zs(p, mblocks, st);
         return launch_pipe<PipeCfg<8, 8, 16, 1>>(p, mblocks, st);
     }
