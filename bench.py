@@ -41,16 +41,30 @@ def conv_flops(n, d, h, w, cin, cout):
     return 2.0 * n * cin * cout * (3 * d - 2) * (3 * h - 2) * (3 * w - 2)
 
 
-def time_calls(fn, iters, warm=3):
-    """Average duration (ms) of fn() over `iters` back-to-back calls, HIP events on the launch stream."""
+def time_calls(fn, iters, warm=3, graph=False):
+    """Average duration (ms) of fn() over `iters` back-to-back calls, HIP events on the launch stream.
+    graph=True: the calls are captured into one HIP graph first (as the benchmark step is), which
+    takes the host's launch cost out of the gaps between the kernels."""
     import torch
     for _ in range(warm):
         fn()
+    run = None
+    if graph:
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            for _ in range(iters):
+                fn()
+        g.replay()
+        run = g.replay
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     e0.record()
-    for _ in range(iters):
-        fn()
+    if run is not None:
+        run()
+    else:
+        for _ in range(iters):
+            fn()
     e1.record()
     e1.synchronize()
     return e0.elapsed_time(e1) / iters
@@ -127,12 +141,13 @@ def bench_cfg2(args):
 
     # per-call timings (events on the launch stream), same launch configuration as the step
     it = max(20, args.steps // 4)
+    gr = not args.no_graph
     kern = {
-        "conv3d_fwd": time_calls(lambda: k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2), it),
-        "conv3d_bwd_data": time_calls(lambda: k3.conv3d_bwd_data_bits(da2, None, w2, pk2, da1, a1bits), it),
-        "conv3d_bwd_weight": time_calls(lambda: k3.conv3d_bwd_weight(a1, da2, None, dW2, db2, ws), it),
-        "pool3d_fwd": time_calls(lambda: k3.pool3d_fwd(a2, p), it),
-        "pool3d_bwd": time_calls(lambda: k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True), it),
+        "conv3d_fwd": time_calls(lambda: k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2), it, graph=gr),
+        "conv3d_bwd_data": time_calls(lambda: k3.conv3d_bwd_data_bits(da2, None, w2, pk2, da1, a1bits), it, graph=gr),
+        "conv3d_bwd_weight": time_calls(lambda: k3.conv3d_bwd_weight(a1, da2, None, dW2, db2, ws), it, graph=gr),
+        "pool3d_fwd": time_calls(lambda: k3.pool3d_fwd(a2, p), it, graph=gr),
+        "pool3d_bwd": time_calls(lambda: k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True), it, graph=gr),
     }
 
     def mix():   # the implicit-GEMM kernel as the step launches it: 2 forward + 2 backward-data passes
@@ -140,7 +155,7 @@ def bench_cfg2(args):
         k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2)
         k3.conv3d_bwd_data_bits(da2, None, w2, pk2, da1, a1bits)
         k3.conv3d_bwd_data(da1, None, w1, pk1, dx)
-    mfma_ms = time_calls(mix, it) / 4.0
+    mfma_ms = time_calls(mix, it, graph=not args.no_graph) / 4.0
     # (the weight-gradient call is two launches: the MFMA kernel and the small split-K reduction)
     wgrad_ms = kern["conv3d_bwd_weight"]
     share = {"conv_mfma_zs_kernel": 4 * mfma_ms, "conv_wgrad_pipe_kernel": 2 * wgrad_ms}
