@@ -900,16 +900,7 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_zs_kernel(MfmaParams p)
     const int nkc = (p.c1 + p.c2) / 16;
     const unsigned lds0 = (unsigned)(size_t)(__attribute__((address_space(3))) unsigned char *)smem;
 
-    // ---- loads the compiler waits for (everything issued before them completes with them), so
-    // they come before the first copy: the slot table and the bias vector
     int coords[C::XOPS];
-#pragma unroll
-    for (int k = 0; k < C::XOPS; ++k) coords[k] = g_zs_slots.v[k * 256 + tid];
-    {
-        float *bl = reinterpret_cast<float *>(smem + C::BIAS_OFF);
-        const int nco = p.cd1 + p.cd2;
-        for (int i = tid; i < nco; i += 256) bl[i] = p.bias ? p.bias[i] : 0.f;
-    }
     // byte offset of each slot from the halo tile's first voxel (the sources have equal strides;
     // every factor is below 2^24 and the product below 2^31: checked at launch)
     const unsigned strideB = p.c1 * 2;
@@ -919,10 +910,18 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_zs_kernel(MfmaParams p)
         const unsigned vox = __umul24(__umul24(ld, p.H) + lh, p.W) + lw;
         return __umul24(vox, strideB) + ((cw >> 24) & 1) * 16;
     };
-    // the slot lies inside the volume for a tile whose halo starts at voxel (dlo, hlo, wlo) - 1 ...
-    auto slot_inside = [&](int cw, unsigned dlo, unsigned hlo, unsigned wlo) __attribute__((always_inline)) {
+    // Validity is separable: bit l of axis_out(t0, n, ext) is set iff halo coordinate l of an axis
+    // lies outside the volume (inside iff 0 <= t0 + l - 1 < n); three scalar words per tile, then
+    // a slot is outside iff any of its three bits is set or it is padding (1 = outside).
+    auto axis_out = [](int t0, int n, int ext) __attribute__((always_inline)) {
+        int lo = 1 - t0, hi = n + 1 - t0;
+        if (lo < 0) lo = 0;
+        if (hi > ext) hi = ext;
+        return ~(((1u << hi) - 1u) & ~((1u << lo) - 1u));
+    };
+    auto slot_out = [](int cw, unsigned od, unsigned oh, unsigned ow) __attribute__((always_inline)) {
         const unsigned ld = cw & 255, lh = (cw >> 8) & 255, lw = (cw >> 16) & 255;
-        return ((cw >> 25) & 1) && ld - dlo < (unsigned)p.D && lh - hlo < (unsigned)p.H && lw - wlo < (unsigned)p.W;
+        return ((od >> ld) | (oh >> lh) | (ow >> lw) | (~(unsigned)cw >> 25)) & 1u;
     };
 
     // persistent workgroups and XCD-aware tile order as in conv_mfma_pipe_kernel
@@ -947,12 +946,11 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_zs_kernel(MfmaParams p)
             t.mb0 = cg;
             t.origin = (((int64_t)t.n * p.D + t.d0) * p.H + t.h0) * p.W + t.w0;
             if (with_mask) {
-                // halo coordinate l is inside the volume iff 0 <= t0 + l - 1 < size
-                unsigned vm = 0;
+                const unsigned od = axis_out(t.d0, p.D, C::HD), oh = axis_out(t.h0, p.H, C::HH), ow = axis_out(t.w0, p.W, C::HW);
+                unsigned nv = 0;
 #pragma unroll
-                for (int k = 0; k < C::XOPS; ++k)
-                    vm |= (slot_inside(coords[k], 1 - t.d0, 1 - t.h0, 1 - t.w0) ? 1u : 0u) << k;
-                t.vmask = vm;
+                for (int k = 0; k < C::XOPS; ++k) nv |= slot_out(coords[k], od, oh, ow) << k;
+                t.vmask = ~nv;
             }
         }
         return t;
@@ -1015,15 +1013,26 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_zs_kernel(MfmaParams p)
         set_src(s0, cur, 0, 0, true);
 #pragma unroll
         for (int j = 0; j < C::WOPS; ++j) issue_w(s0, j);
-        unsigned vm = 0;
+        // Loads the compiler waits for (everything issued before them completes with them): the slot
+        // table and the bias vector (to LDS for the whole kernel; zeros when there is none).  Behind
+        // the weight copies, whose latency they share, and before the halo copies.
+#pragma unroll
+        for (int k = 0; k < C::XOPS; ++k) coords[k] = g_zs_slots.v[k * 256 + tid];
+        {
+            float *bl = reinterpret_cast<float *>(smem + C::BIAS_OFF);
+            const int nco = p.cd1 + p.cd2;
+            for (int i = tid; i < nco; i += 256) bl[i] = p.bias ? p.bias[i] : 0.f;
+        }
+        const unsigned od = axis_out(cur.d0, p.D, C::HD), oh = axis_out(cur.h0, p.H, C::HH), ow = axis_out(cur.w0, p.W, C::HW);
+        unsigned nv = 0;
 #pragma unroll
         for (int k = 0; k < C::XOPS; ++k) {
             xb[k] = slot_offset(coords[k]);
-            const bool in = slot_inside(coords[k], 1 - cur.d0, 1 - cur.h0, 1 - cur.w0);
-            vm |= (in ? 1u : 0u) << k;
-            dma16_buf(k == C::XOPS - 1 ? s0.xl_last : s0.xl + k * 4096, s0.xrs, in ? xb[k] : 0xffffffffu, 0u);
+            const unsigned o = slot_out(coords[k], od, oh, ow);
+            nv |= o << k;
+            dma16_buf(k == C::XOPS - 1 ? s0.xl_last : s0.xl + k * 4096, s0.xrs, xb[k] | (0u - o), 0u);
         }
-        cur.vmask = vm;
+        cur.vmask = ~nv;
     }
     PipeTile nxt = decode(vb_next, true);
     // With more than one chunk the first chunk is consumed while its planes arrive (it is not
