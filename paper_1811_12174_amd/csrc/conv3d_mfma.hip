@@ -251,12 +251,13 @@ __global__ __launch_bounds__(256, 2) void conv_mfma_kernel(MfmaParams p)
 // staging.  A stage is (16-channel chunk c, tap plane kd): 9 taps.  While the waves multiply
 // stage s out of LDS, the data of stage s+1 -- the next tap plane of packed weights and one
 // third of the next chunk's halo tile -- is in flight from global memory straight into the
-// other LDS buffers (global_load_lds_dwordx4: lane l of a wave writes 16 bytes to LDS slot
-// base + l, from any global address; no registers are staged).  One vmcnt wait and one
-// barrier per stage.  Voxels outside the volume and the row-padding slots read a 16-byte
-// block of zeros instead.  This kernel takes no input-side ReLU mask (the asynchronous copy
-// cannot apply one); backward passes feed it gradients that were masked by their producer.
-static __device__ uint4 g_zero_block[4];   // zero-initialised; source of every out-of-volume halo item
+// other LDS buffers (16-byte-per-lane copies to LDS through a buffer descriptor: lane l of a
+// wave writes 16 bytes to LDS slot base + l, from descriptor base + its own offset; no registers
+// are staged).  One vmcnt wait and one barrier per stage.  Voxels outside the volume and the
+// row-padding slots carry an offset beyond the descriptor's range and arrive as zeros.  This
+// kernel takes no input-side ReLU mask (the asynchronous copy cannot apply one); backward passes
+// feed it gradients that were masked by their producer.
+static __device__ uint4 g_zero_block[4];   // zero-initialised; source of the mask requests of out-of-volume lanes
 
 template <int TD_, int TH_, int TW_, int MB_>
 struct PipeCfg {
@@ -473,7 +474,7 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
     constexpr int NOPS = C::WF_WAVE + C::XG_WAVE;
     // Every wave issues exactly NOPS copies per stage, so that the number of copies still in
     // flight at a stage end is known at compile time (s_waitcnt takes an immediate): a slot that
-    // has nothing to copy moves the zero block into a dump area of LDS.
+    // has nothing to copy writes zeros into a dump area of LDS.
     // packed-weight offset of this wave's weight copy j: fragment f = 4 j + wv is (tap f / MB, block f % MB)
     unsigned wso[C::WF_WAVE];
 #pragma unroll
