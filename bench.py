@@ -210,9 +210,24 @@ def cpu_baseline_cfg2(step_flops):
         n += 1
     dt = time.perf_counter() - t0
     threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
-    return {"value": round(n * step_flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
-            "seconds": round(dt, 2),
-            "sample": f"{n} full cfg2 steps (6 conv passes + pool fwd/bwd each) in fp64 direct loops"}
+    out = {"value": round(n * step_flops / dt / 1e12, 5), "unit": "TFLOP/s", "cores": threads, "kind": "oracle",
+           "seconds": round(dt, 2),
+           "sample": f"{n} full cfg2 steps (6 conv passes + pool fwd/bwd each) in fp64 direct loops"}
+    # the same loops on one thread: one forward pass over an eighth of the volume (about a second)
+    try:
+        import ctypes
+        gomp = ctypes.CDLL("libgomp.so.1")
+        gomp.omp_set_num_threads(1)
+        xs = np.ascontiguousarray(x[:, :S // 2, :S // 2, :S // 2, :])
+        t1 = time.perf_counter()
+        oracle.conv3d_fwd(xs, w1, None, relu=True)
+        d1 = time.perf_counter() - t1
+        gomp.omp_set_num_threads(threads)
+        out["one_thread"] = {"value": round(conv_flops(N, S // 2, S // 2, S // 2, C, C) / d1 / 1e12, 6), "unit": "TFLOP/s",
+                             "sample": f"one conv3d_fwd pass, 1 x {S // 2}^3, {C}->{C}"}
+    except OSError:
+        pass
+    return out
 
 
 def load_traffic(kernel, workload):
