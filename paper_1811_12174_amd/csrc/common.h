@@ -63,6 +63,15 @@ __device__ __forceinline__ uint32_t bf16_pair_positive(uint32_t d)
     h = __builtin_elementwise_max(__builtin_elementwise_min(h, one), zero);
     return __builtin_bit_cast(uint32_t, h);
 }
+// the same with the two packed instructions pinned (left to itself the compiler expands the
+// min/max pair into compares, selects and a byte permute where it knows the halves are >= 0)
+__device__ __forceinline__ uint32_t pair_positive_pk(uint32_t d)
+{
+    uint32_t t;
+    asm("v_pk_min_i16 %0, %1, %2" : "=v"(t) : "v"(d), "v"(0x00010001u));
+    asm("v_pk_max_i16 %0, %1, 0" : "=v"(t) : "v"(t));
+    return t;
+}
 __device__ __forceinline__ unsigned relu_bits16(const uint32_t (&d)[8])
 {
     // even elements gather in bits 0..7, odd ones in bits 16..23, then both bytes are spread to

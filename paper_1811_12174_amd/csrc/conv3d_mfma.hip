@@ -366,7 +366,10 @@ struct MaskOrder {
     }
 };
 
-template <class C, int OMASK>   // 0: no output mask, 1: mask given as the bf16 tensor, 2: as one bit per element
+// OMASK 0: no output mask, 1: mask given as the bf16 tensor, 2: as one bit per element.  BITS: the
+// bit mask of the first destination is written (a template parameter, not a test of p.bits_out:
+// a wave-uniform branch per epilogue step costs more than the step)
+template <class C, int OMASK, bool BITS>
 __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
 {
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
@@ -654,8 +657,8 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
                     o1 = make_uint4(dd[4], dd[5], dd[6], dd[7]);
                 }
             }
-            if constexpr (OMASK == 0) {
-                if (p.bits_out && d1) {   // wave-uniform: the bit mask of what is stored below
+            if constexpr (BITS) {
+                if (d1) {   // wave-uniform: the bit mask of what is stored below
                     const uint32_t dd[8] = {o0.x, o0.y, o0.z, o0.w, o1.x, o1.y, o1.z, o1.w};
                     const unsigned m = relu_bits16(dd);
                     unsigned short *bbase = p.bits_out + ubase / 16;
@@ -670,6 +673,66 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             const int boff = inb ? loff * 2 : -1;
             __builtin_amdgcn_raw_buffer_store_b128(u32x4{o0.x, o0.y, o0.z, o0.w}, rsrc, boff, 0, 0);
             __builtin_amdgcn_raw_buffer_store_b128(u32x4{o1.x, o1.y, o1.z, o1.w}, rsrc, boff, 16, 0);
+        };
+
+        // The same in 8 steps per block (the variants without counted waits inside the last stage):
+        // step i rounds values 2i, 2i+1 to bf16 and applies ReLU on the packed pair (as 16-bit
+        // integers the negative bf16 values are the negative numbers), step 3 stores the lower 16
+        // bytes of the lane's 32, step 7 the upper 16 and the mask word.  What does not depend on
+        // the patch is prepared once per tile: descriptors, the lane's byte offset inside a patch.
+        __amdgpu_buffer_rsrc_t ersrc[C::MB], ebrsrc[C::MB];
+        int elane[C::MB], ecd2[C::MB];
+        unsigned eforce[C::MB];   // OMASK == 2: 3 for a block of the unmasked second destination (keeps both halves)
+#pragma unroll
+        for (int mb = 0; mb < C::MB; ++mb) {
+            const int co0 = (cur.mb0 + mb) * 32;
+            const bool d1 = co0 < p.cd1;
+            const int cd = d1 ? p.cd1 : p.cd2;
+            const int64_t ubase = cur.origin * cd + (d1 ? co0 : co0 - p.cd1);
+            ersrc[mb] = __builtin_amdgcn_make_buffer_rsrc((d1 ? p.dst1 : p.dst2) + ubase, 0, 0x7ffffff0, 0x00020000);
+            // (bit masks are written by forward passes, which have one destination)
+            ebrsrc[mb] = __builtin_amdgcn_make_buffer_rsrc((BITS ? p.bits_out : (unsigned short *)p.dst1) + (BITS ? ubase / 16 : 0),
+                                                           0, 0x7ffffff0, 0x00020000);
+            eforce[mb] = d1 ? 0u : 3u;
+            elane[mb] = (lvox * cd + hb * 16) * 2;
+            ecd2[mb] = cd * 2;
+        }
+        const unsigned relu_min = p.relu ? 0u : 0x80008000u;   // per 16-bit half: 0, or the most negative integer (no clamp)
+        uint32_t eob[C::MB][8];
+        unsigned ezb[C::MB];
+        int evoff[C::MB];
+        auto emit_step = [&](int nb, int mb, int i) __attribute__((always_inline)) {
+            if (i == 0) asm volatile("" : "+a"(acc[nb][mb]));
+            uint32_t o = pack2bf(acc[nb][mb][2 * i], acc[nb][mb][2 * i + 1]);
+            o = __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2_t, o), __builtin_bit_cast(s16x2_t, relu_min)));
+            if constexpr (OMASK == 2) {
+                const unsigned kk = ((mkb[nb][mb] >> (2 * i)) & 3u) | eforce[mb];
+                const u16x2_t keep = __builtin_bit_cast(u16x2_t, (kk | (kk << 15)) & 0x00010001u);
+                o = __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2_t, o) * keep);
+            }
+            if constexpr (BITS) ezb[mb] = i == 0 ? pair_positive_pk(o) : (ezb[mb] | (pair_positive_pk(o) << i));
+            eob[mb][i] = o;
+            if (i == 3) {
+                const int bw = (nb % PPL) % C::PW, bh = (nb % PPL) / C::PW, bd = wv * WPL + nb / PPL;
+                const bool inb = bd < dlim && bh * 4 + lrow < hlim && bw * 8 + lcol < wlim;
+                evoff[mb] = inb ? elane[mb] : -1;
+                const int soff = ((bd * p.H + bh * 4) * p.W + bw * 8) * ecd2[mb];   // wave-uniform: the patch's first voxel
+                __builtin_amdgcn_raw_buffer_store_b128(u32x4{eob[mb][0], eob[mb][1], eob[mb][2], eob[mb][3]}, ersrc[mb], evoff[mb], soff, 0);
+            }
+            if (i == 7) {
+                const int bw = (nb % PPL) % C::PW, bh = (nb % PPL) / C::PW, bd = wv * WPL + nb / PPL;
+                const int soff = ((bd * p.H + bh * 4) * p.W + bw * 8) * ecd2[mb];
+                __builtin_amdgcn_raw_buffer_store_b128(u32x4{eob[mb][4], eob[mb][5], eob[mb][6], eob[mb][7]}, ersrc[mb], evoff[mb], soff + 16, 0);
+                if constexpr (BITS) {
+                    unsigned z = ezb[mb];   // even elements in bits 0..7, odd ones in bits 16..23 (see relu_bits16)
+                    z = (z | (z << 4)) & 0x0F0F0F0Fu;
+                    z = (z | (z << 2)) & 0x33333333u;
+                    z = (z | (z << 1)) & 0x55555555u;
+                    z = (z | (z >> 15)) & 0xffffu;
+                    // word of the lane's 16 channels: element offset / 16 words of 2 bytes = byte offset / 16
+                    __builtin_amdgcn_raw_buffer_store_b16((short)z, ebrsrc[mb], evoff[mb] < 0 ? -1 : evoff[mb] / 16, soff / 16, 0);
+                }
+            }
         };
 
         // One stage = 9 taps of one depth plane of one 16-channel chunk.  FINAL marks the last
@@ -721,10 +784,75 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
                     if (i % SP == 0 && i / SP < NOPS) issue_op(ss, i / SP, gtag);
                     __builtin_amdgcn_sched_barrier(0);
                 }
+            } else if constexpr (OMASK != 1) {
+                // The first T0 taps run tap-major like every other stage.  The remaining taps run
+                // patch-major with their weight fragments held in registers: a patch is complete
+                // after them, and the blocks of the previous patch are converted and stored, one
+                // step behind each matrix instruction, while the next patch is multiplied.  (A
+                // wave issues in order: with all nine taps patch-major the weight fragments were
+                // re-read for every patch and the stage took 2.4 times as long as the others.)
+                constexpr int T0 = 4, T1 = 9 - T0;
+                static_assert(T1 <= T0 * C::NBW, "the register-resident fragments are read during the tap-major part");
+                bf16x8 bq[4], aq[2][C::MB], af[T1][C::MB];
+                auto ldb2 = [&](int j) __attribute__((always_inline)) {   // j: item of the combined order
+                    if (j < T0 * C::NBW) return ldb(j / C::NBW, j % C::NBW);
+                    const int r = j - T0 * C::NBW;
+                    return ldb(T0 + r % T1, r / T1);
+                };
+                constexpr int NJ = 9 * C::NBW;
+#pragma unroll
+                for (int mb = 0; mb < C::MB; ++mb) aq[0][mb] = lda(0, mb);
+#pragma unroll
+                for (int j = 0; j < PD; ++j) bq[j] = ldb2(j);
+#pragma unroll
+                for (int j = 0; j < NJ; ++j) {
+                    if (j + PD < NJ) bq[(j + PD) & 3] = ldb2(j + PD);
+                    if (j < T0 * C::NBW) {
+                        const int tl = j / C::NBW, nb = j % C::NBW;
+                        if (nb == 0 && tl + 1 < T0) {
+#pragma unroll
+                            for (int mb = 0; mb < C::MB; ++mb) aq[(tl + 1) & 1][mb] = lda(tl + 1, mb);
+                        }
+                        // the fragments of the patch-major taps, one tap per item at the end of this part
+                        if (j >= T0 * C::NBW - T1) {
+#pragma unroll
+                            for (int mb = 0; mb < C::MB; ++mb) af[j - (T0 * C::NBW - T1)][mb] = lda(T0 + j - (T0 * C::NBW - T1), mb);
+                        }
+#pragma unroll
+                        for (int mb = 0; mb < C::MB; ++mb)
+                            acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aq[tl & 1][mb], bq[j & 3], acc[nb][mb], 0, 0, 0);
+                        if (j % SP == 0 && j / SP < NOPS) issue_op(ss, j / SP, gtag);
+                        __builtin_amdgcn_sched_barrier(0);
+                    } else {
+                        const int r = j - T0 * C::NBW, nb = r / T1, t = r % T1;
+#pragma unroll
+                        for (int mb = 0; mb < C::MB; ++mb) {
+                            acc[nb][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(af[t][mb], bq[j & 3], acc[nb][mb], 0, 0, 0);
+                            // steps of the previous patch's blocks: block mb2 takes steps behind the
+                            // matrix instructions e = t * MB + mb with e / 8 == mb2 (MB = 2: e = 0..9,
+                            // block 0 behind 0..7; block 1 behind 8, 9 and the rest doubled up)
+                            if (nb > 0) {
+                                constexpr int NE = T1 * C::MB;           // matrix instructions per patch
+                                constexpr int NS = 8 * C::MB;            // emit steps per patch
+                                const int e = t * C::MB + mb;
+#pragma unroll
+                                for (int q = e * NS / NE; q < (e + 1) * NS / NE; ++q) emit_step(nb - 1, q / 8, q % 8);
+                            }
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                        if (j % SP == 0 && j / SP < NOPS) issue_op(ss, j / SP, gtag);
+                    }
+                }
+#pragma unroll
+                for (int mb = 0; mb < C::MB; ++mb) {
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) emit_step(C::NBW - 1, mb, e);
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             } else {
-                // patch-major order: a patch is complete after its 9 taps, and its blocks are
-                // converted and stored between the matrix instructions of the next patch (the
-                // weight fragments are re-read per patch; this is one stage in 3 * nkc)
+                // (mask given as the bf16 tensor, waited for by count) patch-major order: a patch is
+                // complete after its 9 taps, and its blocks are converted and stored between the
+                // matrix instructions of the next patch (the weight fragments are re-read per patch)
                 constexpr int PF = 2, RF = PF + 1;   // read-ahead and ring size of this stage
                 bf16x8 bq[RF], aq[RF][C::MB];
 #pragma unroll
@@ -779,7 +907,11 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
             // The next stage needs its weights, issued first in this stage; the halo thirds issued
             // after them are not read before the next chunk starts, so after the first two stages
             // of a chunk they may stay in flight (copies complete in issue order).
+            // The last stage of a tile need not wait for its own stores: behind its last copy the
+            // wave issued at least two stores per block of the patches stored after that copy (all
+            // patches when the copies end inside the tap-major part, else the last patch).
             if constexpr (g < 2) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(C::XG_WAVE) : "memory");
+            else if constexpr (FINAL && OMASK != 1) wait_vm((NOPS - 1) * SP < 4 * C::NBW ? 2 * C::MB * C::NBW : 2 * C::MB);
             else asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
             wpar ^= 1;
@@ -890,7 +1022,7 @@ struct ZsSlotTable {
 };
 static __device__ const ZsSlotTable g_zs_slots = ZsSlotTable();
 
-template <int OMASK>   // 0: no output mask, 2: one bit per element
+template <int OMASK, bool BITS>   // OMASK 0: no output mask, 2: one bit per element; BITS: the output's bit mask is written
 __global__ __launch_bounds__(256, 1) void conv_mfma_zs_kernel(MfmaParams p)
 {
     typedef ZsCfg C;
@@ -1082,11 +1214,11 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_zs_kernel(MfmaParams p)
         __amdgpu_buffer_rsrc_t orsrc = __builtin_amdgcn_make_buffer_rsrc((d1 ? p.dst1 : p.dst2) + ubase, 0, 0x7ffffff0, 0x00020000);
         const int obase = inhw ? (lvox * cd + hb * 16) * 2 : -1;
         const int oplane = p.H * p.W * cd * 2;
-        // bit words (16 channels each): written (forward) or read (masked backward-data)
-        const bool wbits = OMASK == 0 && p.bits_out != nullptr && d1;
+        // bit words (16 channels each): written (forward: one destination) or read (masked backward-data)
         __amdgpu_buffer_rsrc_t brsrc = __builtin_amdgcn_make_buffer_rsrc(
-            (OMASK == 0 ? (p.bits_out ? p.bits_out : (unsigned short *)p.dst1) : (unsigned short *)p.omask_bits) + (d1 ? ubase / 16 : 0),
+            (BITS ? p.bits_out : OMASK == 2 ? (unsigned short *)p.omask_bits : (unsigned short *)p.dst1) + ((BITS || OMASK == 2) && d1 ? ubase / 16 : 0),
             0, 0x7ffffff0, 0x00020000);
+        const unsigned force = d1 ? 0u : 3u;   // OMASK == 2: a block of the unmasked second destination keeps both halves
         const int bbase = inhw ? (lvox * (cd / 16) + hb) * 2 : -1;
         const int bplane = p.H * p.W * (cd / 16) * 2;
 
@@ -1099,24 +1231,20 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_zs_kernel(MfmaParams p)
             const float v0 = fmaxf(acc[d][2 * i], relu_floor), v1 = fmaxf(acc[d][2 * i + 1], relu_floor);
             uint32_t o = pack2bf(v0, v1);
             if constexpr (OMASK == 2) {
-                if (d1) {
-                    const unsigned kk = (mkb[d] >> (2 * i)) & 3u;
-                    const u16x2_t keep = __builtin_bit_cast(u16x2_t, (kk | (kk << 15)) & 0x00010001u);
-                    o = __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2_t, o) * keep);
-                }
+                const unsigned kk = ((mkb[d] >> (2 * i)) & 3u) | force;
+                const u16x2_t keep = __builtin_bit_cast(u16x2_t, (kk | (kk << 15)) & 0x00010001u);
+                o = __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2_t, o) * keep);
             }
             ob[i] = o;
         };
         auto emit_aux = [&](int d, int i) __attribute__((always_inline)) {
-            if constexpr (OMASK == 0) {
-                if (wbits) zb = i == 0 ? bf16_pair_positive(ob[i]) : (zb | (bf16_pair_positive(ob[i]) << i));
-            }
+            if constexpr (BITS) zb = i == 0 ? pair_positive_pk(ob[i]) : (zb | (pair_positive_pk(ob[i]) << i));
             if (i == 3 || i == 7) {
                 const int voff = d < dlim ? obase : -1;
                 if (i == 3) __builtin_amdgcn_raw_buffer_store_b128(u32x4{ob[0], ob[1], ob[2], ob[3]}, orsrc, voff, d * oplane, 0);
                 else __builtin_amdgcn_raw_buffer_store_b128(u32x4{ob[4], ob[5], ob[6], ob[7]}, orsrc, voff, d * oplane + 16, 0);
-                if constexpr (OMASK == 0) {
-                    if (i == 7 && wbits) {
+                if constexpr (BITS) {
+                    if (i == 7) {
                         unsigned z = zb;   // even elements in bits 0..7, odd ones in bits 16..23 (see relu_bits16)
                         z = (z | (z << 4)) & 0x0F0F0F0Fu;
                         z = (z | (z << 2)) & 0x33333333u;
@@ -1275,15 +1403,18 @@ static int launch_zs(MfmaParams p, int64_t mblocks, hipStream_t st)
     if (p.per_xcd * 8 > 0x7fffffffLL) return K3_E_UNSUPPORTED;
     static bool attr_done = false;
     if (!attr_done) {
-        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<0>),
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<0, false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
-        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<2>),
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<0, true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<2, false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
         attr_done = true;
     }
     int64_t grid = p.per_xcd * 8 < 256 ? p.per_xcd * 8 : 256;
-    if (p.omask_bits) conv_mfma_zs_kernel<2><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
-    else conv_mfma_zs_kernel<0><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    if (p.omask_bits) conv_mfma_zs_kernel<2, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    else if (p.bits_out) conv_mfma_zs_kernel<0, true><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    else conv_mfma_zs_kernel<0, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
     K3_LAUNCH_CHECK();
     return K3_OK;
 }
@@ -1300,19 +1431,22 @@ static int launch_pipe(MfmaParams p, int64_t mblocks, hipStream_t st)
     if (p.per_xcd * 8 > 0x7fffffffLL) return K3_E_UNSUPPORTED;
     static bool attr_done = false;
     if (!attr_done) {
-        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, 0>),
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, 0, false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
-        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, 1>),
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, 0, true>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
-        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, 2>),
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, 1, false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_pipe_kernel<C, 2, false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
         attr_done = true;
     }
     // persistent workgroups, one per CU (fewer when there is less work); a multiple of 8
     int64_t grid = p.per_xcd * 8 < 256 ? p.per_xcd * 8 : 256;
-    if (p.omask_bits) conv_mfma_pipe_kernel<C, 2><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
-    else if (p.omask) conv_mfma_pipe_kernel<C, 1><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
-    else conv_mfma_pipe_kernel<C, 0><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    if (p.omask_bits) conv_mfma_pipe_kernel<C, 2, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    else if (p.omask) conv_mfma_pipe_kernel<C, 1, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    else if (p.bits_out) conv_mfma_pipe_kernel<C, 0, true><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    else conv_mfma_pipe_kernel<C, 0, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
     K3_LAUNCH_CHECK();
     return K3_OK;
 }
