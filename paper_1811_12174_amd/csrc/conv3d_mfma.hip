@@ -419,19 +419,24 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_pipe_kernel(MfmaParams p)
         t.d0 = tdi * C::TD; t.h0 = thi * C::TH; t.w0 = twi * C::TW;
         t.mb0 = cg * C::MB;
         t.origin = (((int64_t)t.n * p.D + t.d0) * p.H + t.h0) * p.W + t.w0;
-        // a halo coordinate l is inside the volume iff 0 <= t0 + l - 1 < size, i.e. lo <= l < hi
-        const int dlo = 1 - t.d0, dhi = p.D + 1 - t.d0, hlo = 1 - t.h0, hhi = p.H + 1 - t.h0;
-        const int wlo = 1 - t.w0, whi = p.W + 1 - t.w0;
-        unsigned vm = 0;
+        // A halo coordinate l is inside the volume iff 0 <= t0 + l - 1 < size, i.e. lo <= l < hi.
+        // Separable: one scalar word per axis with bit l set where l lies outside, then three
+        // shifts per slot.
+        auto axis_out = [](int t0, int n, int ext) __attribute__((always_inline)) {
+            int lo = 1 - t0, hi = n + 1 - t0;
+            if (lo < 0) lo = 0;
+            if (hi > ext) hi = ext;
+            return ~(((1u << hi) - 1u) & ~((1u << lo) - 1u));
+        };
+        const unsigned od = axis_out(t.d0, p.D, C::HD), oh = axis_out(t.h0, p.H, C::HH), ow = axis_out(t.w0, p.W, C::HW);
+        unsigned nv = 0;
 #pragma unroll
         for (int idx = 0; idx < 3 * C::XG_WAVE; ++idx) {
-            int cw = coords[idx];
-            asm volatile("" : "+v"(cw));
-            const int ld = cw & 255, lh = (cw >> 8) & 255, lw = cw >> 16;
-            const bool in = ld >= dlo && ld < dhi && lh >= hlo && lh < hhi && lw >= wlo && lw < whi;
-            vm |= (in ? 1u : 0u) << idx;
+            const int cw = coords[idx];
+            const unsigned ld = cw & 255, lh = (cw >> 8) & 255, lw = cw >> 16;
+            nv |= (((od >> ld) | (oh >> lh) | (ow >> lw)) & 1u) << idx;
         }
-        t.vmask = vm & smask;
+        t.vmask = ~nv & smask;
         return t;
     };
 
