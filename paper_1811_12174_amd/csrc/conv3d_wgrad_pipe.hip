@@ -192,6 +192,16 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
         tapoff[t] = lane_x + (((tap / 3) % 3) * HW + tap % 3) * 64;
     }
 
+    // LDS offset of tap t's fragment when x plane i sits at ring position xb (one output block:
+    // kept as a table; with two blocks the registers are needed elsewhere)
+    int xatab[COBN == 1 ? NXB : 1][7];
+    if constexpr (COBN == 1) {
+#pragma unroll
+        for (int xb = 0; xb < NXB; ++xb)
+#pragma unroll
+            for (int t = 0; t < 7; ++t) xatab[xb][t] = ((xb + tapkd[t]) % NXB) * XP_BYTES + tapoff[t];
+    }
+
     f32x16 acc[7][COBN];
 #pragma unroll
     for (int t = 0; t < 7; ++t)
@@ -298,27 +308,55 @@ __global__ __launch_bounds__(256, 1) void conv_wgrad_pipe_kernel(WgradPipeParams
         asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PF - 1) * OPS) : "memory");
         __syncthreads();
 
-        int xb = 0, gb = 0;   // ring buffers of x plane i and g plane i
-        for (int i = 0; i < n_run; ++i) {
-            int xn = xb + 2 + PF; if (xn >= NXB) xn -= NXB; if (xn >= NXB) xn -= NXB;
-            int gn = gb + PF; if (gn >= NGB) gn -= NGB;
-            const bool on = i + PF < n_run;
-            const PlaneSrc sx = x_plane(i + 2 + PF, xn, on), sg = g_plane(i + PF, gn, on);
-            int xa[7];
+        // The loop is unrolled over the x ring, so the ring position of x plane i is a constant in
+        // each body (the taps' LDS offsets come from a table made once); the sources of the planes a
+        // stage fetches advance by one plane per stage.  With a short stage (the KS variant has 28
+        // MFMAs) the scalar bookkeeping of a stage otherwise outweighs its matrix work.
+        int gb = 0, i = 0;   // ring buffer of g plane i; stage
+        int dnext = dlo + 1 + PF;                                  // depth index of the x plane that stage i fetches
+        const bf16_t *xnext = xsrc + (vox0 + dnext * plane - (p.W + 1)) * Cx + chx;
+        const bf16_t *gnext = p.dy + (vox0 + (dlo + PF) * plane) * p.cout;
+        const int64_t xstep = plane * Cx, gstep = plane * p.cout;
+        bool more = n_run > 0;
+        while (more) {
 #pragma unroll
-            for (int t = 0; t < 7; ++t) {
-                int bsel = xb + tapkd[t]; if (bsel >= NXB) bsel -= NXB;
-                xa[t] = bsel * XP_BYTES + tapoff[t];
+            for (int xb = 0; xb < NXB; ++xb) {
+                const int xn = (xb + 2 + PF) % NXB;
+                int gn = gb + PF; if (gn >= NGB) gn -= NGB;
+                const bool on = i + PF < n_run;
+                PlaneSrc sx, sg;
+                sx.rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(xnext), 0, (on && dnext >= 0 && dnext < p.D) ? 0x7ffffff0 : 0, 0x00020000);
+                sx.lds = lds0 + XOFF + xn * XP_BYTES + wv * 1024;
+                sx.on = on;
+                sg.rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(gnext), 0, on ? 0x7ffffff0 : 0, 0x00020000);
+                sg.lds = lds0 + GOFF + gn * GBUF + wv * 1024;
+                sg.on = on;
+                int xa[7];
+#pragma unroll
+                for (int t = 0; t < 7; ++t) {
+                    if constexpr (COBN == 1) {
+                        xa[t] = xatab[xb][t];
+                    } else {
+                        int bsel = xb + tapkd[t]; if (bsel >= NXB) bsel -= NXB;
+                        xa[t] = bsel * XP_BYTES + tapoff[t];
+                    }
+                }
+                const int ga = lane_g + gb * GBUF;
+                wp_stage<COBN, NK, OPS>(acc, smem, xa, ga, ones, tg == 3, [&](int e) __attribute__((always_inline)) {
+                    if (e < XK) x_copy(sx, e);
+                    else g_copy(sg, e - XK);
+                });
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PF - 1) * OPS) : "memory");
+                __syncthreads();
+                if (++gb == NGB) gb = 0;
+                xnext += xstep;
+                gnext += gstep;
+                ++dnext;
+                if (++i >= n_run) {
+                    more = false;
+                    break;
+                }
             }
-            const int ga = lane_g + gb * GBUF;
-            wp_stage<COBN, NK, OPS>(acc, smem, xa, ga, ones, tg == 3, [&](int e) __attribute__((always_inline)) {
-                if (e < XK) x_copy(sx, e);
-                else g_copy(sg, e - XK);
-            });
-            asm volatile("s_waitcnt vmcnt(%0)" ::"n"((PF - 1) * OPS) : "memory");
-            __syncthreads();
-            if (++xb == NXB) xb = 0;
-            if (++gb == NGB) gb = 0;
         }
     }
 
