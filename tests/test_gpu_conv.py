@@ -26,6 +26,7 @@ FWD_CASES = [
     (3, 36, 44, 50, 32, 0, 32, "bf16"),    # plane-streaming kernel (32 output channels, a tile per CU and more): ragged on every axis
     (2, 32, 40, 48, 32, 32, 96, "bf16"),   # plane-streaming forward: two sources, four chunks, three output blocks
     (2, 32, 40, 48, 32, 64, 32, "bf16"),   # plane-streaming backward-data into two destinations (three blocks)
+    (3, 36, 44, 50, 64, 32, 32, "bf16"),   # sources of unequal width: the pipelined kernel with one block per workgroup, 8x8x16 tiles
 ]
 
 
