@@ -146,6 +146,8 @@ def bench_cfg2(args):
         "conv3d_fwd": time_calls(lambda: k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2), it, graph=gr),
         "conv3d_bwd_data": time_calls(lambda: k3.conv3d_bwd_data_bits(da2, None, w2, pk2, da1, a1bits), it, graph=gr),
         "conv3d_bwd_weight": time_calls(lambda: k3.conv3d_bwd_weight(a1, da2, None, dW2, db2, ws), it, graph=gr),
+        # (the fused convolution + pool call saves a launch but lengthens the convolution by as much: not used in the step)
+        "conv3d_fwd_pool": time_calls(lambda: k3.conv3d_fwd_pool(a1, w2, pk2, b2, 1, a2, p), it, graph=gr),
         "pool3d_fwd": time_calls(lambda: k3.pool3d_fwd(a2, p), it, graph=gr),
         "pool3d_bwd": time_calls(lambda: k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True), it, graph=gr),
     }
@@ -170,7 +172,7 @@ def bench_cfg2(args):
         "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms, 5), "higher_is_better": True,
         "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "cfg2: encoder block, 2x(conv3x3x3 32->32 + ReLU) + 2x2x2 max-pool, N=1, 64^3, fwd+bwd",
-                   "hip_graph": graph is not None, "conv_passes_per_step": 6, "flops_per_step": step_flops},
+                   "hip_graph": graph is not None, "launches_per_step": 10, "conv_passes_per_step": 6, "flops_per_step": step_flops},
         "pct_mfma_peak": round(100 * value / MFMA_BF16_PEAK_TFLOPS, 2),
         "voxels_per_s": round(N * S ** 3 / (ms * 1e-3), 1),
         "roofline": roofline,

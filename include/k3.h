@@ -90,6 +90,17 @@ int k3_conv3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *x2d, cons
                   const void *w, const void *packed, const float *bias, int relu,
                   const k3_tensor *yd, void *y, void *stream);
 
+/* k3_conv3d_fwd followed by the 2x2x2 max-pool of its output (the "convolution ... then
+ * max-pooling" pair that ends an encoder level, section 4.1): y receives the convolution
+ * output as k3_conv3d_fwd writes it, y_pooled (n, d/2, h/2, w/2, c; same dtype) what
+ * k3_pool3d_fwd would compute from y, bit for bit.  Where the convolution kernel that serves
+ * the shape can, the pooled planes leave with its output planes (one pass); otherwise the
+ * pooling kernel runs behind it on the same stream.  d, h, w must be even (K3_E_SHAPE).
+ * All pointers dev, caller-owned. */
+int k3_conv3d_fwd_pool(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2,
+                       const void *w, const void *packed, const float *bias, int relu,
+                       const k3_tensor *yd, void *y, const k3_tensor *pd, void *y_pooled, void *stream);
+
 /* Backward-data pass: with g = dy where y_mask > 0 else 0 (g = dy when y_mask is NULL),
  *   dx[n,d,h,w,ci] = sum_{kd,kh,kw,co} g[n,d-kd+1,h-kh+1,w-kw+1,co] * W[kd,kh,kw,ci,co].
  * y_mask is the stored forward output of the same layer (same shape and dtype as dy).

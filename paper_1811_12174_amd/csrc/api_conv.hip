@@ -12,7 +12,7 @@ using namespace k3;
 
 extern "C" {
 
-int k3_version(void) { return 101; }
+int k3_version(void) { return 102; }
 int k3_last_hip_error(void) { return g_last_hip_error; }
 
 const char *k3_status_string(int s)
@@ -70,7 +70,7 @@ static int fill_args(ConvArgs &a, const k3_tensor *xd, const k3_tensor *x2d, con
 
 static int conv_fwd_any(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2, const void *w,
                         const void *packed, const float *bias, int relu, const k3_tensor *yd, void *y, void *relu_bits,
-                        void *stream)
+                        void *stream, void *ypool = nullptr, bool *pooled = nullptr)
 {
     ConvArgs a;
     int rc = fill_args(a, xd, x2d, x2, yd);
@@ -78,10 +78,12 @@ static int conv_fwd_any(const k3_tensor *xd, const void *x, const k3_tensor *x2d
     if (!x || !w || !y) return K3_E_BADARG;
     if (relu_bits && a.cout % 16 != 0) return K3_E_UNSUPPORTED;
     a.x = x; a.x2 = x2; a.w = w; a.packed = packed; a.bias = bias; a.relu = relu ? 1 : 0; a.y = y; a.ybits = relu_bits;
+    a.ypool = ypool;
+    if (pooled) *pooled = false;
     hipStream_t st = (hipStream_t)stream;
     if (mfma_ok(a.dtype, a.c1, a.c2, a.cout)) {
         if (!packed) return K3_E_BADARG;
-        return conv_fwd_mfma(a, st);   // writes the bits itself (or runs the generic pass)
+        return conv_fwd_mfma(a, st, pooled);   // writes the bits itself (or runs the generic pass)
     }
     if (conv_first_ok(a.dtype, a.c1, a.c2, a.cout)) return conv_first_fwd(a, st);   // likewise
     rc = conv_fwd_direct(a, st);
@@ -93,6 +95,21 @@ int k3_conv3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *x2d, cons
                   const void *packed, const float *bias, int relu, const k3_tensor *yd, void *y, void *stream)
 {
     return conv_fwd_any(xd, x, x2d, x2, w, packed, bias, relu, yd, y, nullptr, stream);
+}
+
+int k3_conv3d_fwd_pool(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2, const void *w,
+                       const void *packed, const float *bias, int relu, const k3_tensor *yd, void *y,
+                       const k3_tensor *pd, void *y_pooled, void *stream)
+{
+    if (!desc_ok(yd) || !desc_ok(pd) || !y_pooled) return K3_E_BADARG;
+    if (yd->d % 2 || yd->h % 2 || yd->w % 2) return K3_E_SHAPE;
+    if (pd->n != yd->n || pd->d * 2 != yd->d || pd->h * 2 != yd->h || pd->w * 2 != yd->w || pd->c != yd->c ||
+        pd->dtype != yd->dtype)
+        return K3_E_SHAPE;
+    bool pooled = false;
+    int rc = conv_fwd_any(xd, x, x2d, x2, w, packed, bias, relu, yd, y, nullptr, stream, y_pooled, &pooled);
+    if (rc != K3_OK || pooled) return rc;
+    return k3_pool3d_fwd(yd, y, pd, y_pooled, stream);   // the convolution kernel that ran does not pool: a second pass
 }
 
 int k3_relu_bits_bytes(const k3_tensor *yd, size_t *bytes)

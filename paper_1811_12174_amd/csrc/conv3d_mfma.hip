@@ -75,6 +75,7 @@ struct MfmaParams {
     const bf16_t *omask;               // optional: dst1 is zeroed where omask (same shape) is <= 0
     const unsigned short *omask_bits;  // the same mask as one bit per element (word j of a voxel: channels 16j..16j+15)
     unsigned short *bits_out;          // optional: receives that bit mask of dst1 (set where the stored value is > 0)
+    bf16_t *pool_out;                  // optional (plane-streaming kernel, ReLU on): receives the 2x2x2 max-pool of dst1
     int cd1, cd2;                      // output channels per destination
     int N, D, H, W;
     int ntd, nth, ntw;                 // tiles per axis
@@ -1027,7 +1028,10 @@ struct ZsSlotTable {
 };
 static __device__ const ZsSlotTable g_zs_slots = ZsSlotTable();
 
-template <int OMASK, bool BITS>   // OMASK 0: no output mask, 2: one bit per element; BITS: the output's bit mask is written
+// OMASK 0: no output mask, 2: one bit per element; BITS: the output's bit mask is written; POOL: the
+// 2x2x2 max-pool of the output is written as well (ReLU on: the maxima are taken on the packed bf16
+// pairs as 16-bit integers, which order like the values only where these are not negative)
+template <int OMASK, bool BITS, bool POOL>
 __global__ __launch_bounds__(256, 1) void conv_mfma_zs_kernel(MfmaParams p)
 {
     typedef ZsCfg C;
@@ -1224,6 +1228,16 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_zs_kernel(MfmaParams p)
             (BITS ? p.bits_out : OMASK == 2 ? (unsigned short *)p.omask_bits : (unsigned short *)p.dst1) + ((BITS || OMASK == 2) && d1 ? ubase / 16 : 0),
             0, 0x7ffffff0, 0x00020000);
         const unsigned force = d1 ? 0u : 3u;   // OMASK == 2: a block of the unmasked second destination keeps both halves
+        // POOL: output planes 2k, 2k+1 give pooled plane k; the maximum over the 2x2 (h, w) window is
+        // taken across lanes (the lane's neighbours in w and h are lanes ^ 1 and ^ 8) and the lane
+        // with even h and w stores it
+        const int64_t porigin = ((((int64_t)cur.n * (p.D / 2) + cur.d0 / 2) * (p.H / 2) + cur.h0 / 2) * (p.W / 2) + cur.w0 / 2);
+        __amdgpu_buffer_rsrc_t prsrc = __builtin_amdgcn_make_buffer_rsrc((POOL ? p.pool_out : p.dst1) + (POOL ? porigin * cd + co0 : 0),
+                                                                         0, 0x7ffffff0, 0x00020000);
+        const bool pactive = inhw && !(lrow & 1) && !(lcol & 1);
+        const int pbase = pactive ? ((((bh * 4 + lrow) >> 1) * (p.W / 2) + ((bw * 8 + lcol) >> 1)) * cd + hb * 16) * 2 : -1;
+        const int pplane = (p.H / 2) * (p.W / 2) * cd * 2;
+        uint32_t obe[8], pb[8];
         const int bbase = inhw ? (lvox * (cd / 16) + hb) * 2 : -1;
         const int bplane = p.H * p.W * (cd / 16) * 2;
 
@@ -1241,6 +1255,19 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_zs_kernel(MfmaParams p)
                 o = __builtin_bit_cast(uint32_t, __builtin_bit_cast(u16x2_t, o) * keep);
             }
             ob[i] = o;
+            if constexpr (POOL) {
+                if (d % 2 == 0) {
+                    obe[i] = o;
+                } else {
+                    auto pkmax = [](uint32_t a, uint32_t b) __attribute__((always_inline)) {
+                        return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(s16x2_t, a), __builtin_bit_cast(s16x2_t, b)));
+                    };
+                    uint32_t m = pkmax(obe[i], o);
+                    m = pkmax(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0xB1, 0xf, 0xf, false));    // quad_perm [1,0,3,2]: lane ^ 1
+                    m = pkmax(m, (uint32_t)__builtin_amdgcn_update_dpp(0, (int)m, 0x128, 0xf, 0xf, false));   // row_ror 8: lane ^ 8
+                    pb[i] = m;
+                }
+            }
         };
         auto emit_aux = [&](int d, int i) __attribute__((always_inline)) {
             if constexpr (BITS) zb = i == 0 ? pair_positive_pk(ob[i]) : (zb | (pair_positive_pk(ob[i]) << i));
@@ -1248,6 +1275,13 @@ __global__ __launch_bounds__(256, 1) void conv_mfma_zs_kernel(MfmaParams p)
                 const int voff = d < dlim ? obase : -1;
                 if (i == 3) __builtin_amdgcn_raw_buffer_store_b128(u32x4{ob[0], ob[1], ob[2], ob[3]}, orsrc, voff, d * oplane, 0);
                 else __builtin_amdgcn_raw_buffer_store_b128(u32x4{ob[4], ob[5], ob[6], ob[7]}, orsrc, voff, d * oplane + 16, 0);
+                if constexpr (POOL) {
+                    if (d % 2 == 1) {
+                        const int pvoff = d < dlim ? pbase : -1;
+                        if (i == 3) __builtin_amdgcn_raw_buffer_store_b128(u32x4{pb[0], pb[1], pb[2], pb[3]}, prsrc, pvoff, (d / 2) * pplane, 0);
+                        else __builtin_amdgcn_raw_buffer_store_b128(u32x4{pb[4], pb[5], pb[6], pb[7]}, prsrc, pvoff, (d / 2) * pplane + 16, 0);
+                    }
+                }
                 if constexpr (BITS) {
                     if (i == 7) {
                         unsigned z = zb;   // even elements in bits 0..7, odd ones in bits 16..23 (see relu_bits16)
@@ -1408,18 +1442,21 @@ static int launch_zs(MfmaParams p, int64_t mblocks, hipStream_t st)
     if (p.per_xcd * 8 > 0x7fffffffLL) return K3_E_UNSUPPORTED;
     static bool attr_done = false;
     if (!attr_done) {
-        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<0, false>),
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<0, false, false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
-        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<0, true>),
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<0, true, false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
-        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<2, false>),
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<0, false, true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&conv_mfma_zs_kernel<2, false, false>),
                                    hipFuncAttributeMaxDynamicSharedMemorySize, C::LDS_BYTES));
         attr_done = true;
     }
     int64_t grid = p.per_xcd * 8 < 256 ? p.per_xcd * 8 : 256;
-    if (p.omask_bits) conv_mfma_zs_kernel<2, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
-    else if (p.bits_out) conv_mfma_zs_kernel<0, true><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
-    else conv_mfma_zs_kernel<0, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    if (p.omask_bits) conv_mfma_zs_kernel<2, false, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    else if (p.pool_out) conv_mfma_zs_kernel<0, false, true><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    else if (p.bits_out) conv_mfma_zs_kernel<0, true, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
+    else conv_mfma_zs_kernel<0, false, false><<<dim3((unsigned)grid), 256, C::LDS_BYTES, st>>>(p);
     K3_LAUNCH_CHECK();
     return K3_OK;
 }
@@ -1500,15 +1537,20 @@ static int mfma_variant(const MfmaParams &p, int64_t mblocks)
     return 0;
 }
 
+// the plane-streaming kernel serves the launch: one 32-channel block per workgroup on 8x8x16 tiles,
+// mask as bits or none, sources of equal channel counts
+static bool zs_serves(const MfmaParams &p, int64_t mblocks)
+{
+    return mfma_variant(p, mblocks) == 2 && !p.omask && (p.c2 == 0 || p.c2 == p.c1);
+}
+
 static int launch_mfma(MfmaParams p, int64_t mchannels, hipStream_t st)
 {
     int64_t mblocks = mchannels / 32;
     switch (mfma_variant(p, mblocks)) {
     case 1: return launch_pipe<PipeCfg<8, 8, 16, 2>>(p, mblocks, st);
     case 2: {
-        // the plane-streaming kernel: mask as bits or none, sources of equal channel counts
-        const bool zs = !p.omask && (p.c2 == 0 || p.c2 == p.c1);
-        if (zs) return launch_zs(p, mblocks, st);
+        if (zs_serves(p, mblocks)) return launch_zs(p, mblocks, st);
         return launch_pipe<PipeCfg<8, 8, 16, 1>>(p, mblocks, st);
     }
     case 3: return launch_pipe<PipeCfg<4, 8, 8, 2>>(p, mblocks, st);
@@ -1519,7 +1561,7 @@ static int launch_mfma(MfmaParams p, int64_t mchannels, hipStream_t st)
     return launch_cfg<TileCfg<8, 8, 8, 1, 27>>(p, mblocks, st);
 }
 
-int conv_fwd_mfma(const ConvArgs &a, hipStream_t st)
+int conv_fwd_mfma(const ConvArgs &a, hipStream_t st, bool *pooled)
 {
     MfmaParams p{};
     p.src1 = (const bf16_t *)a.x;
@@ -1539,6 +1581,10 @@ int conv_fwd_mfma(const ConvArgs &a, hipStream_t st)
     // small pass derives it from the stored tensor
     const bool native = mfma_variant(p, a.cout / 32) != 0;
     p.bits_out = native ? (unsigned short *)a.ybits : nullptr;
+    // the pooled output leaves with the plane-streaming kernel's output planes (ReLU on, even sizes, no bit mask asked for)
+    const bool pools = a.ypool && !a.ybits && a.relu && a.D % 2 == 0 && a.H % 2 == 0 && a.W % 2 == 0 && zs_serves(p, a.cout / 32);
+    p.pool_out = pools ? (bf16_t *)a.ypool : nullptr;
+    if (pooled) *pooled = pools;
     int rc = launch_mfma(p, a.cout, st);
     if (rc == K3_OK && a.ybits && !native) rc = launch_relu_bits(a.dtype, a.y, a.ybits, a.V() * a.cout / 16, st);
     return rc;

@@ -22,6 +22,7 @@ struct ConvArgs {
     const void *omask = nullptr;   // optional mask applied to dx (first destination) by the producer
     const void *omask_bits = nullptr;   // the same mask as one bit per element (alternative to omask)
     void *ybits = nullptr;              // optional: bit mask of the forward output (set where y > 0)
+    void *ypool = nullptr;              // optional: 2x2x2 max-pool of the forward output (the kernel may write it itself)
     int64_t V() const { return N * D * H * W; }
 };
 
@@ -38,7 +39,8 @@ size_t conv_wgrad_direct_ws_bytes(int64_t V, int64_t cin, int64_t cout);
 
 size_t conv_packed_bytes(int64_t cin, int64_t cout);
 int conv_pack_weights(const void *w, int64_t cin, int64_t cout, void *packed, hipStream_t st);
-int conv_fwd_mfma(const ConvArgs &a, hipStream_t st);
+// *pooled (when not null) reports whether the kernel wrote a.ypool itself
+int conv_fwd_mfma(const ConvArgs &a, hipStream_t st, bool *pooled = nullptr);
 int conv_dgrad_mfma(const ConvArgs &a, hipStream_t st);
 int conv_wgrad_mfma(const ConvArgs &a, float *dW, float *db, float *ws, hipStream_t st);
 size_t conv_wgrad_mfma_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout);

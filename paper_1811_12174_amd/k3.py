@@ -130,6 +130,12 @@ def conv3d_fwd_bits(x, w, packed, bias, relu, y, relu_bits, x2=None):
                                     _d(y), _p(y), _p(relu_bits), _stream()), "k3_conv3d_fwd_bits")
 
 
+def conv3d_fwd_pool(x, w, packed, bias, relu, y, y_pooled, x2=None):
+    """conv3d_fwd plus the 2x2x2 max-pool of its output into y_pooled."""
+    _check(lib().k3_conv3d_fwd_pool(_d(x), _p(x), _d(x2), _p(x2), _p(w), _p(packed), _p(bias), ctypes.c_int(int(relu)),
+                                    _d(y), _p(y), _d(y_pooled), _p(y_pooled), _stream()), "k3_conv3d_fwd_pool")
+
+
 def conv3d_bwd_data(dy, y_mask, w, packed, dx, dx2=None, dx_mask=None):
     _check(lib().k3_conv3d_bwd_data(_d(dy), _p(dy), _p(y_mask), _p(w), _p(packed), _d(dx), _p(dx), _d(dx2), _p(dx2),
                                     _p(dx_mask), _stream()), "k3_conv3d_bwd_data")

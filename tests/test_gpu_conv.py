@@ -246,3 +246,50 @@ def test_relu_bit_masks(orc, N, D, H, W, c1, c2, co):
         assert torch.equal(dxa, dxb)
         assert c2 == 0 or torch.equal(dx2a, dx2b)
         assert np.array_equal(to_f64(dxb), orc.apply_relu_bits(to_f64(dxb), mbits.cpu().numpy().view(np.uint16)))
+
+
+POOL_CASES = [
+    (3, 36, 44, 50, 32, 0, 32, "bf16", 1),    # plane-streaming kernel pools itself: ragged tiles, two tiles per workgroup
+    (2, 32, 40, 48, 32, 32, 96, "bf16", 1),   # ... two sources, three output blocks
+    (3, 36, 44, 50, 32, 0, 32, "bf16", 0),    # no ReLU: the pooling kernel runs behind the convolution
+    (1, 16, 16, 16, 32, 0, 32, "bf16", 1),    # small tiles: second pass
+    (1, 12, 20, 36, 32, 0, 64, "bf16", 1),    # two blocks per workgroup: second pass
+    (1, 16, 16, 16, 4, 0, 8, "f32", 1),       # direct kernels
+]
+
+
+@pytest.mark.parametrize("case", POOL_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_conv_fwd_pool(orc, case):
+    """The fused call writes exactly what the convolution followed by the pooling call writes, and
+    the pooled tensor is the oracle's pool of the stored output."""
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, to_f64, empty, packed_for
+    N, D, H, W, c1, c2, co, dt, relu = case
+    x, x2, w, b = _mk(case[:8], 40)
+    xd, wd, bd = to_dev(x, dt), to_dev(w, dt), torch.from_numpy(b).cuda()
+    x2d = to_dev(x2, dt) if c2 else None
+    pk = packed_for(wd)
+    y0, y1 = empty((N, D, H, W, co), dt), empty((N, D, H, W, co), dt)
+    p0, p1 = empty((N, D // 2, H // 2, W // 2, co), dt), empty((N, D // 2, H // 2, W // 2, co), dt)
+    y1.fill_(float("nan")); p1.fill_(float("nan"))
+    k3.conv3d_fwd(xd, wd, pk, bd, relu, y0, x2=x2d)
+    k3.pool3d_fwd(y0, p0)
+    k3.conv3d_fwd_pool(xd, wd, pk, bd, relu, y1, p1, x2=x2d)
+    torch.cuda.synchronize()
+    assert torch.equal(y0, y1)
+    assert torch.equal(p0, p1)
+    assert np.array_equal(to_f64(p1), orc.pool3d_fwd(to_f64(y1)))
+
+
+def test_conv_fwd_pool_rejects_odd_sizes():
+    import torch
+    from paper_1811_12174_amd import k3
+    x = torch.zeros((1, 6, 7, 8, 32), device="cuda", dtype=torch.bfloat16)
+    w = torch.zeros((3, 3, 3, 32, 32), device="cuda", dtype=torch.bfloat16)
+    from gpu_util import packed_for
+    y = torch.empty_like(x)
+    p = torch.empty((1, 3, 3, 4, 32), device="cuda", dtype=torch.bfloat16)
+    with pytest.raises(k3.K3Error) as e:
+        k3.conv3d_fwd_pool(x, w, packed_for(w), None, 1, y, p)
+    assert e.value.status == k3.E_SHAPE
