@@ -138,6 +138,7 @@ BIG_CASES = [
     (2, 44, 64, 64, 64, 64, 64),     # decoder conv1: two sources / two destinations, ragged depth
     (1, 64, 64, 64, 128, 0, 128),    # deeper level: four channel blocks, two channel groups
     (1, 66, 70, 72, 64, 0, 32),      # one output block per workgroup, ragged everywhere
+    (1, 128, 128, 128, 32, 0, 32),   # level 0 of the base-32 net: plane-streaming kernel, 8 tiles per workgroup; 32 planes per weight-gradient workgroup
     (1, 32, 32, 32, 128, 0, 128),    # deep level: 4x8x8 tiles, two output blocks per workgroup
     (1, 16, 16, 16, 256, 0, 256),    # bottleneck: 4x8x8 tiles, one output block per workgroup
     (1, 14, 20, 28, 64, 64, 128),    # 4x8x8 tiles, two sources / destinations, ragged
