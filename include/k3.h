@@ -130,7 +130,8 @@ int k3_conv3d_bwd_data_bits(const k3_tensor *dyd, const void *dy, const void *y_
                             const void *packed, const k3_tensor *dxd, void *dx, const k3_tensor *dx2d, void *dx2,
                             const void *dx_mask_bits, void *stream);
 
-/* Workspace bytes k3_conv3d_bwd_weight needs for these shapes (split-K partial sums). */
+/* Workspace bytes k3_conv3d_bwd_weight needs for these shapes (split-K partial sums; the
+ * larger of the call with and without y_mask). */
 int k3_conv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor *x2d,
                                          const k3_tensor *dyd, size_t *bytes);
 
@@ -142,6 +143,22 @@ int k3_conv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor *x
 int k3_conv3d_bwd_weight(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2,
                          const k3_tensor *dyd, const void *dy, const void *y_mask,
                          float *dW, float *db, void *ws, size_t ws_bytes, void *stream);
+
+/* k3_conv3d_bwd_weight for callers that cannot allocate device memory or pass a workspace
+ * (code under HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the
+ * split-K partial sums go to an array of K3_STATIC_SCRATCH_BYTES that is part of the library's
+ * device code, one copy per GPU, held until the process ends.  The call allocates nothing and
+ * frees nothing.  Same arguments, kernels and results (bit for bit) as k3_conv3d_bwd_weight
+ * without ws / ws_bytes; shapes whose partial sums exceed the array return K3_E_WORKSPACE and
+ * enqueue nothing (every bf16 shape with channel counts that are multiples of 32 and no y_mask
+ * fits, at any volume).  The array keeps the previous call's contents; nothing in it has to
+ * start at zero.  All calls on one GPU share it: calls that overlap on one GPU (different
+ * streams, or threads) race and must be serialised by the caller.  The device that is current
+ * at the call must be the one that owns the tensors and the stream. */
+#define K3_STATIC_SCRATCH_BYTES (64u << 20)
+int k3_conv3d_bwd_weight_static(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2,
+                                const k3_tensor *dyd, const void *dy, const void *y_mask,
+                                float *dW, float *db, void *stream);
 
 /* ------------------------------------------------------------------ 2x2x2 max pooling
  * The 2x2x2 max-pooling layer that follows the encoder convolutions (section 4.1):

@@ -2,6 +2,7 @@
 // between the MFMA implicit-GEMM kernels and the direct kernels.
 #include "common.h"
 #include "conv_internal.h"
+#include <mutex>
 
 namespace k3 {
 static thread_local int g_last_hip_error = 0;
@@ -9,6 +10,32 @@ void set_hip_error(hipError_t e) { g_last_hip_error = (int)e; }
 }  // namespace k3
 
 using namespace k3;
+
+// Split-K partial sums of k3_conv3d_bwd_weight_static: one array per GPU, part of the loaded
+// code object, held until the process ends.  In host code the name is only a handle for
+// hipGetSymbolAddress; kernels, and every other use, get the device address kept in g_scratch_ptr.
+static __device__ __align__(256) unsigned char scratch[K3_STATIC_SCRATCH_BYTES];
+
+static constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices];   // device address of `scratch` on each GPU, looked up once
+static std::mutex g_scratch_lock;
+
+// Address of the current device's copy of the array (each GPU has its own, at its own address).
+static int scratch_for_current_device(void **ptr)
+{
+    int dev = -1;
+    K3_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return K3_E_UNSUPPORTED;
+    std::lock_guard<std::mutex> g(g_scratch_lock);
+    if (!g_scratch_ptr[dev]) {
+        void *p = nullptr;
+        K3_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) return K3_E_HIP;
+        g_scratch_ptr[dev] = p;
+    }
+    *ptr = g_scratch_ptr[dev];
+    return K3_OK;
+}
 
 extern "C" {
 
@@ -179,22 +206,55 @@ int k3_conv3d_bwd_weight_workspace_bytes(const k3_tensor *xd, const k3_tensor *x
     return K3_OK;
 }
 
-int k3_conv3d_bwd_weight(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2,
-                         const k3_tensor *dyd, const void *dy, const void *y_mask, float *dW, float *db, void *ws,
-                         size_t ws_bytes, void *stream)
+// Partial-sum bytes of the kernel a backward-weight call with these shapes runs on; the size
+// query of the boundary reports the larger of the masked and the unmasked case.
+static size_t bwd_weight_need(const k3_tensor *xd, const k3_tensor *x2d, const k3_tensor *dyd, bool masked)
+{
+    const int64_t c1 = xd->c, c2 = x2d ? x2d->c : 0;
+    if (mfma_ok(xd->dtype, c1, c2, dyd->c))
+        return conv_wgrad_mfma_ws_bytes_for(xd->n, xd->d, xd->h, xd->w, c1 + c2, dyd->c, masked);
+    if (conv_first_ok(xd->dtype, c1, c2, dyd->c)) return conv_first_wgrad_ws_bytes(xd->n, xd->d, xd->h, xd->w, dyd->c);
+    return conv_wgrad_direct_ws_bytes(voxels(xd), c1 + c2, dyd->c);
+}
+
+// Validation and dispatch shared by the two backward-weight entry points.
+static int bwd_weight_run(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2, const k3_tensor *dyd,
+                          const void *dy, const void *y_mask, float *dW, float *db, void *ws, size_t ws_bytes,
+                          void *stream)
 {
     ConvArgs a;
     int rc = fill_args(a, xd, x2d, x2, dyd);
     if (rc != K3_OK) return rc;
     if (!x || !dy || !dW || !ws) return K3_E_BADARG;
-    size_t need = 0;
-    rc = k3_conv3d_bwd_weight_workspace_bytes(xd, x2d, dyd, &need);
-    if (rc != K3_OK) return rc;
-    if (ws_bytes < need) return K3_E_WORKSPACE;
+    if (ws_bytes < bwd_weight_need(xd, x2d, dyd, y_mask != nullptr)) return K3_E_WORKSPACE;
     a.x = x; a.x2 = x2; a.dy = dy; a.ymask = y_mask;
     if (mfma_ok(a.dtype, a.c1, a.c2, a.cout)) return conv_wgrad_mfma(a, dW, db, (float *)ws, (hipStream_t)stream);
     if (conv_first_ok(a.dtype, a.c1, a.c2, a.cout)) return conv_first_wgrad(a, dW, db, (float *)ws, (hipStream_t)stream);
     return conv_wgrad_direct(a, dW, db, (float *)ws, (hipStream_t)stream);
+}
+
+int k3_conv3d_bwd_weight(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2,
+                         const k3_tensor *dyd, const void *dy, const void *y_mask, float *dW, float *db, void *ws,
+                         size_t ws_bytes, void *stream)
+{
+    return bwd_weight_run(xd, x, x2d, x2, dyd, dy, y_mask, dW, db, ws, ws_bytes, stream);
+}
+
+int k3_conv3d_bwd_weight_static(const k3_tensor *xd, const void *x, const k3_tensor *x2d, const void *x2,
+                                const k3_tensor *dyd, const void *dy, const void *y_mask, float *dW, float *db,
+                                void *stream)
+{
+    // shapes whose partial sums do not fit the array are refused before anything is looked up or launched
+    size_t any = 0;
+    int rc = k3_conv3d_bwd_weight_workspace_bytes(xd, x2d, dyd, &any);   // validates the descriptors
+    if (rc != K3_OK) return rc;
+    if (bwd_weight_need(xd, x2d, dyd, y_mask != nullptr) > (size_t)K3_STATIC_SCRATCH_BYTES) return K3_E_WORKSPACE;
+    void *ws = nullptr;
+    rc = scratch_for_current_device(&ws);
+    if (rc != K3_OK) return rc;
+    // every partial sum the reduction pass reads is written by this call's own first kernel, so
+    // what an earlier call left in the array needs no clearing
+    return bwd_weight_run(xd, x, x2d, x2, dyd, dy, y_mask, dW, db, ws, (size_t)K3_STATIC_SCRATCH_BYTES, stream);
 }
 
 }  // extern "C"

@@ -190,13 +190,20 @@ static void wgrad_plan(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, 
 
 size_t conv_wgrad_mfma_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout)
 {
+    // either kernel may run (the pipelined one takes no ReLU mask): size for both
+    const size_t a = conv_wgrad_mfma_ws_bytes_for(N, D, H, W, cin, cout, true);
+    const size_t b = conv_wgrad_mfma_ws_bytes_for(N, D, H, W, cin, cout, false);
+    return a > b ? a : b;
+}
+
+// What the kernel that conv_wgrad_mfma picks for a call with / without a ReLU mask writes.
+size_t conv_wgrad_mfma_ws_bytes_for(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout, bool masked)
+{
+    if (!masked && conv_wgrad_pipe_ok(N, D, H, W, cin, cout)) return conv_wgrad_pipe_ws_bytes(N, D, H, W, cin, cout);
     int cobn, nsplit;
     int64_t ntiles;
     wgrad_plan(N, D, H, W, cin, cout, &cobn, &ntiles, &nsplit);
-    // either kernel may run (the pipelined one takes no ReLU mask): size for both
-    size_t need = (size_t)nsplit * (size_t)(27 * cin * cout + cout) * sizeof(float);
-    size_t pipe = conv_wgrad_pipe_ok(N, D, H, W, cin, cout) ? conv_wgrad_pipe_ws_bytes(N, D, H, W, cin, cout) : 0;
-    return need > pipe ? need : pipe;
+    return (size_t)nsplit * (size_t)(27 * cin * cout + cout) * sizeof(float);
 }
 
 template <int COBN>

@@ -44,6 +44,7 @@ int conv_fwd_mfma(const ConvArgs &a, hipStream_t st, bool *pooled = nullptr);
 int conv_dgrad_mfma(const ConvArgs &a, hipStream_t st);
 int conv_wgrad_mfma(const ConvArgs &a, float *dW, float *db, float *ws, hipStream_t st);
 size_t conv_wgrad_mfma_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout);
+size_t conv_wgrad_mfma_ws_bytes_for(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout, bool masked);
 
 bool conv_wgrad_pipe_ok(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout);
 size_t conv_wgrad_pipe_ws_bytes(int64_t N, int64_t D, int64_t H, int64_t W, int64_t cin, int64_t cout);

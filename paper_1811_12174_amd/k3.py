@@ -160,6 +160,15 @@ def conv3d_bwd_weight(x, dy, y_mask, dW, db, ws, x2=None):
            "k3_conv3d_bwd_weight")
 
 
+STATIC_SCRATCH_BYTES = 64 << 20
+
+
+def conv3d_bwd_weight_static(x, dy, y_mask, dW, db, x2=None):
+    """conv3d_bwd_weight whose partial sums go to the library's own static device array (allocates nothing)."""
+    _check(lib().k3_conv3d_bwd_weight_static(_d(x), _p(x), _d(x2), _p(x2), _d(dy), _p(dy), _p(y_mask), _p(dW), _p(db),
+                                             _stream()), "k3_conv3d_bwd_weight_static")
+
+
 # ------------------------------------------------------------------ pooling
 def pool3d_fwd(x, y):
     _check(lib().k3_pool3d_fwd(_d(x), _p(x), _d(y), _p(y), _stream()), "k3_pool3d_fwd")
