@@ -134,6 +134,16 @@ def bench_cfg2(args):
         run()
     torch.cuda.synchronize()
     ms = (time.perf_counter() - t0) * 1e3 / args.steps
+    # the same K steps timed REPEATS more times: how much one box scatters (the value above is the first timing)
+    rep = [ms]
+    for _ in range(args.repeats):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            run()
+        torch.cuda.synchronize()
+        rep.append((time.perf_counter() - t0) * 1e3 / args.steps)
+    rep.sort()
 
     f1 = conv_flops(N, S, S, S, C, C)
     step_flops = 6 * f1
@@ -175,6 +185,8 @@ def bench_cfg2(args):
                    "hip_graph": graph is not None, "launches_per_step": 10, "conv_passes_per_step": 6, "flops_per_step": step_flops},
         "pct_mfma_peak": round(100 * value / MFMA_BF16_PEAK_TFLOPS, 2),
         "voxels_per_s": round(N * S ** 3 / (ms * 1e-3), 1),
+        "ms_per_step_spread": {"repeats": len(rep), "min": round(rep[0], 5), "median": round(rep[len(rep) // 2], 5),
+                               "max": round(rep[-1], 5)},
         "roofline": roofline,
         "call_ms": {k: round(v, 5) for k, v in kern.items()},
         "call_tflops": {k: round(f1 / (kern[k] * 1e-3) / 1e12, 2) for k in ("conv3d_fwd", "conv3d_bwd_data", "conv3d_bwd_weight")},
@@ -229,6 +241,94 @@ def cpu_baseline_cfg2(step_flops):
                              "sample": f"one conv3d_fwd pass, 1 x {S // 2}^3, {C}->{C}"}
     except OSError:
         pass
+    return out
+
+
+def measure_peaks():
+    """The two machine rates of this very box: the register-resident bf16 MFMA loop (what the
+    matrix cores sustain at the clock the chip holds under full matrix load) and a plain device
+    copy (what a streaming kernel gets from HBM, bytes read + written).  Best of five launches."""
+    import torch
+    from paper_1811_12174_amd import k3
+    blocks = 256 * 8
+    sink = torch.empty(blocks * 256, device="cuda", dtype=torch.float32)
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    k3.probe_mfma_bf16(200, blocks, sink)
+    best = 0.0
+    for _ in range(5):
+        e0.record()
+        fl = k3.probe_mfma_bf16(20000, blocks, sink)
+        e1.record()
+        e1.synchronize()
+        best = max(best, fl / (e0.elapsed_time(e1) * 1e-3) / 1e12)
+    src = torch.ones(1 << 30, device="cuda", dtype=torch.uint8)
+    dst = torch.empty_like(src)
+    k3.probe_copy(src, dst, 4096)
+    copy = 0.0
+    for grid in (1024, 2048, 4096, 8192, 1024):   # the best launch shape differs a little between boxes
+        e0.record()
+        k3.probe_copy(src, dst, grid)
+        e1.record()
+        e1.synchronize()
+        copy = max(copy, 2.0 * src.numel() / (e0.elapsed_time(e1) * 1e-3) / 1e9)
+    return {"mfma_bf16_tflops": round(best, 1), "mfma_pct_of_nominal": round(100 * best / MFMA_BF16_PEAK_TFLOPS, 1),
+            "hbm_copy_gbs": round(copy, 1), "hbm_pct_of_nominal": round(100 * copy / HBM_PEAK_GBS, 1),
+            "how": "register-resident 32x32x16 bf16 MFMA loop, 2048 workgroups x 4 waves; 1 GiB grid-stride device copy (read + write)"}
+
+
+def bench_layers(args, mfma_measured):
+    """Single 3x3x3 layers at the shapes that carry the base-64 U-Net step (cfg4 / cfg5) and the
+    base-32 level 0 (cfg3): per launch time, TFLOP/s over the exact in-bounds FLOPs, fraction of
+    the nominal and of the measured matrix-core peak.  Launches are captured in a HIP graph."""
+    import torch
+    import synth
+    from paper_1811_12174_amd import k3
+    bf = torch.bfloat16
+    out = []
+    for (n, s, c) in ((2, 128, 64), (2, 64, 128), (1, 128, 32)):
+        x = torch.from_numpy(synth.activations(11, (n, s, s, s, c), "bf16")).cuda().to(bf)
+        g = torch.from_numpy(synth.activations(12, (n, s, s, s, c), "bf16")).cuda().to(bf)
+        w = torch.from_numpy(synth.conv_weights(13, c, c, "bf16")).cuda().to(bf)
+        b = torch.zeros(c, device="cuda")
+        pk = torch.empty(k3.conv3d_packed_bytes(c, c, k3.BF16), device="cuda", dtype=torch.uint8)
+        k3.conv3d_pack_weights(w, pk)
+        y, dx = torch.empty_like(x), torch.empty_like(x)
+        dW, db = torch.empty((3, 3, 3, c, c), device="cuda"), torch.empty(c, device="cuda")
+        ws = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(x, g), device="cuda", dtype=torch.uint8)
+        fl = conv_flops(n, s, s, s, c, c)
+        it = 10 if n * s ** 3 * c > (1 << 26) else 20
+        ms = {"fwd": time_calls(lambda: k3.conv3d_fwd(x, w, pk, b, 1, y), it, graph=True),
+              "dgrad": time_calls(lambda: k3.conv3d_bwd_data(g, None, w, pk, dx), it, graph=True),
+              "wgrad": time_calls(lambda: k3.conv3d_bwd_weight(x, g, None, dW, db, ws), it, graph=True)}
+        row = {"shape": f"{n}x{s}^3 {c}->{c}", "gflop_per_pass": round(fl / 1e9, 2)}
+        for k, v in ms.items():
+            tf = fl / (v * 1e-3) / 1e12
+            row[k] = {"ms": round(v, 4), "tflops": round(tf, 1), "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
+                      "frac_of_measured": round(tf / mfma_measured, 4) if mfma_measured else None}
+        out.append(row)
+        del x, g, y, dx, ws
+    return out
+
+
+def compact_unet(u):
+    """The figures of a bench_unet result that the one-line record carries (the plan listings stay out)."""
+    keep = ("ms_per_step", "voxels_per_s", "overhead_pct", "ms_copies_only", "overlap_fraction", "achieved_gbs_out",
+            "achieved_gbs_in", "achieved_pct_of_one_direction_peak", "copies_only_pct_of_link", "accounted_peak_gb",
+            "device_budget_gb", "no_swap_under_budget", "swap_under_budget")
+    out = {k: u[k] for k in ("workload", "steps", "ms_per_step_no_swap", "voxels_per_s_no_swap", "conv_tflops_no_swap",
+                             "pct_mfma_peak_no_swap", "accounted_peak_gb_no_swap", "link_gbs") if k in u}
+    for leg in ("encoder_activations_swapped", "planned_for_budget"):
+        if leg in u:
+            o = {k: u[leg][k] for k in keep if k in u[leg]}
+            if isinstance(o.get("no_swap_under_budget"), str):
+                o["no_swap_under_budget"] = o["no_swap_under_budget"][:7]
+            if "bytes_out_per_step" in u[leg]:
+                o["gb_out"] = round(u[leg]["bytes_out_per_step"] / 1e9, 2)
+                o["gb_in"] = round(u[leg]["bytes_in_per_step"] / 1e9, 2)
+            if "plan" in u[leg]:
+                o["tensors_swapped"] = len(u[leg]["plan"]["swapped_tensors"])
+                o["predicted_ms"] = u[leg]["plan"]["predicted_ms"]
+            out[leg] = o
     return out
 
 
@@ -603,8 +703,11 @@ def main():
     ap.add_argument("--sweep-budget-gb", type=float, default=32.0, help="device budget of the sweep workload")
     ap.add_argument("--sweep-edges", type=int, nargs="+", default=[192, 208, 224, 240, 256, 272, 288, 304],
                     help="volume edges of the sweep workload (multiples of 8)")
-    ap.add_argument("--unet-steps", type=int, default=3)
-    ap.add_argument("--with-unet", action="store_true", help="also time the full U-Net steps (cfg3, and cfg4 with swapping)")
+    ap.add_argument("--unet-steps", type=int, default=2)
+    ap.add_argument("--repeats", type=int, default=5, help="cfg2: further timings of the same K steps (spread)")
+    ap.add_argument("--quick", action="store_true",
+                    help="cfg2: the block only, without the single-layer list, the machine peaks and the cfg4 U-Net legs")
+    ap.add_argument("--detail", default="", help="also write the full (unabridged) result as JSON to this path")
     ap.add_argument("--no-graph", action="store_true")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-pass", action="store_true", help="run the short workload the HBM-traffic counters are collected on")
@@ -629,9 +732,23 @@ def main():
         return
     if args.workload == "cfg2":
         out = bench_cfg2(args)
-        if args.with_unet:
-            out["unet"] = [bench_unet(args, 32, 128, 1, False, "cfg3: U-Net base 32, 1 x 128^3, no swapping"),
-                           bench_unet(args, 64, 256, 2, True, "cfg4: U-Net base 64, 2 x 256^3, swap plan for a device budget")]
+        if not args.quick:
+            # the rest of the metric: the machine's own peaks, the layers that carry the large steps,
+            # and the cfg4 U-Net step without swapping, with every encoder activation swapped and
+            # under a device budget of three quarters of its unswapped footprint
+            pk = measure_peaks()
+            out["peaks_measured"] = pk
+            out["pct_of_measured_mfma_peak"] = round(100 * out["value"] / pk["mfma_bf16_tflops"], 2)
+            out["roofline"]["frac_of_measured"] = round(out["roofline"]["achieved"] / pk["mfma_bf16_tflops"], 4)
+            out["layers"] = bench_layers(args, pk["mfma_bf16_tflops"])
+            import gc
+            gc.collect()
+            torch.cuda.empty_cache()
+            full = bench_unet(args, 64, 256, 2, True, "cfg4: U-Net base 64, 2 x 256^3, fwd+bwd")
+            out["unet"] = compact_unet(full)
+            if args.detail:
+                with open(args.detail, "w") as f:
+                    json.dump({"line": out, "unet_full": full}, f, indent=1)
     elif args.workload in ("bp64", "bp96"):
         u = bench_bp(args, 64 if args.workload == "bp64" else 96)
         out = {"metric": "encoder/decoder training step voxels/s", "value": u["training_voxels_per_s"], "unit": "voxels/s",

@@ -268,6 +268,17 @@ int k3_upsample3d_bwd(const k3_tensor *dyd, const void *dy, const void *x_mask, 
 int k3_sgd_momentum_step(int64_t n, float *w, float *v, const float *g, float lr, float momentum,
                          float weight_decay, void *w_bf16, void *stream);
 
+/* ------------------------------------------------------------------ measurement aids
+ * The machine rates the benchmark quotes its kernels against, measured on the box it runs on
+ * (not part of the training path; the caller times them with events on `stream`).
+ * k3_probe_mfma_bf16: `blocks` workgroups of 4 waves each run `iters` rounds of four independent
+ * register-resident bf16 32x32x16 MFMAs; *flops (host, may be NULL) receives the FLOPs of the
+ * launch; sink (dev, blocks * 256 floats) receives one value per lane so the loop is kept.
+ * k3_probe_copy: grid-stride device copy of `bytes` (a multiple of 16; src, dst dev, 16-byte
+ * aligned, not overlapping) by `blocks` workgroups of 256 lanes, 16 bytes per lane and round. */
+int k3_probe_mfma_bf16(int64_t iters, int blocks, float *sink, double *flops, void *stream);
+int k3_probe_copy(const void *src, void *dst, size_t bytes, int blocks, void *stream);
+
 /* ------------------------------------------------------------------ LMS swap engine
  * Tensor swapping between device and host memory so that only the tensors a training
  * step currently needs stay on the GPU (section 2.2): a finished forward activation

@@ -232,7 +232,6 @@ def head_softmax_ce_fwd_bwd(a, wh, bh, labels, loss, da, dWh, dbh, logits, ws, r
            "k3_head_softmax_ce_fwd_bwd")
 
 
-# ------------------------------------------------------------------ LMS swap engine
 def head_softmax_wce_fwd_bwd(a, wh, bh, labels, class_w, loss, da, dWh, dbh, logits, ws, relu_mask=False):
     _check(lib().k3_head_softmax_wce_fwd_bwd(_d(a), _p(a), _p(wh), _p(bh), _p(labels), _p(class_w), _p(loss), _p(da),
                                              ctypes.c_int(int(relu_mask)), _p(dWh), _p(dbh), _p(logits), _p(ws),
@@ -269,6 +268,22 @@ def sgd_momentum_step(w, v, g, lr, momentum=0.0, weight_decay=0.0, w_bf16=None):
            "k3_sgd_momentum_step")
 
 
+# ------------------------------------------------------------------ measurement aids
+def probe_mfma_bf16(iters, blocks, sink):
+    """Launches the register-resident MFMA loop; returns the FLOPs of the launch."""
+    fl = ctypes.c_double(0.0)
+    _check(lib().k3_probe_mfma_bf16(ctypes.c_int64(iters), ctypes.c_int(blocks), _p(sink), ctypes.byref(fl), _stream()),
+           "k3_probe_mfma_bf16")
+    return fl.value
+
+
+def probe_copy(src, dst, blocks):
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(lib().k3_probe_copy(_p(src), _p(dst), ctypes.c_size_t(nbytes), ctypes.c_int(blocks), _stream()), "k3_probe_copy")
+
+
+# ------------------------------------------------------------------ LMS swap engine
 def lms_create(device_budget_bytes=0):
     ctx = ctypes.c_void_p(0)
     _check(lib().k3_lms_create(ctypes.c_uint64(device_budget_bytes), ctypes.byref(ctx)), "k3_lms_create")
