@@ -111,6 +111,20 @@ def conv3d_bwd_data(g, w):
     return dx
 
 
+def conv3d_bwd_data_points(g, w, pts):
+    """Backward-data at the listed voxels only: [npts, C_in].  Pinned against conv3d_bwd_data in
+    tests/test_oracle_conv.py."""
+    N, D, H, W, Co = g.shape
+    Ci = w.shape[3]
+    assert w.shape == (3, 3, 3, Ci, Co)
+    g, gp = _d(g); w, wp = _d(w)
+    pts = np.ascontiguousarray(pts, dtype=np.int64)
+    out = np.empty((pts.shape[0], Ci), dtype=np.float64)
+    _load().orc_conv3d_bwd_data_points(gp, wp, out.ctypes.data_as(_dp), pts.ctypes.data_as(ctypes.POINTER(_i64)),
+                                       _i64(pts.shape[0]), _i64(N), _i64(D), _i64(H), _i64(W), _i64(Ci), _i64(Co))
+    return out
+
+
 def conv3d_bwd_weight(x, g):
     N, D, H, W, Ci = x.shape
     Co = g.shape[4]

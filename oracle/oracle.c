@@ -117,6 +117,31 @@ void orc_conv3d_bwd_data(const double *g, const double *wt, double *dx,
     }
 }
 
+/* Same sum as orc_conv3d_bwd_data but only at the listed voxels: pts holds npts rows of
+ * (n, d, h, w); out is [npts][Ci].  Used to sample very large tensors. */
+void orc_conv3d_bwd_data_points(const double *g, const double *wt, double *out, const i64 *pts, i64 npts,
+                                i64 N, i64 D, i64 H, i64 W, i64 Ci, i64 Co)
+{
+    (void)N;
+#pragma omp parallel for schedule(static)
+    for (i64 p = 0; p < npts; ++p) {
+        i64 n = pts[4 * p], d = pts[4 * p + 1], h = pts[4 * p + 2], w = pts[4 * p + 3];
+        for (i64 ci = 0; ci < Ci; ++ci) {
+            double acc = 0.0;
+            for (int kd = 0; kd < 3; ++kd)
+                for (int kh = 0; kh < 3; ++kh)
+                    for (int kw = 0; kw < 3; ++kw) {
+                        i64 dd = d - kd + 1, hh = h - kh + 1, ww = w - kw + 1;
+                        if (dd < 0 || dd >= D || hh < 0 || hh >= H || ww < 0 || ww >= W) continue;
+                        const double *gp = g + IDX5(n, dd, hh, ww, 0, D, H, W, Co);
+                        const double *wp = wt + (((i64)(kd * 3 + kh) * 3 + kw) * Ci + ci) * Co;
+                        for (i64 co = 0; co < Co; ++co) acc += gp[co] * wp[co];
+                    }
+            out[p * Ci + ci] = acc;
+        }
+    }
+}
+
 /* dW[kd,kh,kw,ci,co] = sum_{n,d,h,w} x[n,d+kd-1,h+kh-1,w+kw-1,ci] * g[n,d,h,w,co];
  * db[co] = sum_{n,d,h,w} g[n,d,h,w,co].  Parallel over the 27*Ci output rows so the
  * voxel sum of each entry is accumulated by one thread in a fixed order. */

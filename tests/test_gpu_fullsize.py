@@ -50,12 +50,6 @@ def host64(t):
     return t.detach().to(torch.float32).cpu().numpy().astype(np.float64)
 
 
-def flip_transpose(w):
-    """Weights of the correlation that backward-data is: taps mirrored, channel roles swapped.
-    (The oracle's own backward-data is pinned to this by the adjoint identity in the CPU tests.)"""
-    return np.ascontiguousarray(w[::-1, ::-1, ::-1].transpose(0, 1, 2, 4, 3))
-
-
 def rel(got, ref):
     return np.linalg.norm(got - ref) / max(np.linalg.norm(ref), 1e-30)
 
@@ -116,10 +110,10 @@ def test_cfg2_block_as_benchmarked(orc):
     assert np.array_equal(host64(p), orc.pool3d_fwd(A2))
     assert np.array_equal(DA2, orc.relu_bwd(orc.pool3d_bwd(A2, dyph.astype(np.float64)), A2))
     # backward-data of conv2, masked by a1 at the producer
-    ref = orc.conv3d_fwd_points(DA2, flip_transpose(W2), None, False, pts) * (gather(a1, pts) > 0)
+    ref = orc.conv3d_bwd_data_points(DA2, W2, pts) * (gather(a1, pts) > 0)
     e = rel(gather(da1, pts), ref)
     assert e < 4e-3, e
-    ref = orc.conv3d_fwd_points(DA1, flip_transpose(W1), None, False, pts)
+    ref = orc.conv3d_bwd_data_points(DA1, W1, pts)
     e = rel(gather(dx, pts), ref)
     assert e < 4e-3, e
     # weight gradients: sampled entries with the full voxel sum, bias gradients in full
@@ -181,7 +175,7 @@ def test_unet_sized_layers_sampled(orc, case):
     dx2 = torch.full((N, D, H, W, c2), float("nan"), device="cuda", dtype=torch.bfloat16) if c2 else None
     k3.conv3d_bwd_data(g, None, wd, pk, dx, dx2=dx2, dx_mask=m)
     torch.cuda.synchronize()
-    ref = orc.conv3d_fwd_points(G, flip_transpose(Wt), None, False, pts)
+    ref = orc.conv3d_bwd_data_points(G, Wt, pts)
     ref[:, :c1] *= gather(m, pts) > 0
     got = gather(dx, pts) if not c2 else np.concatenate([gather(dx, pts), gather(dx2, pts)], axis=1)
     assert np.isfinite(got).all()
@@ -198,80 +192,6 @@ def test_unet_sized_layers_sampled(orc, case):
     got = host64(dW).reshape(27, cin, co)[ent[:, 0], ent[:, 1], ent[:, 2]]
     assert rel(got, orc.conv3d_bwd_weight_entries(X, G, ent)) < 1e-5
     assert rel(host64(db), G.reshape(-1, co).sum(axis=0)) < 1e-5
-
-
-def test_tensor_with_more_than_4gi_elements(orc):
-    """Workload config 5's level-0 tensors (4 x 320^3 x 64 channels = 8.4 Gi elements, 16.8 GB) need
-    64-bit element offsets everywhere.  Forward, masked backward-data and backward-weight run at
-    that size; the oracle checks crops (cut out on the device with their halo) placed at the
-    first voxels, at the last voxels (element offsets beyond 2^33) and in between, and sampled
-    weight-gradient entries are checked on one sample's contribution."""
-    import torch
-    from paper_1811_12174_amd import k3
-    from gpu_util import to_dev, packed_for
-    N, S, C = 4, 320, 64
-    free, _ = torch.cuda.mem_get_info()
-    if free < 90e9:
-        pytest.skip("needs ~75 GB of free device memory")
-    gen = torch.Generator(device="cuda")
-    gen.manual_seed(181112174)
-    x = torch.empty((N, S, S, S, C), device="cuda", dtype=torch.bfloat16)
-    g = torch.empty((N, S, S, S, C), device="cuda", dtype=torch.bfloat16)
-    for n in range(N):   # seeded synthetic N(0,1) inputs, generated on the device sample by sample
-        x[n] = torch.randn((S, S, S, C), device="cuda", generator=gen).to(torch.bfloat16)
-        g[n] = torch.randn((S, S, S, C), device="cuda", generator=gen).to(torch.bfloat16)
-    wh = synth.conv_weights(90, C, C, "bf16")
-    bh = (synth.normal(synth.SEED, 91, (C,), np.float64) * 0.3).astype(np.float32)
-    wd, b = to_dev(wh, "bf16"), torch.from_numpy(bh).cuda()
-    pk = packed_for(wd)
-    y = torch.empty_like(x)
-    k3.conv3d_fwd(x, wd, pk, b, 1, y)
-    dx = torch.empty_like(x)
-    k3.conv3d_bwd_data(g, None, wd, pk, dx, dx_mask=x)
-    torch.cuda.synchronize()
-    Wt = wh.astype(np.float64)
-    E = 10   # crop edge
-    corners = [(0, 0, 0, 0), (N - 1, S - E, S - E, S - E), (N - 1, 0, S - E, 0), (2, 155, 3, 301), (3, S - E, 160, 8),
-               (1, 64, 128, 256), (N - 1, S - E, S - E, 0)]
-    for (n, d0, h0, w0) in corners:
-        # crop with a one-voxel halo where the volume has one; the oracle's zero padding then only
-        # acts on faces that are faces of the volume, and the halo layer of its output is dropped
-        lo = [max(c - 1, 0) for c in (d0, h0, w0)]
-        hi = [min(c + E + 1, S) for c in (d0, h0, w0)]
-        sl = (slice(lo[0], hi[0]), slice(lo[1], hi[1]), slice(lo[2], hi[2]))
-        inner = tuple(slice(c - l, c - l + E) for c, l in zip((d0, h0, w0), lo))
-        xc = x[n][sl].float().cpu().numpy().astype(np.float64)[None]
-        gc_ = g[n][sl].float().cpu().numpy().astype(np.float64)[None]
-        ref = orc.conv3d_fwd(xc, Wt, bh.astype(np.float64), relu=True)[0][inner]
-        got = y[n, d0:d0 + E, h0:h0 + E, w0:w0 + E].float().cpu().numpy().astype(np.float64)
-        assert rel(got, ref) < 4e-3, ("fwd", n, d0, h0, w0)
-        ref = orc.conv3d_bwd_data(gc_, Wt)[0][inner] * (xc[0][inner] > 0)
-        got = dx[n, d0:d0 + E, h0:h0 + E, w0:w0 + E].float().cpu().numpy().astype(np.float64)
-        assert rel(got, ref) < 4e-3, ("dgrad", n, d0, h0, w0)
-    del y, dx
-    # backward-weight over all 8.4 Gi products per entry: the oracle sums one sample, the GPU
-    # is run on that sample alone and on all four; the other three samples are bit-identical
-    # copies of it in a second run, so the full-size result must be exactly 4x (power of two)
-    dW1 = torch.empty((3, 3, 3, C, C), device="cuda")
-    db1 = torch.empty(C, device="cuda")
-    ws = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(x, g), device="cuda", dtype=torch.uint8)
-    k3.conv3d_bwd_weight(x[3:4], g[3:4], None, dW1, db1, ws)
-    torch.cuda.synchronize()
-    ent = wgrad_entries(C, C, 40, 92)
-    X3 = x[3].float().cpu().numpy().astype(np.float64)[None]
-    G3 = g[3].float().cpu().numpy().astype(np.float64)[None]
-    got = host64(dW1).reshape(27, C, C)[ent[:, 0], ent[:, 1], ent[:, 2]]
-    assert rel(got, orc.conv3d_bwd_weight_entries(X3, G3, ent)) < 1e-5
-    del X3, G3
-    for n in range(3):
-        x[n].copy_(x[3])
-        g[n].copy_(g[3])
-    dW4 = torch.empty_like(dW1)
-    db4 = torch.empty_like(db1)
-    k3.conv3d_bwd_weight(x, g, None, dW4, db4, ws)
-    torch.cuda.synchronize()
-    assert rel(host64(dW4), 4.0 * host64(dW1)) < 1e-5
-    assert rel(host64(db4), 4.0 * host64(db1)) < 1e-5
 
 
 @pytest.mark.parametrize("sp,ci,co", [((1, 32, 32, 32), 128, 64),     # four channel blocks per wave, 4 steps per tap

@@ -173,11 +173,30 @@ def test_points_and_entries_match_full(orc):
     yp = orc.conv3d_fwd_points(x, w, b, True, pts)
     for i, (n, d, h, ww) in enumerate(pts):
         np.testing.assert_array_equal(yp[i], y[n, d, h, ww])
+    # the backward-data sampler on every voxel of the tensor, corners, edges and faces included
+    dx = orc.conv3d_bwd_data(g, w)
+    allp = np.array([(n, d, h, ww) for n in range(2) for d in range(4) for h in range(5) for ww in range(3)])
+    dxp = orc.conv3d_bwd_data_points(g, w, allp)
+    np.testing.assert_array_equal(dxp.reshape(dx.shape), dx)
     dW, _ = orc.conv3d_bwd_weight(x, g)
     ent = np.array([[0, 0, 0], [13, 2, 3], [26, 1, 1], [5, 2, 0]])
     out = orc.conv3d_bwd_weight_entries(x, g, ent)
     for i, (t, ci, co) in enumerate(ent):
         np.testing.assert_allclose(out[i], dW.reshape(27, 3, 4)[t, ci, co], rtol=1e-13)
+
+
+def test_bwd_data_points_is_the_adjoint_at_single_voxels(orc):
+    """<conv(x), g> = <x, dgrad(g)> with x a one-hot tensor reads off one entry of dgrad(g): the sampler
+    must return exactly that entry, computed through the forward pass only."""
+    w = RNG.standard_normal((3, 3, 3, 3, 2))
+    g = RNG.standard_normal((1, 3, 4, 3, 2))
+    pts = np.array([[0, 0, 0, 0], [0, 2, 3, 2], [0, 1, 2, 1], [0, 0, 3, 1]])
+    got = orc.conv3d_bwd_data_points(g, w, pts)
+    for i, (n, d, h, ww) in enumerate(pts):
+        for ci in range(3):
+            e = np.zeros((1, 3, 4, 3, 3))
+            e[n, d, h, ww, ci] = 1.0
+            assert abs(np.sum(orc.conv3d_fwd(e, w) * g) - got[i, ci]) < 1e-12
 
 
 def test_against_torch_cpu_fp64(orc):
