@@ -311,10 +311,12 @@ int k3_lms_account_free(k3_lms *ctx, uint64_t bytes);
  * of the tensor).  Returns a new handle in OUT_IN_FLIGHT. */
 int k3_lms_swap_out(k3_lms *ctx, const void *dev_ptr, size_t bytes, void *host_ptr,
                     void *compute_stream, int *handle);
-/* 1 in *done once the swap-out copy has finished (handle moves to ON_HOST), else 0. */
+/* 1 in *done once the swap-out copy has finished (handle moves to ON_HOST), else 0; also
+ * after k3_lms_release_after it reports the copy itself, not the hand-over of the block. */
 int k3_lms_swap_out_done(k3_lms *ctx, int handle, int *done);
 /* Makes `stream` wait for the swap-out copy, so that work enqueued on it afterwards
- * may overwrite or free the device block; the handle moves to ON_HOST. */
+ * may overwrite or free the device block.  The handle stays OUT_IN_FLIGHT until the copy
+ * has finished (then ON_HOST); a prefetch may be started at once (it waits for the copy). */
 int k3_lms_release_after(k3_lms *ctx, int handle, void *stream);
 /* Starts the host-to-device copy of the tensor into dev_ptr (a block of at least the
  * swapped size).  The copy waits for work already enqueued on consumer_stream (earlier
@@ -334,7 +336,9 @@ int k3_lms_wait_in(k3_lms *ctx, int handle, void *stream);
  * made to wait for the copy-in first (a no-op once it finished), so that work enqueued
  * on it afterwards may reuse the block.  IN_IN_FLIGHT / RESIDENT -> ON_HOST. */
 int k3_lms_evict(k3_lms *ctx, int handle, void *stream);
-/* Drops the handle (any state but a copy still in flight is waited for first). */
+/* Drops the handle; a copy still in flight (in either direction, also after
+ * k3_lms_release_after) is waited for first, so the host buffer may be reused or freed
+ * once this returns. */
 int k3_lms_release(k3_lms *ctx, int handle);
 /* Blocks the host until both copy streams are idle. */
 int k3_lms_sync(k3_lms *ctx);
@@ -352,6 +356,12 @@ int k3_lms_get_stats(k3_lms *ctx, k3_lms_stats *out);
  * copy stream spent copying (copies of one direction run one after the other, so the sum of
  * their durations is that stream's busy time); copies still in flight are not counted yet. */
 int k3_lms_set_copy_timing(k3_lms *ctx, int on);
+/* Debug switch (off by default): every device block whose tensor has gone to the host
+ * (k3_lms_release_after, k3_lms_evict) is overwritten with 0xFF bytes -- NaN in bf16 and
+ * fp32 -- on the stream that was just ordered behind the copy, so that a kernel which still
+ * reads the block after the swap shows up in the results.  Blocks already handed over when
+ * the switch is turned on are not touched. */
+int k3_lms_set_poison(k3_lms *ctx, int on);
 int k3_lms_copy_busy_ms(k3_lms *ctx, double *out_ms, double *in_ms);
 int k3_lms_handle_state(k3_lms *ctx, int handle, int *state);
 

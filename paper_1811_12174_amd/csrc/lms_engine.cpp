@@ -8,6 +8,9 @@
 //             prefetch_start leaves that wait to a later wait_in so the copy overlaps the
 //             kernels enqueued in between).
 //  evict    : a tensor that came back and was only read goes ON_HOST again without a copy.
+//  A handle stays OUT_IN_FLIGHT until its copy-out has really finished, also after release_after
+//  handed the device block to a stream: swap_out_done and handle_state report the copy, and
+//  release waits for it, so the host buffer is safe to reuse once the handle is released.
 #include "lms_engine.h"
 
 namespace k3lms {
@@ -96,6 +99,7 @@ int Engine::swap_out(const void *dev, size_t bytes, void *host, stream_t compute
         }
     }
     s.dev = dev; s.host = host; s.bytes = bytes;
+    s.handed = false;
     int rc = 0;
     rc |= be_->event_record(s.ev_ready, compute);
     rc |= be_->stream_wait_event(d2h_, s.ev_ready);
@@ -129,10 +133,11 @@ int Engine::release_after(int handle, stream_t st)
     Slot *s = get(handle);
     if (!s) return E_BADARG;
     if (s->state != OUT_IN_FLIGHT && s->state != ON_HOST) return E_STATE;
-    BE(be_->stream_wait_event(st, s->ev_out));
-    s->state = ON_HOST;  // the caller's stream is ordered after the copy from here on
+    BE(be_->stream_wait_event(st, s->ev_out));   // st is ordered after the copy from here on
+    if (poison_ && s->dev) BE(be_->fill_poison(const_cast<void *>(s->dev), s->bytes, st));
+    s->handed = true;
     s->dev = nullptr;
-    return OK;
+    return refresh(*s);   // ON_HOST only once the copy has really finished
 }
 
 int Engine::prefetch_start(int handle, void *dev, stream_t block_stream)
@@ -143,7 +148,8 @@ int Engine::prefetch_start(int handle, void *dev, stream_t block_stream)
         int rc = refresh(*s);
         if (rc) return rc;
     }
-    if (s->state != ON_HOST) return E_STATE;
+    // a copy-out still in flight is fine once the block was handed over: the copy-in waits for it
+    if (s->state != ON_HOST && !(s->state == OUT_IN_FLIGHT && s->handed)) return E_STATE;
     BE(be_->event_record(s->ev_ready, block_stream));
     BE(be_->stream_wait_event(h2d_, s->ev_ready));
     BE(be_->stream_wait_event(h2d_, s->ev_out));  // no-op when the swap-out already finished
@@ -171,6 +177,7 @@ int Engine::evict(int handle, stream_t st)
     if (s->state != IN_IN_FLIGHT && s->state != RESIDENT) return E_STATE;
     // work enqueued on st from here on (the next user of the block) runs after the copy-in
     BE(be_->stream_wait_event(st, s->ev_in));
+    if (poison_ && s->dev) BE(be_->fill_poison(const_cast<void *>(s->dev), s->bytes, st));
     s->state = ON_HOST;  // the host copy made by the swap-out is still the tensor's value
     s->dev = nullptr;
     return OK;
@@ -192,6 +199,7 @@ int Engine::release(int handle)
     if (s->state == OUT_IN_FLIGHT) BE(be_->event_sync(s->ev_out));
     if (s->state == IN_IN_FLIGHT) BE(be_->event_sync(s->ev_in));
     s->state = FREE_SLOT;
+    s->handed = false;
     s->dev = nullptr;
     s->host = nullptr;
     s->bytes = 0;

@@ -31,6 +31,8 @@ struct Backend {
     virtual int copy_d2h(void *host, const void *dev, size_t bytes, stream_t s) = 0;
     virtual int copy_h2d(void *dev, const void *host, size_t bytes, stream_t s) = 0;
     virtual bool is_pinned(const void *host, size_t bytes) = 0;
+    // debug aid: overwrite a device block with 0xFF bytes on stream s (see Engine::set_poison)
+    virtual int fill_poison(void *dev, size_t bytes, stream_t s) = 0;
 };
 
 struct Stats {
@@ -55,6 +57,10 @@ public:
     int release(int handle);
     int sync();
     int handle_state(int handle, int *state);
+    // Debug switch: every device block whose tensor has gone to the host (release_after, evict) is
+    // overwritten with 0xFF bytes (a bf16 / fp32 NaN pattern) on the stream that was just ordered
+    // behind the copy, so a kernel that still reads the block after the swap is found out.
+    void set_poison(bool on) { poison_ = on; }
     const Stats &stats() const { return stats_; }
     static const int kMaxHandles = 1 << 16;
 
@@ -64,6 +70,7 @@ private:
         const void *dev = nullptr;
         void *host = nullptr;
         size_t bytes = 0;
+        bool handed = false;         // release_after gave the device block back while the copy-out may still run
         event_t ev_ready = nullptr;  // recorded on the compute stream before a copy may start
         event_t ev_out = nullptr;    // end of the device-to-host copy
         event_t ev_in = nullptr;     // end of the host-to-device copy
@@ -72,6 +79,7 @@ private:
     int refresh(Slot &s);
     Backend *be_;
     uint64_t budget_;
+    bool poison_ = false;
     stream_t d2h_ = nullptr, h2d_ = nullptr;
     std::vector<Slot> slots_;
     std::vector<int> free_;

@@ -9,6 +9,19 @@
 
 namespace {
 
+// debug aid of the swap engine: a block whose tensor has gone to the host is overwritten
+__global__ __launch_bounds__(256) void lms_poison_kernel(unsigned char *p, size_t bytes)
+{
+    const size_t stride = (size_t)gridDim.x * 256 * 16;
+    for (size_t i = ((size_t)blockIdx.x * 256 + threadIdx.x) * 16; i < bytes; i += stride) {
+        if (i + 16 <= bytes && (((uintptr_t)p + i) & 15) == 0) {
+            *reinterpret_cast<uint4 *>(p + i) = make_uint4(0xffffffffu, 0xffffffffu, 0xffffffffu, 0xffffffffu);
+        } else {
+            for (size_t j = i; j < bytes && j < i + 16; ++j) p[j] = 0xff;
+        }
+    }
+}
+
 struct HipBackend : k3lms::Backend {
     int last = 0;
     // optional timing of the copies (off by default): a timed event pair around every copy; the
@@ -108,6 +121,14 @@ struct HipBackend : k3lms::Backend {
     {
         return timed_copy(dev, const_cast<void *>(host), bytes, hipMemcpyHostToDevice, (hipStream_t)s, 1);
     }
+    int fill_poison(void *dev, size_t bytes, k3lms::stream_t s) override
+    {
+        if (bytes == 0) return 0;
+        size_t blocks = (bytes + 4095) / 4096;
+        if (blocks > 8192) blocks = 8192;
+        lms_poison_kernel<<<dim3((unsigned)blocks), 256, 0, (hipStream_t)s>>>((unsigned char *)dev, bytes);
+        return chk(hipGetLastError());
+    }
     bool is_pinned(const void *host, size_t bytes) override
     {
         hipPointerAttribute_t at;
@@ -200,6 +221,13 @@ int k3_lms_wait_in(k3_lms *ctx, int handle, void *stream) { return ctx ? map_sta
 int k3_lms_release(k3_lms *ctx, int handle) { return ctx ? map_status(ctx->eng.release(handle)) : K3_E_BADARG; }
 int k3_lms_sync(k3_lms *ctx) { return ctx ? map_status(ctx->eng.sync()) : K3_E_BADARG; }
 int k3_lms_handle_state(k3_lms *ctx, int handle, int *state) { return ctx ? map_status(ctx->eng.handle_state(handle, state)) : K3_E_BADARG; }
+
+int k3_lms_set_poison(k3_lms *ctx, int on)
+{
+    if (!ctx) return K3_E_BADARG;
+    ctx->eng.set_poison(on != 0);
+    return K3_OK;
+}
 
 int k3_lms_set_copy_timing(k3_lms *ctx, int on)
 {

@@ -369,6 +369,10 @@ def lms_set_copy_timing(ctx, on):
     _check(lib().k3_lms_set_copy_timing(ctx, ctypes.c_int(1 if on else 0)), "k3_lms_set_copy_timing")
 
 
+def lms_set_poison(ctx, on):
+    _check(lib().k3_lms_set_poison(ctx, ctypes.c_int(1 if on else 0)), "k3_lms_set_poison")
+
+
 def lms_copy_busy_ms(ctx):
     """(device-to-host, host-to-device) busy milliseconds of the copy streams since the context was created."""
     a, b = ctypes.c_double(0.0), ctypes.c_double(0.0)

@@ -202,8 +202,9 @@ class Program:
                 before.setdefault(g.last, []).append((-1, ("wait", t)))
         out = []
         for k, c in enumerate(self.calls):
-            # waits (key -1) first, then prefetches in the order their consumers run
-            for _, ins in sorted(before.get(k, []), key=lambda e: e[0]):
+            # a prefetch placed at its own reader call (lead 0) first, so that the wait below fences
+            # it; then the waits; then the prefetches for later readers in the order these run
+            for _, ins in sorted(before.get(k, []), key=lambda e: -2 if e[0] == k else e[0]):
                 out.append(ins)
             for t in c.allocs:
                 out.append(("alloc", t))

@@ -72,12 +72,16 @@ class StepNet:
             else:
                 self.kind[name] = "upconv" if name.endswith(".up") else "conv"
                 if self.work is not None:
-                    self.work[o:o + n].copy_(self.master[o:o + n])
                     self.w[name] = self.work[o:o + n].view(shape)
                 else:
                     self.w[name] = self.master[o:o + n].view(shape)
             self.gw[name] = self.gflat[o:o + n].view(shape)
             self.gb[name] = self.gflat[ob:ob + nb]
+        if self.work is not None:
+            # the bf16 working copy comes from the library's own rounding: an update with a zero
+            # step (momentum and gradient buffers are still zero) leaves the master weights as they
+            # are and writes their round-to-nearest-even bf16 values
+            k3.sgd_momentum_step(self.master, self.mom, self.gflat, 0.0, 0.0, 0.0, w_bf16=self.work)
         self.repack()
         self._ws = None
         self._host = {}        # tensor name -> (pinned host pointer, bytes), kept across steps

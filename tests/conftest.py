@@ -17,3 +17,17 @@ def orc():
     import oracle
     oracle.build(force=False)
     return oracle
+
+
+def pytest_sessionfinish(session, exitstatus):
+    """GPU runs leave the worst relative error each parity assertion saw (by test and line)."""
+    mod = sys.modules.get("gpu_util")
+    if mod is None or not getattr(mod, "MEASURED", None):
+        return
+    import json
+    out = os.path.join(ROOT, "gpurun_out")
+    os.makedirs(out, exist_ok=True)
+    rows = sorted(({"file": k[0], "test": k[1], "line": k[2], "max_rel_l2": v} for k, v in mod.MEASURED.items()),
+                  key=lambda r: (r["file"], r["line"]))
+    with open(os.path.join(out, "measured_errors.json"), "w") as f:
+        json.dump(rows, f, indent=1)

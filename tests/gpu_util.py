@@ -1,4 +1,7 @@
 """Helpers for the GPU parity tests: host <-> device conversion and error norms."""
+import os
+import sys
+
 import numpy as np
 import torch
 
@@ -20,12 +23,21 @@ def empty(shape, dtype):
     return torch.empty(shape, device="cuda", dtype=torch.bfloat16 if dtype == "bf16" else torch.float32)
 
 
-def rel_l2(got, ref):
+MEASURED = {}   # (test function, line) -> largest relative L2 error seen there in this session
+
+
+def rel_l2(got, ref, depth=1, tag=""):
+    """Relative L2 distance; every value is also noted under the calling test and line (the
+    session's worst cases are written to gpurun_out/measured_errors.json by conftest.py)."""
     ref = np.asarray(ref, dtype=np.float64)
     got = np.asarray(got, dtype=np.float64)
     den = np.linalg.norm(ref.reshape(-1))
     num = np.linalg.norm((got - ref).reshape(-1))
-    return num / den if den > 0 else num
+    e = num / den if den > 0 else num
+    f = sys._getframe(depth)
+    key = (os.path.basename(f.f_code.co_filename), f.f_code.co_name + ("[" + tag + "]" if tag else ""), f.f_lineno)
+    MEASURED[key] = max(MEASURED.get(key, 0.0), float(e))
+    return e
 
 
 def packed_for(w):

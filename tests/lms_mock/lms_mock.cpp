@@ -129,6 +129,14 @@ struct MockBackend : Backend {
         ((MockStream *)s)->q.push_back(op);
         return 0;
     }
+    int fill_poison(void *dev, size_t bytes, stream_t s) override
+    {
+        char *src = new char[bytes];   // leaked: the deferred copy reads it when the stream is pumped
+        memset(src, 0xFF, bytes);
+        Op op; op.kind = Op::COPY; op.dst = dev; op.src = src; op.bytes = bytes;
+        ((MockStream *)s)->q.push_back(op);
+        return 0;
+    }
     bool is_pinned(const void *host, size_t bytes) override
     {
         for (auto &kv : pinned) {
@@ -182,6 +190,7 @@ int mock_evict(void *c, int h, void *stream) { return ((Ctx *)c)->eng.evict(h, s
 int mock_wait_in(void *c, int h, void *stream) { return ((Ctx *)c)->eng.wait_in(h, stream); }
 int mock_release(void *c, int h) { return ((Ctx *)c)->eng.release(h); }
 int mock_sync(void *c) { return ((Ctx *)c)->eng.sync(); }
+void mock_set_poison(void *c, int on) { ((Ctx *)c)->eng.set_poison(on != 0); }
 int mock_state(void *c, int h, int *s) { return ((Ctx *)c)->eng.handle_state(h, s); }
 void mock_stats(void *c, uint64_t *out)
 {

@@ -293,3 +293,77 @@ def test_conv_fwd_pool_rejects_odd_sizes():
     with pytest.raises(k3.K3Error) as e:
         k3.conv3d_fwd_pool(x, w, packed_for(w), None, 1, y, p)
     assert e.value.status == k3.E_SHAPE
+
+
+# ------------------------------------------------------------------ exact arithmetic: structure pinned with zero tolerance
+# (N, D, H, W, c1, c2, cout): one shape per MFMA kernel variant, bench-sized where that selects the kernel
+EXACT_CASES = [
+    (1, 64, 64, 64, 32, 0, 32),     # plane-streaming kernel, the benchmark's layer (K-split weight gradient)
+    (1, 40, 36, 50, 64, 0, 64),     # pipelined kernel, two output blocks, ragged 8x8x16 tiles
+    (2, 20, 24, 24, 32, 32, 64),    # two sources / two destinations
+    (1, 16, 16, 16, 128, 0, 128),   # 4x8x8 tiles
+    (1, 12, 20, 9, 32, 0, 64),      # small-volume kernel
+    (1, 24, 20, 36, 1, 0, 64),      # single-channel first layer
+]
+
+
+@pytest.mark.parametrize("case", EXACT_CASES, ids=lambda c: "x".join(map(str, c)))
+def test_integer_valued_tensors_give_exact_results(orc, case):
+    """With inputs in {-1, 0, 1} and sparse weights in {-1, 0, 1} (at most 200 non-zero weights
+    per output channel, per input channel for backward-data) every product and every partial sum is
+    a small integer: exact in bf16 operands, exact in fp32 accumulation in any order, and the
+    result (|y| <= 200 < 2^8) is exact in the bf16 output.  The kernels must therefore match the
+    fp64 oracle bit for bit -- at every voxel, corner, edge and tile border, for every tap at once.
+    A bf16-rounded output with ordinary inputs hides structural slips smaller than its rounding
+    (about 2e-3); here nothing is rounded, so there is nothing to hide behind."""
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, to_f64, empty, packed_for
+    N, D, H, W, c1, c2, co = case
+    cin = c1 + c2
+    rng = np.random.default_rng(1811 + cin + co + D)
+    x = rng.integers(-1, 2, size=(N, D, H, W, cin)).astype(np.float32)
+    g = rng.integers(-1, 2, size=(N, D, H, W, co)).astype(np.float32)
+    w = np.zeros((27, cin, co), dtype=np.float32)
+    # at most 200 non-zeros in every column (the 27 * cin weights of one output channel) and, where
+    # backward-data runs, in every row group (the 27 * co weights of one input channel): up to 100
+    # per column placed at random, fewer when co > cin so that a row group gets 100 on average
+    # and never more than 200 (checked below)
+    per_col = min(27 * cin, 100 if (co <= cin or c1 == 1) else 100 * cin // co)
+    for o in range(co):
+        idx = rng.choice(27 * cin, size=per_col, replace=False)
+        w.reshape(27 * cin, co)[idx, o] = rng.choice([-1.0, 1.0], size=idx.size)
+    assert np.abs(w).sum(axis=(0, 1)).max() <= 200 and (c1 == 1 or np.abs(w).sum(axis=(0, 2)).max() <= 200)
+    w = w.reshape(3, 3, 3, cin, co)
+    b = rng.integers(-3, 4, size=(co,)).astype(np.float32)
+    xd, gd, wd, bd = to_dev(x, "bf16"), to_dev(g, "bf16"), to_dev(w, "bf16"), torch.from_numpy(b).cuda()
+    x1 = xd[..., :c1].contiguous()
+    x2 = xd[..., c1:].contiguous() if c2 else None
+    pk = packed_for(wd)
+    X, G, Wt = x.astype(np.float64), g.astype(np.float64), w.astype(np.float64)
+
+    y = empty((N, D, H, W, co), "bf16")
+    bits = torch.empty((N, D, H, W, co // 16), device="cuda", dtype=torch.int16)
+    k3.conv3d_fwd_bits(x1, wd, pk, bd, 1, y, bits, x2=x2)
+    torch.cuda.synchronize()
+    ref = orc.conv3d_fwd(X, Wt, b.astype(np.float64), relu=True)
+    assert np.array_equal(to_f64(y), ref)
+    assert np.array_equal(bits.cpu().numpy().view(np.uint16), orc.relu_bits(ref))
+
+    if c1 > 1:
+        dx1 = empty((N, D, H, W, c1), "bf16")
+        dx2 = empty((N, D, H, W, c2), "bf16") if c2 else None
+        k3.conv3d_bwd_data(gd, None, wd, pk, dx1, dx2=dx2, dx_mask=x1)
+        torch.cuda.synchronize()
+        ref = orc.conv3d_bwd_data(G, Wt)
+        ref[..., :c1] *= X[..., :c1] > 0
+        got = to_f64(dx1) if not c2 else np.concatenate([to_f64(dx1), to_f64(dx2)], axis=-1)
+        assert np.array_equal(got, ref)
+
+    dW, db = torch.empty((3, 3, 3, cin, co), device="cuda"), torch.empty(co, device="cuda")
+    ws = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(x1, gd, x2=x2), device="cuda", dtype=torch.uint8)
+    k3.conv3d_bwd_weight(x1, gd, None, dW, db, ws, x2=x2)
+    torch.cuda.synchronize()
+    rW, rb = orc.conv3d_bwd_weight(X, G)      # integer sums below 2^24: exact in fp32
+    assert np.array_equal(to_f64(dW), rW)
+    assert np.array_equal(to_f64(db), rb)

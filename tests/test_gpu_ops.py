@@ -142,7 +142,7 @@ def test_head(orc, sp, C, dt):
     assert rel_l2(to_f64(logits), ref["logits"].reshape(-1, 3)) < 1e-5
     assert rel_l2(to_f64(da), ref["da"]) < TOL[dt]
     assert rel_l2(to_f64(dam), orc.relu_bwd(ref["da"], a.astype(np.float64))) < TOL[dt]
-    assert rel_l2(to_f64(dW), ref["dW"]) < 1e-4      # fp32 exp/log + fp32 sums of mixed-sign terms
+    assert rel_l2(to_f64(dW), ref["dW"]) < 1e-5
     assert np.abs(to_f64(db) - ref["db"]).max() < 1e-5 * max(1e-3, np.abs(ref["db"]).max()) + 1e-7
 
 

@@ -85,7 +85,7 @@ def test_training_run_matches_oracle(orc, base, levels, size, dt, steps):
         assert abs(a - b) < tol * abs(b), (losses, rl)
     for k in rp:
         # parameters move by lr * (accumulated gradient): compare the movement, not the value
-        moved = rel_l2(to_f64(final[k]) - params[k].astype(np.float64), rp[k] - params[k].astype(np.float64))
+        moved = rel_l2(to_f64(final[k]) - params[k].astype(np.float64), rp[k] - params[k].astype(np.float64), tag=dt)
         assert moved < (8e-2 if dt == "bf16" else 1e-3), (k, moved)
 
 

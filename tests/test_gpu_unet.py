@@ -29,11 +29,11 @@ def test_unet_step_matches_oracle(orc, base, levels, size, n, dt):
     store = orc.round_bf16 if dt == "bf16" else None
     p64 = {k: v.astype(np.float64) for k, v in params.items()}
     rl, rg, ra = unet_step(x.astype(np.float64), lab, p64, base=base, levels=levels, store=store)
-    tol_l, tol_g = (2e-2, 2e-2) if dt == "bf16" else (1e-5, 1e-4)
+    tol_l, tol_g = (2e-2, 2e-2) if dt == "bf16" else (1e-5, 1e-5)
     assert abs(loss.item() - rl) < tol_l * abs(rl), (loss.item(), rl)
     # forward activations, chained
     for k, t in acts.items():
-        e = rel_l2(to_f64(t), ra[k])
+        e = rel_l2(to_f64(t), ra[k], tag=dt)
         assert e < tol_g, (k, e)
     # Parameter gradients, chained through the whole backward pass.  In bf16 the chained result
     # is only defined up to the sensitivity of the step to the rounding of every stored tensor
@@ -44,9 +44,9 @@ def test_unet_step_matches_oracle(orc, base, levels, size, n, dt):
         _, rg_exact, _ = unet_step(x.astype(np.float64), lab, p64, base=base, levels=levels)
     worst = 0.0
     for k, g in net.grads().items():
-        e = rel_l2(to_f64(g), rg[k])
+        e = rel_l2(to_f64(g), rg[k], tag=dt)
         worst = max(worst, e)
-        bound = 1e-4 if dt != "bf16" else max(2e-2, 3.0 * rel_l2(rg[k], rg_exact[k]))
+        bound = 1e-5 if dt != "bf16" else max(2e-2, 3.0 * rel_l2(rg[k], rg_exact[k]))
         assert e < bound, (k, e, bound)
     print("worst chained gradient error", worst)
     net.close()
@@ -106,6 +106,38 @@ def test_swapping_is_bit_identical(base, levels, size):
         assert net.last_stats["bytes_out"] - before == run.bytes_out
         before = net.last_stats["bytes_out"]
     net.close()
+
+
+def test_swapping_with_poisoned_blocks_is_bit_identical():
+    """The swap engine's debug switch overwrites every device block whose tensor has gone to the
+    host; a kernel that still read such a block would turn the loss or a gradient into NaN.  The
+    budgeted step (blocks are really reused) must stay bit-identical, and the poison must really
+    have been written (a freed block of the slab holds it)."""
+    import torch
+    from gpu_util import to_dev
+    from paper_1811_12174_amd import k3, planner
+    net, loss0, params, x, lab = _run(32, 4, 32, 1, "bf16")
+    g0 = {k: v.clone() for k, v in net.grads().items()}
+    l0 = net.loss.clone()
+    xd, labd = to_dev(x, "bf16"), torch.from_numpy(lab).cuda()
+    prog = net.program(xd.shape)
+    fixed = net.fixed_bytes(prog)
+    plan = planner.swap_all(prog, only=planner.is_encoder_activation, fixed_bytes=fixed)
+    net.step(xd, labd, swap=plan)                      # creates the swap context
+    k3.lms_set_poison(net.lms, True)
+    try:
+        for rep in range(2):
+            net._slab.zero_()
+            net.step(xd, labd, swap=plan)
+            torch.cuda.synchronize()
+            assert torch.equal(net.loss, l0)
+            for k, v in net.grads().items():
+                assert torch.equal(v, g0[k]), k
+            assert net.last_run.releases > 0
+        assert int((net._slab == 0xFF).sum().item()) > 4096      # poison was written somewhere in the slab
+    finally:
+        k3.lms_set_poison(net.lms, False)
+        net.close()
 
 
 def test_step_under_a_device_memory_limit():

@@ -46,6 +46,7 @@ def mock(tmp_path_factory):
     L.mock_sync.argtypes = [ctypes.c_void_p]
     L.mock_state.argtypes = [ctypes.c_void_p, ctypes.c_int, ctypes.POINTER(ctypes.c_int)]
     L.mock_stats.argtypes = [ctypes.c_void_p, ctypes.POINTER(ctypes.c_uint64)]
+    L.mock_set_poison.argtypes = [ctypes.c_void_p, ctypes.c_int]
     return L
 
 
@@ -269,5 +270,62 @@ def test_evict_keeps_the_host_copy_and_allows_a_second_prefetch(mock):
     assert st[0] == e.n and st[1] == 2 * e.n and st[2] == 1 and st[3] == 2   # one copy out, two in
     assert mock.mock_evict(e.c, h.value, e.compute) == OK                     # RESIDENT -> ON_HOST
     assert mock.mock_evict(e.c, 999, e.compute) == E_BADARG
+    assert mock.mock_release(e.c, h.value) == OK
+    e.close()
+
+
+def test_release_after_keeps_reporting_the_copy_until_it_has_finished(mock):
+    """release_after hands the device block to a stream; the copy-out may still be running.  The
+    handle must keep saying so (swap_out_done, handle_state), and release must wait for the copy:
+    a caller that reuses the host buffer after release would otherwise be overwritten by it."""
+    e = Env(mock)
+    h = ctypes.c_int(-1)
+    assert mock.mock_swap_out(e.c, e.dev.ctypes.data, e.n, e.host.ctypes.data, e.compute, ctypes.byref(h)) == OK
+    assert mock.mock_release_after(e.c, h.value, e.compute) == OK
+    done = ctypes.c_int(5)
+    assert mock.mock_swap_out_done(e.c, h.value, ctypes.byref(done)) == OK and done.value == 0
+    assert e.state(h.value) == OUT_IN_FLIGHT
+    assert not np.array_equal(e.host, e.orig)           # the copy has not run
+    assert mock.mock_release(e.c, h.value) == OK        # waits for it
+    assert np.array_equal(e.host, e.orig)
+    # the same with the copy finishing in between
+    assert mock.mock_swap_out(e.c, e.dev.ctypes.data, e.n, e.host.ctypes.data, e.compute, ctypes.byref(h)) == OK
+    assert mock.mock_release_after(e.c, h.value, e.compute) == OK
+    mock.mock_pump(e.c)
+    assert mock.mock_swap_out_done(e.c, h.value, ctypes.byref(done)) == OK and done.value == 1
+    assert e.state(h.value) == ON_HOST
+    assert mock.mock_release(e.c, h.value) == OK
+    e.close()
+
+
+def test_poison_mode_overwrites_blocks_whose_tensor_went_to_the_host(mock):
+    e = Env(mock)
+    mock.mock_set_poison(e.c, 1)
+    h = ctypes.c_int(-1)
+    assert mock.mock_swap_out(e.c, e.dev.ctypes.data, e.n, e.host.ctypes.data, e.compute, ctypes.byref(h)) == OK
+    assert mock.mock_release_after(e.c, h.value, e.compute) == OK
+    assert np.array_equal(e.dev, e.orig)                # ordered behind the copy: nothing ran yet
+    mock.mock_pump(e.c)
+    assert np.array_equal(e.host, e.orig)               # the copy saw the data, then the block was poisoned
+    assert np.all(e.dev == 0xFF)
+    back = np.zeros(e.n, dtype=np.uint8)
+    assert mock.mock_prefetch_in(e.c, h.value, back.ctypes.data, e.compute) == OK
+    mock.mock_pump(e.c)
+    assert np.array_equal(back, e.orig)
+    assert mock.mock_evict(e.c, h.value, e.compute) == OK   # dropped again without a copy: poisoned too
+    mock.mock_pump(e.c)
+    assert np.all(back == 0xFF)
+    again = np.zeros(e.n, dtype=np.uint8)
+    assert mock.mock_prefetch_in(e.c, h.value, again.ctypes.data, e.compute) == OK
+    mock.mock_pump(e.c)
+    assert np.array_equal(again, e.orig)
+    assert mock.mock_release(e.c, h.value) == OK
+    # switched off: blocks are left alone
+    mock.mock_set_poison(e.c, 0)
+    e.dev[:] = e.orig
+    assert mock.mock_swap_out(e.c, e.dev.ctypes.data, e.n, e.host.ctypes.data, e.compute, ctypes.byref(h)) == OK
+    assert mock.mock_release_after(e.c, h.value, e.compute) == OK
+    mock.mock_pump(e.c)
+    assert np.array_equal(e.dev, e.orig)
     assert mock.mock_release(e.c, h.value) == OK
     e.close()

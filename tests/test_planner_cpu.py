@@ -278,3 +278,68 @@ def test_random_plans_keep_the_interpreter_consistent():
         assert ex.bytes_in <= sum(p.tensors[g.tensor].nbytes for g in chosen)
         assert be.seconds >= planner.simulate(p, fixed_bytes=1000)[1].seconds - 1e-12
     assert ran > 20 and refused > 0
+
+
+class _FenceCheckingBackend:
+    """Backend that tracks, per tensor, whether its copy-in has been fenced on the compute stream:
+    a call that touches a tensor whose prefetch was started and not waited for is a read-before-copy."""
+
+    def __init__(self):
+        self.unfenced = set()     # handles with a prefetch started and no wait yet
+        self.handle_of = {}       # block serial -> handle
+        self.serial = 0
+        self.next_handle = 0
+        self.violations = []
+
+    def slab(self, nbytes):
+        pass
+
+    def alloc(self, info, offset):
+        self.serial += 1
+        return (info.name, self.serial)
+
+    def free(self, block):
+        pass
+
+    def swap_out(self, info, block):
+        self.next_handle += 1
+        return self.next_handle
+
+    def release_after(self, h):
+        pass
+
+    def prefetch_start(self, h, block):
+        self.unfenced.add(h)
+        self.handle_of[block[1]] = h
+
+    def wait_in(self, h):
+        self.unfenced.discard(h)
+
+    def evict(self, h):
+        pass
+
+    def release(self, h):
+        pass
+
+    def call(self, c, blocks):
+        for t in c.touches():
+            b = blocks.get(t)
+            if b is not None and self.handle_of.get(b[1]) in self.unfenced:
+                self.violations.append((c.fn, c.layer, t))
+
+
+def test_every_reader_of_an_incoming_tensor_is_fenced_even_with_zero_lead():
+    """Prefetch positions equal to the reader call (gaps(min_calls=1), lead 0, explicit at = last):
+    the wait must come after the prefetch it fences, or the reader runs before its copy."""
+    p = unet_program(8, 1, 3, 1, 16, 16, 16)
+    for gaps, lead, at in [(p.gaps(1), 1, None), (p.gaps(), 0, None),
+                           (p.gaps(), 2, {(g.tensor, g.index): g.last for g in p.gaps()})]:
+        ins = p.instructions(gaps, lead, at)
+        # static order: no ("wait", t) directly precedes the ("prefetch", t) it belongs to
+        for i in range(len(ins) - 1):
+            assert not (ins[i][0] == "wait" and ins[i + 1] == ("prefetch", ins[i][1])), ins[i]
+        be = _FenceCheckingBackend()
+        ex = Executor(be, p, budget=None, eager=True)
+        ex.run(ins, {"x": ("x", -1), "labels": ("labels", -2)})
+        assert not be.violations, be.violations[:3]
+        assert ex.bytes_in > 0
