@@ -52,14 +52,20 @@ def test_unet_step_matches_oracle(orc, base, levels, size, n, dt):
     net.close()
 
 
-def test_unet_forward_per_kernel_parity(orc):
-    """Each conv / pool / upconv output against the oracle applied to the GPU's own input tensors."""
+@pytest.mark.parametrize("levels,size", [(3, 16), (4, 128)], ids=["small", "cfg3_in_full"])
+def test_unet_forward_per_kernel_parity(orc, levels, size):
+    """Each conv / pool / upconv output against the oracle applied to the GPU's own input tensors,
+    and the loss against the oracle's head on the GPU's last activation.  The second case is
+    workload config 3 in full (base 32, 1 x 128^3, 4 levels): the oracle runs the whole forward
+    pass of that step once (0.9 TFLOP of fp64 loops; its time is printed)."""
+    import time
     from gpu_util import to_f64, rel_l2
-    base, levels = 32, 3
-    net, (loss, acts), params, x, lab = _run(base, levels, 16, 1, "bf16", keep=True)
+    base = 32
+    net, (loss, acts), params, x, lab = _run(base, levels, size, 1, "bf16", keep=True)
     P = {k: v.astype(np.float64) for k, v in params.items()}
     A = {k: to_f64(v) for k, v in acts.items()}
     A["x"] = x.astype(np.float64)
+    t0 = time.perf_counter()
     prev = "x"
     for l in range(levels):
         e = rel_l2(A[f"enc{l}.a1"], orc.conv3d_fwd(A[prev], P[f"enc{l}.conv1.w"], P[f"enc{l}.conv1.b"], relu=True))
@@ -76,9 +82,13 @@ def test_unet_forward_per_kernel_parity(orc):
         cat = np.concatenate([A[f"enc{l}.a2"], A[f"dec{l}.up"]], axis=-1)
         e = rel_l2(A[f"dec{l}.a1"], orc.conv3d_fwd(cat, P[f"dec{l}.conv1.w"], P[f"dec{l}.conv1.b"], relu=True))
         assert e < 4e-3, (l, e)
+        del cat
         e = rel_l2(A[f"dec{l}.a2"], orc.conv3d_fwd(A[f"dec{l}.a1"], P[f"dec{l}.conv2.w"], P[f"dec{l}.conv2.b"], relu=True))
         assert e < 4e-3, (l, e)
         cur = A[f"dec{l}.a2"]
+    ref = orc.head_softmax_ce(cur, P["head.w"], P["head.b"], lab)
+    assert abs(loss.item() - ref["loss"]) < 1e-5 * abs(ref["loss"]), (loss.item(), ref["loss"])
+    print(f"oracle forward pass of the {levels}-level base-{base} U-Net at 1 x {size}^3: {time.perf_counter() - t0:.1f} s")
     net.close()
 
 
