@@ -286,15 +286,8 @@ def bench_layers(args, mfma_measured):
     bf = torch.bfloat16
     out = []
     for (n, s, c) in ((2, 128, 64), (2, 64, 128), (1, 128, 32)):
-        x = torch.from_numpy(synth.activations(11, (n, s, s, s, c), "bf16")).cuda().to(bf)
-        g = torch.from_numpy(synth.activations(12, (n, s, s, s, c), "bf16")).cuda().to(bf)
-        w = torch.from_numpy(synth.conv_weights(13, c, c, "bf16")).cuda().to(bf)
-        b = torch.zeros(c, device="cuda")
-        pk = torch.empty(k3.conv3d_packed_bytes(c, c, k3.BF16), device="cuda", dtype=torch.uint8)
-        k3.conv3d_pack_weights(w, pk)
-        y, dx = torch.empty_like(x), torch.empty_like(x)
-        dW, db = torch.empty((3, 3, 3, c, c), device="cuda"), torch.empty(c, device="cuda")
-        ws = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(x, g), device="cuda", dtype=torch.uint8)
+        t = layer_tensors(n, s, c)
+        x, g, w, b, pk, y, dx, dW, db, ws = (t[k] for k in ("x", "g", "w", "b", "pk", "y", "dx", "dW", "db", "ws"))
         fl = conv_flops(n, s, s, s, c, c)
         it = 10 if n * s ** 3 * c > (1 << 26) else 20
         ms = {"fwd": time_calls(lambda: k3.conv3d_fwd(x, w, pk, b, 1, y), it, graph=True),
@@ -306,7 +299,7 @@ def bench_layers(args, mfma_measured):
             row[k] = {"ms": round(v, 4), "tflops": round(tf, 1), "frac": round(tf / MFMA_BF16_PEAK_TFLOPS, 4),
                       "frac_of_measured": round(tf / mfma_measured, 4) if mfma_measured else None}
         out.append(row)
-        del x, g, y, dx, ws
+        del t, x, g, y, dx, ws
     return out
 
 
@@ -346,9 +339,47 @@ def load_traffic(kernel, workload):
 
 
 # ----------------------------------------------------------------------------- HBM traffic counters
+def layer_tensors(n, s, c):
+    """Seeded tensors, packed weights and outputs of one n x s^3, c -> c layer."""
+    import torch
+    import synth
+    from paper_1811_12174_amd import k3
+    bf = torch.bfloat16
+    t = {}
+    if n * s ** 3 * c <= (1 << 28):
+        t["x"] = torch.from_numpy(synth.activations(11, (n, s, s, s, c), "bf16")).cuda().to(bf)
+        t["g"] = torch.from_numpy(synth.activations(12, (n, s, s, s, c), "bf16")).cuda().to(bf)
+    else:   # the host generator would need minutes: seeded N(0,1) values made on the device
+        gen = torch.Generator(device="cuda")
+        gen.manual_seed(181112174)
+        t["x"] = torch.empty((n, s, s, s, c), device="cuda", dtype=bf)
+        t["g"] = torch.empty((n, s, s, s, c), device="cuda", dtype=bf)
+        for i in range(n):
+            t["x"][i] = torch.randn((s, s, s, c), device="cuda", generator=gen).to(bf)
+            t["g"][i] = torch.randn((s, s, s, c), device="cuda", generator=gen).to(bf)
+    t["w"] = torch.from_numpy(synth.conv_weights(13, c, c, "bf16")).cuda().to(bf)
+    t["b"] = torch.zeros(c, device="cuda")
+    t["pk"] = torch.empty(k3.conv3d_packed_bytes(c, c, k3.BF16), device="cuda", dtype=torch.uint8)
+    k3.conv3d_pack_weights(t["w"], t["pk"])
+    t["y"], t["dx"] = torch.empty_like(t["x"]), torch.empty_like(t["x"])
+    t["dW"], t["db"] = torch.empty((3, 3, 3, c, c), device="cuda"), torch.empty(c, device="cuda")
+    t["ws"] = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(t["x"], t["g"]), device="cuda", dtype=torch.uint8)
+    return t
+
+
+def run_layer(t, reps):
+    from paper_1811_12174_amd import k3
+    for _ in range(reps):
+        k3.conv3d_fwd(t["x"], t["w"], t["pk"], t["b"], 1, t["y"])
+        k3.conv3d_bwd_data(t["g"], None, t["w"], t["pk"], t["dx"])
+        k3.conv3d_bwd_weight(t["x"], t["g"], None, t["dW"], t["db"], t["ws"])
+
+
 def pmc_pass(args):
-    """Workload for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE`: a device copy of known size (the
-    calibration of the counter) followed by a few launches of every cfg2 call."""
+    """Workload for `rocprofv3 --pmc FETCH_SIZE` / `--pmc WRITE_SIZE` (and for kernel traces of single
+    layers): a device copy of known size (the calibration of the counter) followed by a few launches of
+    every cfg2 call, or -- with --layer N,S,C -- of the forward, backward-data and backward-weight pass
+    of one N x S^3, C -> C layer."""
     import torch
     import synth
     from paper_1811_12174_amd import k3
@@ -358,6 +389,13 @@ def pmc_pass(args):
     dst = torch.empty_like(src)
     for _ in range(3):
         torch.add(src, 1.0, out=dst)   # a plain elementwise kernel: reads 256 MiB, writes 256 MiB
+    if args.layer:
+        n, s, c = args.layer
+        run_layer(layer_tensors(n, s, c), args.layer_reps)
+        torch.cuda.synchronize()
+        print(json.dumps({"pmc_pass": "done", "layer": [n, s, c], "copy_bytes_read": src.numel() * 4,
+                          "copy_bytes_written": src.numel() * 4}))
+        return
     x = torch.from_numpy(synth.activations(1, (N, S, S, S, C), "bf16")).cuda().to(bf)
     w = torch.from_numpy(synth.conv_weights(2, C, C, "bf16")).cuda().to(bf)
     dyp = torch.from_numpy(synth.activations(4, (N, S // 2, S // 2, S // 2, C), "bf16")).cuda().to(bf)
@@ -381,8 +419,9 @@ def pmc_pass(args):
     print(json.dumps({"pmc_pass": "done", "copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4}))
 
 
-def pmc_parse(fetch_csv, write_csv):
-    """Turns the two counter_collection.csv files of the pmc passes into profiles/traffic.json."""
+def pmc_parse(fetch_csv, write_csv, key="cfg2"):
+    """Turns the two counter_collection.csv files of a pair of pmc passes into the entry `key` of
+    profiles/traffic.json (other entries of the file are kept)."""
     import csv
     import collections
 
@@ -397,31 +436,53 @@ def pmc_parse(fetch_csv, write_csv):
         return {k: acc[k] / cnt[k] for k in acc}
 
     fetch, write = per_kernel(fetch_csv, "FETCH_SIZE"), per_kernel(write_csv, "WRITE_SIZE")
-    copy = sorted((k for k in fetch if "elementwise" in k), key=lambda k: -fetch[k])[:1]   # the 256 MiB one
+    copy = [k for k in fetch if "FunctorOnSelf_add" in k][:1]   # the 256 MiB elementwise add of the pass
     if not copy:
         raise SystemExit("no copy kernel found in the counter files")
     known = float(64 << 20) * 4
     f_scale = known / (fetch[copy[0]] * 1024.0)    # counters are in KiB per dispatch
     w_scale = known / (write[copy[0]] * 1024.0)
-    out = {"_calibration": {"copy_kernel": copy[0], "known_bytes_each_way": known,
-                            "fetch_counter_kib": fetch[copy[0]], "write_counter_kib": write[copy[0]],
-                            "fetch_scale": f_scale, "write_scale": w_scale}, "cfg2": {}}
+    path = os.path.join(ROOT, "profiles", "traffic.json")
+    try:
+        with open(path) as f:
+            out = json.load(f)
+    except (OSError, ValueError):
+        out = {}
+    cal = {"copy_kernel": copy[0], "known_bytes_each_way": known, "fetch_counter_kib": fetch[copy[0]],
+           "write_counter_kib": write[copy[0]], "fetch_scale": f_scale, "write_scale": w_scale}
+    out.setdefault("_calibration", {})
+    if "copy_kernel" in out["_calibration"]:      # older layout: one calibration for the file
+        out["_calibration"] = {"cfg2": out["_calibration"]}
+    out["_calibration"][key] = cal
+    out[key] = {}
     for k in fetch:
         if "k3::" not in k:
             continue
         short = k.split("k3::")[1].split("<")[0].split("(")[0]
         fb, wb = fetch[k] * 1024.0 * f_scale, write.get(k, 0.0) * 1024.0 * w_scale
-        rec = out["cfg2"].setdefault(short, {"variants": {}})
+        rec = out[key].setdefault(short, {"variants": {}})
         rec["variants"][k] = {"fetch_bytes": round(fb), "write_bytes": round(wb)}
-    for short, rec in out["cfg2"].items():
+    for short, rec in out[key].items():
         v = list(rec["variants"].values())
         rec["fetch_bytes"] = round(sum(x["fetch_bytes"] for x in v) / len(v))
         rec["write_bytes"] = round(sum(x["write_bytes"] for x in v) / len(v))
         rec["bytes_per_launch"] = rec["fetch_bytes"] + rec["write_bytes"]
-    path = os.path.join(ROOT, "profiles", "traffic.json")
     with open(path, "w") as f:
         json.dump(out, f, indent=1, sort_keys=True)
-    print("wrote", path)
+    print("wrote", path, "entry", key)
+
+
+def stats_md(csv_path, top=12):
+    """rocprofv3's kernel_stats.csv as a markdown table (durations in microseconds), for profiles/*.md."""
+    import csv
+    import re
+    rows = list(csv.DictReader(open(csv_path)))
+    out = ["| kernel | calls | total us | avg us | min us | max us | % |", "|---|---|---|---|---|---|---|"]
+    for r in rows[:top]:
+        name = re.sub(r"\(.*$", "", r["Name"])[:110]
+        out.append(f"| `{name}` | {r['Calls']} | {float(r['TotalDurationNs']) / 1e3:.1f} | {float(r['AverageNs']) / 1e3:.2f} | "
+                   f"{float(r['MinNs']) / 1e3:.2f} | {float(r['MaxNs']) / 1e3:.2f} | {float(r['Percentage']):.2f} |")
+    print("\n".join(out))
 
 
 # ----------------------------------------------------------------------------- U-Net steps
@@ -712,10 +773,19 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-pass", action="store_true", help="run the short workload the HBM-traffic counters are collected on")
     ap.add_argument("--pmc-parse", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"),
-                    help="write profiles/traffic.json from the counter files of two --pmc-pass runs")
+                    help="write an entry of profiles/traffic.json from the counter files of two --pmc-pass runs")
+    ap.add_argument("--pmc-key", default="cfg2", help="name of that entry (the workload the passes ran)")
+    ap.add_argument("--layer", type=lambda v: tuple(int(x) for x in v.split(",")), default=None, metavar="N,S,C",
+                    help="--pmc-pass: run the three passes of one N x S^3, C -> C layer instead of the cfg2 calls")
+    ap.add_argument("--layer-reps", type=int, default=5)
+    ap.add_argument("--stats-md", default="", metavar="KERNEL_STATS_CSV",
+                    help="print rocprofv3's kernel_stats.csv as a markdown table and exit")
     args = ap.parse_args()
     if args.pmc_parse:
-        pmc_parse(*args.pmc_parse)
+        pmc_parse(*args.pmc_parse, key=args.pmc_key)
+        return
+    if args.stats_md:
+        stats_md(args.stats_md)
         return
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (the paper's multi-GPU all-reduce is out of scope); use --gpus 1",
