@@ -6,19 +6,26 @@ Default workload ("cfg2"): the 3-D U-Net encoder block -- two 3x3x3 conv + ReLU 
 accumulation, forward + backward (both weight gradients, both data gradients, pool
 backward).  A step is one pass of that block; the step is captured in a HIP graph so the
 ~10 kernel launches are not bound by host launch latency.  The headline value is the
-exact (in-bounds) convolution FLOPs of the step divided by the step time.
+exact (in-bounds) convolution FLOPs of the step divided by the step time; the same K steps
+are timed five more times and the spread (min / median / max) is reported beside it.
+
+The default run also carries the rest of the metric (skipped with --quick):
+"peaks_measured" -- this box's own matrix-core and HBM rates (a register-resident bf16 MFMA
+loop, a device copy), against which every rate is printed beside the nominal peaks;
+"layers" -- per-launch time and TFLOP/s of single 3x3x3 layers at the shapes that carry the
+large U-Net steps; "unet" -- the base-64 U-Net step on 2 x 256^3 (workload config 4)
+without swapping, with every stored encoder activation swapped, and under a device-memory
+budget of three quarters of its unswapped footprint (refused without swapping, completed
+with the planner's swap plan): voxels/s, overhead, overlap fraction and the link rates the
+copies reached against the box's own pinned-memory copy rates.
 
 Other workloads: "unet128" (full 4-level U-Net, base 32, 1 x 128^3, no swapping),
-"unet256" (base 64, 2 x 256^3) and "unet320" (base 64, 4 x 320^3); they report voxels/s
-without swapping and, for the two large ones, (1) with every stored encoder activation swapped
-and (2) under a device-memory budget (--budget-gb, default three quarters of what the step
-holds unswapped): without swapping the step is refused, with the swap plan the planner makes
-for that budget it runs.  The "unet" object reports for each its time, its footprint, the
-bytes moved each way, the time of the same copies without the kernels, the overlap fraction
-and the link rates (with the box's pinned-memory copy rates beside them).  "bp64" / "bp96" time
+"unet256" (base 64, 2 x 256^3) and "unet320" (base 64, 4 x 320^3) print the unabridged
+"unet" object (the plan listings included; --budget-gb sets the budget).  "bp64" / "bp96" time
 the paper's second model (section 4.1: two conv+pool encoder layers, two conv+up-sampling
 decoder layers, 128 channels, batch of 8 blocks, class-weighted loss) in training and inference.  "sweep" plans
 and runs a row of resolutions under one fixed budget and reports the swap overhead of each.
+--pmc-pass / --pmc-parse / --stats-md are the helpers the summaries under profiles/ were made with.
 
 Prints ONE JSON line on stdout.
 """
@@ -126,6 +133,26 @@ def bench_cfg2(args):
         with torch.cuda.graph(graph):
             step()
         run = graph.replay
+    # per-call timings (events on the launch stream), same launch configuration as the step
+    it = max(20, args.steps // 4)
+    gr = not args.no_graph
+    kern = {
+        "conv3d_fwd": time_calls(lambda: k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2), it, graph=gr),
+        "conv3d_bwd_data": time_calls(lambda: k3.conv3d_bwd_data_bits(da2, None, w2, pk2, da1, a1bits), it, graph=gr),
+        "conv3d_bwd_weight": time_calls(lambda: k3.conv3d_bwd_weight(a1, da2, None, dW2, db2, ws), it, graph=gr),
+        # (the fused convolution + pool call saves a launch but lengthens the convolution by as much: not used in the step)
+        "conv3d_fwd_pool": time_calls(lambda: k3.conv3d_fwd_pool(a1, w2, pk2, b2, 1, a2, p), it, graph=gr),
+        "pool3d_fwd": time_calls(lambda: k3.pool3d_fwd(a2, p), it, graph=gr),
+        "pool3d_bwd": time_calls(lambda: k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True), it, graph=gr),
+    }
+
+    def mix():   # the implicit-GEMM kernel as the step launches it: 2 forward + 2 backward-data passes
+        k3.conv3d_fwd_bits(x, w1, pk1, b1, 1, a1, a1bits)
+        k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2)
+        k3.conv3d_bwd_data_bits(da2, None, w2, pk2, da1, a1bits)
+        k3.conv3d_bwd_data(da1, None, w1, pk1, dx)
+    mfma_ms = time_calls(mix, it, graph=not args.no_graph) / 4.0
+    # the step itself, timed last: the GPU has then been busy for a while and holds its steady clocks
     for _ in range(args.warmup):
         run()
     torch.cuda.synchronize()
@@ -149,25 +176,6 @@ def bench_cfg2(args):
     step_flops = 6 * f1
     value = step_flops / (ms * 1e-3) / 1e12
 
-    # per-call timings (events on the launch stream), same launch configuration as the step
-    it = max(20, args.steps // 4)
-    gr = not args.no_graph
-    kern = {
-        "conv3d_fwd": time_calls(lambda: k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2), it, graph=gr),
-        "conv3d_bwd_data": time_calls(lambda: k3.conv3d_bwd_data_bits(da2, None, w2, pk2, da1, a1bits), it, graph=gr),
-        "conv3d_bwd_weight": time_calls(lambda: k3.conv3d_bwd_weight(a1, da2, None, dW2, db2, ws), it, graph=gr),
-        # (the fused convolution + pool call saves a launch but lengthens the convolution by as much: not used in the step)
-        "conv3d_fwd_pool": time_calls(lambda: k3.conv3d_fwd_pool(a1, w2, pk2, b2, 1, a2, p), it, graph=gr),
-        "pool3d_fwd": time_calls(lambda: k3.pool3d_fwd(a2, p), it, graph=gr),
-        "pool3d_bwd": time_calls(lambda: k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True), it, graph=gr),
-    }
-
-    def mix():   # the implicit-GEMM kernel as the step launches it: 2 forward + 2 backward-data passes
-        k3.conv3d_fwd_bits(x, w1, pk1, b1, 1, a1, a1bits)
-        k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2)
-        k3.conv3d_bwd_data_bits(da2, None, w2, pk2, da1, a1bits)
-        k3.conv3d_bwd_data(da1, None, w1, pk1, dx)
-    mfma_ms = time_calls(mix, it, graph=not args.no_graph) / 4.0
     # (the weight-gradient call is two launches: the MFMA kernel and the small split-K reduction)
     wgrad_ms = kern["conv3d_bwd_weight"]
     share = {"conv_mfma_zs_kernel": 4 * mfma_ms, "conv_wgrad_pipe_kernel": 2 * wgrad_ms}
