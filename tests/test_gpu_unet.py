@@ -92,6 +92,52 @@ def test_unet_forward_per_kernel_parity(orc, levels, size):
     net.close()
 
 
+def test_config3_step_in_full_against_the_chained_oracle(orc):
+    """Workload config 3 end to end: the whole training step (base 32, 4 levels, 1 x 128^3, bf16) on the
+    GPU against ONE run of the oracle's chained step with bf16 storage emulation (2.7 TFLOP of fp64 loops,
+    about a minute and a half on the machine's host cores; progress goes to gpurun_out/cfg3_full_step.log).
+    Checked at the stated 2e-2: the loss, every chained forward activation and EVERY parameter gradient.
+    (On the scaled-down nets of test_unet_step_matches_oracle single ReLU-sign or arg-max flips move a
+    deep gradient by several percent and the bound there follows the oracle's own sensitivity; at this
+    size, on the smooth synthetic volume, they average out: measured worst 4.0e-3.)"""
+    import os
+    import time
+    from oracle.unet import unet_step
+    from gpu_util import to_f64, rel_l2
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
+    log = open(os.path.join(root, "gpurun_out", "cfg3_full_step.log"), "w")
+
+    def say(msg):
+        log.write(msg + "\n")
+        log.flush()
+    base, levels, size = 32, 4, 128
+    net, (loss, acts), params, x, lab = _run(base, levels, size, 1, "bf16", keep=True)
+    say(f"GPU step done, loss {loss.item():.6f}")
+    p64 = {k: v.astype(np.float64) for k, v in params.items()}
+    t0 = time.perf_counter()
+    # the oracle's operators report through the store hook after every stored tensor
+    count = [0]
+
+    def store(t):
+        count[0] += 1
+        say(f"oracle stored tensor {count[0]} after {time.perf_counter() - t0:.1f} s")
+        return orc.round_bf16(t)
+    rl, rg, ra = unet_step(x.astype(np.float64), lab, p64, base=base, levels=levels, store=store)
+    say(f"oracle step done in {time.perf_counter() - t0:.1f} s, loss {rl:.6f}")
+    assert abs(loss.item() - rl) < 2e-2 * abs(rl), (loss.item(), rl)
+    for k, t in acts.items():
+        e = rel_l2(to_f64(t), ra[k])
+        say(f"activation {k}: {e:.3e}")
+        assert e < 2e-2, (k, e)
+    for k, g in net.grads().items():
+        e = rel_l2(to_f64(g), rg[k])
+        say(f"gradient {k}: {e:.3e}")
+        assert e < 2e-2, (k, e)
+    log.close()
+    net.close()
+
+
 @pytest.mark.parametrize("base,levels,size", [(32, 4, 32), (4, 3, 16)])
 def test_swapping_is_bit_identical(base, levels, size):
     """The step with every encoder activation spending its idle gaps in host memory gives exactly
