@@ -427,7 +427,7 @@ def pmc_pass(args):
     print(json.dumps({"pmc_pass": "done", "copy_bytes_read": src.numel() * 4, "copy_bytes_written": src.numel() * 4}))
 
 
-def pmc_parse(fetch_csv, write_csv, key="cfg2"):
+def pmc_parse(fetch_csv, write_csv, key="cfg2", path=None):
     """Turns the two counter_collection.csv files of a pair of pmc passes into the entry `key` of
     profiles/traffic.json (other entries of the file are kept)."""
     import csv
@@ -450,7 +450,7 @@ def pmc_parse(fetch_csv, write_csv, key="cfg2"):
     known = float(64 << 20) * 4
     f_scale = known / (fetch[copy[0]] * 1024.0)    # counters are in KiB per dispatch
     w_scale = known / (write[copy[0]] * 1024.0)
-    path = os.path.join(ROOT, "profiles", "traffic.json")
+    path = path or os.path.join(ROOT, "profiles", "traffic.json")
     try:
         with open(path) as f:
             out = json.load(f)
