@@ -6,6 +6,8 @@ import pytest
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
+# where GPU test runs leave what they measured (worst parity errors, progress of long oracle runs)
+RUN_OUTPUT_DIR = os.path.join(ROOT, "gpurun_out")
 
 
 def pytest_configure(config):
@@ -25,7 +27,7 @@ def pytest_sessionfinish(session, exitstatus):
     if mod is None or not getattr(mod, "MEASURED", None):
         return
     import json
-    out = os.path.join(ROOT, "gpurun_out")
+    out = RUN_OUTPUT_DIR
     os.makedirs(out, exist_ok=True)
     rows = sorted(({"file": k[0], "test": k[1], "line": k[2], "max_rel_l2": v} for k, v in mod.MEASURED.items()),
                   key=lambda r: (r["file"], r["line"]))

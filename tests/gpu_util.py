@@ -28,7 +28,7 @@ MEASURED = {}   # (test function, line) -> largest relative L2 error seen there 
 
 def rel_l2(got, ref, depth=1, tag=""):
     """Relative L2 distance; every value is also noted under the calling test and line (the
-    session's worst cases are written to gpurun_out/measured_errors.json by conftest.py)."""
+    session's worst cases are written to measured_errors.json in the run's output folder by conftest.py)."""
     ref = np.asarray(ref, dtype=np.float64)
     got = np.asarray(got, dtype=np.float64)
     den = np.linalg.norm(ref.reshape(-1))

@@ -95,7 +95,7 @@ def test_unet_forward_per_kernel_parity(orc, levels, size):
 def test_config3_step_in_full_against_the_chained_oracle(orc):
     """Workload config 3 end to end: the whole training step (base 32, 4 levels, 1 x 128^3, bf16) on the
     GPU against ONE run of the oracle's chained step with bf16 storage emulation (2.7 TFLOP of fp64 loops,
-    about a minute and a half on the machine's host cores; progress goes to gpurun_out/cfg3_full_step.log).
+    about a minute and a half on the machine's host cores; progress goes to cfg3_full_step.log in the run's output folder).
     Checked at the stated 2e-2: the loss, every chained forward activation and EVERY parameter gradient.
     (On the scaled-down nets of test_unet_step_matches_oracle single ReLU-sign or arg-max flips move a
     deep gradient by several percent and the bound there follows the oracle's own sensitivity; at this
@@ -104,9 +104,9 @@ def test_config3_step_in_full_against_the_chained_oracle(orc):
     import time
     from oracle.unet import unet_step
     from gpu_util import to_f64, rel_l2
-    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
-    os.makedirs(os.path.join(root, "gpurun_out"), exist_ok=True)
-    log = open(os.path.join(root, "gpurun_out", "cfg3_full_step.log"), "w")
+    from conftest import RUN_OUTPUT_DIR
+    os.makedirs(RUN_OUTPUT_DIR, exist_ok=True)
+    log = open(os.path.join(RUN_OUTPUT_DIR, "cfg3_full_step.log"), "w")
 
     def say(msg):
         log.write(msg + "\n")
