@@ -156,12 +156,33 @@ __global__ __launch_bounds__(256) void head_stream_kernel(const bf16_t *__restri
     const float b0 = bh ? bh[0] : 0.f, b1 = bh ? bh[1] : 0.f, b2 = bh ? bh[2] : 0.f;
     float lossacc = 0.f, db0 = 0.f, db1 = 0.f, db2 = 0.f;
     const int64_t nstep = (V + VPB - 1) / VPB;
+    // The loads of the next step are requested before this step is computed: one 32-byte load
+    // per thread and iteration leaves too few bytes in flight to cover the memory latency.
+    auto voxel_of = [&](int64_t st) __attribute__((always_inline)) {
+        const int64_t v = st * VPB + tid / LPV;
+        return v < V ? v : V - 1;
+    };
+    uint4 n0 = make_uint4(0u, 0u, 0u, 0u), n1 = n0;
+    int nlab = 0;
+    if ((int64_t)blockIdx.x < nstep) {
+        const int64_t vv = voxel_of(blockIdx.x);
+        const uint4 *src = reinterpret_cast<const uint4 *>(a + vv * C + sub * 16);
+        n0 = src[0];
+        n1 = src[1];
+        nlab = labels[vv];
+    }
     for (int64_t st = blockIdx.x; st < nstep; st += gridDim.x) {
         const int64_t v = st * VPB + tid / LPV;
         const bool on = v < V;
-        const int64_t vv = on ? v : V - 1;
-        const uint4 *src = reinterpret_cast<const uint4 *>(a + vv * C + sub * 16);
-        const uint4 r0 = src[0], r1 = src[1];
+        const uint4 r0 = n0, r1 = n1;
+        const int lab = nlab;
+        if (st + gridDim.x < nstep) {
+            const int64_t vn = voxel_of(st + gridDim.x);
+            const uint4 *src = reinterpret_cast<const uint4 *>(a + vn * C + sub * 16);
+            n0 = src[0];
+            n1 = src[1];
+            nlab = labels[vn];
+        }
         const uint32_t raw[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
         float av[16];
 #pragma unroll
@@ -183,7 +204,6 @@ __global__ __launch_bounds__(256) void head_stream_kernel(const bf16_t *__restri
             z2 += __shfl_xor(z2, m);
         }
         z0 += b0; z1 += b1; z2 += b2;
-        const int lab = labels[vv];
         const float mx = fmaxf(z0, fmaxf(z1, z2));
         const float e0 = expf(z0 - mx), e1 = expf(z1 - mx), e2 = expf(z2 - mx);
         const float den = e0 + e1 + e2, inv = 1.f / den;
@@ -375,12 +395,29 @@ __global__ __launch_bounds__(256) void head_classify_stream_kernel(const bf16_t 
     }
     const float b0 = bh ? bh[0] : 0.f, b1 = bh ? bh[1] : 0.f, b2 = bh ? bh[2] : 0.f;
     const int64_t nstep = (V + VPB - 1) / VPB;
+    // The loads of the next step are requested before this step is computed: one 32-byte load
+    // per thread and iteration leaves too few bytes in flight to cover the memory latency.
+    auto voxel_of = [&](int64_t st) __attribute__((always_inline)) {
+        const int64_t v = st * VPB + tid / LPV;
+        return v < V ? v : V - 1;
+    };
+    uint4 n0 = make_uint4(0u, 0u, 0u, 0u), n1 = n0;
+    if ((int64_t)blockIdx.x < nstep) {
+        const int64_t vv = voxel_of(blockIdx.x);
+        const uint4 *src = reinterpret_cast<const uint4 *>(a + vv * C + sub * 16);
+        n0 = src[0];
+        n1 = src[1];
+    }
     for (int64_t st = blockIdx.x; st < nstep; st += gridDim.x) {
         const int64_t v = st * VPB + tid / LPV;
         const bool on = v < V;
-        const int64_t vv = on ? v : V - 1;
-        const uint4 *src = reinterpret_cast<const uint4 *>(a + vv * C + sub * 16);
-        const uint4 r0 = src[0], r1 = src[1];
+        const uint4 r0 = n0, r1 = n1;
+        if (st + gridDim.x < nstep) {
+            const int64_t vn = voxel_of(st + gridDim.x);
+            const uint4 *src = reinterpret_cast<const uint4 *>(a + vn * C + sub * 16);
+            n0 = src[0];
+            n1 = src[1];
+        }
         const uint32_t raw[8] = {r0.x, r0.y, r0.z, r0.w, r1.x, r1.y, r1.z, r1.w};
         float z0 = 0.f, z1 = 0.f, z2 = 0.f;
 #pragma unroll
