@@ -107,17 +107,20 @@ def bench_cfg2(args):
     ws = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(x, a1), device="cuda", dtype=torch.uint8)
 
     a1bits = torch.empty(k3.relu_bits_bytes(a1) // 2, device="cuda", dtype=torch.int16)
+    a2route = torch.empty(k3.relu_bits_bytes(a2) // 2, device="cuda", dtype=torch.int16)
 
     def step():
         # conv1 also writes the one-bit-per-element ReLU mask of its output, which conv2's
         # backward-data pass applies to the gradient it produces
         k3.conv3d_fwd_bits(x, w1, pk1, b1, 1, a1, a1bits)
         k3.conv3d_fwd(a1, w2, pk2, b2, 1, a2)
-        k3.pool3d_fwd(a2, p)
+        # the pooling layer keeps one routing bit per element of a2 (first maximum of its window
+        # and > 0) and its backward pass reads those instead of a2
+        k3.pool3d_fwd_bits(a2, p, a2route)
         # each producer of an activation gradient applies the ReLU mask of the tensor it
         # differentiates (pool backward: a2; conv2 backward-data: a1), so the conv backward
         # passes read no mask
-        k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True)
+        k3.pool3d_bwd_bits(a2route, dyp, da2)
         k3.conv3d_bwd_weight(a1, da2, None, dW2, db2, ws)
         k3.conv3d_bwd_data_bits(da2, None, w2, pk2, da1, a1bits)
         k3.conv3d_bwd_weight(x, da1, None, dW1, db1, ws)
@@ -142,6 +145,9 @@ def bench_cfg2(args):
         "conv3d_bwd_weight": time_calls(lambda: k3.conv3d_bwd_weight(a1, da2, None, dW2, db2, ws), it, graph=gr),
         # (the fused convolution + pool call saves a launch but lengthens the convolution by as much: not used in the step)
         "conv3d_fwd_pool": time_calls(lambda: k3.conv3d_fwd_pool(a1, w2, pk2, b2, 1, a2, p), it, graph=gr),
+        "pool3d_fwd_bits": time_calls(lambda: k3.pool3d_fwd_bits(a2, p, a2route), it, graph=gr),
+        "pool3d_bwd_bits": time_calls(lambda: k3.pool3d_bwd_bits(a2route, dyp, da2), it, graph=gr),
+        # (the forms that keep and re-read a2 instead of the routing bits: not used in the step)
         "pool3d_fwd": time_calls(lambda: k3.pool3d_fwd(a2, p), it, graph=gr),
         "pool3d_bwd": time_calls(lambda: k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True), it, graph=gr),
     }
@@ -415,11 +421,12 @@ def pmc_pass(args):
     dW, db = torch.empty((3, 3, 3, C, C), device="cuda"), torch.empty(C, device="cuda")
     ws = torch.empty(k3.conv3d_bwd_weight_workspace_bytes(x, a1), device="cuda", dtype=torch.uint8)
     a1bits = torch.empty(k3.relu_bits_bytes(a1) // 2, device="cuda", dtype=torch.int16)
+    a2route = torch.empty(k3.relu_bits_bytes(a2) // 2, device="cuda", dtype=torch.int16)
     for _ in range(3):
         k3.conv3d_fwd_bits(x, w, pk, b, 1, a1, a1bits)
         k3.conv3d_fwd(a1, w, pk, b, 1, a2)
-        k3.pool3d_fwd(a2, p)
-        k3.pool3d_bwd(a2, dyp, None, da2, relu_mask=True)
+        k3.pool3d_fwd_bits(a2, p, a2route)
+        k3.pool3d_bwd_bits(a2route, dyp, da2)
         k3.conv3d_bwd_weight(a1, da2, None, dW, db, ws)
         k3.conv3d_bwd_data_bits(da2, None, w, pk, da1, a1bits)
         k3.conv3d_bwd_data(da1, None, w, pk, a2)

@@ -175,6 +175,20 @@ int k3_pool3d_fwd(const k3_tensor *xd, const void *x, const k3_tensor *yd, void 
 int k3_pool3d_bwd(const k3_tensor *xd, const void *x, const k3_tensor *dyd, const void *dy,
                   const void *add, int relu_mask, void *dx, void *stream);
 
+/* The same pair with the backward pass's routing kept as one bit per element of x instead of
+ * x itself, for a pooling layer whose input is a stored ReLU output that nothing else reads
+ * again (the encoder layers of section 4.1's model: the activation can then be dropped, or
+ * need not be swapped, once it is pooled).  k3_pool3d_fwd_bits computes y as k3_pool3d_fwd
+ * does and writes route_bits (dev; layout and size of k3_relu_bits_bytes(xd)): the bit of
+ * x[n,2d+i,2h+j,2w+k,c] is set iff that element is the first maximum of its window (order
+ * i, j, k) and > 0.  k3_pool3d_bwd_bits writes dx = the window's dy where the bit is set and
+ * zero elsewhere, which is what k3_pool3d_bwd(x, dy, add = NULL, relu_mask = 1) computes.
+ * bf16 with c a multiple of 16 only (K3_E_UNSUPPORTED otherwise); shapes as above. */
+int k3_pool3d_fwd_bits(const k3_tensor *xd, const void *x, const k3_tensor *yd, void *y,
+                       void *route_bits, void *stream);
+int k3_pool3d_bwd_bits(const k3_tensor *xd, const void *route_bits, const k3_tensor *dyd,
+                       const void *dy, void *dx, void *stream);
+
 /* ------------------------------------------------------------------ 2x2x2 stride-2 transposed convolution
  * The decoder's up-sampling layer (section 4.1) in its learned form:
  *   y[n,2d+i,2h+j,2w+k,co] = bias[co] + sum_ci x[n,d,h,w,ci] * W[i,j,k,ci,co]

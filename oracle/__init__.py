@@ -258,3 +258,37 @@ def apply_relu_bits(dy, bits):
     for i in range(16):
         keep[..., i] = ((b >> i) & 1).astype(bool)
     return dy * keep.reshape(dy.shape)
+
+
+def _windows(a):
+    """[N, D, H, W, C] -> [N, D/2, H/2, W/2, 8, C]: the eight elements of each 2x2x2 window in the
+    order (i, j, k), i the depth offset."""
+    N, D, H, W, C = a.shape
+    return a.reshape(N, D // 2, 2, H // 2, 2, W // 2, 2, C).transpose(0, 1, 3, 5, 2, 4, 6, 7).reshape(
+        N, D // 2, H // 2, W // 2, 8, C)
+
+
+def _unwindows(a):
+    N, Do, Ho, Wo, _, C = a.shape
+    return a.reshape(N, Do, Ho, Wo, 2, 2, 2, C).transpose(0, 1, 4, 2, 5, 3, 6, 7).reshape(N, 2 * Do, 2 * Ho, 2 * Wo, C)
+
+
+def pool3d_route_bits(x):
+    """Routing of the 2x2x2 max-pool's backward pass (section 4.1) as one bit per element of x, in
+    the layout of relu_bits: the bit is set iff the element is the first maximum of its window
+    (order i, j, k) and > 0, i.e. where the pooled gradient arrives and passes the ReLU that
+    produced x.  Pinned in tests/test_oracle_pool_upconv_head.py against pool3d_bwd + relu_bwd."""
+    x = np.asarray(x, dtype=np.float64)
+    xw = _windows(x)
+    first = np.argmax(xw, axis=4)                       # numpy: the first of equal maxima
+    hit = np.arange(8).reshape(1, 1, 1, 1, 8, 1) == first[:, :, :, :, None, :]
+    hit &= (np.max(xw, axis=4) > 0)[:, :, :, :, None, :]
+    return relu_bits(_unwindows(hit).astype(np.float64))
+
+
+def pool3d_bwd_bits(bits, dy):
+    """dx[n, 2d+i, 2h+j, 2w+k, c] = dy[n, d, h, w, c] where the element's routing bit is set, else 0."""
+    dy = np.asarray(dy, dtype=np.float64)
+    spread = _unwindows(np.repeat(dy[:, :, :, :, None, :], 8, axis=4))
+    return apply_relu_bits(spread, bits)
+

@@ -130,6 +130,94 @@ static int pool_launch(bool bwd, const void *x, const void *dy, const void *add,
     return K3_OK;
 }
 
+// Forward pooling that also writes the backward pass's routing as one bit per INPUT element, in
+// the layout of the ReLU bit masks (a uint16 word per 16 channels of a voxel): the bit is set
+// where the element is the first maximum of its window (order i, j, k; strict >, as
+// pool_bwd_kernel decides) and greater than zero, i.e. where the pooled gradient arrives AND
+// passes the ReLU that produced x.  One thread: 8 channels of one output window, i.e. one byte of
+// bits per input voxel; the lanes of a pair (QUAD: of a quad, when C is a multiple of 32) hold
+// neighbouring bytes of the same voxel, exchange them across lanes and the first lane stores the
+// word (C / 8 is even, and a multiple of 4 with QUAD, so pairs / quads never straddle a voxel or
+// the end of the grid).
+template <bool QUAD>
+__global__ __launch_bounds__(256) void pool_fwd_bits_kernel(const bf16_t *__restrict__ x, bf16_t *__restrict__ y,
+                                                           unsigned char *__restrict__ route, int64_t total, int D, int H,
+                                                           int W, int C)
+{
+    int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= total) return;
+    int cv = C / 8;
+    int c = (int)(gid % cv) * 8;
+    int64_t o = gid / cv;
+    int w = (int)(o % W);
+    int h = (int)((o / W) % H);
+    int d = (int)((o / ((int64_t)W * H)) % D);
+    int64_t n = o / ((int64_t)W * H * D);
+    float m[8], v[8];
+    int arg[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        int64_t u = ((n * 2 * D + 2 * d + (p >> 2)) * 2 * H + 2 * h + ((p >> 1) & 1)) * (2 * (int64_t)W) + 2 * w + (p & 1);
+        vec_io<bf16_t, 8>::ld(x + u * C + c, v);
+#pragma unroll
+        for (int e = 0; e < 8; ++e)
+            if (p == 0 || v[e] > m[e]) { m[e] = v[e]; arg[e] = p; }
+    }
+    vec_io<bf16_t, 8>::st(y + o * C + c, m);
+#pragma unroll
+    for (int e = 0; e < 8; ++e)
+        if (!(m[e] > 0.f)) arg[e] = 8;   // nothing is routed through a ReLU that was off
+    const int sub = threadIdx.x & (QUAD ? 3 : 1);
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        int64_t u = ((n * 2 * D + 2 * d + (p >> 2)) * 2 * H + 2 * h + ((p >> 1) & 1)) * (2 * (int64_t)W) + 2 * w + (p & 1);
+        unsigned b = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) b |= (arg[e] == p ? 1u : 0u) << e;
+        b |= (unsigned)__builtin_amdgcn_mov_dpp((int)b, 0xB1, 0xf, 0xf, true) << 8;        // lanes ^ 1
+        if (QUAD) {
+            b |= (unsigned)__builtin_amdgcn_mov_dpp((int)b, 0x4E, 0xf, 0xf, true) << 16;   // lanes ^ 2
+            if (sub == 0) *reinterpret_cast<unsigned *>(route + ((u * C + c) >> 3)) = b;
+        } else {
+            if (sub == 0) *reinterpret_cast<unsigned short *>(route + ((u * C + c) >> 3)) = (unsigned short)b;
+        }
+    }
+}
+
+// Backward pooling from those bits: dx = the window's dy where the bit is set, zero elsewhere (the
+// 16-bit patterns are passed through, nothing is computed).  Reads 1/16 of what pool_bwd_kernel
+// reads for x.
+__global__ __launch_bounds__(256) void pool_bwd_bits_kernel(const unsigned char *__restrict__ route,
+                                                           const bf16_t *__restrict__ dy, bf16_t *__restrict__ dx,
+                                                           int64_t total, int D, int H, int W, int C)
+{
+    int64_t gid = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (gid >= total) return;
+    int cv = C / 8;
+    int c = (int)(gid % cv) * 8;
+    int64_t o = gid / cv;
+    int w = (int)(o % W);
+    int h = (int)((o / W) % H);
+    int d = (int)((o / ((int64_t)W * H)) % D);
+    int64_t n = o / ((int64_t)W * H * D);
+    const uint4 g = *reinterpret_cast<const uint4 *>(dy + o * C + c);
+    unsigned b[8];
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        int64_t u = ((n * 2 * D + 2 * d + (p >> 2)) * 2 * H + 2 * h + ((p >> 1) & 1)) * (2 * (int64_t)W) + 2 * w + (p & 1);
+        b[p] = route[(u * C + c) >> 3];
+    }
+#pragma unroll
+    for (int p = 0; p < 8; ++p) {
+        int64_t u = ((n * 2 * D + 2 * d + (p >> 2)) * 2 * H + 2 * h + ((p >> 1) & 1)) * (2 * (int64_t)W) + 2 * w + (p & 1);
+        auto keep = [&](unsigned word, int pair) {   // channels 2 pair, 2 pair + 1 of the thread's eight
+            const unsigned lo = (b[p] >> (2 * pair)) & 1u, hi = (b[p] >> (2 * pair + 1)) & 1u;
+            return word & (((0u - lo) & 0x0000ffffu) | ((0u - hi) & 0xffff0000u));
+        };
+        *reinterpret_cast<uint4 *>(dx + u * C + c) = make_uint4(keep(g.x, 0), keep(g.y, 1), keep(g.z, 2), keep(g.w, 3));
+    }
+}
+
 // Nearest-neighbour up-sampling by 2 per axis.  D, H, W are the INPUT sizes; the output is
 // (2D, 2H, 2W).  Forward: one thread per VEC channels of one OUTPUT voxel (each input vector is
 // read by the eight threads of its block, served by the cache; every store is coalesced).
@@ -256,6 +344,49 @@ extern "C" int k3_pool3d_bwd(const k3_tensor *xd, const void *x, const k3_tensor
     if (rc != K3_OK) return rc;
     if (!x || !dy || !dx) return K3_E_BADARG;
     return pool_dispatch(true, xd->dtype, x, dy, add, relu_mask ? 1 : 0, dx, dyd->n, dyd->d, dyd->h, dyd->w, dyd->c, (hipStream_t)stream);
+}
+
+static int pool_bits_check(const k3_tensor *xd, const k3_tensor *yd)
+{
+    int rc = pool_check(xd, yd);
+    if (rc != K3_OK) return rc;
+    if (xd->dtype != K3_BF16 || xd->c % 16 != 0) return K3_E_UNSUPPORTED;
+    return K3_OK;
+}
+
+extern "C" int k3_pool3d_fwd_bits(const k3_tensor *xd, const void *x, const k3_tensor *yd, void *y, void *route_bits,
+                                  void *stream)
+{
+    int rc = pool_bits_check(xd, yd);
+    if (rc != K3_OK) return rc;
+    if (!x || !y || !route_bits) return K3_E_BADARG;
+    const int64_t total = yd->n * yd->d * yd->h * yd->w * (yd->c / 8);
+    const int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+    if (yd->c % 32 == 0)
+        pool_fwd_bits_kernel<true><<<dim3((unsigned)blocks), 256, 0, (hipStream_t)stream>>>(
+            (const bf16_t *)x, (bf16_t *)y, (unsigned char *)route_bits, total, (int)yd->d, (int)yd->h, (int)yd->w, (int)yd->c);
+    else
+        pool_fwd_bits_kernel<false><<<dim3((unsigned)blocks), 256, 0, (hipStream_t)stream>>>(
+            (const bf16_t *)x, (bf16_t *)y, (unsigned char *)route_bits, total, (int)yd->d, (int)yd->h, (int)yd->w, (int)yd->c);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
+extern "C" int k3_pool3d_bwd_bits(const k3_tensor *xd, const void *route_bits, const k3_tensor *dyd, const void *dy, void *dx,
+                                  void *stream)
+{
+    int rc = pool_bits_check(xd, dyd);
+    if (rc != K3_OK) return rc;
+    if (!route_bits || !dy || !dx) return K3_E_BADARG;
+    const int64_t total = dyd->n * dyd->d * dyd->h * dyd->w * (dyd->c / 8);
+    const int64_t blocks = (total + 255) / 256;
+    if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+    pool_bwd_bits_kernel<<<dim3((unsigned)blocks), 256, 0, (hipStream_t)stream>>>(
+        (const unsigned char *)route_bits, (const bf16_t *)dy, (bf16_t *)dx, total, (int)dyd->d, (int)dyd->h, (int)dyd->w,
+        (int)dyd->c);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
 }
 
 // xd: the small tensor (D, H, W); yd: the large one (2D, 2H, 2W): the same relation pool_check tests,

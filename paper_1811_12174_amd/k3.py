@@ -179,6 +179,16 @@ def pool3d_bwd(x, dy, add, dx, relu_mask=False):
            "k3_pool3d_bwd")
 
 
+def pool3d_fwd_bits(x, y, route_bits):
+    """pool3d_fwd that also writes one routing bit per element of x (size: relu_bits_bytes(x))."""
+    _check(lib().k3_pool3d_fwd_bits(_d(x), _p(x), _d(y), _p(y), _p(route_bits), _stream()), "k3_pool3d_fwd_bits")
+
+
+def pool3d_bwd_bits(route_bits, dy, dx):
+    """pool3d_bwd(x, dy, None, dx, relu_mask=True) from the bits pool3d_fwd_bits wrote for x."""
+    _check(lib().k3_pool3d_bwd_bits(_d(dx), _p(route_bits), _d(dy), _p(dy), _p(dx), _stream()), "k3_pool3d_bwd_bits")
+
+
 # ------------------------------------------------------------------ transposed convolution
 def upconv3d_packed_bytes(cin, cout, dtype):
     out = ctypes.c_size_t(0)

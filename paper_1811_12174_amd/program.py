@@ -16,8 +16,8 @@ from collections import namedtuple
 
 
 class TensorInfo:
-    """kind: "act" (an activation or gradient in the network's dtype), "bits" (a one-bit-per-element
-    ReLU mask: uint16 words, one per 16 channels) or "labels"."""
+    """kind: "act" (an activation or gradient in the network's dtype), "bits" (one bit per element of an
+    activation, a ReLU mask or a pooling layer's routing: uint16 words, one per 16 channels) or "labels"."""
     __slots__ = ("name", "shape", "ebytes", "external", "kind")
 
     def __init__(self, name, shape, ebytes, external=False, kind="act"):
@@ -107,12 +107,17 @@ class Program:
         self._add(Call("conv_dgrad", layer, dict(g=g, dx=dx, dx2=dx2, mask=mask, mask_bits=mask_bits), [g, mask, mask_bits],
                        [dx, dx2], 2 * 27 * v * ci * co, self._nb(g, mask, mask_bits, dx, dx2), v, ci, co))
 
-    def pool_fwd(self, x, y):
-        self._add(Call("pool_fwd", None, dict(x=x, y=y), [x], [y], 0, self._nb(x, y), self._vox(x), 0, 0))
+    def pool_fwd(self, x, y, route=None):
+        """route: a bit tensor (new_bits of x) that receives the backward pass's routing."""
+        self._add(Call("pool_fwd", None, dict(x=x, y=y, route=route), [x], [y, route], 0, self._nb(x, y, route),
+                       self._vox(x), 0, 0))
 
-    def pool_bwd(self, x, dy, add, dx, relu_mask):
-        self._add(Call("pool_bwd", None, dict(x=x, dy=dy, add=add, dx=dx, relu_mask=relu_mask), [x, dy, add], [dx],
-                       0, self._nb(x, dy, add, dx), self._vox(x), 0, 0))
+    def pool_bwd(self, x, dy, add, dx, relu_mask, route=None):
+        """With route (the bits pool_fwd wrote) the pass reads those in place of x: x is None, and
+        the result is the one of relu_mask=True without add."""
+        assert route is None or (x is None and add is None and relu_mask)
+        self._add(Call("pool_bwd", None, dict(x=x, dy=dy, add=add, dx=dx, relu_mask=relu_mask, route=route),
+                       [x, dy, add, route], [dx], 0, self._nb(x, dy, add, route, dx), self._vox(dx), 0, 0))
 
     def up_fwd(self, layer, x, y, ci, co):
         v = self._vox(x)
@@ -303,10 +308,13 @@ def bp_program(cin, channels, n, d, h, w, ebytes=2, keep_acts=False):
         return (n, d >> l, h >> l, w >> l, c)
     p.external("x", sh(0, cin))
     p.external("labels", (n, d, h, w), 1)
+    # Nothing but its pooling layer reads an encoder activation here, so (bf16, whole 16-channel
+    # words) the pooling keeps one routing bit per element and the activation ends with it.
+    route = ebytes == 2 and C % 16 == 0
     p.conv_fwd("enc0.conv", "x", None, p.new("a1", sh(0, C)), cin, C)
-    p.pool_fwd("a1", p.new("p1", sh(1, C)))
+    p.pool_fwd("a1", p.new("p1", sh(1, C)), route=p.new_bits("r:a1", "a1") if route else None)
     p.conv_fwd("enc1.conv", "p1", None, p.new("a2", sh(1, C)), C, C)
-    p.pool_fwd("a2", p.new("p2", sh(2, C)))
+    p.pool_fwd("a2", p.new("p2", sh(2, C)), route=p.new_bits("r:a2", "a2") if route else None)
     p.conv_fwd("dec1.conv", "p2", None, p.new("a3", sh(2, C)), C, C)
     p.upsample_fwd("a3", p.new("u1", sh(1, C)))
     p.conv_fwd("dec0.conv", "u1", None, p.new("a4", sh(1, C)), C, C)
@@ -318,10 +326,10 @@ def bp_program(cin, channels, n, d, h, w, ebytes=2, keep_acts=False):
     p.upsample_bwd("g:u1", p.new("g:a3", sh(2, C)), "a3")
     p.conv_wgrad("dec1.conv", "p2", None, "g:a3", C, C)
     p.conv_dgrad("dec1.conv", "g:a3", p.new("g:p2", sh(2, C)), None, None, C, C)
-    p.pool_bwd("a2", "g:p2", None, p.new("g:a2", sh(1, C)), True)
+    p.pool_bwd(None if route else "a2", "g:p2", None, p.new("g:a2", sh(1, C)), True, route="r:a2" if route else None)
     p.conv_wgrad("enc1.conv", "p1", None, "g:a2", C, C)
     p.conv_dgrad("enc1.conv", "g:a2", p.new("g:p1", sh(1, C)), None, None, C, C)
-    p.pool_bwd("a1", "g:p1", None, p.new("g:a1", sh(0, C)), True)
+    p.pool_bwd(None if route else "a1", "g:p1", None, p.new("g:a1", sh(0, C)), True, route="r:a1" if route else None)
     p.conv_wgrad("enc0.conv", "x", None, "g:a1", cin, C)
-    keep = [t for t, i in p.tensors.items() if not i.external and not t.startswith("g")] if keep_acts else []
+    keep = [t for t, i in p.tensors.items() if not i.external and i.kind == "act" and not t.startswith("g")] if keep_acts else []
     return p.finish(keep)

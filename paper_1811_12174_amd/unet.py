@@ -240,9 +240,15 @@ class StepNet:
                 k3.conv3d_bwd_data_bits(t[a["g"]], None, self.w[c.layer], self.pk[c.layer], t[a["dx"]], t[a["mask_bits"]],
                                         dx2=t.get(a["dx2"]))
         elif c.fn == "pool_fwd":
-            k3.pool3d_fwd(t[a["x"]], t[a["y"]])
+            if a.get("route") is None:
+                k3.pool3d_fwd(t[a["x"]], t[a["y"]])
+            else:
+                k3.pool3d_fwd_bits(t[a["x"]], t[a["y"]], t[a["route"]])
         elif c.fn == "pool_bwd":
-            k3.pool3d_bwd(t[a["x"]], t[a["dy"]], t.get(a["add"]), t[a["dx"]], relu_mask=a["relu_mask"])
+            if a.get("route") is None:
+                k3.pool3d_bwd(t[a["x"]], t[a["dy"]], t.get(a["add"]), t[a["dx"]], relu_mask=a["relu_mask"])
+            else:
+                k3.pool3d_bwd_bits(t[a["route"]], t[a["dy"]], t[a["dx"]])
         elif c.fn == "up_fwd":
             k3.upconv3d_fwd(t[a["x"]], self.w[c.layer], self.pk[c.layer], self.b[c.layer], t[a["y"]])
         elif c.fn == "up_wgrad":

@@ -45,6 +45,56 @@ def test_pool_fwd_bwd_exact(orc, shape, dt):
         np.testing.assert_allclose(to_f64(dx3), ref3, rtol=1e-6, atol=1e-7)
 
 
+@pytest.mark.parametrize("shape", [(1, 8, 8, 8, 32), (2, 6, 4, 10, 16), (1, 2, 2, 2, 48), (1, 20, 12, 36, 64), (3, 4, 2, 6, 128)])
+def test_pool_with_route_bits_is_bit_exact(orc, shape):
+    """Forward with routing bits, backward from the bits alone: y, the bits and dx equal the oracle's
+    element for element, and dx equals what the x-reading backward pass with the ReLU mask gives."""
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, to_f64, empty
+    N, D, H, W, C = shape
+    x = synth.activations(53, shape, "bf16")
+    x[x < 0] = 0.0                           # post-ReLU statistics: windows that are all zero, ties at zero
+    x = np.round(x * 4) / 4                  # and ties among positive values
+    dy = synth.activations(54, (N, D // 2, H // 2, W // 2, C), "bf16")
+    xd, dyd = to_dev(x, "bf16"), to_dev(dy, "bf16")
+    y = empty((N, D // 2, H // 2, W // 2, C), "bf16")
+    assert k3.relu_bits_bytes(xd) == x.size // 8
+    bits = torch.full((N, D, H, W, C // 16), 0x5555, device="cuda", dtype=torch.int16)
+    k3.pool3d_fwd_bits(xd, y, bits)
+    dx = torch.full_like(xd, 7.0)
+    k3.pool3d_bwd_bits(bits, dyd, dx)
+    dx_ref = empty(shape, "bf16")
+    k3.pool3d_bwd(xd, dyd, None, dx_ref, relu_mask=True)
+    torch.cuda.synchronize()
+    x64, dy64 = x.astype(np.float64), dy.astype(np.float64)
+    assert np.array_equal(to_f64(y), orc.pool3d_fwd(x64))
+    ref_bits = orc.pool3d_route_bits(x64)
+    assert np.array_equal(bits.cpu().numpy().view(np.uint16), ref_bits)
+    assert np.array_equal(to_f64(dx), orc.pool3d_bwd_bits(ref_bits, dy64))
+    assert np.array_equal(to_f64(dx), orc.relu_bwd(orc.pool3d_bwd(x64, dy64), x64))
+    assert torch.equal(dx, dx_ref)
+
+
+def test_pool_with_route_bits_rejects_what_it_does_not_serve():
+    from paper_1811_12174_amd import k3
+    from gpu_util import empty
+    import torch
+    bits = torch.zeros(64, device="cuda", dtype=torch.int16)
+    with pytest.raises(k3.K3Error) as e:      # 8 channels: no whole 16-channel word
+        k3.pool3d_fwd_bits(empty((1, 4, 4, 4, 8), "bf16"), empty((1, 2, 2, 2, 8), "bf16"), bits)
+    assert e.value.status == k3.E_UNSUPPORTED
+    with pytest.raises(k3.K3Error) as e:      # fp32
+        k3.pool3d_fwd_bits(empty((1, 4, 4, 4, 16), "f32"), empty((1, 2, 2, 2, 16), "f32"), bits)
+    assert e.value.status == k3.E_UNSUPPORTED
+    with pytest.raises(k3.K3Error) as e:
+        k3.pool3d_bwd_bits(bits, empty((1, 2, 2, 3, 16), "bf16"), empty((1, 4, 4, 4, 16), "bf16"))
+    assert e.value.status == k3.E_SHAPE
+    with pytest.raises(k3.K3Error) as e:
+        k3.pool3d_bwd_bits(None, empty((1, 2, 2, 2, 16), "bf16"), empty((1, 4, 4, 4, 16), "bf16"))
+    assert e.value.status == k3.E_BADARG
+
+
 def test_pool_odd_dim_is_rejected():
     from paper_1811_12174_amd import k3
     from gpu_util import empty

@@ -51,6 +51,44 @@ def test_pool_bwd_conserves_mass_and_is_gradient(orc):
     assert abs(fd - np.sum(dx * v)) < 1e-6
 
 
+def test_pool_route_bits_by_hand(orc):
+    """One window, 16 channels: channel 0 has its maximum at (0,1,1) twice-tied with (1,0,0), channel 1
+    is all negative (nothing routed), channel 2 all zero (nothing routed: ReLU off), channel 3 peaks
+    at (1,1,1); the other channels are constant 2 -> the first element (0,0,0)."""
+    x = np.full((1, 2, 2, 2, 16), 2.0)
+    x[..., 0] = 0.0; x[0, 0, 1, 1, 0] = 5.0; x[0, 1, 0, 0, 0] = 5.0
+    x[..., 1] = -1.0; x[0, 1, 1, 0, 1] = -0.5
+    x[..., 2] = 0.0
+    x[..., 3] = 1.0; x[0, 1, 1, 1, 3] = 9.0
+    bits = orc.pool3d_route_bits(x)
+    assert bits.shape == (1, 2, 2, 2, 1) and bits.dtype == np.uint16
+    exp = np.zeros((1, 2, 2, 2, 1), dtype=np.uint16)
+    exp[0, 0, 0, 0, 0] = 0xFFF0            # channels 4..15 at the first element
+    exp[0, 0, 1, 1, 0] = 0x0001            # channel 0
+    exp[0, 1, 1, 1, 0] = 0x0008            # channel 3
+    assert np.array_equal(bits, exp)
+    dy = np.arange(1, 17, dtype=np.float64).reshape(1, 1, 1, 1, 16)
+    dx = orc.pool3d_bwd_bits(bits, dy)
+    assert dx[0, 0, 1, 1, 0] == 1.0 and dx[0, 1, 1, 1, 3] == 4.0 and dx[0, 0, 0, 0, 15] == 16.0
+    assert np.count_nonzero(dx) == 14
+
+
+@pytest.mark.parametrize("ties", [False, True])
+def test_pool_route_bits_equal_pool_bwd_then_relu_bwd(orc, ties):
+    """The bit form is the loop form: routing by the C loops (strict >, first maximum) followed by
+    the ReLU mask of x, on data with and without many equal values and zeros."""
+    shape = (2, 4, 6, 8, 32)
+    x = RNG.integers(-2, 3, shape).astype(np.float64) if ties else RNG.standard_normal(shape)
+    dy = RNG.standard_normal((2, 2, 3, 4, 32))
+    bits = orc.pool3d_route_bits(x)
+    assert bits.shape == (2, 4, 6, 8, 2)
+    ref = orc.relu_bwd(orc.pool3d_bwd(x, dy), x)
+    assert np.array_equal(orc.pool3d_bwd_bits(bits, dy), ref)
+    # at most one bit per window and channel; exactly one where the pooled value is positive
+    per_window = orc.pool3d_bwd_bits(bits, np.ones_like(dy)).reshape(2, 2, 2, 3, 2, 4, 2, 32).sum(axis=(2, 4, 6))
+    assert np.array_equal(per_window, (orc.pool3d_fwd(x) > 0).astype(np.float64))
+
+
 def test_pool_against_torch(orc):
     torch = pytest.importorskip("torch")
     x = RNG.standard_normal((1, 4, 6, 4, 5))

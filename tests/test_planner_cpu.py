@@ -3,7 +3,7 @@ import pytest
 
 from paper_1811_12174_amd import planner
 from paper_1811_12174_amd.executor import Executor, OutOfBudget
-from paper_1811_12174_amd.program import unet_program
+from paper_1811_12174_amd.program import bp_program, unet_program
 
 
 def _prog(levels=3, base=8, n=1, s=16):
@@ -54,6 +54,28 @@ def test_gaps_of_the_stored_activations():
                      [("conv_fwd", "dec0.conv1"), ("conv_wgrad", "dec0.conv1")],
                      [("conv_wgrad", "dec0.conv1"), ("pool_bwd", None)]]
     assert all(not p.tensors[g.tensor].external for g in gaps.values())
+
+
+def test_encoder_decoder_program_keeps_routing_bits_instead_of_pooled_activations():
+    """bf16 with whole 16-channel words: the encoder activations end with their pooling call (the
+    backward pooling reads the routing bits, 1/16 of the bytes), so the step's peak is lower than
+    in fp32 accounting scaled to the same element size; with 8 channels the activations stay."""
+    p = bp_program(1, 32, 2, 16, 16, 16, ebytes=2)
+    uses = p.uses()
+    pool1 = next(k for k, c in enumerate(p.calls) if c.fn == "pool_fwd")
+    assert uses["a1"][-1] == pool1 and p.tensors["r:a1"].kind == "bits"
+    assert p.tensors["r:a1"].nbytes * 16 == p.tensors["a1"].nbytes
+    back = [c for c in p.calls if c.fn == "pool_bwd"]
+    assert [c.args["x"] for c in back] == [None, None] and [c.args["route"] for c in back] == ["r:a2", "r:a1"]
+    assert all("a1" not in c.reads and "a2" not in c.reads for c in back)
+    ins = p.instructions()
+    assert sorted(a for op, a in ins if op == "alloc") == sorted(t for t, i in p.tensors.items() if not i.external)
+    plain = bp_program(1, 8, 2, 16, 16, 16, ebytes=2)          # 8 channels: no whole word, x-reading pooling
+    assert all(c.args["route"] is None for c in plain.calls if c.fn.startswith("pool"))
+    assert plain.uses()["a1"][-1] > pool1
+    peak = planner.simulate(p)[0].peak
+    peak_plain = planner.simulate(plain)[0].peak * 4            # same program at 32 channels, activations kept
+    assert peak < peak_plain
 
 
 def test_rewrite_places_swap_instructions():
