@@ -276,7 +276,8 @@ def test_first_layer(orc, big):
 
 
 def test_pool(orc, big):
-    """2x2x2 max-pool forward and backward (with the skip gradient added and the ReLU mask of x applied): exact."""
+    """2x2x2 max-pool forward and backward (with the skip gradient added and the ReLU mask of x applied; from
+    routing bits): exact."""
     import torch
     from paper_1811_12174_amd import k3
     x = torch.relu(big.x)      # a stored ReLU output: ties at zero, positive bf16 ties
@@ -299,6 +300,25 @@ def test_pool(orc, big):
         assert np.array_equal(block(dx, n, d0, h0, w0)[None], ref), ("pool bwd", n, d0, h0, w0)
         ref = orc.round_bf16(orc.relu_bwd(ref + block(big.g, n, d0, h0, w0)[None], xc))
         assert np.array_equal(block(dxa, n, d0, h0, w0)[None], ref), ("pool bwd add", n, d0, h0, w0)
+    # the form that keeps routing bits in place of x: same pooled tensor; bits and dx against the
+    # oracle on the crops; dx against the x-reading pass over the whole tensor
+    del dxa
+    p2 = torch.empty_like(p)
+    bits = torch.empty((N, S, S, S, C // 16), device="cuda", dtype=torch.int16)
+    k3.pool3d_fwd_bits(x, p2, bits)
+    dxr = torch.empty_like(x)
+    k3.pool3d_bwd_bits(bits, dy, dxr)
+    k3.pool3d_bwd(x, dy, None, dx, relu_mask=True)
+    torch.cuda.synchronize()
+    assert torch.equal(p2, p) and torch.equal(dxr, dx)
+    for (n, d0, h0, w0) in CORNERS:
+        d0, h0, w0 = d0 & ~1, h0 & ~1, w0 & ~1
+        xc = block(x, n, d0, h0, w0)[None]
+        dyc = block(dy, n, d0 // 2, h0 // 2, w0 // 2, E // 2)[None]
+        rb = orc.pool3d_route_bits(xc)
+        got = bits[n, d0:d0 + E, h0:h0 + E, w0:w0 + E].cpu().numpy().view(np.uint16)[None]
+        assert np.array_equal(got, rb), ("route bits", n, d0, h0, w0)
+        assert np.array_equal(block(dxr, n, d0, h0, w0)[None], orc.pool3d_bwd_bits(rb, dyc)), ("pool bwd bits", n, d0, h0, w0)
 
 
 def test_upconv(orc, big):
