@@ -221,8 +221,10 @@ int k3_upconv3d_bwd_weight(const k3_tensor *xd, const void *x, const k3_tensor *
  * a: dev, ad->dtype; wh [C][3], bh [3]: fp32 dev; labels: uint8 dev, one per voxel;
  * loss: one fp32 (dev); da: dev, same shape and dtype as a; dWh [C][3], dbh [3]: fp32
  * dev; logits: optional fp32 [V][3] dev (NULL to skip).  When relu_mask is non-zero da is
- * zeroed where a <= 0 (a is a stored ReLU output; see k3_conv3d_bwd_data, dx_mask).  ws
- * holds per-workgroup partial sums. */
+ * zeroed where a <= 0 (a is a stored ReLU output; see k3_conv3d_bwd_data, dx_mask).  da may
+ * be a itself: the gradient then replaces the activations, which nothing reads after this
+ * call in a training step (one tensor less at the step's memory peak).  ws holds
+ * per-workgroup partial sums. */
 int k3_head_workspace_bytes(const k3_tensor *ad, size_t *bytes);
 int k3_head_softmax_ce_fwd_bwd(const k3_tensor *ad, const void *a, const float *wh, const float *bh,
                                const uint8_t *labels, float *loss, void *da, int relu_mask,

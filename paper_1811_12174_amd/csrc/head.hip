@@ -15,10 +15,12 @@ namespace k3 {
 constexpr int HB = 256;       // voxels per batch
 constexpr int HEAD_K = 3;
 
+// da may be a itself: a workgroup reads the rows of a batch into LDS before it writes that batch's
+// rows of da, and no other workgroup touches them (hence no __restrict__ on the two).
 template <typename T>
-__global__ __launch_bounds__(256) void head_kernel(const T *__restrict__ a, const float *__restrict__ wh,
+__global__ __launch_bounds__(256) void head_kernel(const T *a, const float *__restrict__ wh,
                                                   const float *__restrict__ bh, const uint8_t *__restrict__ labels,
-                                                  T *__restrict__ da, float *__restrict__ logits,
+                                                  T *da, float *__restrict__ logits,
                                                   float *__restrict__ partial, int64_t V, int C, float invV, int relu_mask,
                                                   const float *__restrict__ cw)
 {
@@ -132,11 +134,12 @@ __global__ __launch_bounds__(256) void head_kernel(const T *__restrict__ a, cons
 // reads and writes whole contiguous 2 KB runs and nothing goes through LDS.  The lanes of a
 // voxel add their partial logits with xor-shuffles, every lane then forms the softmax terms,
 // its 16 values of da, and its share of dWh in 48 register accumulators.  Workgroup partials
-// are merged in a fixed order.
+// are merged in a fixed order.  da may be a itself: a lane writes the 32 bytes it has read, after
+// reading them, and nobody else's (the clamped loads of lanes beyond the last voxel are not used).
 template <int LPV>
-__global__ __launch_bounds__(256) void head_stream_kernel(const bf16_t *__restrict__ a, const float *__restrict__ wh,
+__global__ __launch_bounds__(256) void head_stream_kernel(const bf16_t *a, const float *__restrict__ wh,
                                                          const float *__restrict__ bh,
-                                                         const uint8_t *__restrict__ labels, bf16_t *__restrict__ da,
+                                                         const uint8_t *__restrict__ labels, bf16_t *da,
                                                          float *__restrict__ logits, float *__restrict__ partial,
                                                          int64_t V, float invV, int relu_mask, const float *__restrict__ cw)
 {

@@ -18,7 +18,8 @@ the memory high-water mark is a property of the program and the budget, not of t
     overlaps the kernels enqueued after it); a tensor that was never dropped is simply kept.
   * wait fences the compute stream behind the copy-in, right before the first reader.
   * A tensor that came back and is evicted again is dropped without a copy: its host copy is
-    still valid because stored activations are never rewritten.
+    still valid because stored activations are never rewritten (a tensor that a call rewrites
+    in place is offered no gap: Program.gaps).
 """
 
 

@@ -133,6 +133,7 @@ class Program:
                        2 * 8 * v * ci * co, self._nb(dy, dx, mask), v, ci, co))
 
     def head(self, a, da, c, relu_mask=True):
+        """da may be a: the gradient then replaces the activations (see gaps for what that excludes)."""
         v = self._vox(a)
         self._add(Call("head", "head", dict(a=a, da=da, relu_mask=relu_mask), [a, "labels"], [da], 2 * 2 * 3 * v * c,
                        self._nb(a, da) + v, v, c, 3))
@@ -168,12 +169,23 @@ class Program:
                     u.setdefault(t, []).append(k)
         return u
 
+    def rewritten(self):
+        """Tensors more than one call writes (a call that works in place)."""
+        n = {}
+        for c in self.calls:
+            for t in set(c.writes):
+                n[t] = n.get(t, 0) + 1
+        return {t for t, k in n.items() if k > 1}
+
     def gaps(self, min_calls=3):
-        """Idle intervals: consecutive uses of a step-owned tensor at least `min_calls` calls apart."""
+        """Idle intervals: consecutive uses of a step-owned tensor at least `min_calls` calls apart.
+        A tensor that is rewritten in place has none: the swap scheme copies a tensor out once,
+        behind its producer, and relies on that host copy for every later gap."""
         out = []
+        rewritten = self.rewritten()
         for t, ks in self.uses().items():
             info = self.tensors[t]
-            if info.external or t in self.keep:
+            if info.external or t in self.keep or t in rewritten:
                 continue
             for i in range(len(ks) - 1):
                 if ks[i + 1] - ks[i] >= min_calls:
@@ -263,8 +275,14 @@ def unet_program(base, cin, levels, n, d, h, w, ebytes=2, keep_acts=False):
                    bits=bits_of(f"da1_{l}"))
         p.conv_fwd(f"dec{l}.conv2", f"da1_{l}", None, p.new(f"da2_{l}", sh(l, F[l])), F[l], F[l])
         cur = f"da2_{l}"
-    p.head(cur, p.new("g:" + cur, p.tensors[cur].shape), F[0])
-    g = "g:" + cur
+    # The head's gradient replaces its input, which nothing else reads: one full-resolution tensor
+    # less at the step's memory peak (not when the caller wants the activations back).
+    if keep_acts:
+        p.head(cur, p.new("g:" + cur, p.tensors[cur].shape), F[0])
+        g = "g:" + cur
+    else:
+        p.head(cur, cur, F[0])
+        g = cur
     for l in range(0, L - 1):
         Fl = F[l]
         p.conv_wgrad(f"dec{l}.conv2", f"da1_{l}", None, g, Fl, Fl)
@@ -319,8 +337,9 @@ def bp_program(cin, channels, n, d, h, w, ebytes=2, keep_acts=False):
     p.upsample_fwd("a3", p.new("u1", sh(1, C)))
     p.conv_fwd("dec0.conv", "u1", None, p.new("a4", sh(1, C)), C, C)
     p.upsample_fwd("a4", p.new("u2", sh(0, C)))
-    p.head("u2", p.new("g:u2", sh(0, C)), C, relu_mask=False)
-    p.upsample_bwd("g:u2", p.new("g:a4", sh(1, C)), "a4")
+    gu2 = p.new("g:u2", sh(0, C)) if keep_acts else "u2"     # in place unless the activations are wanted back
+    p.head("u2", gu2, C, relu_mask=False)
+    p.upsample_bwd(gu2, p.new("g:a4", sh(1, C)), "a4")
     p.conv_wgrad("dec0.conv", "u1", None, "g:a4", C, C)
     p.conv_dgrad("dec0.conv", "g:a4", p.new("g:u1", sh(1, C)), None, None, C, C)
     p.upsample_bwd("g:u1", p.new("g:a3", sh(2, C)), "a3")

@@ -141,6 +141,25 @@ def test_encoder_decoder_step_matches_oracle(orc, channels, size, n, dt):
     net.close()
 
 
+def test_encoder_decoder_step_in_place_equals_the_step_that_keeps_activations():
+    """The ordinary step (head gradient in place, pooling from routing bits) against the step that
+    hands the activations back, which the oracle comparison above runs: bit-identical."""
+    import torch
+    from gpu_util import to_dev
+    net, (loss, acts), params, x, lab, cw = _bp_run(32, 16, 2, "bf16", keep=True)
+    l0 = net.loss.clone()
+    g0 = {k: v.clone() for k, v in net.grads().items()}
+    for v in net.grads().values():
+        v.fill_(float("nan"))
+    net.step(to_dev(x, "bf16"), torch.from_numpy(lab).cuda())
+    torch.cuda.synchronize()
+    assert net.program((2, 16, 16, 16, 1)).rewritten() == {"u2"}
+    assert torch.equal(net.loss, l0)
+    for k, v in net.grads().items():
+        assert torch.equal(v, g0[k]), k
+    net.close()
+
+
 def test_encoder_decoder_at_the_paper_shape():
     """Batch of 8 blocks of 64^3 voxels, 128 channels: swapping is bit-identical, a few SGD steps
     lower the loss, and the arg-max read-out agrees with the logits of the training pass."""

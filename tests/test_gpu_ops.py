@@ -194,6 +194,16 @@ def test_head(orc, sp, C, dt):
     assert rel_l2(to_f64(dam), orc.relu_bwd(ref["da"], a.astype(np.float64))) < TOL[dt]
     assert rel_l2(to_f64(dW), ref["dW"]) < 1e-5
     assert np.abs(to_f64(db) - ref["db"]).max() < 1e-5 * max(1e-3, np.abs(ref["db"]).max()) + 1e-7
+    # in place (da = a): every output is the one of the separate-buffer call, bit for bit
+    for mask, want in ((False, da), (True, dam)):
+        k3.head_softmax_ce_fwd_bwd(ad, whd, bhd, labd, loss, empty(a.shape, dt), dW, db, logits, ws, relu_mask=mask)
+        inpl = ad.clone()
+        loss2, dW2, db2 = torch.full_like(loss, float("nan")), torch.full_like(dW, float("nan")), torch.full_like(db, float("nan"))
+        logits2 = torch.full_like(logits, float("nan"))
+        k3.head_softmax_ce_fwd_bwd(inpl, whd, bhd, labd, loss2, inpl, dW2, db2, logits2, ws, relu_mask=mask)
+        torch.cuda.synchronize()
+        assert torch.equal(inpl, want) and torch.equal(loss2, loss) and torch.equal(dW2, dW) and torch.equal(db2, db)
+        assert torch.equal(logits2, logits)
 
 
 # ------------------------------------------------------------------ swap engine

@@ -164,6 +164,28 @@ def test_swapping_is_bit_identical(base, levels, size):
     net.close()
 
 
+@pytest.mark.parametrize("base,levels,size,dt", [(32, 4, 32, "bf16"), (16, 3, 16, "bf16"), (4, 3, 16, "f32")])
+def test_step_with_the_head_gradient_in_place_equals_the_step_that_keeps_activations(base, levels, size, dt):
+    """The ordinary step lets the head write its gradient over its input; the step that hands the
+    activations back (the one the oracle comparisons above run) uses a separate tensor.  Same loss
+    and gradients, bit for bit."""
+    import torch
+    from gpu_util import to_dev
+    net, (loss, acts), params, x, lab = _run(base, levels, size, 1, dt, keep=True)
+    l0 = net.loss.clone()
+    g0 = {k: v.clone() for k, v in net.grads().items()}
+    prog = net.program((1, size, size, size, 1))
+    assert prog.rewritten() == {"da2_0"}
+    for v in net.grads().values():
+        v.fill_(float("nan"))
+    net.step(to_dev(x, dt), torch.from_numpy(lab).cuda())
+    torch.cuda.synchronize()
+    assert torch.equal(net.loss, l0)
+    for k, v in net.grads().items():
+        assert torch.equal(v, g0[k]), k
+    net.close()
+
+
 def test_swapping_with_poisoned_blocks_is_bit_identical():
     """The swap engine's debug switch overwrites every device block whose tensor has gone to the
     host; a kernel that still read such a block would turn the loss or a gradient into NaN.  The

@@ -78,6 +78,35 @@ def test_encoder_decoder_program_keeps_routing_bits_instead_of_pooled_activation
     assert peak < peak_plain
 
 
+def test_head_gradient_replaces_its_input_and_that_tensor_is_never_swapped():
+    """Without keep_acts the head writes its gradient over the last activation: one full-resolution
+    tensor less at the peak (which sits at the head otherwise), and the rewritten tensor is offered
+    no gap, whatever the minimum length, because a swapped tensor is copied out once only."""
+    p = unet_program(8, 1, 3, 1, 16, 16, 16)
+    kept = unet_program(8, 1, 3, 1, 16, 16, 16, keep_acts=True)
+    head = next(c for c in p.calls if c.fn == "head")
+    assert head.args["a"] == head.args["da"] == "da2_0" and "g:da2_0" not in p.tensors
+    assert p.rewritten() == {"da2_0"} and kept.rewritten() == set()
+    assert all(g.tensor != "da2_0" for g in p.gaps(1)) and any(g.tensor == "da2_0" for g in kept.gaps(1)) is False
+    # bytes held while each call runs, from the instruction stream; with a separate gradient tensor
+    # the head call would hold one more full-resolution tensor and be the step's peak
+    p = unet_program(16, 1, 3, 1, 16, 16, 16)
+    held, cur = {}, 0
+    for op, a in p.instructions():
+        if op == "alloc":
+            cur += p.tensors[a].nbytes
+        elif op == "free":
+            cur -= p.tensors[a].nbytes
+        elif op == "call":
+            held[(a.fn, a.layer)] = cur
+    peak = planner.simulate(p)[0].peak
+    assert peak == max(held.values())
+    assert held[("head", "head")] <= peak < held[("head", "head")] + p.tensors["da2_0"].nbytes
+    q = bp_program(1, 32, 2, 16, 16, 16)
+    assert q.rewritten() == {"u2"} and "g:u2" not in q.tensors
+    assert next(c for c in q.calls if c.fn == "upsample_bwd").args["dy"] == "u2"
+
+
 def test_rewrite_places_swap_instructions():
     p = _prog(3)
     gs = [g for g in p.gaps() if g.tensor in ("a1_0", "a2_0")]
