@@ -35,15 +35,17 @@ __device__ __forceinline__ void load4(const bf16_t *p, float *v)
 struct FirstTile {
     int n, d0, h0, w0;
 };
-__device__ __forceinline__ FirstTile first_tile(int64_t tile, int ntd, int nth, int ntw)
+// (the tile count fits 31 bits, checked at launch: 32-bit divisions, a fraction of the 64-bit ones' cost)
+__device__ __forceinline__ FirstTile first_tile(int64_t tile64, int ntd, int nth, int ntw)
 {
     FirstTile t;
-    t.w0 = (int)(tile % ntw) * first::TW;
-    tile /= ntw;
-    t.h0 = (int)(tile % nth) * first::TH;
-    tile /= nth;
-    t.d0 = (int)(tile % ntd) * first::TD;
-    t.n = (int)(tile / ntd);
+    unsigned tile = (unsigned)tile64;
+    t.w0 = (int)(tile % (unsigned)ntw) * first::TW;
+    tile /= (unsigned)ntw;
+    t.h0 = (int)(tile % (unsigned)nth) * first::TH;
+    tile /= (unsigned)nth;
+    t.d0 = (int)(tile % (unsigned)ntd) * first::TD;
+    t.n = (int)(tile / (unsigned)ntd);
     return t;
 }
 
@@ -193,6 +195,41 @@ __device__ __forceinline__ void stage_x_bf16(const bf16_t *__restrict__ x, bf16_
     }
 }
 
+// The same in two halves, so that the loads of the next tile are in flight while the current tile is
+// computed: a thread holds its (at most) five halo values in registers in between.  Loads and stores
+// of a wave complete in issue order on one counter, so everything between the two halves must be
+// straight-line code (no conditional memory operation): the compiler can then wait for exactly these
+// loads and leave the tile's later stores in flight; behind a branch it would wait for everything.
+constexpr int FIRST_XPT = (firstm::NHALO + 255) / 256;
+constexpr int FIRST_XS = FIRST_XPT * 256;   // entries of a halo buffer: every thread stores all its values (zeros beyond the tile)
+struct FirstHaloRegs {
+    bf16_t v[FIRST_XPT];
+    unsigned inside;   // bit k: value k lies inside the volume (else a zero is stored)
+};
+__device__ __forceinline__ void load_x_regs(const bf16_t *__restrict__ x, FirstHaloRegs &r, const FirstTile &t, int D, int H, int W)
+{
+    using namespace firstm;
+    r.inside = 0;
+#pragma unroll
+    for (int k = 0; k < FIRST_XPT; ++k) {
+        const int i = threadIdx.x + k * 256;
+        const int lw = i % HW, lh = (i / HW) % HH, ld = i / (HW * HH);
+        const int gd = t.d0 + ld - 1, gh = t.h0 + lh - 1, gw = t.w0 + lw - 1;
+        // every lane loads from a clamped (valid) position, and what lies outside is replaced by zero only
+        // when the values are stored: no branch and no use of a loaded value here, so the loads leave back
+        // to back and the only wait is in store_x_regs
+        const int cd = gd < 0 ? 0 : (gd < D ? gd : D - 1), ch = gh < 0 ? 0 : (gh < H ? gh : H - 1), cw = gw < 0 ? 0 : (gw < W ? gw : W - 1);
+        r.v[k] = x[(((int64_t)t.n * D + cd) * H + ch) * W + cw];
+        r.inside |= (i < NHALO && cd == gd && ch == gh && cw == gw ? 1u : 0u) << k;
+    }
+}
+__device__ __forceinline__ void store_x_regs(bf16_t *xs, const FirstHaloRegs &r)
+{
+#pragma unroll
+    for (int k = 0; k < FIRST_XPT; ++k)   // unconditional stores (the buffer is padded): a load whose use is conditional sinks to it
+        xs[threadIdx.x + k * 256] = (r.inside >> k) & 1u ? r.v[k] : (bf16_t)0;
+}
+
 // eight halo values at byte offsets o0..o7 from p, packed as an MFMA operand
 template <int O0, int O1, int O2, int O3, int O4, int O5, int O6, int O7>
 __device__ __forceinline__ bf16x8 gather8(const unsigned char *p)
@@ -209,10 +246,31 @@ __device__ __forceinline__ bf16x8 gather8(const unsigned char *p)
     v[7] = *reinterpret_cast<const unsigned short *>(p + O7);
     return __builtin_bit_cast(bf16x8, v);
 }
+// The same with volatile reads, for scattered offsets: left to itself the compiler merges taps that are
+// neighbours in w into 4-byte reads at 2-byte-aligned addresses, which the LDS serves far slower than
+// separate 2-byte reads (forward pass, 32 channels: 75 -> 55 us at 128^3).  A run of eight consecutive values
+// (backward-weight) is better served by the merged wide read.
+template <int O0, int O1, int O2, int O3, int O4, int O5, int O6, int O7>
+__device__ __forceinline__ bf16x8 gather8_scattered(const unsigned char *p)
+{
+    typedef __attribute__((ext_vector_type(8))) unsigned short u16x8;
+    u16x8 v;
+    v[0] = *reinterpret_cast<const volatile unsigned short *>(p + O0);
+    v[1] = *reinterpret_cast<const volatile unsigned short *>(p + O1);
+    v[2] = *reinterpret_cast<const volatile unsigned short *>(p + O2);
+    v[3] = *reinterpret_cast<const volatile unsigned short *>(p + O3);
+    v[4] = *reinterpret_cast<const volatile unsigned short *>(p + O4);
+    v[5] = *reinterpret_cast<const volatile unsigned short *>(p + O5);
+    v[6] = *reinterpret_cast<const volatile unsigned short *>(p + O6);
+    v[7] = *reinterpret_cast<const volatile unsigned short *>(p + O7);
+    return __builtin_bit_cast(bf16x8, v);
+}
+
+typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 
 // Forward: D[co][voxel] = sum_tap W[tap][co] * x[voxel + tap]; K = 32 (27 taps + 5 zero rows) = 2 MFMAs
 // per 32 voxels and 32-channel block.  Persistent blocks walk the 4x8x16 tiles.
-template <int MB>
+template <int MB, bool BITS>
 __global__ __launch_bounds__(256) void conv_first_fwd_mfma_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
                                                                  const float *__restrict__ bias, int relu,
                                                                  bf16_t *__restrict__ y, unsigned short *__restrict__ ybits,
@@ -221,9 +279,19 @@ __global__ __launch_bounds__(256) void conv_first_fwd_mfma_kernel(const bf16_t *
 {
     using namespace firstm;
     constexpr int cout = 32 * MB;
-    __shared__ __attribute__((aligned(16))) bf16_t xs[2][NHALO + 8];
+    __shared__ __attribute__((aligned(16))) bf16_t xs[2][FIRST_XS];
+    // A wave's results pass through LDS on their way out: the accumulator layout gives a lane 32 bytes of
+    // one voxel, so a store instruction would write 64 separate 16-byte pieces; read back row-major, a
+    // store instruction writes whole runs of voxels (1 KB per half row of a patch).  Rows are padded by 16
+    // bytes against bank conflicts.  Private to the wave: no barrier, LDS operations of a wave are in order.
+    constexpr int ROWB = 64 * MB, ROWP = ROWB + 16;
+    constexpr int LPVX = ROWB / 16, VPI = 64 / LPVX;       // lanes per voxel / voxels per store instruction when reading back
+    __shared__ __attribute__((aligned(16))) unsigned char ost[4][32 * ROWP];
+    __shared__ __attribute__((aligned(16))) unsigned short obits[4][32 * 2 * MB];   // the bit words of a patch, voxel-major
+    __shared__ __attribute__((aligned(16))) float bl[cout];
     const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6;
     const int hb = lane >> 5, vl = lane & 31;
+    for (int i = threadIdx.x; i < cout; i += 256) bl[i] = bias ? bias[i] : 0.f;
     // A operand: weights, rows permuted so that a lane ends up with 16 consecutive channels
     bf16x8 aw[MB][2];
 #pragma unroll
@@ -239,54 +307,98 @@ __global__ __launch_bounds__(256) void conv_first_fwd_mfma_kernel(const bf16_t *
             }
             aw[mb][m] = __builtin_bit_cast(bf16x8, v);
         }
-    float bv[MB][16];
-#pragma unroll
-    for (int mb = 0; mb < MB; ++mb)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) bv[mb][i] = bias ? bias[mb * 32 + hb * 16 + i] : 0.f;
     const float floor_ = relu ? 0.f : -__builtin_inff();
+    unsigned char *ow = ost[wv];
     int buf = 0;
+    if ((int64_t)blockIdx.x < ntiles) stage_x_bf16(x, xs[0], first_tile(blockIdx.x, ntd, nth, ntw), D, H, W);
+    __syncthreads();
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x, buf ^= 1) {
         const FirstTile t = first_tile(tile, ntd, nth, ntw);
-        stage_x_bf16(x, xs[buf], t, D, H, W);
-        __syncthreads();   // (the other buffer is still being read by slower waves: two buffers, one barrier)
+        // The next tile's halo is requested now and stored to the other buffer behind this tile's work
+        // (that buffer was last read before the barrier that ended the previous iteration).  The last
+        // tile requests itself again: the loop body has no conditional memory operation (see load_x_regs).
+        const bool more = tile + gridDim.x < ntiles;
+        FirstHaloRegs xnext;
+        load_x_regs(x, xnext, first_tile(more ? tile + gridDim.x : tile, ntd, nth, ntw), D, H, W);
+        // results leave through descriptors at the tile's first voxel: a lane whose voxel lies outside the
+        // volume gets an offset beyond the range, and such stores are dropped
+        const int64_t origin = (((int64_t)t.n * D + t.d0) * H + t.h0) * W + t.w0;
+        __amdgpu_buffer_rsrc_t yrs = __builtin_amdgcn_make_buffer_rsrc(y + origin * cout, 0, 0x7ffffff0, 0x00020000);
+        __amdgpu_buffer_rsrc_t brs = __builtin_amdgcn_make_buffer_rsrc(BITS ? ybits + origin * (cout / 16) : (unsigned short *)y, 0,
+                                                                       0x7ffffff0, 0x00020000);
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
             const int patch = wv * 4 + q;                 // 16 patches: depth plane patch / 4, rows 2 * (patch % 4) ..+1
             const int ld = patch >> 2, lh = (patch & 3) * 2 + (vl >> 4), lw = vl & 15;
             const unsigned char *p = reinterpret_cast<const unsigned char *>(xs[buf]) + ((ld * HH + lh) * HW + lw) * 2;
             // taps 0-7 / 8-15 (first K chunk) and 16-23 / 24-26 (second), by lane half
-            const bf16x8 lo0 = gather8<tapoff(0), tapoff(1), tapoff(2), tapoff(3), tapoff(4), tapoff(5), tapoff(6), tapoff(7)>(p);
-            const bf16x8 hi0 = gather8<tapoff(8), tapoff(9), tapoff(10), tapoff(11), tapoff(12), tapoff(13), tapoff(14), tapoff(15)>(p);
-            const bf16x8 lo1 = gather8<tapoff(16), tapoff(17), tapoff(18), tapoff(19), tapoff(20), tapoff(21), tapoff(22), tapoff(23)>(p);
-            bf16x8 hi1 = gather8<tapoff(24), tapoff(25), tapoff(26), tapoff(26), tapoff(26), tapoff(26), tapoff(26), tapoff(26)>(p);
+            const bf16x8 lo0 = gather8_scattered<tapoff(0), tapoff(1), tapoff(2), tapoff(3), tapoff(4), tapoff(5), tapoff(6), tapoff(7)>(p);
+            const bf16x8 hi0 = gather8_scattered<tapoff(8), tapoff(9), tapoff(10), tapoff(11), tapoff(12), tapoff(13), tapoff(14), tapoff(15)>(p);
+            const bf16x8 lo1 = gather8_scattered<tapoff(16), tapoff(17), tapoff(18), tapoff(19), tapoff(20), tapoff(21), tapoff(22), tapoff(23)>(p);
+            bf16x8 hi1 = gather8_scattered<tapoff(24), tapoff(25), tapoff(26), tapoff(26), tapoff(26), tapoff(26), tapoff(26), tapoff(26)>(p);
 #pragma unroll
             for (int e = 3; e < 8; ++e) hi1[e] = (__bf16)0.f;   // rows 27-31 of the contraction do not exist
             const bf16x8 b0 = hb ? hi0 : lo0, b1 = hb ? hi1 : lo1;
-            const int gd = t.d0 + ld, gh = t.h0 + lh, gw = t.w0 + lw;
-            const bool inb = gd < D && gh < H && gw < W;
-            const int64_t vox = (((int64_t)t.n * D + gd) * H + gh) * W + gw;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
                 f32x16 acc;
+                {
+                    const f32x4 *bq = reinterpret_cast<const f32x4 *>(bl + mb * 32 + hb * 16);
 #pragma unroll
-                for (int i = 0; i < 16; ++i) acc[i] = bv[mb][i];
+                    for (int i = 0; i < 4; ++i) {
+                        const f32x4 qv = bq[i];
+                        acc[4 * i] = qv[0]; acc[4 * i + 1] = qv[1]; acc[4 * i + 2] = qv[2]; acc[4 * i + 3] = qv[3];
+                    }
+                }
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aw[mb][0], b0, acc, 0, 0, 0);
                 acc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aw[mb][1], b1, acc, 0, 0, 0);
-                if (inb) {
-                    float v[16];
+                float v[16];
 #pragma unroll
-                    for (int i = 0; i < 16; ++i) v[i] = fmaxf(acc[i], floor_);
-                    uint4 *dst = reinterpret_cast<uint4 *>(y + vox * cout + mb * 32 + hb * 16);
-                    const uint32_t dd[8] = {pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]),
-                                            pack2bf(v[8], v[9]), pack2bf(v[10], v[11]), pack2bf(v[12], v[13]), pack2bf(v[14], v[15])};
-                    dst[0] = make_uint4(dd[0], dd[1], dd[2], dd[3]);
-                    dst[1] = make_uint4(dd[4], dd[5], dd[6], dd[7]);
-                    if (ybits)   // one bit per stored element: set where it is > 0
-                        ybits[vox * (cout / 16) + mb * 2 + hb] = (unsigned short)relu_bits16(dd);
+                for (int i = 0; i < 16; ++i) v[i] = fmaxf(acc[i], floor_);
+                const uint32_t dd[8] = {pack2bf(v[0], v[1]), pack2bf(v[2], v[3]), pack2bf(v[4], v[5]), pack2bf(v[6], v[7]),
+                                        pack2bf(v[8], v[9]), pack2bf(v[10], v[11]), pack2bf(v[12], v[13]), pack2bf(v[14], v[15])};
+                uint4 *od = reinterpret_cast<uint4 *>(ow + vl * ROWP + mb * 64 + hb * 32);
+                od[0] = make_uint4(dd[0], dd[1], dd[2], dd[3]);
+                od[1] = make_uint4(dd[4], dd[5], dd[6], dd[7]);
+                if (BITS)   // one bit per stored element: set where it is > 0
+                    obits[wv][vl * (2 * MB) + mb * 2 + hb] = (unsigned short)relu_bits16(dd);
+            }
+            // read the patch back row-major: instruction k carries voxels k * VPI ... of the patch (voxel j:
+            // row j / 16, column j % 16 of the patch's two rows), LPVX lanes of 16 bytes per voxel
+#pragma unroll
+            for (int k = 0; k < 32 / VPI; ++k) {
+                const int j = k * VPI + lane / LPVX, piece = lane % LPVX;
+                const int jh = (patch & 3) * 2 + (j >> 4), jw = j & 15;
+                const bool jin = t.d0 + ld < D && t.h0 + jh < H && t.w0 + jw < W;
+                const int voff = jin ? (((ld * H + jh) * W + jw) * cout) * 2 + piece * 16 : -1;
+                uint4 d = *reinterpret_cast<const uint4 *>(ow + j * ROWP + piece * 16);
+                __builtin_amdgcn_raw_buffer_store_b128(u32x4{d.x, d.y, d.z, d.w}, yrs, voff, 0, 0);
+                // With several waves on a SIMD a 16-byte buffer store still reads its data registers a few
+                // cycles after it has issued; the two wait states the compiler leaves before the next write
+                // of such a register were not enough (single lanes stored a later value at 4 x 320^3).
+                // Keep the registers untouched for eight more cycles.
+                asm volatile("s_nop 7" : "+v"(d.x), "+v"(d.y), "+v"(d.z), "+v"(d.w));
+            }
+            if (BITS) {   // lane j < 32 stores the 2 * MB bit words of voxel j in one piece
+                const int j = lane & 31, jh = (patch & 3) * 2 + (j >> 4), jw = j & 15;
+                const bool jin = lane < 32 && t.d0 + ld < D && t.h0 + jh < H && t.w0 + jw < W;
+                const int boff = jin ? ((ld * H + jh) * W + jw) * (cout / 8) : -1;
+                const unsigned short *ob = &obits[wv][j * (2 * MB)];
+                if (MB == 1) {
+                    __builtin_amdgcn_raw_buffer_store_b32(*reinterpret_cast<const unsigned *>(ob), brs, boff, 0, 0);
+                } else if (MB == 2) {
+                    typedef __attribute__((ext_vector_type(2))) unsigned u32x2;
+                    const uint2 w2 = *reinterpret_cast<const uint2 *>(ob);
+                    __builtin_amdgcn_raw_buffer_store_b64(u32x2{w2.x, w2.y}, brs, boff, 0, 0);
+                } else {
+                    uint4 w4 = *reinterpret_cast<const uint4 *>(ob);
+                    __builtin_amdgcn_raw_buffer_store_b128(u32x4{w4.x, w4.y, w4.z, w4.w}, brs, boff, 0, 0);
+                    asm volatile("s_nop 7" : "+v"(w4.x), "+v"(w4.y), "+v"(w4.z), "+v"(w4.w));
                 }
             }
         }
+        store_x_regs(xs[buf ^ 1], xnext);
+        __syncthreads();
     }
 }
 
@@ -308,7 +420,7 @@ __global__ __launch_bounds__(256) void conv_first_wgrad_mfma_kernel(const bf16_t
     constexpr int GSTAGE = MB * GB;
     extern __shared__ __attribute__((aligned(16))) unsigned char smem[];   // [2][GSTAGE] dy, then 2 x halo tiles, then 4 KB
     bf16_t *xs0 = reinterpret_cast<bf16_t *>(smem + 2 * GSTAGE);
-    float *red = reinterpret_cast<float *>(smem + 2 * GSTAGE + 2 * (NHALO + 8) * 2);
+    float *red = reinterpret_cast<float *>(smem + 2 * GSTAGE + 2 * FIRST_XS * 2);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int hb = lane >> 5, r = lane & 31, g16 = (lane >> 4) & 1, j = lane & 15;
@@ -353,14 +465,20 @@ __global__ __launch_bounds__(256) void conv_first_wgrad_mfma_kernel(const bf16_t
         for (int i = 0; i < 16; ++i) acc[mb][i] = 0.f;
 
     int buf = 0;
-    if ((int64_t)blockIdx.x < ntiles) issue_g(blockIdx.x, 0);
+    if ((int64_t)blockIdx.x < ntiles) {
+        issue_g(blockIdx.x, 0);
+        stage_x_bf16(x, xs0, first_tile(blockIdx.x, ntd, nth, ntw), D, H, W);
+    }
     for (int64_t tile = blockIdx.x; tile < ntiles; tile += gridDim.x, buf ^= 1) {
-        const FirstTile t = first_tile(tile, ntd, nth, ntw);
-        bf16_t *xs = xs0 + buf * (NHALO + 8);
-        stage_x_bf16(x, xs, t, D, H, W);
+        bf16_t *xs = xs0 + buf * FIRST_XS;
         asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
         __syncthreads();   // dy tile and halo tile of this stage are in LDS; the other buffers are free
-        if (tile + gridDim.x < ntiles) issue_g(tile + gridDim.x, buf ^ 1);
+        // the next tile: its dy copies and its halo loads are in flight while this tile is multiplied; the
+        // halo values wait in registers and go to the other halo buffer behind the work
+        const bool more = tile + gridDim.x < ntiles;
+        FirstHaloRegs xnext;
+        if (more) issue_g(tile + gridDim.x, buf ^ 1);
+        load_x_regs(x, xnext, first_tile(more ? tile + gridDim.x : tile, ntd, nth, ntw), D, H, W);   // (the last tile: itself again, unused)
         const unsigned char *gs = smem + buf * GSTAGE;
 #pragma unroll
         for (int q = 0; q < 8; ++q) {
@@ -381,6 +499,7 @@ __global__ __launch_bounds__(256) void conv_first_wgrad_mfma_kernel(const bf16_t
                 acc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ax, __builtin_bit_cast(bf16x8, v), acc[mb], 0, 0, 0);
             }
         }
+        store_x_regs(xs0 + (buf ^ 1) * FIRST_XS, xnext);
     }
     // add the four waves in wave order; acc[mb][i] is row (i/4)*8 + hb*4 + i%4, column mb*32 + lane%32
     float *out = ws + (int64_t)blockIdx.x * per_split;
@@ -418,25 +537,25 @@ static bool first_mfma_ok(const ConvArgs &a)
     return (a.cout == 32 || a.cout == 64 || a.cout == 128) && (int64_t)(first::TD + 1) * a.H * a.W * a.cout * 2 < 0x7fffffffLL;
 }
 
+template <int MB, bool BITS>
+static void launch_first_fwd_mfma(const ConvArgs &a, int ntd, int nth, int ntw, int64_t ntiles, hipStream_t st)
+{
+    const unsigned grid = (unsigned)(ntiles < 2048 ? ntiles : 2048);
+    conv_first_fwd_mfma_kernel<MB, BITS><<<dim3(grid), 256, 0, st>>>((const bf16_t *)a.x, (const bf16_t *)a.w, a.bias, a.relu,
+                                                                    (bf16_t *)a.y, (unsigned short *)a.ybits, (int)a.D, (int)a.H,
+                                                                    (int)a.W, ntd, nth, ntw, ntiles);
+}
+
 int conv_first_fwd(const ConvArgs &a, hipStream_t st)
 {
     int ntd, nth, ntw;
     int64_t ntiles = first_tiles(a, &ntd, &nth, &ntw);
     if (ntiles > 0x7fffffffLL) return K3_E_UNSUPPORTED;
     if (first_mfma_ok(a)) {
-        const unsigned grid = (unsigned)(ntiles < 2048 ? ntiles : 2048);
-        if (a.cout == 128)
-            conv_first_fwd_mfma_kernel<4><<<dim3(grid), 256, 0, st>>>((const bf16_t *)a.x, (const bf16_t *)a.w, a.bias, a.relu,
-                                                                     (bf16_t *)a.y, (unsigned short *)a.ybits, (int)a.D, (int)a.H,
-                                                                     (int)a.W, ntd, nth, ntw, ntiles);
-        else if (a.cout == 64)
-            conv_first_fwd_mfma_kernel<2><<<dim3(grid), 256, 0, st>>>((const bf16_t *)a.x, (const bf16_t *)a.w, a.bias, a.relu,
-                                                                     (bf16_t *)a.y, (unsigned short *)a.ybits, (int)a.D, (int)a.H,
-                                                                     (int)a.W, ntd, nth, ntw, ntiles);
-        else
-            conv_first_fwd_mfma_kernel<1><<<dim3(grid), 256, 0, st>>>((const bf16_t *)a.x, (const bf16_t *)a.w, a.bias, a.relu,
-                                                                     (bf16_t *)a.y, (unsigned short *)a.ybits, (int)a.D, (int)a.H,
-                                                                     (int)a.W, ntd, nth, ntw, ntiles);
+        const bool bits = a.ybits != nullptr;
+        if (a.cout == 128) bits ? launch_first_fwd_mfma<4, true>(a, ntd, nth, ntw, ntiles, st) : launch_first_fwd_mfma<4, false>(a, ntd, nth, ntw, ntiles, st);
+        else if (a.cout == 64) bits ? launch_first_fwd_mfma<2, true>(a, ntd, nth, ntw, ntiles, st) : launch_first_fwd_mfma<2, false>(a, ntd, nth, ntw, ntiles, st);
+        else bits ? launch_first_fwd_mfma<1, true>(a, ntd, nth, ntw, ntiles, st) : launch_first_fwd_mfma<1, false>(a, ntd, nth, ntw, ntiles, st);
         K3_LAUNCH_CHECK();
         return K3_OK;
     }
@@ -455,7 +574,7 @@ template <int MB>
 static int launch_first_wgrad_mfma(const ConvArgs &a, float *ws, int64_t per, int ntd, int nth, int ntw, int64_t ntiles,
                                    hipStream_t st, int coff = 0)
 {
-    constexpr int lds = 2 * MB * firstm::NVOX * 64 + 2 * (firstm::NHALO + 8) * 2 + 256 * 4;
+    constexpr int lds = 2 * MB * firstm::NVOX * 64 + 2 * FIRST_XS * 2 + 256 * 4;
     static_assert(lds <= 160 * 1024, "LDS budget");
     static bool attr_done = false;
     if (!attr_done) {
@@ -480,6 +599,7 @@ int conv_first_wgrad(const ConvArgs &a, float *dW, float *db, float *ws, hipStre
 {
     int ntd, nth, ntw;
     int64_t ntiles = first_tiles(a, &ntd, &nth, &ntw);
+    if (ntiles > 0x7fffffffLL) return K3_E_UNSUPPORTED;
     int64_t nsplit = first_nsplit(ntiles);
     int64_t per = 28 * a.cout;   // 27 tap rows + the bias row: canonical [27][1][cout] followed by db
     if (first_mfma_ok(a) && !a.ymask) {
