@@ -197,6 +197,161 @@ static int launch_up_fwd_lds(const bf16_t *x, const bf16_t *packed, const float 
     return K3_OK;
 }
 
+// ------------------------------------------------------------------ MFMA forward, deep levels (C_in = 256, 512)
+// With 256 or 512 input channels the op is as much a GEMM as a stream (16 or 32 MFMAs per tap, block
+// and 32 voxels) and a wave is alone on its SIMD (the weights fill the LDS), so the kernel above loses
+// its time to latencies: its loads are waited for right where they are issued, and the MFMAs of a
+// (tap, block) form one dependent chain on a single accumulator.  Here
+//   * a workgroup owns one 32-channel output block and NT taps (blockIdx.z picks the tap group:
+//     NT x NKC KB of packed weights in LDS, 128 KB for both channel counts),
+//   * the B fragments of the NEXT block of voxels are requested before the current block is multiplied
+//     (two register sets used in turn; clamped addresses, so the loop has no conditional memory
+//     operation and the waits are counted),
+//   * two accumulator chains run interleaved: two groups of 32 voxels against the same weight fragment
+//     (VG = 2, C_in = 256: one LDS read per two MFMAs) or two taps against the same voxels (VG = 1,
+//     C_in = 512, where two voxel groups would not fit the registers twice),
+//   * results leave through a descriptor at the block's first output voxel with 32-bit offsets; lanes
+//     beyond the last voxel get an offset outside its range and their stores are dropped.
+template <int NKC, int NT, int VG>
+__global__ __launch_bounds__(256, 1) void up_fwd_deep_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ packed,
+                                                            const float *__restrict__ bias, bf16_t *__restrict__ y,
+                                                            int64_t V, int D, int H, int W, int cout)
+{
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int cin = NKC * 16;
+    constexpr int BV = 128 * VG;                      // voxels per block
+    const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int hb = lane >> 5, vl = lane & 31;
+    const int cob = blockIdx.y, ncob = cout / 32, tap0 = blockIdx.z * NT;
+    {   // weights of this workgroup's output block and taps: LDS [tap][kc][lane] x 16 bytes
+        const uint4 *src = reinterpret_cast<const uint4 *>(packed);
+        uint4 *dst = reinterpret_cast<uint4 *>(smem);
+        for (int i = threadIdx.x; i < NT * NKC * 64; i += 256) {
+            const int ln = i & 63, kc = (i >> 6) % NKC, t = i / (64 * NKC);
+            dst[i] = src[(((int64_t)(tap0 + t) * ncob + cob) * NKC + kc) * 64 + ln];
+        }
+    }
+    float bv[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) bv[i] = bias ? bias[cob * 32 + hb * 16 + i] : 0.f;
+    __syncthreads();
+    const int64_t nblk = (V + BV - 1) / BV;
+    const unsigned HW = (unsigned)H * (unsigned)W;
+
+    auto load_b = [&](int64_t blk, bf16x8 (&b)[VG][NKC]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int g = 0; g < VG; ++g) {
+            int64_t v = blk * BV + (g * 4 + wv) * 32 + vl;
+            v = v < V ? v : V - 1;
+            const uint4 *xp = reinterpret_cast<const uint4 *>(x + v * cin + hb * 8);
+#pragma unroll
+            for (int kc = 0; kc < NKC; ++kc) b[g][kc] = __builtin_bit_cast(bf16x8, xp[kc * 2]);
+        }
+    };
+    // output voxel index of input voxel v (tap 0): 8 H W (n D + d) + 4 h W + 2 w
+    auto out_index = [&](unsigned v) __attribute__((always_inline)) {
+        const unsigned plane = v / HW, r = v - plane * HW, h = r / (unsigned)W, w = r - h * (unsigned)W;
+        return (int64_t)plane * (8 * (int64_t)HW) + (int64_t)(4 * h * (unsigned)W + 2 * w);
+    };
+    auto store16 = [&](const f32x16 &acc, __amdgpu_buffer_rsrc_t rs, int off) __attribute__((always_inline)) {
+        typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+        u32x4 lo = {pack2bf(acc[0], acc[1]), pack2bf(acc[2], acc[3]), pack2bf(acc[4], acc[5]), pack2bf(acc[6], acc[7])};
+        u32x4 hi = {pack2bf(acc[8], acc[9]), pack2bf(acc[10], acc[11]), pack2bf(acc[12], acc[13]), pack2bf(acc[14], acc[15])};
+        __builtin_amdgcn_raw_buffer_store_b128(lo, rs, off, 0, 0);
+        __builtin_amdgcn_raw_buffer_store_b128(hi, rs, off, 16, 0);
+        // a 16-byte buffer store may read its data registers a few cycles after it has issued: keep them untouched
+        asm volatile("s_nop 7" : "+v"(lo), "+v"(hi));
+    };
+    auto compute = [&](int64_t blk, const bf16x8 (&b)[VG][NKC]) __attribute__((always_inline)) {
+        const unsigned vfirst = (unsigned)(blk * BV);                  // (V fits 31 bits: checked at launch)
+        const int64_t ofirst = out_index(vfirst);
+        __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(y + ofirst * cout + cob * 32, 0, 0x7ffffff0, 0x00020000);
+        int off0[VG];                                                  // byte offset of the lane's tap-0 output voxel, or "dropped"
+#pragma unroll
+        for (int g = 0; g < VG; ++g) {
+            const int64_t v = blk * BV + (g * 4 + wv) * 32 + vl;
+            const bool live = v < V;
+            const int64_t o = out_index(live ? (unsigned)v : vfirst) - ofirst;
+            off0[g] = live ? ((int)o * cout + hb * 16) * 2 : -1;
+        }
+        const bf16x8 *aw = reinterpret_cast<const bf16x8 *>(smem) + lane;
+        if (VG == 2) {
+#pragma unroll
+            for (int t = 0; t < NT; ++t) {
+                const int tap = tap0 + t;
+                const int toff = (((tap >> 2) * 2 * H + ((tap >> 1) & 1)) * (2 * W) + (tap & 1)) * cout * 2;
+                f32x16 a0, a1;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) a0[i] = a1[i] = bv[i];
+#pragma unroll
+                for (int kc = 0; kc < NKC; ++kc) {
+                    const bf16x8 a = aw[(t * NKC + kc) * 64];
+                    a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[0][kc], a0, 0, 0, 0);
+                    a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, b[VG - 1][kc], a1, 0, 0, 0);
+                }
+                store16(a0, rs, off0[0] < 0 ? -1 : off0[0] + toff);
+                store16(a1, rs, off0[VG - 1] < 0 ? -1 : off0[VG - 1] + toff);
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < NT; t += 2) {
+                const int tapa = tap0 + t, tapb = tap0 + t + 1;
+                const int toffa = (((tapa >> 2) * 2 * H + ((tapa >> 1) & 1)) * (2 * W) + (tapa & 1)) * cout * 2;
+                const int toffb = (((tapb >> 2) * 2 * H + ((tapb >> 1) & 1)) * (2 * W) + (tapb & 1)) * cout * 2;
+                f32x16 a0, a1;
+#pragma unroll
+                for (int i = 0; i < 16; ++i) a0[i] = a1[i] = bv[i];
+#pragma unroll
+                for (int kc = 0; kc < NKC; ++kc) {
+                    a0 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aw[(t * NKC + kc) * 64], b[0][kc], a0, 0, 0, 0);
+                    a1 = __builtin_amdgcn_mfma_f32_32x32x16_bf16(aw[((t + 1) * NKC + kc) * 64], b[0][kc], a1, 0, 0, 0);
+                }
+                store16(a0, rs, off0[0] < 0 ? -1 : off0[0] + toffa);
+                store16(a1, rs, off0[0] < 0 ? -1 : off0[0] + toffb);
+            }
+        }
+    };
+
+    if ((int64_t)blockIdx.x >= nblk) return;
+    bf16x8 b0[VG][NKC], b1[VG][NKC];
+    load_b(blockIdx.x, b0);
+    for (int64_t blk = blockIdx.x; blk < nblk; blk += 2 * (int64_t)gridDim.x) {
+        const int64_t nx = blk + gridDim.x, nx2 = blk + 2 * (int64_t)gridDim.x;
+        load_b(nx < nblk ? nx : nblk - 1, b1);          // (beyond the end: the last block again, unused)
+        compute(blk, b0);
+        if (nx >= nblk) break;
+        load_b(nx2 < nblk ? nx2 : nblk - 1, b0);
+        compute(nx, b1);
+    }
+}
+
+template <int NKC, int NT, int VG>
+static int launch_up_fwd_deep(const bf16_t *x, const bf16_t *packed, const float *bias, bf16_t *y, int64_t V, int D, int H,
+                              int W, int cout, hipStream_t st)
+{
+    constexpr int lds = NT * NKC * 1024;
+    static_assert(lds <= 160 * 1024 && 8 % NT == 0 && (VG == 2 || NT % 2 == 0), "LDS budget / tap groups");
+    // 32-bit voxel arithmetic and byte offsets from a block's first output voxel (a block of BV consecutive
+    // input voxels spans at most 8 BV + 12 H W output voxels, a tap adds at most 4 H W + 2 W + 1)
+    const int64_t span = 8 * (int64_t)(128 * VG) + 16 * (int64_t)H * W + 2 * (int64_t)W + 2;
+    if (V > 0x7fffffffLL || span * cout * 2 + 64 > 0x7fffffffLL) return K3_E_UNSUPPORTED;
+    static bool attr_done = false;
+    if (!attr_done) {
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&up_fwd_deep_kernel<NKC, NT, VG>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        attr_done = true;
+    }
+    const int ncob = cout / 32, ntg = 8 / NT;
+    const int64_t nblk = (V + 128 * VG - 1) / (128 * VG);
+    int64_t gx = 256 / (ncob * ntg);   // one workgroup per CU in total (the weights fill its LDS)
+    if (gx < 1) gx = 1;
+    if (gx > nblk) gx = nblk;
+    up_fwd_deep_kernel<NKC, NT, VG><<<dim3((unsigned)gx, (unsigned)ncob, (unsigned)ntg), 256, lds, st>>>(x, packed, bias, y, V, D, H,
+                                                                                                      W, cout);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
 // returns K3_E_UNSUPPORTED when the shape has no LDS-resident variant (the caller falls back)
 static int up_fwd_lds_dispatch(const bf16_t *x, const bf16_t *packed, const float *bias, bf16_t *y, int64_t V, int D, int H,
                                int W, int cin, int cout, hipStream_t st)
@@ -209,7 +364,11 @@ static int up_fwd_lds_dispatch(const bf16_t *x, const bf16_t *packed, const floa
                         : launch_up_fwd_lds<4, 1>(x, packed, bias, y, V, D, H, W, cout, st);
     case 128: return two ? launch_up_fwd_lds<8, 2>(x, packed, bias, y, V, D, H, W, cout, st)
                          : launch_up_fwd_lds<8, 1>(x, packed, bias, y, V, D, H, W, cout, st);
-    case 256: return launch_up_fwd_lds<16, 1>(x, packed, bias, y, V, D, H, W, cout, st);
+    case 256: {
+        const int rc = launch_up_fwd_deep<16, 8, 2>(x, packed, bias, y, V, D, H, W, cout, st);
+        return rc != K3_E_UNSUPPORTED ? rc : launch_up_fwd_lds<16, 1>(x, packed, bias, y, V, D, H, W, cout, st);
+    }
+    case 512: return launch_up_fwd_deep<32, 4, 1>(x, packed, bias, y, V, D, H, W, cout, st);
     default: return K3_E_UNSUPPORTED;
     }
 }

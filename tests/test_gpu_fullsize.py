@@ -229,6 +229,40 @@ def test_upconv_bwd_data_at_unet_sizes(orc, sp, ci, co):
         assert rel(gotm[sl], orc.relu_bwd(ref, x[sl].astype(np.float64))) < 4e-3, (d0, h0, w0)
 
 
+@pytest.mark.parametrize("sp,ci,co", [((2, 32, 32, 32), 256, 128),    # level 2 -> 1 of a base-64 net: 4 blocks of 256 voxels per workgroup
+                                      ((1, 17, 16, 19), 512, 256),    # level 3 -> 2: 3 blocks per workgroup, ragged last block, two tap groups
+                                      ((1, 9, 7, 5), 256, 64),        # fewer blocks than workgroups, ragged
+                                      ((1, 40, 36, 28), 512, 512)])   # 16 output blocks x 2 tap groups: 8 workgroups per pair, 40 blocks each
+def test_upconv_fwd_at_deep_levels(orc, sp, ci, co):
+    """The transposed-conv forward kernel of the 256- and 512-channel levels (voxel blocks walked by
+    persistent workgroups with the next block's loads in flight).  The pass is local (an output voxel
+    reads one input voxel), so the oracle runs on crops of input voxels, cut at the corners, at the
+    ragged end and inside; every output voxel is also checked to have been written."""
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev, to_f64, empty
+    N, D, H, W = sp
+    x = synth.activations(67, (N, D, H, W, ci), "bf16")
+    w = synth.upconv_weights(68, ci, co, "bf16")
+    b = (synth.normal(synth.SEED, 69, (co,), np.float64) * 0.5).astype(np.float32)
+    xd, wd, bd = to_dev(x, "bf16"), to_dev(w, "bf16"), torch.from_numpy(b).cuda()
+    pk = torch.empty(k3.upconv3d_packed_bytes(ci, co, k3.BF16), device="cuda", dtype=torch.uint8)
+    k3.upconv3d_pack_weights(wd, pk)
+    y = empty((N, 2 * D, 2 * H, 2 * W, co), "bf16")
+    y.fill_(float("nan"))
+    k3.upconv3d_fwd(xd, wd, pk, bd, y)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(y).any())
+    got = to_f64(y)
+    cd, ch, cw = min(3, D), min(3, H), min(4, W)
+    for n in sorted({0, N - 1}):
+        for (d0, h0, w0) in [(0, 0, 0), (D - cd, H - ch, W - cw), (D // 2, H // 3, W // 2 - 1), (D - cd, 0, W // 2)]:
+            crop = x[n:n + 1, d0:d0 + cd, h0:h0 + ch, w0:w0 + cw, :].astype(np.float64)
+            ref = orc.upconv3d_fwd(crop, w.astype(np.float64), b.astype(np.float64))
+            sl = (slice(n, n + 1), slice(2 * d0, 2 * (d0 + cd)), slice(2 * h0, 2 * (h0 + ch)), slice(2 * w0, 2 * (w0 + cw)))
+            assert rel(got[sl], ref) < 4e-3, (n, d0, h0, w0)
+
+
 @pytest.mark.parametrize("N,S,c1,c2,co", [(1, 64, 32, 0, 32),      # 8x8x16 tiles, one output block per workgroup (the benchmark's layer)
                                            (1, 64, 64, 0, 64),      # two blocks per workgroup: ring of mask words vs bits
                                            (1, 32, 128, 0, 128),    # 4x8x8 tiles, two blocks
