@@ -543,6 +543,202 @@ static bool up_dgrad_tap_dispatch(const bf16_t *dy, const bf16_t *pb, bf16_t *dx
     return false;
 }
 
+// ------------------------------------------------------------------ MFMA backward-data, weights in LDS
+// The kernels above read every weight fragment from global memory / L2 right before its matrix
+// instruction: 1 KB per MFMA, which at the 64- to 256-channel levels of a large volume is several
+// times the traffic of dy itself and sets the pace.  Here a persistent workgroup keeps the packed
+// weights of its MBW 32-channel blocks of dx in LDS (MBW x 8 taps x NKC KB = 128 KB for the three
+// shapes served) and walks blocks of 128 * VG input voxels.  Per tap the NKC dy fragments of a voxel
+// group are in registers; the fragments of the NEXT tap (or of the next block's first tap) are
+// requested before the current tap is multiplied, into the other of two register sets.  VG * MBW
+// accumulators give independent MFMA chains, and with VG = 2 a weight fragment read from LDS serves
+// two matrix instructions.  All loads go through descriptors at the block's first voxel with
+// 32-bit offsets and are unconditional (lanes beyond the last voxel read the block's first voxel
+// and their stores are dropped), so the waits are counted.  The ReLU mask of dx, when given, is
+// requested at the start of a block and applied at its end.
+template <int NKC, int MBW, int VG, bool MASK>
+__global__ __launch_bounds__(256, 1) void up_dgrad_lds_kernel(const bf16_t *__restrict__ dy, const bf16_t *__restrict__ packed,
+                                                             bf16_t *__restrict__ dx, const bf16_t *__restrict__ omask,
+                                                             int64_t V, int D, int H, int W, int cin)
+{
+    typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
+    extern __shared__ __attribute__((aligned(16))) unsigned char smem[];
+    constexpr int cout = NKC * 16;
+    constexpr int BV = 128 * VG;
+    const int lane = threadIdx.x & 63, wv = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int hb = lane >> 5, vl = lane & 31;
+    const int cib0 = blockIdx.y * MBW;
+    {   // weights of this workgroup's blocks of dx: LDS [m][tap][kc][lane] x 16 bytes (the packed order)
+        const uint4 *src = reinterpret_cast<const uint4 *>(packed) + (int64_t)cib0 * 8 * NKC * 64;
+        uint4 *dst = reinterpret_cast<uint4 *>(smem);
+        for (int i = threadIdx.x; i < MBW * 8 * NKC * 64; i += 256) dst[i] = src[i];
+    }
+    __syncthreads();
+    const int64_t nblk = (V + BV - 1) / BV;
+    if ((int64_t)blockIdx.x >= nblk) return;
+    const unsigned HW = (unsigned)H * (unsigned)W;
+    // output voxel index of input voxel v (tap 0): 8 H W (n D + d) + 4 h W + 2 w
+    auto out_index = [&](unsigned v) __attribute__((always_inline)) {
+        const unsigned plane = v / HW, r = v - plane * HW, h = r / (unsigned)W, w = r - h * (unsigned)W;
+        return (int64_t)plane * (8 * (int64_t)HW) + (int64_t)(4 * h * (unsigned)W + 2 * w);
+    };
+    struct Src {
+        __amdgpu_buffer_rsrc_t rs;   // dy at the block's first output voxel
+        int voff[VG];                // the lane's tap-0 byte offset from there
+    };
+    auto make_src = [&](int64_t blk) __attribute__((always_inline)) {
+        Src s;
+        const unsigned vfirst = (unsigned)(blk * BV);                  // (V fits 31 bits: checked at launch)
+        const int64_t ofirst = out_index(vfirst);
+        s.rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(dy) + ofirst * cout, 0, 0x7ffffff0, 0x00020000);
+#pragma unroll
+        for (int g = 0; g < VG; ++g) {
+            const int64_t v = blk * BV + (g * 4 + wv) * 32 + vl;
+            const int64_t o = out_index(v < V ? (unsigned)v : vfirst) - ofirst;
+            s.voff[g] = (int)o * cout * 2 + hb * 16;
+        }
+        return s;
+    };
+    auto load_tap = [&](const Src &s, int t, u32x4 (&b)[VG][NKC]) __attribute__((always_inline)) {
+        const int toff = (((t >> 2) * 2 * H + ((t >> 1) & 1)) * (2 * W) + (t & 1)) * cout * 2;
+#pragma unroll
+        for (int g = 0; g < VG; ++g)
+#pragma unroll
+            for (int kc = 0; kc < NKC; ++kc) b[g][kc] = __builtin_amdgcn_raw_buffer_load_b128(s.rs, s.voff[g] + kc * 32, toff, 0);
+    };
+    f32x16 acc[VG][MBW];
+    auto zero_acc = [&]() __attribute__((always_inline)) {
+#pragma unroll
+        for (int g = 0; g < VG; ++g)
+#pragma unroll
+            for (int m = 0; m < MBW; ++m)
+#pragma unroll
+                for (int i = 0; i < 16; ++i) acc[g][m][i] = 0.f;
+    };
+    const bf16x8 *aw = reinterpret_cast<const bf16x8 *>(smem) + lane;
+    auto mfma_tap = [&](int t, const u32x4 (&b)[VG][NKC]) __attribute__((always_inline)) {
+#pragma unroll
+        for (int kc = 0; kc < NKC; ++kc)
+#pragma unroll
+            for (int m = 0; m < MBW; ++m) {
+                const bf16x8 a = aw[((m * 8 + t) * NKC + kc) * 64];
+#pragma unroll
+                for (int g = 0; g < VG; ++g)
+                    acc[g][m] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(a, __builtin_bit_cast(bf16x8, b[g][kc]), acc[g][m], 0, 0, 0);
+            }
+    };
+
+    int64_t blk = blockIdx.x;
+    Src cur = make_src(blk);
+    u32x4 b0[VG][NKC], b1[VG][NKC];
+    load_tap(cur, 0, b0);
+    zero_acc();
+    for (;;) {
+        // dx (and its mask) of this block: descriptors at the block's first voxel, first channel of the workgroup
+        const int64_t vfirst = blk * BV;
+        __amdgpu_buffer_rsrc_t xrs = __builtin_amdgcn_make_buffer_rsrc(dx + vfirst * cin + cib0 * 32, 0, 0x7ffffff0, 0x00020000);
+        __amdgpu_buffer_rsrc_t mrs = __builtin_amdgcn_make_buffer_rsrc(const_cast<bf16_t *>(MASK ? omask : dx) + vfirst * cin + cib0 * 32,
+                                                                       0, 0x7ffffff0, 0x00020000);
+        int xoff[VG];
+        u32x4 mk[VG][MBW][2];
+#pragma unroll
+        for (int g = 0; g < VG; ++g) {
+            const int64_t v = vfirst + (g * 4 + wv) * 32 + vl;
+            const int lo = ((int)(v - vfirst) * cin + hb * 16) * 2;
+            xoff[g] = v < V ? lo : -1;
+            if (MASK) {
+                const int mo = v < V ? lo : hb * 32;
+#pragma unroll
+                for (int m = 0; m < MBW; ++m) {
+                    mk[g][m][0] = __builtin_amdgcn_raw_buffer_load_b128(mrs, mo, m * 64, 0);
+                    mk[g][m][1] = __builtin_amdgcn_raw_buffer_load_b128(mrs, mo, m * 64 + 16, 0);
+                }
+            }
+        }
+        const int64_t nb = blk + gridDim.x;
+        Src nxt = cur;
+#pragma unroll
+        for (int t = 0; t < 8; ++t) {
+            if (t < 7) {
+                load_tap(cur, t + 1, (t & 1) ? b0 : b1);
+            } else {
+                nxt = make_src(nb < nblk ? nb : nblk - 1);      // (beyond the end: the last block again, unused)
+                load_tap(nxt, 0, b0);
+            }
+            mfma_tap(t, (t & 1) ? b1 : b0);
+        }
+#pragma unroll
+        for (int g = 0; g < VG; ++g)
+#pragma unroll
+            for (int m = 0; m < MBW; ++m) {
+                const f32x16 &a = acc[g][m];
+                u32x4 o0 = {pack2bf(a[0], a[1]), pack2bf(a[2], a[3]), pack2bf(a[4], a[5]), pack2bf(a[6], a[7])};
+                u32x4 o1 = {pack2bf(a[8], a[9]), pack2bf(a[10], a[11]), pack2bf(a[12], a[13]), pack2bf(a[14], a[15])};
+                if (MASK) {
+#pragma unroll
+                    for (int i = 0; i < 4; ++i) {
+                        o0[i] = up_mask_pair(o0[i], mk[g][m][0][i]);
+                        o1[i] = up_mask_pair(o1[i], mk[g][m][1][i]);
+                    }
+                }
+                __builtin_amdgcn_raw_buffer_store_b128(o0, xrs, xoff[g], m * 64, 0);
+                __builtin_amdgcn_raw_buffer_store_b128(o1, xrs, xoff[g], m * 64 + 16, 0);
+                // a 16-byte buffer store may read its data registers a few cycles after it has issued: keep them untouched
+                asm volatile("s_nop 7" : "+v"(o0), "+v"(o1));
+            }
+        zero_acc();
+        blk = nb;
+        if (blk >= nblk) break;
+        cur = nxt;
+    }
+}
+
+template <int NKC, int MBW, int VG>
+static int launch_up_dgrad_lds(const bf16_t *dy, const bf16_t *pb, bf16_t *dx, const bf16_t *mask, int64_t V, int D, int H, int W,
+                               int cin, hipStream_t st)
+{
+    constexpr int lds = MBW * 8 * NKC * 1024;
+    static_assert(lds <= 160 * 1024, "LDS budget");
+    constexpr int cout = NKC * 16;
+    // 32-bit voxel arithmetic and byte offsets from a block's first voxel (a block of BV consecutive input
+    // voxels spans at most 8 BV + 12 H W output voxels, a tap adds at most 4 H W + 2 W + 1)
+    const int64_t span = 8 * (int64_t)(128 * VG) + 16 * (int64_t)H * W + 2 * (int64_t)W + 2;
+    if (V > 0x7fffffffLL || span * cout * 2 + 64 > 0x7fffffffLL || (int64_t)128 * VG * cin * 2 > 0x7fffffffLL ||
+        (cin / 32) % MBW != 0)
+        return K3_E_UNSUPPORTED;
+    static bool attr_done = false;
+    if (!attr_done) {
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&up_dgrad_lds_kernel<NKC, MBW, VG, false>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        K3_HIP(hipFuncSetAttribute(reinterpret_cast<const void *>(&up_dgrad_lds_kernel<NKC, MBW, VG, true>),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, lds));
+        attr_done = true;
+    }
+    const int ngrp = cin / 32 / MBW;
+    const int64_t nblk = (V + 128 * VG - 1) / (128 * VG);
+    int64_t gx = 256 / ngrp;   // one workgroup per CU in total (the weights fill its LDS)
+    if (gx < 1) gx = 1;
+    if (gx > nblk) gx = nblk;
+    if (mask)
+        up_dgrad_lds_kernel<NKC, MBW, VG, true><<<dim3((unsigned)gx, (unsigned)ngrp), 256, lds, st>>>(dy, pb, dx, mask, V, D, H, W, cin);
+    else
+        up_dgrad_lds_kernel<NKC, MBW, VG, false><<<dim3((unsigned)gx, (unsigned)ngrp), 256, lds, st>>>(dy, pb, dx, mask, V, D, H, W, cin);
+    K3_LAUNCH_CHECK();
+    return K3_OK;
+}
+
+// The LDS-resident form serves the levels of a large volume: enough voxel blocks to give every compute unit
+// several, and a channel pair it has an instantiation for.  K3_E_UNSUPPORTED: the caller uses the forms above.
+static int up_dgrad_lds_dispatch(const bf16_t *dy, const bf16_t *pb, bf16_t *dx, const bf16_t *mask, int64_t V, int D, int H,
+                                 int W, int cin, int cout, hipStream_t st)
+{
+    if (V < 4 * 256 * 128) return K3_E_UNSUPPORTED;
+    if (cout == 64 && cin % 128 == 0) return launch_up_dgrad_lds<4, 4, 1>(dy, pb, dx, mask, V, D, H, W, cin, st);
+    if (cout == 128 && cin % 64 == 0) return launch_up_dgrad_lds<8, 2, 2>(dy, pb, dx, mask, V, D, H, W, cin, st);
+    if (cout == 256) return launch_up_dgrad_lds<16, 1, 2>(dy, pb, dx, mask, V, D, H, W, cin, st);
+    return K3_E_UNSUPPORTED;
+}
+
 // ------------------------------------------------------------------ MFMA backward-weight
 // dW[t][ci][co] = sum_v x[v][ci] * dy[2v + t][co]: the contraction runs over input voxels and
 // dy is the large tensor (8 voxels per input voxel), so the pass is HBM-bound and every byte
@@ -989,6 +1185,8 @@ int k3_upconv3d_bwd_data(const k3_tensor *dyd, const void *dy, const void *w, co
         int64_t blocks = (V + 127) / 128;
         if (blocks > 0x7fffffffLL) return K3_E_UNSUPPORTED;
         int nb = cin / 32;
+        rc = up_dgrad_lds_dispatch((const bf16_t *)dy, pb, (bf16_t *)dx, (const bf16_t *)dx_mask, V, D, H, W, cin, cout, st);
+        if (rc != K3_E_UNSUPPORTED) return rc;
         if (up_dgrad_tap_dispatch((const bf16_t *)dy, pb, (bf16_t *)dx, (const bf16_t *)dx_mask, V, D, H, W, cin, cout, st)) {
             K3_LAUNCH_CHECK();
             return K3_OK;

@@ -229,6 +229,45 @@ def test_upconv_bwd_data_at_unet_sizes(orc, sp, ci, co):
         assert rel(gotm[sl], orc.relu_bwd(ref, x[sl].astype(np.float64))) < 4e-3, (d0, h0, w0)
 
 
+@pytest.mark.parametrize("sp,ci,co", [((2, 40, 42, 40), 128, 64),      # all four blocks of dx in one workgroup, dy read once; ragged last block
+                                      ((1, 52, 51, 50), 256, 128),    # two blocks per workgroup, two voxel groups per wave
+                                      ((1, 51, 52, 50), 512, 256),    # one block per workgroup, 16 groups
+                                      ((1, 64, 64, 40), 256, 64)])    # two groups of four blocks
+def test_upconv_bwd_data_with_weights_in_lds(orc, sp, ci, co):
+    """The transposed-conv backward-data kernel that large volumes select (weights resident in LDS, persistent
+    workgroups, the next tap's loads in flight), without and with the ReLU mask of dx.  Tensors are made on
+    the device; the pass is local, so the oracle runs on crops of input voxels (corners, the ragged end,
+    inside), and every element of dx is checked to have been written."""
+    import torch
+    from paper_1811_12174_amd import k3
+    from gpu_util import to_dev
+    N, D, H, W = sp
+    assert N * D * H * W >= 4 * 256 * 128            # what the dispatch asks for before it picks this kernel
+    gen = torch.Generator(device="cuda")
+    gen.manual_seed(1811 + ci + co)
+    dyd = torch.randn((N, 2 * D, 2 * H, 2 * W, co), device="cuda", generator=gen).to(torch.bfloat16)
+    xd = torch.relu(torch.randn((N, D, H, W, ci), device="cuda", generator=gen)).to(torch.bfloat16)   # the stored ReLU output used as mask
+    w = synth.upconv_weights(65, ci, co, "bf16")
+    wd = to_dev(w, "bf16")
+    pk = torch.empty(k3.upconv3d_packed_bytes(ci, co, k3.BF16), device="cuda", dtype=torch.uint8)
+    k3.upconv3d_pack_weights(wd, pk)
+    dx = torch.full_like(xd, float("nan"))
+    dxm = torch.full_like(xd, float("nan"))
+    k3.upconv3d_bwd_data(dyd, wd, pk, dx)
+    k3.upconv3d_bwd_data(dyd, wd, pk, dxm, dx_mask=xd)
+    torch.cuda.synchronize()
+    assert not bool(torch.isnan(dx).any()) and not bool(torch.isnan(dxm).any())
+    f64 = lambda t: t.to(torch.float32).cpu().numpy().astype(np.float64)
+    cd, ch, cw = 3, 3, 4
+    for n in sorted({0, N - 1}):
+        for (d0, h0, w0) in [(0, 0, 0), (D - cd, H - ch, W - cw), (D // 2, H // 3, W // 2 - 1), (D - cd, 0, W // 2), (1, H - ch, 3)]:
+            crop = f64(dyd[n:n + 1, 2 * d0:2 * (d0 + cd), 2 * h0:2 * (h0 + ch), 2 * w0:2 * (w0 + cw), :])
+            ref = orc.upconv3d_bwd_data(crop, w.astype(np.float64))
+            sl = (slice(n, n + 1), slice(d0, d0 + cd), slice(h0, h0 + ch), slice(w0, w0 + cw))
+            assert rel(f64(dx[sl]), ref) < 4e-3, (n, d0, h0, w0)
+            assert rel(f64(dxm[sl]), orc.relu_bwd(ref, f64(xd[sl]))) < 4e-3, (n, d0, h0, w0)
+
+
 @pytest.mark.parametrize("sp,ci,co", [((2, 32, 32, 32), 256, 128),    # level 2 -> 1 of a base-64 net: 4 blocks of 256 voxels per workgroup
                                       ((1, 17, 16, 19), 512, 256),    # level 3 -> 2: 3 blocks per workgroup, ragged last block, two tap groups
                                       ((1, 9, 7, 5), 256, 64),        # fewer blocks than workgroups, ragged
