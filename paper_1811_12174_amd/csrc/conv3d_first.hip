@@ -271,7 +271,7 @@ typedef __attribute__((ext_vector_type(4))) unsigned u32x4;
 // Forward: D[co][voxel] = sum_tap W[tap][co] * x[voxel + tap]; K = 32 (27 taps + 5 zero rows) = 2 MFMAs
 // per 32 voxels and 32-channel block.  Persistent blocks walk the 4x8x16 tiles.
 template <int MB, bool BITS>
-__global__ __launch_bounds__(256) void conv_first_fwd_mfma_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
+__global__ __launch_bounds__(256, MB <= 2 ? 4 : 3) void conv_first_fwd_mfma_kernel(const bf16_t *__restrict__ x, const bf16_t *__restrict__ w,
                                                                  const float *__restrict__ bias, int relu,
                                                                  bf16_t *__restrict__ y, unsigned short *__restrict__ ybits,
                                                                  int D, int H, int W, int ntd, int nth, int ntw,
@@ -335,9 +335,15 @@ __global__ __launch_bounds__(256) void conv_first_fwd_mfma_kernel(const bf16_t *
             const bf16x8 lo0 = gather8_scattered<tapoff(0), tapoff(1), tapoff(2), tapoff(3), tapoff(4), tapoff(5), tapoff(6), tapoff(7)>(p);
             const bf16x8 hi0 = gather8_scattered<tapoff(8), tapoff(9), tapoff(10), tapoff(11), tapoff(12), tapoff(13), tapoff(14), tapoff(15)>(p);
             const bf16x8 lo1 = gather8_scattered<tapoff(16), tapoff(17), tapoff(18), tapoff(19), tapoff(20), tapoff(21), tapoff(22), tapoff(23)>(p);
-            bf16x8 hi1 = gather8_scattered<tapoff(24), tapoff(25), tapoff(26), tapoff(26), tapoff(26), tapoff(26), tapoff(26), tapoff(26)>(p);
-#pragma unroll
-            for (int e = 3; e < 8; ++e) hi1[e] = (__bf16)0.f;   // rows 27-31 of the contraction do not exist
+            bf16x8 hi1;                                         // taps 24-26; rows 27-31 of the contraction do not exist
+            {
+                typedef __attribute__((ext_vector_type(8))) unsigned short u16x8;
+                u16x8 v = {0, 0, 0, 0, 0, 0, 0, 0};
+                v[0] = *reinterpret_cast<const volatile unsigned short *>(p + tapoff(24));
+                v[1] = *reinterpret_cast<const volatile unsigned short *>(p + tapoff(25));
+                v[2] = *reinterpret_cast<const volatile unsigned short *>(p + tapoff(26));
+                hi1 = __builtin_bit_cast(bf16x8, v);
+            }
             const bf16x8 b0 = hb ? hi0 : lo0, b1 = hb ? hi1 : lo1;
 #pragma unroll
             for (int mb = 0; mb < MB; ++mb) {
