@@ -39,7 +39,7 @@ static int scratch_for_current_device(void **ptr)
 
 extern "C" {
 
-int k3_version(void) { return 103; }
+int k3_version(void) { return 104; }
 int k3_last_hip_error(void) { return g_last_hip_error; }
 
 const char *k3_status_string(int s)

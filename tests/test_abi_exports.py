@@ -15,7 +15,7 @@ def test_every_declared_symbol_is_exported():
     lib = k3.lib()
     missing = [n for n in names if not hasattr(lib, n)]
     assert not missing, missing
-    assert k3.version() == 103
+    assert k3.version() == 104
     assert k3.status_string(k3.E_STATE) == "illegal swap-state transition"
 
 
